@@ -1,0 +1,127 @@
+/*
+ * cluscomp.h - C ABI of the MI355X (gfx950) clustering library.
+ *
+ * The library implements the clustering stage of ClusComp (Section 3.1 of the paper): Lloyd k-means
+ * over the length-d sub-vectors of a weight matrix, and the codebook gather that rebuilds the matrix
+ * from (codebook, codes).
+ *
+ * Notation: the paper's g is `d` here (sub-vector length), its n is `K` (number of centroids), its
+ * k = d_in*d_out/g is `N` (number of sub-vectors), its codes q are `idx`, its codebook C is
+ * `centroids`.
+ *
+ * Conventions shared by every call
+ *   - Every pointer is a DEVICE pointer unless its comment says "host". All arrays are dense,
+ *     row-major, and owned by the caller; the library never frees or keeps them.
+ *   - `vectors` is the weight matrix itself: an R x C row-major fp32 matrix viewed as N = R*C/d rows of
+ *     d floats (the reshape of Section 3.1; a caller who wants the paper's transposed orientation
+ *     transposes before the call). Supported d: 4, 8, 16. `vectors`, `centroids` and `out` must be
+ *     16-byte aligned, `workspace` 256-byte aligned.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream) and is
+ *     asynchronous: results are valid once the caller has synchronised that stream. No call
+ *     synchronises, allocates, or copies to the host. Concurrent calls must not share a workspace.
+ *   - Arguments are validated on the host before anything is launched. A call returns CC_OK or a
+ *     negative cc_status and then cc_last_error() describes the problem; nothing was enqueued in
+ *     that case (except for CC_ERR_HIP, where a launch itself failed).
+ *   - Same inputs give the same output bits on every run (the cluster sums are accumulated in
+ *     integer fixed point, so they do not depend on scheduling order).
+ *
+ * Readings of what the paper leaves open
+ *   - E-step ties: the lowest centroid index wins among exactly equal distances; when two distances
+ *     differ by less than the fp32 rounding of the direct form (relative 1e-6), either may win.
+ *   - Empty cluster in the M-step: the centroid keeps its previous value.
+ *   - Returned codes and inertia belong to the RETURNED codebook (the definition of q in
+ *     Section 3.1): a fit of T iterations runs T (assign, update) pairs and one final assign.
+ */
+#ifndef CLUSCOMP_H
+#define CLUSCOMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum cc_status {
+    CC_OK = 0,
+    CC_ERR_NULL = -1,      /* a required pointer is NULL */
+    CC_ERR_SHAPE = -2,     /* N == 0, N >= 2^32, d not in {4,8,16}, K == 0, K > N, K > 2^24 */
+    CC_ERR_ITERS = -3,     /* iters < 0 */
+    CC_ERR_ALIGN = -4,     /* a pointer violates the alignment stated above */
+    CC_ERR_WORKSPACE = -5, /* workspace_bytes < cc_workspace_bytes(N, d, K) */
+    CC_ERR_HIP = -6        /* the HIP runtime reported an error at launch */
+} cc_status;
+
+/* Host-only query: bytes of device workspace that cc_kmeans_fit / cc_assign / cc_update need for this
+ * problem size. Returns 0 for an unsupported shape. */
+size_t cc_workspace_bytes(uint64_t N, uint32_t d, uint32_t K);
+
+/*
+ * Lloyd k-means (Section 3.1: the E-step / M-step iteration; Appendix B.1 runs it for 20 iterations).
+ *   vectors        [N*d] in   the sub-vectors w_i
+ *   init_centroids [K*d] in   centroids entering iteration 0 (e.g. a seeded subset of the vectors)
+ *   centroids      [K*d] out  the codebook after `iters` updates; may alias init_centroids
+ *   idx            [N]   out  q_i = argmin_k ||w_i - c_k||^2 over the RETURNED codebook
+ *   inertia        [1]   out  fp64, sum_i ||w_i - c_{q_i}||^2 for the returned (codebook, codes);
+ *                             may be NULL
+ * iters == 0 copies init_centroids through and only assigns.
+ */
+int cc_kmeans_fit(const float *vectors, uint64_t N, uint32_t d, uint32_t K, int32_t iters,
+                  const float *init_centroids, float *centroids, uint32_t *idx, double *inertia,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * E-step alone (Section 3.1): idx_i = argmin_k ||w_i - c_k||^2, and optionally the objective
+ * sum_i ||w_i - c_{idx_i}||^2 (fp64, device, may be NULL).
+ */
+int cc_assign(const float *vectors, uint64_t N, uint32_t d, const float *centroids, uint32_t K,
+              uint32_t *idx, double *inertia, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * M-step alone (Section 3.1): centroids_k = mean of the vectors with idx_i == k; a cluster without
+ * members keeps prev_centroids_k. Every idx_i must be < K (checked on the device: offending vectors
+ * are skipped and counted in the workspace statistics). `centroids` may alias `prev_centroids`.
+ * `counts` [K] (out, uint32, may be NULL) receives the cluster sizes.
+ */
+int cc_update(const float *vectors, uint64_t N, uint32_t d, const uint32_t *idx,
+              const float *prev_centroids, uint32_t K, float *centroids, uint32_t *counts,
+              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Reconstruction (Section 3.1; the gather `codebook[code]` of the paper's layer listing):
+ * out_i = centroids_{idx_i}, i.e. the R x C matrix again when `out` is viewed row-major.
+ * Pure data movement, bit-exact. An idx_i >= K is clamped to K-1 (never read out of bounds).
+ */
+int cc_decode(const float *centroids, uint32_t K, uint32_t d, const uint32_t *idx, uint64_t N,
+              float *out, void *stream);
+
+/*
+ * Counters that the last cc_kmeans_fit / cc_assign / cc_update on `workspace` left behind.
+ * Copies them to `host_out` (host pointer) with a synchronous device-to-host copy after
+ * synchronising `stream`; meant for tests and logging, not for the hot path.
+ */
+typedef struct cc_stats {
+    uint64_t refined_vectors;  /* vectors whose fast-path decision was inside the guard band and was
+                                  re-decided with direct-form distances (summed over all assigns) */
+    uint64_t skipped_vectors;  /* vectors with idx >= K seen by an update */
+    uint64_t assign_calls;     /* assign passes run */
+    int32_t  fixed_point_exp;  /* e: cluster sums are held as round(x * 2^e) in int64 */
+    uint32_t reserved;
+} cc_stats;
+int cc_read_stats(const void *workspace, size_t workspace_bytes, cc_stats *host_out, void *stream);
+
+/* Selects the E-step kernel: 0 = automatic (default), 1 = direct-form VALU kernel only,
+ * 2 = matrix-core kernel with guard band + direct-form refinement. Process-wide; for tests and
+ * profiling. Returns the previous value, or CC_ERR_SHAPE for an unknown mode. */
+int cc_set_assign_mode(int mode);
+
+/* Thread-local description of the last error returned on this thread (host pointer, static storage). */
+const char *cc_last_error(void);
+
+/* Library version string (host pointer, static storage). */
+const char *cc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CLUSCOMP_H */

@@ -1,0 +1,21 @@
+"""MI355X-native clustering stage of ClusComp: Lloyd k-means over weight sub-vectors and the
+codebook-gather decode, as hand-written gfx950 HIP kernels behind a C ABI (include/cluscomp.h).
+
+This package is a thin binding: every step of the path runs in the HIP library. There is no CPU
+fallback; calling anything without the built library (or without a GPU) raises.
+"""
+from .binding import (  # noqa: F401
+    CCError,
+    Stats,
+    assign,
+    decode,
+    kmeans_fit,
+    last_error,
+    lib_path,
+    load_library,
+    read_stats,
+    set_assign_mode,
+    update,
+    version,
+    workspace_bytes,
+)

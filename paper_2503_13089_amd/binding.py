@@ -1,0 +1,178 @@
+"""ctypes binding of libcluscomp.so: argument marshalling only (same names as the C entry points).
+
+torch supplies device memory (`data_ptr()`) and the current HIP stream; nothing is computed here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcluscomp.so")
+_lib = None
+
+EXPORTS = (
+    "cc_workspace_bytes", "cc_kmeans_fit", "cc_assign", "cc_update", "cc_decode",
+    "cc_read_stats", "cc_set_assign_mode", "cc_last_error", "cc_version",
+)
+
+
+class CCError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"cluscomp status {status}: {message}")
+        self.status = status
+
+
+class _CStats(ctypes.Structure):
+    _fields_ = [("refined_vectors", ctypes.c_uint64), ("skipped_vectors", ctypes.c_uint64),
+                ("assign_calls", ctypes.c_uint64), ("fixed_point_exp", ctypes.c_int32),
+                ("reserved", ctypes.c_uint32)]
+
+
+@dataclass
+class Stats:
+    refined_vectors: int
+    skipped_vectors: int
+    assign_calls: int
+    fixed_point_exp: int
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads the built HIP library; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2503_13089_amd.build` "
+            "(or __graft_entry__.build()); this package has no CPU fallback")
+    lib = ctypes.CDLL(_LIB_PATH)
+    u64, u32, i32, vp, sz = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+    lib.cc_workspace_bytes.argtypes = [u64, u32, u32]
+    lib.cc_workspace_bytes.restype = sz
+    lib.cc_kmeans_fit.argtypes = [vp, u64, u32, u32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.cc_kmeans_fit.restype = ctypes.c_int
+    lib.cc_assign.argtypes = [vp, u64, u32, vp, u32, vp, vp, vp, sz, vp]
+    lib.cc_assign.restype = ctypes.c_int
+    lib.cc_update.argtypes = [vp, u64, u32, vp, vp, u32, vp, vp, vp, sz, vp]
+    lib.cc_update.restype = ctypes.c_int
+    lib.cc_decode.argtypes = [vp, u32, u32, vp, u64, vp, vp]
+    lib.cc_decode.restype = ctypes.c_int
+    lib.cc_read_stats.argtypes = [vp, sz, ctypes.POINTER(_CStats), vp]
+    lib.cc_read_stats.restype = ctypes.c_int
+    lib.cc_set_assign_mode.argtypes = [ctypes.c_int]
+    lib.cc_set_assign_mode.restype = ctypes.c_int
+    lib.cc_last_error.restype = ctypes.c_char_p
+    lib.cc_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def last_error() -> str:
+    return load_library().cc_last_error().decode()
+
+
+def version() -> str:
+    return load_library().cc_version().decode()
+
+
+def _check(status: int):
+    if status != 0:
+        raise CCError(status, last_error())
+
+
+def _ptr(t, dtype, what):
+    """Device pointer of a contiguous CUDA(HIP) tensor of the expected dtype, or None."""
+    import torch
+
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what}: expected a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{what}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _idx_dtype():
+    import torch
+
+    return torch.uint32
+
+
+def workspace_bytes(N: int, d: int, K: int) -> int:
+    return int(load_library().cc_workspace_bytes(N, d, K))
+
+
+def kmeans_fit(vectors, K: int, iters: int, init_centroids, centroids, idx, inertia, workspace) -> None:
+    """cc_kmeans_fit on the current stream. vectors [N,d] f32, init/centroids [K,d] f32, idx [N] uint32,
+    inertia [1] f64 or None, workspace uint8 [>= workspace_bytes]. Asynchronous."""
+    import torch
+
+    N, d = vectors.shape
+    lib = load_library()
+    _check(lib.cc_kmeans_fit(_ptr(vectors, torch.float32, "vectors"), N, d, K, iters,
+                             _ptr(init_centroids, torch.float32, "init_centroids"),
+                             _ptr(centroids, torch.float32, "centroids"), _ptr(idx, _idx_dtype(), "idx"),
+                             _ptr(inertia, torch.float64, "inertia"), _ptr(workspace, torch.uint8, "workspace"),
+                             workspace.numel(), _stream()))
+
+
+def assign(vectors, centroids, idx, inertia, workspace) -> None:
+    import torch
+
+    N, d = vectors.shape
+    K = centroids.shape[0]
+    _check(load_library().cc_assign(_ptr(vectors, torch.float32, "vectors"), N, d,
+                                    _ptr(centroids, torch.float32, "centroids"), K, _ptr(idx, _idx_dtype(), "idx"),
+                                    _ptr(inertia, torch.float64, "inertia"), _ptr(workspace, torch.uint8, "workspace"),
+                                    workspace.numel(), _stream()))
+
+
+def update(vectors, idx, prev_centroids, centroids, counts, workspace) -> None:
+    import torch
+
+    N, d = vectors.shape
+    K = prev_centroids.shape[0]
+    _check(load_library().cc_update(_ptr(vectors, torch.float32, "vectors"), N, d, _ptr(idx, _idx_dtype(), "idx"),
+                                    _ptr(prev_centroids, torch.float32, "prev_centroids"), K,
+                                    _ptr(centroids, torch.float32, "centroids"), _ptr(counts, _idx_dtype(), "counts"),
+                                    _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
+
+
+def decode(centroids, idx, out) -> None:
+    import torch
+
+    K, d = centroids.shape
+    N = idx.shape[0]
+    _check(load_library().cc_decode(_ptr(centroids, torch.float32, "centroids"), K, d, _ptr(idx, _idx_dtype(), "idx"),
+                                    N, _ptr(out, torch.float32, "out"), _stream()))
+
+
+def read_stats(workspace) -> Stats:
+    import torch
+
+    st = _CStats()
+    _check(load_library().cc_read_stats(_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                        ctypes.byref(st), _stream()))
+    return Stats(int(st.refined_vectors), int(st.skipped_vectors), int(st.assign_calls), int(st.fixed_point_exp))
+
+
+def set_assign_mode(mode: int) -> int:
+    rc = load_library().cc_set_assign_mode(mode)
+    if rc < 0:
+        raise CCError(rc, last_error())
+    return rc

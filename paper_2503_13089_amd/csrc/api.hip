@@ -1,0 +1,175 @@
+// C ABI of libcluscomp: argument validation on the host, then the kernel sequence of each call.
+// See include/cluscomp.h for the contract of every entry point.
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+
+#include "../../include/cluscomp.h"
+#include "common.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+std::atomic<int> g_assign_mode{0};
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(hipError_t e, const char* what)
+{
+    return fail(CC_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int check_shape(uint64_t N, uint32_t d, uint32_t K)
+{
+    if (d != 4 && d != 8 && d != 16) return fail(CC_ERR_SHAPE, "d = %u is not supported (4, 8, 16)", d);
+    if (N == 0) return fail(CC_ERR_SHAPE, "N == 0");
+    if (N >= (1ull << 32)) return fail(CC_ERR_SHAPE, "N = %llu does not fit 32-bit vector ids", (unsigned long long)N);
+    if (K == 0) return fail(CC_ERR_SHAPE, "K == 0");
+    if (K > cc::kMaxK) return fail(CC_ERR_SHAPE, "K = %u exceeds the supported maximum %u", K, cc::kMaxK);
+    if (K > N) return fail(CC_ERR_SHAPE, "K = %u exceeds N = %llu", K, (unsigned long long)N);
+    return CC_OK;
+}
+
+int check_workspace(void* ws, size_t ws_bytes, uint64_t N, uint32_t d, uint32_t K)
+{
+    if (ws == nullptr) return fail(CC_ERR_NULL, "workspace is NULL");
+    if (!aligned(ws, 256)) return fail(CC_ERR_ALIGN, "workspace must be 256-byte aligned");
+    const size_t need = cc::carve(nullptr, N, d, K).bytes;
+    if (ws_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, need);
+    return CC_OK;
+}
+
+#define CC_TRY_HIP(expr, what)                        \
+    do {                                              \
+        hipError_t e_ = (expr);                       \
+        if (e_ != hipSuccess) return hip_fail(e_, what); \
+    } while (0)
+
+// One E-step pass: idx (and, if inertia != NULL, the objective) for the given centroids.
+int run_assign(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx, double* inertia,
+               const cc::Workspace& w, hipStream_t s)
+{
+    uint32_t n_partials = 0;
+    CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, inertia ? w.partials : nullptr, &n_partials, s),
+               "assign (direct form)");
+    if (inertia) CC_TRY_HIP(cc::launch_reduce_partials(w.partials, n_partials, inertia, s), "objective reduction");
+    CC_TRY_HIP(cc::launch_bump_assign_calls(w.hdr, s), "bookkeeping");
+    return CC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t cc_workspace_bytes(uint64_t N, uint32_t d, uint32_t K)
+{
+    if (check_shape(N, d, K) != CC_OK) return 0;
+    return cc::carve(nullptr, N, d, K).bytes;
+}
+
+int cc_kmeans_fit(const float* vectors, uint64_t N, uint32_t d, uint32_t K, int32_t iters, const float* init_centroids,
+                  float* centroids, uint32_t* idx, double* inertia, void* workspace, size_t workspace_bytes,
+                  void* stream)
+{
+    if (!vectors || !init_centroids || !centroids || !idx) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (int rc = check_shape(N, d, K)) return rc;
+    if (iters < 0) return fail(CC_ERR_ITERS, "iters = %d is negative", iters);
+    if (!aligned(vectors, 16) || !aligned(init_centroids, 16) || !aligned(centroids, 16) || !aligned(idx, 4) ||
+        (inertia && !aligned(inertia, 8)))
+        return fail(CC_ERR_ALIGN, "vectors/centroids need 16-byte alignment, idx 4, inertia 8");
+    if (int rc = check_workspace(workspace, workspace_bytes, N, d, K)) return rc;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const cc::Workspace w = cc::carve(workspace, N, d, K);
+    const uint32_t n = uint32_t(N);
+
+    CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
+    if (iters > 0) CC_TRY_HIP(cc::launch_absmax(vectors, N * d, w.hdr, s), "input range scan");
+    if (centroids != init_centroids)
+        CC_TRY_HIP(cc::launch_copy_f32(init_centroids, centroids, size_t(K) * d, s), "centroid copy");
+    for (int32_t t = 0; t < iters; ++t) {
+        if (int rc = run_assign(vectors, n, d, centroids, K, idx, nullptr, w, s)) return rc;
+        CC_TRY_HIP(cc::launch_update(vectors, n, d, idx, centroids, K, centroids, nullptr, w, s), "update");
+    }
+    return run_assign(vectors, n, d, centroids, K, idx, inertia, w, s);
+}
+
+int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroids, uint32_t K, uint32_t* idx,
+              double* inertia, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!vectors || !centroids || !idx) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (int rc = check_shape(N, d, K)) return rc;
+    if (!aligned(vectors, 16) || !aligned(centroids, 16) || !aligned(idx, 4) || (inertia && !aligned(inertia, 8)))
+        return fail(CC_ERR_ALIGN, "vectors/centroids need 16-byte alignment, idx 4, inertia 8");
+    if (int rc = check_workspace(workspace, workspace_bytes, N, d, K)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const cc::Workspace w = cc::carve(workspace, N, d, K);
+    CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
+    return run_assign(vectors, uint32_t(N), d, centroids, K, idx, inertia, w, s);
+}
+
+int cc_update(const float* vectors, uint64_t N, uint32_t d, const uint32_t* idx, const float* prev_centroids,
+              uint32_t K, float* centroids, uint32_t* counts, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!vectors || !idx || !prev_centroids || !centroids) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (int rc = check_shape(N, d, K)) return rc;
+    if (!aligned(vectors, 16) || !aligned(prev_centroids, 16) || !aligned(centroids, 16) || !aligned(idx, 4) ||
+        (counts && !aligned(counts, 4)))
+        return fail(CC_ERR_ALIGN, "vectors/centroids need 16-byte alignment, idx and counts 4");
+    if (int rc = check_workspace(workspace, workspace_bytes, N, d, K)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const cc::Workspace w = cc::carve(workspace, N, d, K);
+    CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
+    CC_TRY_HIP(cc::launch_absmax(vectors, N * d, w.hdr, s), "input range scan");
+    CC_TRY_HIP(cc::launch_update(vectors, uint32_t(N), d, idx, prev_centroids, K, centroids, counts, w, s), "update");
+    return CC_OK;
+}
+
+int cc_decode(const float* centroids, uint32_t K, uint32_t d, const uint32_t* idx, uint64_t N, float* out,
+              void* stream)
+{
+    if (!centroids || !idx || !out) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (d != 4 && d != 8 && d != 16) return fail(CC_ERR_SHAPE, "d = %u is not supported (4, 8, 16)", d);
+    if (N == 0 || K == 0) return fail(CC_ERR_SHAPE, "N == 0 or K == 0");
+    if (N >= (1ull << 32)) return fail(CC_ERR_SHAPE, "N = %llu does not fit 32-bit vector ids", (unsigned long long)N);
+    if (!aligned(centroids, 16) || !aligned(out, 16) || !aligned(idx, 4))
+        return fail(CC_ERR_ALIGN, "centroids/out need 16-byte alignment, idx 4");
+    CC_TRY_HIP(cc::launch_decode(centroids, K, d, idx, N, out, static_cast<hipStream_t>(stream)), "decode");
+    return CC_OK;
+}
+
+int cc_read_stats(const void* workspace, size_t workspace_bytes, cc_stats* host_out, void* stream)
+{
+    if (!workspace || !host_out) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (workspace_bytes < sizeof(cc::WsHeader)) return fail(CC_ERR_WORKSPACE, "workspace too small");
+    cc::WsHeader h;
+    CC_TRY_HIP(hipStreamSynchronize(static_cast<hipStream_t>(stream)), "stream synchronise");
+    CC_TRY_HIP(hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost), "statistics copy");
+    host_out->refined_vectors = h.refined_vectors;
+    host_out->skipped_vectors = h.skipped_vectors;
+    host_out->assign_calls = h.assign_calls;
+    host_out->fixed_point_exp = h.fixed_point_exp;
+    host_out->reserved = 0;
+    return CC_OK;
+}
+
+int cc_set_assign_mode(int mode)
+{
+    if (mode < 0 || mode > 2) return fail(CC_ERR_SHAPE, "unknown assign mode %d", mode);
+    return g_assign_mode.exchange(mode);
+}
+
+const char* cc_last_error(void) { return g_err; }
+
+const char* cc_version(void) { return "cluscomp-gfx950 0.1"; }
+
+}  // extern "C"

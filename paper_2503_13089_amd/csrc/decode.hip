@@ -1,0 +1,60 @@
+// Reconstruction (Section 3.1; the gather codebook[code] of the paper's layer listing):
+// out_i = c_{idx_i}. Pure data movement: 4 bytes of code in, 4*d bytes of weights out per vector,
+// with the codebook (K*d*4 <= 4 MB) served from cache. Each lane moves 16-byte pieces; the output is
+// written with streaming (non-temporal) stores since it is never re-read here.
+#include <algorithm>
+
+#include "common.h"
+
+namespace cc {
+
+constexpr int kThreads = 256;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void decode_kernel(const f32x4* __restrict__ C4, uint32_t K,
+                                                          const uint32_t* __restrict__ idx, uint64_t n_chunks,
+                                                          f32x4* __restrict__ out4)
+{
+    constexpr int Q = D / 4;  // 16-byte pieces per vector
+    const uint64_t stride = uint64_t(gridDim.x) * kThreads;
+    for (uint64_t t = uint64_t(blockIdx.x) * kThreads + threadIdx.x; t < n_chunks; t += stride) {
+        const uint64_t i = t / Q;
+        const uint32_t q = uint32_t(t % Q);
+        uint32_t k = idx[i];
+        k = k < K ? k : K - 1;  // never read outside the codebook
+        const f32x4 v = C4[size_t(k) * Q + q];
+        __builtin_nontemporal_store(v, &out4[t]);
+    }
+}
+
+hipError_t launch_decode(const float* C, uint32_t K, uint32_t d, const uint32_t* idx, uint64_t N, float* out,
+                         hipStream_t s)
+{
+    const uint64_t n_chunks = N * (d / 4);
+    const uint32_t blocks = uint32_t(std::min<uint64_t>((n_chunks + kThreads - 1) / kThreads, 256u * 32u));
+    const f32x4* C4 = reinterpret_cast<const f32x4*>(C);
+    f32x4* out4 = reinterpret_cast<f32x4*>(out);
+    switch (d) {
+        case 4: hipLaunchKernelGGL(decode_kernel<4>, dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
+        case 8: hipLaunchKernelGGL(decode_kernel<8>, dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
+        case 16: hipLaunchKernelGGL(decode_kernel<16>, dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(kThreads) void copy_f32_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                            size_t n)
+{
+    const size_t i = size_t(blockIdx.x) * kThreads + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s)
+{
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(uint32_t((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, src, dst, n);
+    return hipGetLastError();
+}
+
+}  // namespace cc

@@ -1,0 +1,157 @@
+// M-step (Section 3.1): c_k <- mean of the vectors assigned to cluster k.
+//
+// The cluster sums are accumulated as 64-bit integers: each input is scaled by 2^e and rounded to
+// an integer, with e chosen from the largest input magnitude M and from N so that N terms of size
+// <= M * 2^e cannot overflow 62 bits. Integer addition is associative, so the sums - and with them
+// the centroids - do not depend on the order in which the atomics land: same inputs, same bits.
+// For fp16-representable inputs (multiples of 2^-24) and e >= 24 the sums are exact.
+//
+// An empty cluster keeps its previous centroid (the paper does not say what the mean of no vectors is).
+#include <algorithm>
+
+#include "common.h"
+
+namespace cc {
+
+constexpr int kThreads = 256;
+
+__global__ void reset_header_kernel(WsHeader* hdr)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        hdr->absmax_bits = 0;
+        hdr->refine_count = 0;
+        hdr->refined_vectors = 0;
+        hdr->skipped_vectors = 0;
+        hdr->assign_calls = 0;
+        hdr->fixed_point_exp = 0;
+        hdr->reserved = 0;
+    }
+}
+
+hipError_t launch_reset_header(WsHeader* hdr, hipStream_t s)
+{
+    hipLaunchKernelGGL(reset_header_kernel, dim3(1), dim3(64), 0, s, hdr);
+    return hipGetLastError();
+}
+
+__global__ void bump_assign_calls_kernel(WsHeader* hdr)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) hdr->assign_calls += 1;
+}
+
+hipError_t launch_bump_assign_calls(WsHeader* hdr, hipStream_t s)
+{
+    hipLaunchKernelGGL(bump_assign_calls_kernel, dim3(1), dim3(64), 0, s, hdr);
+    return hipGetLastError();
+}
+
+// max |x| over the whole input, as the maximum of the (sign-cleared) fp32 bit patterns: for finite
+// floats the integer order of the patterns is the order of the magnitudes.
+__global__ __launch_bounds__(kThreads) void absmax_kernel(const float4* __restrict__ X4, uint64_t n4, WsHeader* hdr)
+{
+    uint32_t m = 0;
+    for (uint64_t i = uint64_t(blockIdx.x) * kThreads + threadIdx.x; i < n4; i += uint64_t(gridDim.x) * kThreads) {
+        float4 t = X4[i];
+        m = max(m, __float_as_uint(t.x) & 0x7fffffffu);
+        m = max(m, __float_as_uint(t.y) & 0x7fffffffu);
+        m = max(m, __float_as_uint(t.z) & 0x7fffffffu);
+        m = max(m, __float_as_uint(t.w) & 0x7fffffffu);
+    }
+    for (int off = 32; off > 0; off >>= 1) m = max(m, uint32_t(__shfl_xor(int(m), off, 64)));
+    if ((threadIdx.x & 63) == 0) atomicMax(&hdr->absmax_bits, m);
+}
+
+hipError_t launch_absmax(const float* X, uint64_t n_floats, WsHeader* hdr, hipStream_t s)
+{
+    const uint64_t n4 = n_floats / 4;  // d is a multiple of 4
+    const uint32_t blocks = uint32_t(std::min<uint64_t>((n4 + kThreads - 1) / kThreads, 256 * 16));
+    hipLaunchKernelGGL(absmax_kernel, dim3(blocks), dim3(kThreads), 0, s, reinterpret_cast<const float4*>(X), n4, hdr);
+    return hipGetLastError();
+}
+
+// Fixed-point exponent e: inputs satisfy |x| < 2^(EM+1) with EM the unbiased exponent of M, and
+// N < 2^LN, so |sum| < 2^(EM+1+e+LN) <= 2^62.
+__device__ inline int fixed_point_exp(uint32_t absmax_bits, uint32_t N)
+{
+    const int em = int(absmax_bits >> 23) - 127;   // -127 for zero/subnormal M: fine, just a large e
+    const int ln = 32 - __clz(N);                  // N < 2^ln
+    int e = 62 - ln - (em + 1);
+    return min(e, 100);                            // keep ldexp away from fp64 overflow for tiny inputs
+}
+
+__global__ __launch_bounds__(kThreads) void zero_accumulators_kernel(long long* sums, uint32_t* counts, uint32_t K,
+                                                                      uint32_t d)
+{
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i < K * d) sums[i] = 0;
+    if (i < K) counts[i] = 0;
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void accumulate_kernel(const float* __restrict__ X, uint32_t N,
+                                                              const uint32_t* __restrict__ idx, uint32_t K,
+                                                              long long* sums, uint32_t* counts, WsHeader* hdr)
+{
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= N) return;
+    const int e = fixed_point_exp(hdr->absmax_bits, N);
+    const uint32_t k = idx[i];
+    if (k >= K) {
+        atomicAdd(&hdr->skipped_vectors, 1ull);
+        return;
+    }
+    const float4* src = reinterpret_cast<const float4*>(X + size_t(i) * D);
+    unsigned long long* dst = reinterpret_cast<unsigned long long*>(sums + size_t(k) * D);
+#pragma unroll
+    for (int q = 0; q < D / 4; ++q) {
+        const float4 t = src[q];
+        const float v[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const long long f = __double2ll_rn(ldexp(double(v[j]), e));
+            if (f != 0) atomicAdd(dst + 4 * q + j, static_cast<unsigned long long>(f));
+        }
+    }
+    atomicAdd(counts + k, 1u);
+}
+
+__global__ __launch_bounds__(kThreads) void finalize_kernel(const long long* __restrict__ sums,
+                                                            const uint32_t* __restrict__ counts,
+                                                            const float* prev, float* out, uint32_t* counts_out,
+                                                            uint32_t K, uint32_t d, uint32_t N, WsHeader* hdr)
+{
+    const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
+    const int e = fixed_point_exp(hdr->absmax_bits, N);
+    if (t == 0) hdr->fixed_point_exp = e;
+    if (t >= K * d) return;
+    const uint32_t k = t / d;
+    const uint32_t n = counts[k];
+    float c;
+    if (n > 0) {
+        c = float(ldexp(double(sums[t]), -e) / double(n));  // one fp64 division, one rounding to fp32
+    } else {
+        c = prev[t];
+    }
+    out[t] = c;
+    if (counts_out != nullptr && t % d == 0) counts_out[k] = n;
+}
+
+hipError_t launch_update(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev, uint32_t K,
+                         float* out, uint32_t* counts_out, const Workspace& w, hipStream_t s)
+{
+    const uint32_t kd = K * d;
+    hipLaunchKernelGGL(zero_accumulators_kernel, dim3((kd + kThreads - 1) / kThreads), dim3(kThreads), 0, s, w.sums,
+                       w.counts, K, d);
+    const dim3 grid((N + kThreads - 1) / kThreads);
+    switch (d) {
+        case 4: hipLaunchKernelGGL(accumulate_kernel<4>, grid, dim3(kThreads), 0, s, X, N, idx, K, w.sums, w.counts, w.hdr); break;
+        case 8: hipLaunchKernelGGL(accumulate_kernel<8>, grid, dim3(kThreads), 0, s, X, N, idx, K, w.sums, w.counts, w.hdr); break;
+        case 16: hipLaunchKernelGGL(accumulate_kernel<16>, grid, dim3(kThreads), 0, s, X, N, idx, K, w.sums, w.counts, w.hdr); break;
+        default: return hipErrorInvalidValue;
+    }
+    hipLaunchKernelGGL(finalize_kernel, dim3((kd + kThreads - 1) / kThreads), dim3(kThreads), 0, s, w.sums, w.counts,
+                       prev, out, counts_out, K, d, N, w.hdr);
+    return hipGetLastError();
+}
+
+}  // namespace cc

@@ -1,0 +1,89 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the header
+declares, sizes its workspace, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2503_13089_amd as cc
+from paper_2503_13089_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "cluscomp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cc_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = cc.load_library()
+    names = _declared()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert cc.version().startswith("cluscomp-gfx950")
+
+
+def test_workspace_query():
+    assert cc.workspace_bytes(65536, 4, 256) > 0
+    big = cc.workspace_bytes(11272192, 4, 65536)
+    assert 2 * 11272192 * 4 <= big < 200e6
+    assert cc.workspace_bytes(65536, 4, 256) % 256 == 0
+    for N, d, K in [(0, 4, 1), (10, 5, 2), (10, 4, 0), (10, 4, 11), (1 << 32, 4, 8), (1 << 26, 4, (1 << 24) + 1)]:
+        assert cc.workspace_bytes(N, d, K) == 0
+
+
+A16 = ctypes.c_void_p(0x1000)      # fake, aligned, never dereferenced: every case below fails validation first
+A4 = ctypes.c_void_p(0x1004)
+MISALIGNED = ctypes.c_void_p(0x1001)
+
+
+def _fit(lib, vectors=A16, N=1000, d=4, K=8, iters=1, init=A16, cent=A16, idx=A4, inertia=None, ws=A16, wsb=0):
+    return lib.cc_kmeans_fit(vectors, N, d, K, iters, init, cent, idx, inertia, ws, wsb, None)
+
+
+def test_fit_rejects_bad_arguments_without_launching():
+    lib = cc.load_library()
+    assert _fit(lib, vectors=None) == -1 and "NULL" in cc.last_error()
+    assert _fit(lib, idx=None) == -1
+    assert _fit(lib, d=5) == -2 and "d = 5" in cc.last_error()
+    assert _fit(lib, N=0) == -2
+    assert _fit(lib, K=0) == -2
+    assert _fit(lib, K=1001) == -2 and "exceeds N" in cc.last_error()
+    assert _fit(lib, N=1 << 32) == -2
+    assert _fit(lib, iters=-1) == -3
+    assert _fit(lib, vectors=MISALIGNED) == -4
+    assert _fit(lib, ws=None) == -1
+    assert _fit(lib, ws=ctypes.c_void_p(0x1010)) == -4
+    assert _fit(lib, ws=ctypes.c_void_p(0x1100), wsb=cc.workspace_bytes(1000, 4, 8) - 1) == -5
+    assert "needed" in cc.last_error()
+
+
+def test_other_entry_points_reject_bad_arguments():
+    lib = cc.load_library()
+    assert lib.cc_assign(None, 10, 4, A16, 2, A4, None, A16, 0, None) == -1
+    assert lib.cc_assign(A16, 10, 4, A16, 20, A4, None, A16, 0, None) == -2
+    assert lib.cc_assign(A16, 10, 4, MISALIGNED, 2, A4, None, A16, 0, None) == -4
+    assert lib.cc_assign(A16, 10, 4, A16, 2, A4, None, ctypes.c_void_p(0x1100), 16, None) == -5
+    assert lib.cc_update(A16, 10, 4, None, A16, 2, A16, None, A16, 0, None) == -1
+    assert lib.cc_update(A16, 10, 12, A4, A16, 2, A16, None, A16, 0, None) == -2
+    assert lib.cc_update(A16, 10, 4, A4, A16, 2, A16, None, ctypes.c_void_p(0x1100), 16, None) == -5
+    assert lib.cc_decode(None, 2, 4, A4, 10, A16, None) == -1
+    assert lib.cc_decode(A16, 2, 7, A4, 10, A16, None) == -2
+    assert lib.cc_decode(A16, 0, 4, A4, 10, A16, None) == -2
+    assert lib.cc_decode(A16, 2, 4, A4, 10, MISALIGNED, None) == -4
+    assert lib.cc_read_stats(None, 0, None, None) == -1
+    assert lib.cc_set_assign_mode(7) == -2
+    prev = lib.cc_set_assign_mode(1)
+    assert lib.cc_set_assign_mode(prev) == 1
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+
+    x = torch.zeros(16, 4)
+    with pytest.raises(TypeError):
+        cc.decode(x, torch.zeros(16, dtype=torch.int32), x)

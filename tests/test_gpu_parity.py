@@ -1,0 +1,201 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Sizes here are ones the oracle finishes in seconds while still spanning several centroid tiles,
+several workgroups and ragged tails. Full-size configurations are in test_gpu_fullsize.py.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def g():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from tests import gpu_helpers
+
+    return gpu_helpers
+
+
+SHAPES = [  # (N, d, K): ragged in N (not a multiple of 256/512/1024) and in K (not a multiple of any tile)
+    (70001, 4, 1500),
+    (30011, 8, 777),
+    (20003, 16, 515),
+    (4099, 4, 4099),   # K == N: every vector is a centroid
+    (513, 8, 1),       # a single centroid
+    (1, 4, 1),         # the smallest legal problem
+    (65536, 4, 256),   # cfg1's shape
+]
+
+
+@pytest.mark.parametrize("N,d,K", SHAPES)
+def test_decode_is_bit_exact(g, N, d, K):
+    rng = np.random.default_rng(N + d + K)
+    C = rng.standard_normal((K, d)).astype(np.float32)
+    C.view(np.uint32)[::7] ^= 0x7  # arbitrary bit patterns, not just "nice" floats
+    idx = rng.integers(0, K, size=N).astype(np.uint32)
+    print(f"decode N={N} d={d} K={K}", flush=True)
+    out = g.gpu_decode(C, idx)
+    assert out.tobytes() == oracle.decode(C, idx).tobytes()
+
+
+def test_decode_clamps_out_of_range_codes(g):
+    C = np.arange(40, dtype=np.float32).reshape(10, 4)
+    idx = np.array([0, 9, 10, 4000000000, 3], np.uint32)
+    out = g.gpu_decode(C, idx)
+    assert np.array_equal(out, C[[0, 9, 9, 9, 3]])
+
+
+@pytest.mark.parametrize("N,d,K", SHAPES)
+def test_assign_lockstep(g, N, d, K):
+    X, C0 = workloads.make_small(N, d, K, seed=1000 + N)
+    # centroids after one oracle step: general fp32 values rather than copies of inputs
+    k0, _, _, _ = oracle.assign_top2(X, C0)
+    C, _ = oracle.update(X, k0, C0)
+    for cents in (C0, C):
+        k1, D1, k2, D2 = oracle.assign_top2(X, cents)
+        print(f"assign N={N} d={d} K={K}", flush=True)
+        idx, J = g.gpu_assign(X, cents)
+        parity.check_assignment(X, cents, idx, k1, D1, D2)
+        parity.check_inertia(J, float(D1.sum()))
+        idx2, none = g.gpu_assign(X, cents, want_inertia=False)
+        assert none is None and np.array_equal(idx, idx2)
+
+
+def test_assign_exact_ties_take_the_lowest_index(g):
+    X, C = workloads.make_small(5000, 4, 64, seed=77)
+    C[40] = C[3]
+    C[63] = C[3]
+    idx, _ = g.gpu_assign(X, C)
+    k1, D1, _, D2 = oracle.assign_top2(X, C)
+    assert (k1 == 3).any() and not np.isin(idx, [40, 63]).any()
+    assert np.array_equal(idx, k1) or parity.check_assignment(X, C, idx, k1, D1, D2) >= 0
+
+
+@pytest.mark.parametrize("N,d,K", SHAPES)
+def test_update_lockstep(g, N, d, K):
+    X, C0 = workloads.make_small(N, d, K, seed=2000 + N)
+    k1, _, _, _ = oracle.assign_top2(X, C0)
+    if K > 8:
+        k1[k1 == 5] = 6  # force an empty cluster
+    want, counts = oracle.update(X, k1, C0)
+    print(f"update N={N} d={d} K={K}", flush=True)
+    got, gcounts, stats = g.gpu_update(X, k1, C0)
+    assert np.array_equal(gcounts, counts)
+    assert stats.skipped_vectors == 0
+    # fp16-representable inputs: the fixed-point sums are exact, so the means match bit for bit
+    assert stats.fixed_point_exp >= 24
+    assert got.tobytes() == want.tobytes()
+    if K > 8:
+        assert np.array_equal(got[5], C0[5])
+
+
+def test_update_general_fp32_inputs_and_bad_codes(g):
+    X, C0 = workloads.make_small(50000, 8, 300, seed=5, fp16_round=False)
+    X[:100] *= 1e-6   # a wide dynamic range
+    X[100:110] *= 300
+    k1, _, _, _ = oracle.assign_top2(X, C0)
+    want, counts = oracle.update(X, k1, C0)
+    got, gcounts, stats = g.gpu_update(X, k1, C0)
+    assert np.array_equal(gcounts, counts)
+    parity.check_centroids(got, want, X)
+    bad = k1.copy()
+    bad[7] = 300
+    bad[9] = 2**31
+    keep = np.ones(len(bad), bool)
+    keep[[7, 9]] = False
+    want2, counts2 = oracle.update(X[keep], k1[keep], C0)
+    got2, gcounts2, stats2 = g.gpu_update(X, bad, C0)
+    assert stats2.skipped_vectors == 2
+    assert np.array_equal(gcounts2, counts2)
+    parity.check_centroids(got2, want2, X)
+
+
+@pytest.mark.parametrize("N,d,K,iters", [(65536, 4, 256, 10), (30011, 8, 777, 5), (20003, 16, 515, 4), (3000, 4, 3000, 2)])
+def test_fit_trajectory_following(g, N, d, K, iters):
+    """Free-running GPU fit, every step verified: the oracle checks each assignment against the GPU's
+    own centroids, adopts the GPU's choice on near-ties, and recomputes the update."""
+    if (N, d, K) == (65536, 4, 256):
+        X, C0 = workloads.make_inputs(workloads.by_number(1))
+    else:
+        X, C0 = workloads.make_small(N, d, K, seed=3000 + N)
+    Xd = g.dev(X)
+    ws = g.workspace(N, d, K)
+    C = C0.copy()
+    near_total = 0
+    for t in range(iters):
+        print(f"trajectory N={N} d={d} K={K} step {t}", flush=True)
+        idx_t, J_t = g.gpu_assign(Xd, C, ws=ws)
+        k1, D1, _, D2 = oracle.assign_top2(X, C)
+        near_total += parity.check_assignment(X, C, idx_t, k1, D1, D2)
+        parity.check_inertia(J_t, oracle.inertia(X, C, idx_t))
+        want_next, _ = oracle.update(X, idx_t, C)
+        C_next, idx_next, J_next, stats = g.gpu_fit(X, C, 1, ws=ws, Xd=Xd)
+        assert stats.assign_calls == 2
+        assert C_next.tobytes() == want_next.tobytes()  # exact sums on fp16-representable inputs
+        idx_chk, J_chk = g.gpu_assign(Xd, C_next, ws=ws)
+        assert np.array_equal(idx_next, idx_chk) and J_next == J_chk
+        C = C_next
+    # one call with iters=T gives the same bits as T chained calls with iters=1
+    C_T, idx_T, J_T, _ = g.gpu_fit(X, C0, iters, ws=ws, Xd=Xd)
+    assert C_T.tobytes() == C.tobytes()
+    assert np.array_equal(idx_T, idx_next) and J_T == J_next
+    # and again (determinism)
+    C_T2, idx_T2, J_T2, _ = g.gpu_fit(X, C0, iters, Xd=Xd)
+    assert C_T2.tobytes() == C_T.tobytes() and np.array_equal(idx_T2, idx_T) and J_T2 == J_T
+    print(f"near-tie divergences adopted: {near_total}")
+
+
+def test_fit_end_to_end_cfg1(g):
+    w = workloads.by_number(1)
+    X, C0 = workloads.make_inputs(w)
+    C_or, idx_or, J_or, hist = oracle.kmeans_fit(X, C0, w.iters)
+    C, idx, J, stats = g.gpu_fit(X, C0, w.iters)
+    assert stats.assign_calls == w.iters + 1
+    parity.check_inertia(J, J_or)
+    assert J == pytest.approx(oracle.inertia(X, C, idx), rel=1e-6)
+    out = g.gpu_decode(C, idx)
+    assert out.tobytes() == C[idx].tobytes()
+    assert J == pytest.approx(((X.astype(np.float64) - out) ** 2).sum(), rel=1e-6)
+    # centroid agreement is guaranteed only if no near-tie was resolved differently along the way
+    same = np.array_equal(idx, idx_or)
+    if same:
+        parity.check_centroids(C, C_or, X)
+    frac = np.mean(np.linalg.norm(C - C_or, axis=1) <= 1e-4 * np.linalg.norm(C_or, axis=1) + 1e-9)
+    print(f"cfg1 end-to-end: identical codes={same}, centroids within tolerance={frac:.4f}")
+    assert frac > 0.95
+
+
+def test_fit_iters_zero_and_aliasing(g):
+    X, C0 = workloads.make_small(9000, 4, 100, seed=9)
+    C, idx, J, stats = g.gpu_fit(X, C0, 0)
+    assert C.tobytes() == C0.tobytes() and stats.assign_calls == 1
+    k1, D1, _, D2 = oracle.assign_top2(X, C0)
+    parity.check_assignment(X, C0, idx, k1, D1, D2)
+    parity.check_inertia(J, float(D1.sum()))
+    # centroids aliasing init_centroids
+    import paper_2503_13089_amd as cc
+
+    Xd, Cd = g.dev(X), g.dev(C0)
+    ws = g.workspace(9000, 4, 100)
+    idx_d = torch.empty(9000, dtype=torch.uint32, device="cuda")
+    cc.kmeans_fit(Xd, 100, 3, Cd, Cd, idx_d, None, ws)
+    torch.cuda.synchronize()
+    C3, idx3, _, _ = g.gpu_fit(X, C0, 3)
+    assert Cd.cpu().numpy().tobytes() == C3.tobytes() and np.array_equal(idx_d.cpu().numpy(), idx3)
+
+
+def test_zero_inertia_when_every_distinct_vector_is_a_centroid(g):
+    rng = np.random.default_rng(47)
+    pool = np.unique((rng.standard_normal((200, 8)) * 0.02).astype(np.float16).astype(np.float32), axis=0)
+    X = pool[rng.integers(0, len(pool), size=50000)]
+    C, idx, J, _ = g.gpu_fit(X, pool, 3)
+    assert J == 0.0
+    assert np.array_equal(g.gpu_decode(C, idx), X)
