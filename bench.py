@@ -1,0 +1,138 @@
+"""Benchmark of the clustering hot path on one MI355X.
+
+One "step" is one Lloyd iteration of the whole path through the C ABI, on centroids chained from the
+previous step: cc_assign (E-step + objective), cc_update (M-step), cc_decode (reconstruction).
+The headline value is Lloyd iterations per second on the 4096x11008, d=4, K=65536 workload with all
+inputs resident in HBM. The JSON line also carries the roofline position of the dominant kernel (the
+E-step) and the CPU oracle timed on this machine's host cores on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP32_PEAK_TFLOPS = 157.3   # MI355X fp32 vector = fp32 matrix peak
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
+
+
+def cpu_baseline(w, X, C0, sample_log2=17):
+    """The oracle as it stands, timed on this host: one E-step over the first 2^sample_log2 vectors against
+    all K centroids, scaled linearly in N (its cost is exactly proportional to N), plus one full-N M-step."""
+    import numpy as np
+
+    import oracle
+
+    n = min(1 << sample_log2, X.shape[0])
+    t0 = time.perf_counter()
+    k1, _, _, _ = oracle.assign_top2(X[:n], C0)
+    t_assign = time.perf_counter() - t0
+    idx_full = np.resize(k1, X.shape[0])
+    t0 = time.perf_counter()
+    oracle.update(X, idx_full, C0)
+    t_update = time.perf_counter() - t0
+    t_iter = t_assign * (X.shape[0] / n) + t_update
+    return {
+        "value": 1.0 / t_iter, "unit": "Lloyd iter/s", "cores": oracle.threads(), "kind": "oracle",
+        "sample": f"E-step on the first {n} of {X.shape[0]} vectors x all {w.K} centroids "
+                  f"({t_assign:.2f} s, scaled by N/n) + one full-N M-step ({t_update:.2f} s)",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--assign-mode", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (matrices are independent, so "
+              "a multi-GPU job is one such process per GPU). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2503_13089_amd as cc
+    import workloads
+
+    w = next(v for k, v in workloads.WORKLOADS.items() if k.startswith(args.workload))
+    cc.load_library()  # raises if the HIP library has not been built: there is no fallback
+    cc.set_assign_mode(args.assign_mode)
+    torch.cuda.set_device(0)
+    X, C0 = workloads.make_inputs(w)
+    N, d, K = X.shape[0], w.d, w.K
+    Xd = torch.from_numpy(X).cuda()
+    Cd = torch.from_numpy(C0).cuda()
+    ws = torch.empty(cc.workspace_bytes(N, d, K), dtype=torch.uint8, device="cuda")
+    idx = torch.empty(N, dtype=torch.uint32, device="cuda")
+    J = torch.zeros(1, dtype=torch.float64, device="cuda")
+    out = torch.empty_like(Xd)
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        cc.assign(Xd, Cd, idx, J, ws)
+        if ev: ev[1].record()
+        cc.update(Xd, idx, Cd, Cd, None, ws)
+        if ev: ev[2].record()
+        cc.decode(Cd, idx, out)
+        if ev: ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    refined0 = 0
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(events[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in events) / args.steps
+    assign_ms, update_ms, decode_ms = ms(0, 1), ms(1, 2), ms(2, 3)
+    ms_per_step = wall * 1e3 / args.steps
+    stats = cc.read_stats(ws)
+
+    assign_flop = 2.0 * d * N * K
+    update_bytes = 4.0 * d * N + 4.0 * N + 4.0 * K * (d + 1)
+    decode_bytes = 4.0 * N + 4.0 * K * d + 4.0 * d * N
+    achieved = assign_flop / (assign_ms * 1e-3) / 1e12
+    line = {
+        "metric": "Lloyd iter/s (assign+update) at 4096x11008,d=4,K=65536; % FP32 peak",
+        "value": args.steps / wall, "unit": "Lloyd iter/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "rows": w.rows, "cols": w.cols, "d": d, "N": N, "K": K,
+                   "step": "cc_assign(+objective) + cc_update + cc_decode, centroids chained",
+                   "assign_mode": args.assign_mode, "final_objective": float(J.item())},
+        "roofline": {"bound": "mfma" if args.assign_mode != 1 else "alu", "kernel": "assign (E-step)",
+                     "achieved": achieved, "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / FP32_PEAK_TFLOPS, "traffic": None,
+                     "flop_per_launch": assign_flop, "avg_ms": assign_ms},
+        "other_kernels": {
+            "update": {"bound": "hbm", "achieved": update_bytes / (update_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                       "unit": "GB/s", "frac": update_bytes / (update_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "bytes_per_launch": update_bytes, "avg_ms": update_ms},
+            "decode": {"bound": "hbm", "achieved": decode_bytes / (decode_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                       "unit": "GB/s", "frac": decode_bytes / (decode_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "bytes_per_launch": decode_bytes, "avg_ms": decode_ms},
+        },
+        "refined_vectors_last_assign": stats.refined_vectors,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, X, C0)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
