@@ -58,11 +58,16 @@ int check_workspace(void* ws, size_t ws_bytes, uint64_t N, uint32_t d, uint32_t 
 int run_assign(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx, double* inertia,
                const cc::Workspace& w, hipStream_t s)
 {
-    uint32_t n_partials = 0;
-    CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, inertia ? w.partials : nullptr, &n_partials, s),
-               "assign (direct form)");
-    if (inertia) CC_TRY_HIP(cc::launch_reduce_partials(w.partials, n_partials, inertia, s), "objective reduction");
-    CC_TRY_HIP(cc::launch_bump_assign_calls(w.hdr, s), "bookkeeping");
+    const int mode = g_assign_mode.load();
+    const bool matrix_cores = mode == 2 || (mode == 0 && K >= 128);
+    if (matrix_cores) {
+        CC_TRY_HIP(cc::launch_assign_mfma(X, N, d, C, K, idx, w, s), "assign (matrix cores)");
+    } else {
+        CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s), "assign (direct form)");
+        CC_TRY_HIP(cc::launch_bump_assign_calls(w.hdr, s), "bookkeeping");
+    }
+    if (inertia)
+        CC_TRY_HIP(cc::launch_reduce_dmin(w.dmin, N, w.partials, w.partial_slots, inertia, s), "objective reduction");
     return CC_OK;
 }
 

@@ -14,19 +14,15 @@ namespace cc {
 
 constexpr int kThreads = 256;
 
-template <int D>
-struct VecRegs {
-    float v[D];
-};
-
 template <int D, int VPT, int TILE>
 __global__ __launch_bounds__(kThreads) void assign_direct_kernel(const float* __restrict__ X, uint32_t N,
                                                                  const float* __restrict__ C, uint32_t K,
-                                                                 uint32_t* __restrict__ idx,
-                                                                 double* __restrict__ partials)
+                                                                 uint32_t* __restrict__ idx, float* __restrict__ dmin,
+                                                                 const uint32_t* __restrict__ gate,
+                                                                 uint32_t gate_limit)
 {
     __shared__ float4 tile[TILE * D / 4];
-    __shared__ double red[kThreads / 64];
+    if (gate != nullptr && *gate <= gate_limit) return;  // uniform over the grid
 
     const uint32_t base = blockIdx.x * (kThreads * VPT) + threadIdx.x;
     float x[VPT][D];
@@ -36,12 +32,7 @@ __global__ __launch_bounds__(kThreads) void assign_direct_kernel(const float* __
     for (int v = 0; v < VPT; ++v) {
         const uint32_t i = base + v * kThreads;
         const uint32_t ic = i < N ? i : N - 1;  // out-of-range lanes recompute the last vector, never store
-        const float4* src = reinterpret_cast<const float4*>(X + size_t(ic) * D);
-#pragma unroll
-        for (int q = 0; q < D / 4; ++q) {
-            float4 t = src[q];
-            x[v][4 * q + 0] = t.x; x[v][4 * q + 1] = t.y; x[v][4 * q + 2] = t.z; x[v][4 * q + 3] = t.w;
-        }
+        load_row<D>(X + size_t(ic) * D, x[v]);
         best[v] = INFINITY;
         arg[v] = 0;
     }
@@ -54,20 +45,10 @@ __global__ __launch_bounds__(kThreads) void assign_direct_kernel(const float* __
         __syncthreads();
         for (uint32_t k = 0; k < nk; ++k) {
             float c[D];
-#pragma unroll
-            for (int q = 0; q < D / 4; ++q) {
-                float4 t = tile[k * (D / 4) + q];
-                c[4 * q + 0] = t.x; c[4 * q + 1] = t.y; c[4 * q + 2] = t.z; c[4 * q + 3] = t.w;
-            }
+            load_row<D>(reinterpret_cast<const float*>(tile + k * (D / 4)), c);
 #pragma unroll
             for (int v = 0; v < VPT; ++v) {
-                float t0 = x[v][0] - c[0];
-                float acc = t0 * t0;
-#pragma unroll
-                for (int j = 1; j < D; ++j) {
-                    float t = x[v][j] - c[j];
-                    acc = fmaf(t, t, acc);
-                }
+                const float acc = direct_sqdist<D>(x[v], c);
                 if (acc < best[v]) {
                     best[v] = acc;
                     arg[v] = k0 + k;
@@ -76,48 +57,57 @@ __global__ __launch_bounds__(kThreads) void assign_direct_kernel(const float* __
         }
     }
 
-    double local = 0.0;
 #pragma unroll
     for (int v = 0; v < VPT; ++v) {
         const uint32_t i = base + v * kThreads;
         if (i < N) {
             idx[i] = arg[v];
-            local += double(best[v]);
+            if (dmin != nullptr) dmin[i] = best[v];
         }
-    }
-    if (partials != nullptr) {
-        // fixed-shape reduction: lanes of a wave by xor-shuffle, then the four waves in order
-        for (int off = 32; off > 0; off >>= 1) local += __shfl_xor(local, off, 64);
-        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = local;
-        __syncthreads();
-        if (threadIdx.x == 0) partials[blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
     }
 }
 
 template <int D, int VPT, int TILE>
-static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, double* partials,
-                           uint32_t* n_partials_out, hipStream_t s)
+static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, float* dmin,
+                           const uint32_t* gate, uint32_t gate_limit, hipStream_t s)
 {
     const uint32_t blocks = (N + kThreads * VPT - 1) / (kThreads * VPT);
-    if (n_partials_out) *n_partials_out = blocks;
-    hipLaunchKernelGGL((assign_direct_kernel<D, VPT, TILE>), dim3(blocks), dim3(kThreads), 0, s, X, N, C, K, idx,
-                       partials);
+    hipLaunchKernelGGL((assign_direct_kernel<D, VPT, TILE>), dim3(blocks), dim3(kThreads), 0, s, X, N, C, K, idx, dmin,
+                       gate, gate_limit);
     return hipGetLastError();
 }
 
 hipError_t launch_assign_direct(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                                double* partials, uint32_t* n_partials_out, hipStream_t s)
+                                float* dmin, const uint32_t* gate, uint32_t gate_limit, hipStream_t s)
 {
     switch (d) {
-        case 4: return launch_t<4, 4, 1024>(X, N, C, K, idx, partials, n_partials_out, s);
-        case 8: return launch_t<8, 2, 512>(X, N, C, K, idx, partials, n_partials_out, s);
-        case 16: return launch_t<16, 1, 256>(X, N, C, K, idx, partials, n_partials_out, s);
+        case 4: return launch_t<4, 4, 1024>(X, N, C, K, idx, dmin, gate, gate_limit, s);
+        case 8: return launch_t<8, 2, 512>(X, N, C, K, idx, dmin, gate, gate_limit, s);
+        case 16: return launch_t<16, 1, 256>(X, N, C, K, idx, dmin, gate, gate_limit, s);
         default: return hipErrorInvalidValue;
     }
 }
 
-// Sums the per-block partial objectives in index order (one block, fixed tree) so that the result does
-// not depend on scheduling.
+// Objective: sum of dmin in fp64. Stage 1: a fixed grid of blocks, block b sums a fixed contiguous
+// range with a fixed tree; stage 2: one block sums the partials in index order. The shape depends
+// only on N, so the result is reproducible.
+__global__ __launch_bounds__(kThreads) void reduce_dmin_kernel(const float* __restrict__ dmin, uint32_t N,
+                                                               double* __restrict__ partials)
+{
+    __shared__ double red[kThreads];
+    const uint64_t per = (uint64_t(N) + gridDim.x - 1) / gridDim.x;
+    const uint64_t lo = per * blockIdx.x, hi = min(lo + per, uint64_t(N));
+    double acc = 0.0;
+    for (uint64_t i = lo + threadIdx.x; i < hi; i += kThreads) acc += double(dmin[i]);
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int off = kThreads / 2; off > 0; off >>= 1) {
+        if (int(threadIdx.x) < off) red[threadIdx.x] += red[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partials[blockIdx.x] = red[0];
+}
+
 __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double* __restrict__ partials, uint32_t n,
                                                                    double* __restrict__ out)
 {
@@ -133,9 +123,12 @@ __global__ __launch_bounds__(kThreads) void reduce_partials_kernel(const double*
     if (threadIdx.x == 0) *out = red[0];
 }
 
-hipError_t launch_reduce_partials(const double* partials, uint32_t n, double* out, hipStream_t s)
+hipError_t launch_reduce_dmin(const float* dmin, uint32_t N, double* partials, uint32_t partial_slots, double* out,
+                              hipStream_t s)
 {
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(kThreads), 0, s, partials, n, out);
+    const uint32_t blocks = partial_slots;
+    hipLaunchKernelGGL(reduce_dmin_kernel, dim3(blocks), dim3(kThreads), 0, s, dmin, N, partials);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3(1), dim3(kThreads), 0, s, partials, blocks, out);
     return hipGetLastError();
 }
 

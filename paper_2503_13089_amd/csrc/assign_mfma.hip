@@ -1,0 +1,336 @@
+// E-step on the matrix cores (Section 3.1: w_i goes to the centroid minimising ||w_i - c||^2).
+//
+// ||x - c||^2 = ||x||^2 + (||c||^2 - 2 x.c), and ||x||^2 does not affect the argmin, so the hot loop
+// evaluates the score s(x, c) = ||c||^2 + sum_j c_j * (-2 x_j) for every (vector, centroid) pair:
+// d fused multiply-adds on an accumulator preset to ||c||^2, which is exactly what the fp32 MFMA
+// instruction v_mfma_f32_32x32x2_f32 computes when ||c||^2 is its C operand (k = 2 per instruction,
+// d/2 chained instructions per 32 x 32 tile of pairs).
+//
+// Operand roles: centroids are the A rows, vectors the B columns, so each lane ends up with the 16
+// scores of ONE vector (column lane%32) against 16 centroids; lanes l and l+32 share a vector.
+// The vector ALUs then only have to fold those scores into a running minimum: v_min3_f32 folds
+// two new scores per instruction. Tracking the argmin per score would cost several instructions per
+// pair, so the loop tracks, per lane, only
+//     best   = smallest score seen,          grp = the group of centroids it came from,
+//     second = smallest score of any OTHER group
+// at group granularity (one group = kGroupTiles tiles = 16*kGroupTiles centroids per lane).
+//
+// Epilogue, per vector: the winning group of each half-wave is re-evaluated in direct form
+// (sum_j (x_j - c_j)^2, accurate to ~1e-6 relative of the distance itself) to get the index; the two
+// halves are merged by direct-form distance. The fp32 score carries an absolute rounding error of
+// up to E = 2^-24 ((2d+1) ||c||^2 + d ||x||^2), which is NOT small against the distance when the
+// centroid is close (||x - c||^2 << ||x||^2). So a vector is only accepted if no other group came
+// within the guard band `delta` >= E(winner) + E(true nearest) of the best score; otherwise it is
+// appended to a refine list and re-decided over all K centroids in direct form by a second kernel.
+// With ||c||^2 <= 2||x||^2 + 2 D for both the winner and the true nearest centroid (triangle
+// inequality, D = the winner's distance), delta = 2 * 2^-24 * ((5d+2) ||x||^2 + (4d+2) D).
+//
+// The codebook is re-laid out once per call ("packed") so that every LDS read in the hot loop is a
+// conflict-free wide read of exactly the MFMA operand a lane needs, with rows permuted such that
+// lane-half h, accumulator register r of tile t is centroid 32 t + 16 h + r.
+#include "common.h"
+
+namespace cc {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;  // 4 waves, one per SIMD
+constexpr float kUnit = 5.9604644775390625e-08f;  // 2^-24
+constexpr float kGuardSafety = 1.5f;
+
+// ---------------------------------------------------------------------------------------------
+// Packed codebook: per 32-centroid tile, [64 lanes][KS] A-operand values, then 32 x ||c||^2.
+// Rows past K are padded with c = 0 and ||c||^2 = +inf, which can never win.
+template <int D>
+__global__ __launch_bounds__(kThreads) void pack_codebook_kernel(const float* __restrict__ C, uint32_t K,
+                                                                 uint32_t ntiles, float* __restrict__ packed,
+                                                                 WsHeader* hdr)
+{
+    constexpr uint32_t KS = D / 2, TF = 64 * KS + 32;
+    const size_t o = size_t(blockIdx.x) * kThreads + threadIdx.x;
+    if (o == 0) hdr->refine_count = 0;
+    if (o >= size_t(ntiles) * TF) return;
+    const uint32_t tile = uint32_t(o / TF), r = uint32_t(o % TF);
+    float val;
+    if (r < 64 * KS) {
+        const uint32_t lane = r / KS, ks = r % KS, h = lane >> 5, m = lane & 31;
+        // MFMA output row m lives in half (m/4)%2, register (m%4) + 4*(m/8): give it centroid 16*half + register
+        const uint32_t k = 32 * tile + 16 * ((m >> 2) & 1) + (m & 3) + 4 * (m >> 3);
+        val = k < K ? C[size_t(k) * D + 2 * ks + h] : 0.0f;
+    } else {
+        const uint32_t k = 32 * tile + (r - 64 * KS);
+        if (k < K) {
+            double s = 0.0;
+            for (int j = 0; j < D; ++j) {
+                const double c = double(C[size_t(k) * D + j]);
+                s += c * c;
+            }
+            val = float(s);  // one rounding
+        } else {
+            val = INFINITY;
+        }
+    }
+    packed[o] = val;
+}
+
+// ---------------------------------------------------------------------------------------------
+template <int D, int VT, int ST, int GT>
+__global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* __restrict__ X, uint32_t N,
+                                                               const float* __restrict__ C, uint32_t K,
+                                                               const float* __restrict__ packed, uint32_t ntiles,
+                                                               uint32_t* __restrict__ idx, float* __restrict__ dmin,
+                                                               WsHeader* hdr, uint32_t* __restrict__ refine_list,
+                                                               unsigned long long* __restrict__ refine_best,
+                                                               uint32_t refine_cap)
+{
+    constexpr int KS = D / 2;                 // MFMA k-steps per tile
+    constexpr int TF = 64 * KS + 32;          // floats per packed tile
+    constexpr int STAGE_F4 = ST * TF / 4;     // float4 per LDS stage
+    constexpr int NPF = (STAGE_F4 + kThreads - 1) / kThreads;
+    static_assert(ST % GT == 0, "a tracking group must not straddle LDS stages");
+    static_assert(int(kStageTilesMax) % ST == 0, "the packed codebook is padded to whole stages");
+    __shared__ float4 lds[2][STAGE_F4];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int h = lane >> 5, n = lane & 31;
+    const uint32_t vbase = (blockIdx.x * 4 + wave) * (32 * VT);
+
+    // B operands: lane (n, h) supplies -2 * x_n[2 ks + h] for k-step ks
+    float b[VT][KS];
+#pragma unroll
+    for (int vt = 0; vt < VT; ++vt) {
+        const uint32_t i = min(vbase + vt * 32 + n, N - 1);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) b[vt][ks] = -2.0f * X[size_t(i) * D + 2 * ks + h];
+    }
+    float best[VT], second[VT];
+    uint32_t grp[VT];
+#pragma unroll
+    for (int vt = 0; vt < VT; ++vt) {
+        best[vt] = INFINITY;
+        second[vt] = INFINITY;
+        grp[vt] = 0;
+    }
+
+    // ntiles is a multiple of ST (padding rows carry ||c||^2 = +inf), so every stage is whole
+    const float4* P4 = reinterpret_cast<const float4*>(packed);
+    const uint32_t nstages = ntiles / ST;
+#pragma unroll
+    for (int p = 0; p < NPF; ++p) {
+        const uint32_t j = threadIdx.x + p * kThreads;
+        if (NPF * kThreads == STAGE_F4 || j < STAGE_F4) lds[0][j] = P4[j];
+    }
+    __syncthreads();
+
+    for (uint32_t s = 0; s < nstages; ++s) {
+        const int cur = s & 1;
+        // prefetch the next stage into registers while this one is consumed (the last iteration
+        // re-reads its own stage; the copy is never used)
+        const uint32_t sn = min(s + 1, nstages - 1);
+        float4 pf[NPF];
+#pragma unroll
+        for (int p = 0; p < NPF; ++p) {
+            const uint32_t j = min(threadIdx.x + p * kThreads, uint32_t(STAGE_F4 - 1));
+            pf[p] = P4[size_t(sn) * STAGE_F4 + j];
+        }
+
+        const float* L = reinterpret_cast<const float*>(lds[cur]);
+#pragma unroll 1
+        for (uint32_t tt = 0; tt < ST; tt += GT) {
+            float m[VT];
+#pragma unroll
+            for (int vt = 0; vt < VT; ++vt) m[vt] = INFINITY;
+#pragma unroll
+            for (int g = 0; g < GT; ++g) {
+                const float* T = L + (tt + g) * TF;
+                float a[KS];
+                if constexpr (KS == 2) {
+                    const float2 t = *reinterpret_cast<const float2*>(T + lane * 2);
+                    a[0] = t.x; a[1] = t.y;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < KS / 4; ++q) {
+                        const float4 t = *reinterpret_cast<const float4*>(T + lane * KS + 4 * q);
+                        a[4 * q + 0] = t.x; a[4 * q + 1] = t.y; a[4 * q + 2] = t.z; a[4 * q + 3] = t.w;
+                    }
+                }
+                f32x16 cn;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 t = *reinterpret_cast<const float4*>(T + 64 * KS + 16 * h + 4 * q);
+                    cn[4 * q + 0] = t.x; cn[4 * q + 1] = t.y; cn[4 * q + 2] = t.z; cn[4 * q + 3] = t.w;
+                }
+#pragma unroll
+                for (int vt = 0; vt < VT; ++vt) {
+                    f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[vt][0], cn, 0, 0, 0);
+#pragma unroll
+                    for (int ks = 1; ks < KS; ++ks)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ks], b[vt][ks], acc, 0, 0, 0);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) m[vt] = __builtin_fminf(__builtin_fminf(m[vt], acc[2 * q]), acc[2 * q + 1]);
+                }
+            }
+            const uint32_t gid = (s * ST + tt) / GT;
+#pragma unroll
+            for (int vt = 0; vt < VT; ++vt) {
+                second[vt] = __builtin_amdgcn_fmed3f(best[vt], second[vt], m[vt]);
+                grp[vt] = m[vt] < best[vt] ? gid : grp[vt];
+                best[vt] = __builtin_fminf(best[vt], m[vt]);
+            }
+        }
+
+#pragma unroll
+        for (int p = 0; p < NPF; ++p) {
+            const uint32_t j = threadIdx.x + p * kThreads;
+            if (NPF * kThreads == STAGE_F4 || j < STAGE_F4) lds[cur ^ 1][j] = pf[p];
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: index recovery in direct form, merge of the two half-waves, guard-band test
+#pragma unroll
+    for (int vt = 0; vt < VT; ++vt) {
+        const uint32_t i_raw = vbase + vt * 32 + n;
+        const uint32_t i = min(i_raw, N - 1);
+        float x[D];
+        load_row<D>(X + size_t(i) * D, x);
+        float bd = INFINITY;
+        uint32_t bk = 0;
+        for (int g = 0; g < GT; ++g) {
+            const uint32_t k0 = 32 * (grp[vt] * GT + g) + 16 * h;
+            for (int r = 0; r < 16; ++r) {
+                const uint32_t k = k0 + r;
+                if (k < K) {
+                    float c[D];
+                    load_row<D>(C + size_t(k) * D, c);
+                    const float dk = direct_sqdist<D>(x, c);
+                    if (dk < bd) {
+                        bd = dk;
+                        bk = k;
+                    }
+                }
+            }
+        }
+        const float od = __shfl_xor(bd, 32, 64);
+        const uint32_t ok = uint32_t(__shfl_xor(int(bk), 32, 64));
+        const float ob = __shfl_xor(best[vt], 32, 64);
+        const float os = __shfl_xor(second[vt], 32, 64);
+        const bool take = od < bd || (od == bd && ok < bk);
+        const float dstar = take ? od : bd;
+        const uint32_t kstar = take ? ok : bk;
+        const float bstar = __builtin_fminf(best[vt], ob);
+        const float sstar = __builtin_fminf(second[vt], os);
+        float xn = 0.0f;
+#pragma unroll
+        for (int j = 0; j < D; ++j) xn = __builtin_fmaf(x[j], x[j], xn);
+        const float delta = kGuardSafety * 2.0f * kUnit * (float(5 * D + 2) * xn + float(4 * D + 2) * dstar) + 1e-36f;
+        const bool safe = (sstar - bstar) > delta;  // false for NaN as well
+        if (h == 0 && i_raw < N) {
+            idx[i] = kstar;
+            dmin[i] = dstar;
+            if (!safe) {
+                const uint32_t pos = atomicAdd(&hdr->refine_count, 1u);
+                if (pos < refine_cap) {
+                    refine_list[pos] = i;
+                    refine_best[pos] = ~0ull;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Refinement: the listed vectors are re-decided over ALL K centroids in direct form. Work item =
+// (chunk of 64 listed vectors, slice of the codebook); each lane keeps the best (distance, index) of
+// its slice and merges it with a 64-bit atomicMin on (distance bits << 32 | index): distances are
+// non-negative, so the integer order is (distance, then lowest index) - order independent.
+template <int D>
+__global__ __launch_bounds__(64) void refine_kernel(const float* __restrict__ X, const float* __restrict__ C,
+                                                    uint32_t K, const WsHeader* __restrict__ hdr,
+                                                    const uint32_t* __restrict__ refine_list,
+                                                    unsigned long long* __restrict__ refine_best,
+                                                    uint32_t refine_cap, uint32_t slices)
+{
+    const uint32_t count = hdr->refine_count;
+    if (count == 0 || count > refine_cap) return;  // overflow is handled by the full direct pass
+    const uint32_t chunks = (count + 63) / 64;
+    const uint32_t per = (K + slices - 1) / slices;
+    for (uint32_t w = blockIdx.x; w < chunks * slices; w += gridDim.x) {
+        const uint32_t chunk = w / slices, slice = w % slices;
+        const uint32_t e = chunk * 64 + threadIdx.x;
+        const uint32_t ec = min(e, count - 1);
+        float x[D];
+        load_row<D>(X + size_t(refine_list[ec]) * D, x);
+        const uint32_t k_lo = slice * per, k_hi = min(k_lo + per, K);
+        float bd = INFINITY;
+        uint32_t bk = 0;
+        for (uint32_t k = k_lo; k < k_hi; ++k) {  // k is wave-uniform: the centroid is fetched once per wave
+            float c[D];
+            load_row<D>(C + size_t(k) * D, c);
+            const float dk = direct_sqdist<D>(x, c);
+            if (dk < bd) {
+                bd = dk;
+                bk = k;
+            }
+        }
+        if (e < count && k_lo < k_hi)
+            atomicMin(&refine_best[e], (static_cast<unsigned long long>(__float_as_uint(bd)) << 32) | bk);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void refine_finish_kernel(WsHeader* hdr, const uint32_t* __restrict__ refine_list,
+                                                                 const unsigned long long* __restrict__ refine_best,
+                                                                 uint32_t refine_cap, uint32_t* __restrict__ idx,
+                                                                 float* __restrict__ dmin)
+{
+    const uint32_t count = hdr->refine_count;
+    const uint32_t e = blockIdx.x * kThreads + threadIdx.x;
+    if (e == 0) {
+        hdr->refined_vectors += count;
+        hdr->assign_calls += 1;
+    }
+    if (count > refine_cap) return;
+    for (uint32_t j = e; j < count; j += gridDim.x * kThreads) {
+        const unsigned long long v = refine_best[j];
+        const uint32_t i = refine_list[j];
+        idx[i] = uint32_t(v & 0xffffffffull);
+        dmin[i] = __uint_as_float(uint32_t(v >> 32));
+    }
+}
+
+template <int D, int VT, int ST>
+static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, const Workspace& w,
+                           hipStream_t s)
+{
+    constexpr int GT = int(kGroupTiles);
+    constexpr uint32_t TF = 64 * (D / 2) + 32;
+    const size_t packed_floats = size_t(w.packed_tiles) * TF;
+    hipLaunchKernelGGL(pack_codebook_kernel<D>, dim3(uint32_t((packed_floats + kThreads - 1) / kThreads)),
+                       dim3(kThreads), 0, s, C, K, w.packed_tiles, w.packed, w.hdr);
+    const uint32_t per_block = 4 * 32 * VT;
+    hipLaunchKernelGGL((assign_mfma_kernel<D, VT, ST, GT>), dim3((N + per_block - 1) / per_block), dim3(kThreads), 0, s,
+                       X, N, C, K, w.packed, w.packed_tiles, idx, w.dmin, w.hdr, w.refine_list, w.refine_best,
+                       w.refine_cap);
+    const uint32_t slices = K >= 4096 ? 32 : (K >= 256 ? 4 : 1);
+    hipLaunchKernelGGL(refine_kernel<D>, dim3(4096), dim3(64), 0, s, X, C, K, w.hdr, w.refine_list, w.refine_best,
+                       w.refine_cap, slices);
+    hipLaunchKernelGGL(refine_finish_kernel, dim3(256), dim3(kThreads), 0, s, w.hdr, w.refine_list, w.refine_best,
+                       w.refine_cap, idx, w.dmin);
+    // overflow path: more guard-band vectors than the list holds -> decide everything in direct form
+    hipError_t e = launch_assign_direct(X, N, D, C, K, idx, w.dmin, &w.hdr->refine_count, w.refine_cap, s);
+    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+hipError_t launch_assign_mfma(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
+                              const Workspace& w, hipStream_t s)
+{
+    switch (d) {
+        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, s);
+        case 8: return launch_t<8, 4, 8>(X, N, C, K, idx, w, s);
+        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace cc

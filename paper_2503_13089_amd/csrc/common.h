@@ -26,11 +26,19 @@ struct Workspace {
     long long* sums;           // [K*d]  fixed-point cluster sums
     uint32_t* counts;          // [K]
     double* partials;          // [partial_slots] per-block partial objective
-    uint32_t* refine_list;     // [N]    ids of vectors to re-decide in direct form
-    float* fast_best;          // [N]    scratch of the matrix-core assign
+    float* dmin;               // [N]    ||x_i - c_idx_i||^2 of the last assign (fp32, direct form)
+    float* packed;             // codebook re-laid out as matrix-core operand tiles (+ ||c||^2)
+    uint32_t* refine_list;     // [refine_cap] ids of vectors to re-decide in direct form
+    unsigned long long* refine_best;  // [refine_cap] (distance bits << 32 | index), reduced with atomicMin
+    uint32_t refine_cap;
     uint32_t partial_slots;
+    uint32_t packed_tiles;     // number of 32-centroid tiles in `packed` (K rounded up, padded)
     size_t bytes;
 };
+
+constexpr uint32_t kTileCentroids = 32;   // centroids per matrix-core tile
+constexpr uint32_t kGroupTiles = 2;       // tiles per tracking group of the matrix-core E-step
+constexpr uint32_t kStageTilesMax = 8;    // the packed codebook is padded to whole LDS stages of this many tiles
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -45,22 +53,35 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     w.cnorm = reinterpret_cast<float*>(take(size_t(K) * 4));
     w.sums = reinterpret_cast<long long*>(take(size_t(K) * d * 8));
     w.counts = reinterpret_cast<uint32_t*>(take(size_t(K) * 4));
-    w.partial_slots = uint32_t((N + 255) / 256 + 1);
+    w.partial_slots = 1024;
     w.partials = reinterpret_cast<double*>(take(size_t(w.partial_slots) * 8));
-    w.refine_list = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
-    w.fast_best = reinterpret_cast<float*>(take(size_t(N) * 4));
+    w.dmin = reinterpret_cast<float*>(take(size_t(N) * 4));
+    const uint32_t stage = kTileCentroids * kStageTilesMax;
+    w.packed_tiles = uint32_t((uint64_t(K) + stage - 1) / stage) * kStageTilesMax;
+    w.packed = reinterpret_cast<float*>(take(size_t(w.packed_tiles) * kTileCentroids * (d + 1) * 4));
+    w.refine_cap = uint32_t(N / 8 + 4096);
+    w.refine_list = reinterpret_cast<uint32_t*>(take(size_t(w.refine_cap) * 4));
+    w.refine_best = reinterpret_cast<unsigned long long*>(take(size_t(w.refine_cap) * 8));
     w.bytes = off;
     return w;
 }
 
 // ---- launchers (each enqueues on `s` and returns the launch status) -------------------------------
 
-// Direct-form E-step over all N vectors. partials may be NULL (no objective wanted).
+// Direct-form E-step over all N vectors; dmin may be NULL. With gate != NULL the kernel does nothing
+// unless *gate > gate_limit (used as the overflow path of the matrix-core E-step).
 hipError_t launch_assign_direct(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K,
-                                uint32_t* idx, double* partials, uint32_t* n_partials_out, hipStream_t s);
+                                uint32_t* idx, float* dmin, const uint32_t* gate, uint32_t gate_limit,
+                                hipStream_t s);
 
-// Sums partials[0..n) in index order into *out (fp64).
-hipError_t launch_reduce_partials(const double* partials, uint32_t n, double* out, hipStream_t s);
+// Matrix-core E-step: packs the codebook, runs the fp32 MFMA kernel with min/second tracking, then
+// re-decides the guard-band vectors in direct form. Writes idx and w.dmin.
+hipError_t launch_assign_mfma(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K,
+                              uint32_t* idx, const Workspace& w, hipStream_t s);
+
+// *out = sum_i dmin[i] in fp64 with a fixed reduction shape.
+hipError_t launch_reduce_dmin(const float* dmin, uint32_t N, double* partials, uint32_t partial_slots,
+                              double* out, hipStream_t s);
 
 // Header bookkeeping.
 hipError_t launch_reset_header(WsHeader* hdr, hipStream_t s);
@@ -76,5 +97,32 @@ hipError_t launch_decode(const float* C, uint32_t K, uint32_t d, const uint32_t*
                          hipStream_t s);
 
 hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s);
+
+// ||x - c||^2 in fp32, direct form: first square, then one fused multiply-add per further component.
+// Every kernel that needs a distance uses this exact operation order, so that a vector decided by
+// one kernel and re-decided by another sees identical values.
+template <int D>
+__device__ __forceinline__ float direct_sqdist(const float (&x)[D], const float (&c)[D])
+{
+    const float t0 = x[0] - c[0];
+    float acc = t0 * t0;
+#pragma unroll
+    for (int j = 1; j < D; ++j) {
+        const float t = x[j] - c[j];
+        acc = __builtin_fmaf(t, t, acc);
+    }
+    return acc;
+}
+
+template <int D>
+__device__ __forceinline__ void load_row(const float* __restrict__ p, float (&v)[D])
+{
+    const float4* s = reinterpret_cast<const float4*>(p);
+#pragma unroll
+    for (int q = 0; q < D / 4; ++q) {
+        const float4 t = s[q];
+        v[4 * q + 0] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+    }
+}
 
 }  // namespace cc

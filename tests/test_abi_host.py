@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 def test_workspace_query():
     assert cc.workspace_bytes(65536, 4, 256) > 0
     big = cc.workspace_bytes(11272192, 4, 65536)
-    assert 2 * 11272192 * 4 <= big < 200e6
+    assert 11272192 * 4 <= big < 200e6  # at least the per-vector distance array
     assert cc.workspace_bytes(65536, 4, 256) % 256 == 0
     for N, d, K in [(0, 4, 1), (10, 5, 2), (10, 4, 0), (10, 4, 11), (1 << 32, 4, 8), (1 << 26, 4, (1 << 24) + 1)]:
         assert cc.workspace_bytes(N, d, K) == 0

@@ -24,6 +24,16 @@ def g():
     return gpu_helpers
 
 
+@pytest.fixture(params=[1, 2], ids=["direct", "matrix-core"])
+def mode(request, g):
+    """Runs a test once per E-step kernel: 1 = direct form only, 2 = matrix cores + guard band + refinement."""
+    import paper_2503_13089_amd as cc
+
+    cc.set_assign_mode(request.param)
+    yield request.param
+    cc.set_assign_mode(0)
+
+
 SHAPES = [  # (N, d, K): ragged in N (not a multiple of 256/512/1024) and in K (not a multiple of any tile)
     (70001, 4, 1500),
     (30011, 8, 777),
@@ -54,7 +64,7 @@ def test_decode_clamps_out_of_range_codes(g):
 
 
 @pytest.mark.parametrize("N,d,K", SHAPES)
-def test_assign_lockstep(g, N, d, K):
+def test_assign_lockstep(g, mode, N, d, K):
     X, C0 = workloads.make_small(N, d, K, seed=1000 + N)
     # centroids after one oracle step: general fp32 values rather than copies of inputs
     k0, _, _, _ = oracle.assign_top2(X, C0)
@@ -69,7 +79,7 @@ def test_assign_lockstep(g, N, d, K):
         assert none is None and np.array_equal(idx, idx2)
 
 
-def test_assign_exact_ties_take_the_lowest_index(g):
+def test_assign_exact_ties_take_the_lowest_index(g, mode):
     X, C = workloads.make_small(5000, 4, 64, seed=77)
     C[40] = C[3]
     C[63] = C[3]
@@ -119,7 +129,7 @@ def test_update_general_fp32_inputs_and_bad_codes(g):
 
 
 @pytest.mark.parametrize("N,d,K,iters", [(65536, 4, 256, 10), (30011, 8, 777, 5), (20003, 16, 515, 4), (3000, 4, 3000, 2)])
-def test_fit_trajectory_following(g, N, d, K, iters):
+def test_fit_trajectory_following(g, mode, N, d, K, iters):
     """Free-running GPU fit, every step verified: the oracle checks each assignment against the GPU's
     own centroids, adopts the GPU's choice on near-ties, and recomputes the update."""
     if (N, d, K) == (65536, 4, 256):
@@ -153,7 +163,7 @@ def test_fit_trajectory_following(g, N, d, K, iters):
     print(f"near-tie divergences adopted: {near_total}")
 
 
-def test_fit_end_to_end_cfg1(g):
+def test_fit_end_to_end_cfg1(g, mode):
     w = workloads.by_number(1)
     X, C0 = workloads.make_inputs(w)
     C_or, idx_or, J_or, hist = oracle.kmeans_fit(X, C0, w.iters)
@@ -173,7 +183,7 @@ def test_fit_end_to_end_cfg1(g):
     assert frac > 0.95
 
 
-def test_fit_iters_zero_and_aliasing(g):
+def test_fit_iters_zero_and_aliasing(g, mode):
     X, C0 = workloads.make_small(9000, 4, 100, seed=9)
     C, idx, J, stats = g.gpu_fit(X, C0, 0)
     assert C.tobytes() == C0.tobytes() and stats.assign_calls == 1
@@ -192,7 +202,7 @@ def test_fit_iters_zero_and_aliasing(g):
     assert Cd.cpu().numpy().tobytes() == C3.tobytes() and np.array_equal(idx_d.cpu().numpy(), idx3)
 
 
-def test_zero_inertia_when_every_distinct_vector_is_a_centroid(g):
+def test_zero_inertia_when_every_distinct_vector_is_a_centroid(g, mode):
     rng = np.random.default_rng(47)
     pool = np.unique((rng.standard_normal((200, 8)) * 0.02).astype(np.float16).astype(np.float32), axis=0)
     X = pool[rng.integers(0, len(pool), size=50000)]
