@@ -55,13 +55,22 @@ int check_workspace(void* ws, size_t ws_bytes, uint64_t N, uint32_t d, uint32_t 
     } while (0)
 
 // One E-step pass: idx (and, if inertia != NULL, the objective) for the given centroids.
+// The input scan (WsHeader::x_not_f16) must have run on this workspace since the last header reset.
 int run_assign(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx, double* inertia,
                const cc::Workspace& w, hipStream_t s)
 {
     const int mode = g_assign_mode.load();
     const bool matrix_cores = mode == 2 || (mode == 0 && K >= 128);
     if (matrix_cores) {
-        CC_TRY_HIP(cc::launch_assign_mfma(X, N, d, C, K, idx, w, s), "assign (matrix cores)");
+        if (mode == 0) {
+            // both variants are enqueued; the device-side gate lets exactly one of them run
+            CC_TRY_HIP(cc::launch_assign_mfma_f16(X, N, d, C, K, idx, w, cc::kGateIfF16, s), "assign (fp16 matrix cores)");
+            CC_TRY_HIP(cc::launch_assign_mfma_f32(X, N, d, C, K, idx, w, cc::kGateIfNotF16, s),
+                       "assign (fp32 matrix cores)");
+        } else {
+            CC_TRY_HIP(cc::launch_assign_mfma_f32(X, N, d, C, K, idx, w, cc::kGateAlways, s), "assign (fp32 matrix cores)");
+        }
+        CC_TRY_HIP(cc::launch_refine(X, N, d, C, K, idx, w, s), "assign (refinement)");
     } else {
         CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s), "assign (direct form)");
         CC_TRY_HIP(cc::launch_bump_assign_calls(w.hdr, s), "bookkeeping");
@@ -98,7 +107,7 @@ int cc_kmeans_fit(const float* vectors, uint64_t N, uint32_t d, uint32_t K, int3
     const uint32_t n = uint32_t(N);
 
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
-    if (iters > 0) CC_TRY_HIP(cc::launch_absmax(vectors, N * d, w.hdr, s), "input range scan");
+    CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
     if (centroids != init_centroids)
         CC_TRY_HIP(cc::launch_copy_f32(init_centroids, centroids, size_t(K) * d, s), "centroid copy");
     for (int32_t t = 0; t < iters; ++t) {
@@ -119,6 +128,7 @@ int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroi
     hipStream_t s = static_cast<hipStream_t>(stream);
     const cc::Workspace w = cc::carve(workspace, N, d, K);
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
+    CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
     return run_assign(vectors, uint32_t(N), d, centroids, K, idx, inertia, w, s);
 }
 
@@ -134,7 +144,7 @@ int cc_update(const float* vectors, uint64_t N, uint32_t d, const uint32_t* idx,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const cc::Workspace w = cc::carve(workspace, N, d, K);
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
-    CC_TRY_HIP(cc::launch_absmax(vectors, N * d, w.hdr, s), "input range scan");
+    CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
     CC_TRY_HIP(cc::launch_update(vectors, uint32_t(N), d, idx, prev_centroids, K, centroids, counts, w, s), "update");
     return CC_OK;
 }

@@ -44,9 +44,10 @@ constexpr float kGuardSafety = 1.5f;
 template <int D>
 __global__ __launch_bounds__(kThreads) void pack_codebook_kernel(const float* __restrict__ C, uint32_t K,
                                                                  uint32_t ntiles, float* __restrict__ packed,
-                                                                 WsHeader* hdr)
+                                                                 WsHeader* hdr, int gate)
 {
     constexpr uint32_t KS = D / 2, TF = 64 * KS + 32;
+    if (!gate_open(hdr, gate)) return;
     const size_t o = size_t(blockIdx.x) * kThreads + threadIdx.x;
     if (o == 0) hdr->refine_count = 0;
     if (o >= size_t(ntiles) * TF) return;
@@ -81,9 +82,10 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
                                                                uint32_t* __restrict__ idx, float* __restrict__ dmin,
                                                                WsHeader* hdr, uint32_t* __restrict__ refine_list,
                                                                unsigned long long* __restrict__ refine_best,
-                                                               uint32_t refine_cap)
+                                                               uint32_t refine_cap, int gate)
 {
     constexpr int KS = D / 2;                 // MFMA k-steps per tile
+    if (!gate_open(hdr, gate)) return;        // uniform over the grid
     constexpr int TF = 64 * KS + 32;          // floats per packed tile
     constexpr int STAGE_F4 = ST * TF / 4;     // float4 per LDS stage
     constexpr int NPF = (STAGE_F4 + kThreads - 1) / kThreads;
@@ -239,96 +241,29 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Refinement: the listed vectors are re-decided over ALL K centroids in direct form. Work item =
-// (chunk of 64 listed vectors, slice of the codebook); each lane keeps the best (distance, index) of
-// its slice and merges it with a 64-bit atomicMin on (distance bits << 32 | index): distances are
-// non-negative, so the integer order is (distance, then lowest index) - order independent.
-template <int D>
-__global__ __launch_bounds__(64) void refine_kernel(const float* __restrict__ X, const float* __restrict__ C,
-                                                    uint32_t K, const WsHeader* __restrict__ hdr,
-                                                    const uint32_t* __restrict__ refine_list,
-                                                    unsigned long long* __restrict__ refine_best,
-                                                    uint32_t refine_cap, uint32_t slices)
-{
-    const uint32_t count = hdr->refine_count;
-    if (count == 0 || count > refine_cap) return;  // overflow is handled by the full direct pass
-    const uint32_t chunks = (count + 63) / 64;
-    const uint32_t per = (K + slices - 1) / slices;
-    for (uint32_t w = blockIdx.x; w < chunks * slices; w += gridDim.x) {
-        const uint32_t chunk = w / slices, slice = w % slices;
-        const uint32_t e = chunk * 64 + threadIdx.x;
-        const uint32_t ec = min(e, count - 1);
-        float x[D];
-        load_row<D>(X + size_t(refine_list[ec]) * D, x);
-        const uint32_t k_lo = slice * per, k_hi = min(k_lo + per, K);
-        float bd = INFINITY;
-        uint32_t bk = 0;
-        for (uint32_t k = k_lo; k < k_hi; ++k) {  // k is wave-uniform: the centroid is fetched once per wave
-            float c[D];
-            load_row<D>(C + size_t(k) * D, c);
-            const float dk = direct_sqdist<D>(x, c);
-            if (dk < bd) {
-                bd = dk;
-                bk = k;
-            }
-        }
-        if (e < count && k_lo < k_hi)
-            atomicMin(&refine_best[e], (static_cast<unsigned long long>(__float_as_uint(bd)) << 32) | bk);
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void refine_finish_kernel(WsHeader* hdr, const uint32_t* __restrict__ refine_list,
-                                                                 const unsigned long long* __restrict__ refine_best,
-                                                                 uint32_t refine_cap, uint32_t* __restrict__ idx,
-                                                                 float* __restrict__ dmin)
-{
-    const uint32_t count = hdr->refine_count;
-    const uint32_t e = blockIdx.x * kThreads + threadIdx.x;
-    if (e == 0) {
-        hdr->refined_vectors += count;
-        hdr->assign_calls += 1;
-    }
-    if (count > refine_cap) return;
-    for (uint32_t j = e; j < count; j += gridDim.x * kThreads) {
-        const unsigned long long v = refine_best[j];
-        const uint32_t i = refine_list[j];
-        idx[i] = uint32_t(v & 0xffffffffull);
-        dmin[i] = __uint_as_float(uint32_t(v >> 32));
-    }
-}
-
 template <int D, int VT, int ST>
 static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, const Workspace& w,
-                           hipStream_t s)
+                           int gate, hipStream_t s)
 {
     constexpr int GT = int(kGroupTiles);
     constexpr uint32_t TF = 64 * (D / 2) + 32;
     const size_t packed_floats = size_t(w.packed_tiles) * TF;
     hipLaunchKernelGGL(pack_codebook_kernel<D>, dim3(uint32_t((packed_floats + kThreads - 1) / kThreads)),
-                       dim3(kThreads), 0, s, C, K, w.packed_tiles, w.packed, w.hdr);
+                       dim3(kThreads), 0, s, C, K, w.packed_tiles, w.packed, w.hdr, gate);
     const uint32_t per_block = 4 * 32 * VT;
     hipLaunchKernelGGL((assign_mfma_kernel<D, VT, ST, GT>), dim3((N + per_block - 1) / per_block), dim3(kThreads), 0, s,
                        X, N, C, K, w.packed, w.packed_tiles, idx, w.dmin, w.hdr, w.refine_list, w.refine_best,
-                       w.refine_cap);
-    const uint32_t slices = K >= 4096 ? 32 : (K >= 256 ? 4 : 1);
-    hipLaunchKernelGGL(refine_kernel<D>, dim3(4096), dim3(64), 0, s, X, C, K, w.hdr, w.refine_list, w.refine_best,
-                       w.refine_cap, slices);
-    hipLaunchKernelGGL(refine_finish_kernel, dim3(256), dim3(kThreads), 0, s, w.hdr, w.refine_list, w.refine_best,
-                       w.refine_cap, idx, w.dmin);
-    // overflow path: more guard-band vectors than the list holds -> decide everything in direct form
-    hipError_t e = launch_assign_direct(X, N, D, C, K, idx, w.dmin, &w.hdr->refine_count, w.refine_cap, s);
-    if (e != hipSuccess) return e;
+                       w.refine_cap, gate);
     return hipGetLastError();
 }
 
-hipError_t launch_assign_mfma(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                              const Workspace& w, hipStream_t s)
+hipError_t launch_assign_mfma_f32(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
+                                  const Workspace& w, int gate, hipStream_t s)
 {
     switch (d) {
-        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, s);
-        case 8: return launch_t<8, 4, 8>(X, N, C, K, idx, w, s);
-        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, s);
+        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, gate, s);
+        case 8: return launch_t<8, 4, 8>(X, N, C, K, idx, w, gate, s);
+        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, gate, s);
         default: return hipErrorInvalidValue;
     }
 }

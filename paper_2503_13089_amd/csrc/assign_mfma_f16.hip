@@ -1,0 +1,367 @@
+// E-step on the fp16 matrix cores with fp32-grade scores, for fp16-representable inputs
+// (Section 3.1: w_i goes to the centroid minimising ||w_i - c||^2; the paper's tensors are 16-bit).
+//
+// Same scheme as the fp32 MFMA kernel (scores s = ||c||^2 - 2 x.c, lane = one vector, running
+// min / second-min per centroid group, direct-form index recovery, guard band + refinement), but
+// the products run on v_mfma_f32_32x32x16_f16, whose rate is 16x that of the fp32 MFMA and which,
+// unlike the fp32 MFMA, leaves the vector ALUs free for the min-reduction while it runs.
+//
+// Exactness: every input x is an fp16 number (checked on the device; otherwise the fp32 kernel runs).
+// Each fp32 centroid component, scaled by a power of two sigma so that it fits the fp16 range, is
+// split into three fp16 parts c*sigma = h1 + h2 + h3 (each part the fp16 rounding of what is left;
+// the residual is below 2^-33 |c*sigma| or the fp16 subnormal step 2^-24). An fp16 x fp16 product
+// has at most 22 significant bits, so every product h_p * (-2 x) is exact in the fp32 accumulator:
+// the only rounding is in the accumulation. The k = 16 slots of one MFMA hold, for d = 4, the 12
+// products (3 parts x 4 components) and three more slots that add sigma * ||c||^2, itself split into
+// three fp16 parts against the fixed multipliers 2^8, 2^-3, 2^-14 (d = 8: 27 of 32 slots in two
+// MFMAs; d = 16: 48 slots in three MFMAs and sigma * ||c||^2 as the fp32 C operand instead).
+//
+// Guard band: measured on gfx950, the accumulated result differs from the exact sum by at most
+// ~3 * 2^-24 * (sum of |terms|); the band assumes kAccumUlps = 8 times that unit, plus the split
+// residual. A vector whose best and second-best group scores are closer than the band is re-decided
+// in direct form over all K (refine.hip), exactly as for the fp32 kernel.
+#include "common.h"
+
+namespace cc {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kThreads = 256;
+constexpr float kUnit = 5.9604644775390625e-08f;  // 2^-24
+constexpr float kGuardSafety = 1.5f;
+constexpr float kAccumUlps = 8.0f;
+
+template <int D>
+struct F16Shape {
+    static constexpr bool kNormInK = (D != 16);             // ||c||^2 rides in spare k slots
+    static constexpr int kSlots = 3 * D + (kNormInK ? 3 : 0);
+    static constexpr int KM = (kSlots + 15) / 16;           // MFMAs per tile
+    static constexpr int kTileBytes = 64 * KM * 16 + (kNormInK ? 0 : 128);
+};
+
+// log2 of the centroid scale sigma: max|c| * sigma <= 2^15 and d * max|c|^2 * sigma <= 2^23
+__device__ __forceinline__ int centroid_scale_log2(uint32_t cmax_bits, int d)
+{
+    if (cmax_bits == 0) return 0;
+    const int ec = int(cmax_bits >> 23) - 127;  // max|c| < 2^(ec+1)
+    const int ld = 32 - __clz(uint32_t(d - 1)); // d <= 2^ld
+    int s = min(14 - ec, 21 - 2 * ec - ld);
+    return max(-100, min(100, s));
+}
+
+// The three fp16 parts of a scaled fp32 value.
+__device__ __forceinline__ void split3(float v, _Float16 (&h)[3])
+{
+    h[0] = _Float16(v);
+    const float r1 = v - float(h[0]);  // exact
+    h[1] = _Float16(r1);
+    const float r2 = r1 - float(h[1]);  // exact
+    h[2] = _Float16(r2);
+}
+
+// sigma*||c||^2 as g0*2^8 + g1*2^-3 + g2*2^-14
+__device__ __forceinline__ void split_norm(float v, _Float16 (&g)[3])
+{
+    g[0] = _Float16(v * 0.00390625f);
+    const float r1 = v - float(g[0]) * 256.0f;
+    g[1] = _Float16(r1 * 8.0f);
+    const float r2 = r1 - float(g[1]) * 0.125f;
+    g[2] = _Float16(r2 * 16384.0f);
+}
+
+__global__ __launch_bounds__(1024) void codebook_absmax_kernel(const float* __restrict__ C, size_t n, WsHeader* hdr,
+                                                               int gate)
+{
+    if (!gate_open(hdr, gate)) return;
+    __shared__ uint32_t red[16];
+    uint32_t m = 0;
+    for (size_t i = threadIdx.x; i < n; i += 1024) m = max(m, __float_as_uint(C[i]) & 0x7fffffffu);
+    for (int off = 32; off > 0; off >>= 1) m = max(m, uint32_t(__shfl_xor(int(m), off, 64)));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w) m = max(m, red[w]);
+        hdr->cmax_bits = m;
+        hdr->refine_count = 0;
+    }
+}
+
+// Packed codebook: per 32-centroid tile, [64 lanes][KM] x 8 fp16 A-operand values (lane (m, h) holds
+// k slots 16*mi + 8h .. +7 of MFMA mi for output row m), then for d = 16 the 32 scaled norms (fp32).
+// Output row m of a tile is centroid 32*tile + 16*((m/4)%2) + (m%4) + 4*(m/8), so that lane-half h,
+// accumulator register r is centroid 32*tile + 16h + r. Rows past K: all-zero parts, norm = +inf.
+template <int D>
+__global__ __launch_bounds__(kThreads) void pack_codebook_f16_kernel(const float* __restrict__ C, uint32_t K,
+                                                                     uint32_t ntiles, char* __restrict__ packed,
+                                                                     const WsHeader* __restrict__ hdr, int gate)
+{
+    using S = F16Shape<D>;
+    if (!gate_open(hdr, gate)) return;
+    const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
+    const uint32_t tile = t / 64, lane = t % 64;
+    if (tile >= ntiles) return;
+    const float sigma = __builtin_ldexpf(1.0f, centroid_scale_log2(hdr->cmax_bits, D));
+    const uint32_t h = lane >> 5, m = lane & 31;
+    const uint32_t k = 32 * tile + 16 * ((m >> 2) & 1) + (m & 3) + 4 * (m >> 3);
+    const bool valid = k < K;
+    _Float16 parts[D][3];
+    double norm = 0.0;
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+        const float c = valid ? C[size_t(k) * D + j] : 0.0f;
+        norm += double(c) * double(c);
+        split3(c * sigma, parts[j]);
+    }
+    _Float16 g[3];
+    if (valid) {
+        split_norm(float(norm * double(sigma)), g);  // one rounding of the exact norm
+    } else {
+        g[0] = _Float16(INFINITY);  // times the 2^8 multiplier: a score of +inf, never the minimum
+        g[1] = _Float16(0.0f);
+        g[2] = _Float16(0.0f);
+    }
+    char* tile_base = packed + size_t(tile) * S::kTileBytes;
+#pragma unroll
+    for (int mi = 0; mi < S::KM; ++mi) {
+        f16x8 lo, hi;  // the slots of half 0 and of half 1
+#pragma unroll
+        for (int q8 = 0; q8 < 8; ++q8) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const int q = 16 * mi + 8 * half + q8;
+                _Float16 v = _Float16(0.0f);
+                if (q < 3 * D) v = parts[q % D][q / D];
+                else if (S::kNormInK && q < 3 * D + 3) v = g[q - 3 * D];
+                if (half == 0) lo[q8] = v; else hi[q8] = v;
+            }
+        }
+        *reinterpret_cast<f16x8*>(tile_base + (size_t(lane) * S::KM + mi) * 16) = h ? hi : lo;
+    }
+    if (!S::kNormInK && lane < 32) {
+        // norms in centroid order 32*tile + lane (this thread's own k is a permuted row, so recompute)
+        const uint32_t kc = 32 * tile + lane;
+        float v = INFINITY;
+        if (kc < K) {
+            double s = 0.0;
+            for (int j = 0; j < D; ++j) {
+                const double c = double(C[size_t(kc) * D + j]);
+                s += c * c;
+            }
+            v = float(s * double(sigma));
+        }
+        *reinterpret_cast<float*>(tile_base + 64 * S::KM * 16 + 4 * lane) = v;
+    }
+}
+
+template <int D, int VT, int ST, int GT>
+__global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
+    const float* __restrict__ X, uint32_t N, const float* __restrict__ C, uint32_t K, const char* __restrict__ packed,
+    uint32_t ntiles, uint32_t* __restrict__ idx, float* __restrict__ dmin, WsHeader* hdr,
+    uint32_t* __restrict__ refine_list, unsigned long long* __restrict__ refine_best, uint32_t refine_cap, int gate)
+{
+    using S = F16Shape<D>;
+    constexpr int KM = S::KM;
+    constexpr int TILE_F4 = S::kTileBytes / 16;
+    constexpr int STAGE_F4 = ST * TILE_F4;
+    constexpr int NPF = (STAGE_F4 + kThreads - 1) / kThreads;
+    static_assert(ST % GT == 0, "a tracking group must not straddle LDS stages");
+    static_assert(int(kStageTilesMax) % ST == 0, "the packed codebook is padded to whole stages");
+    if (!gate_open(hdr, gate)) return;  // uniform over the grid
+    __shared__ float4 lds[2][STAGE_F4];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int h = lane >> 5, n = lane & 31;
+    const uint32_t vbase = (blockIdx.x * 4 + wave) * (32 * VT);
+
+    // B operands: lane (n, h) supplies k slots 16*mi + 8h .. +7 of vector n: -2 x_j for the product
+    // slots, the fixed multipliers for the norm slots, 0 for unused slots
+    f16x8 b[VT][KM];
+#pragma unroll
+    for (int vt = 0; vt < VT; ++vt) {
+        const uint32_t i = min(vbase + vt * 32 + n, N - 1);
+        float x[D];
+        load_row<D>(X + size_t(i) * D, x);
+#pragma unroll
+        for (int mi = 0; mi < KM; ++mi) {
+#pragma unroll
+            for (int q8 = 0; q8 < 8; ++q8) {
+                _Float16 v[2];
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int q = 16 * mi + 8 * half + q8;
+                    v[half] = _Float16(0.0f);
+                    if (q < 3 * D) v[half] = _Float16(-2.0f * x[q % D]);
+                    else if (S::kNormInK && q == 3 * D) v[half] = _Float16(256.0f);
+                    else if (S::kNormInK && q == 3 * D + 1) v[half] = _Float16(0.125f);
+                    else if (S::kNormInK && q == 3 * D + 2) v[half] = _Float16(6.103515625e-05f);  // 2^-14
+                }
+                b[vt][mi][q8] = h ? v[1] : v[0];
+            }
+        }
+    }
+    float best[VT], second[VT];
+    uint32_t grp[VT];
+#pragma unroll
+    for (int vt = 0; vt < VT; ++vt) {
+        best[vt] = INFINITY;
+        second[vt] = INFINITY;
+        grp[vt] = 0;
+    }
+
+    const float4* P4 = reinterpret_cast<const float4*>(packed);
+    const uint32_t nstages = ntiles / ST;
+#pragma unroll
+    for (int p = 0; p < NPF; ++p) {
+        const uint32_t j = threadIdx.x + p * kThreads;
+        if (NPF * kThreads == STAGE_F4 || j < STAGE_F4) lds[0][j] = P4[j];
+    }
+    __syncthreads();
+
+    for (uint32_t s = 0; s < nstages; ++s) {
+        const int cur = s & 1;
+        const uint32_t sn = min(s + 1, nstages - 1);  // the last iteration re-reads its own stage; never used
+        float4 pf[NPF];
+#pragma unroll
+        for (int p = 0; p < NPF; ++p) {
+            const uint32_t j = min(threadIdx.x + p * kThreads, uint32_t(STAGE_F4 - 1));
+            pf[p] = P4[size_t(sn) * STAGE_F4 + j];
+        }
+
+        const char* L = reinterpret_cast<const char*>(lds[cur]);
+#pragma unroll 1
+        for (uint32_t tt = 0; tt < ST; tt += GT) {
+            float m[VT];
+#pragma unroll
+            for (int vt = 0; vt < VT; ++vt) m[vt] = INFINITY;
+#pragma unroll
+            for (int g = 0; g < GT; ++g) {
+                const char* T = L + (tt + g) * S::kTileBytes;
+                f16x8 a[KM];
+#pragma unroll
+                for (int mi = 0; mi < KM; ++mi) a[mi] = *reinterpret_cast<const f16x8*>(T + (lane * KM + mi) * 16);
+                f32x16 cn;
+                if constexpr (S::kNormInK) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) cn[r] = 0.0f;
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 t = *reinterpret_cast<const float4*>(T + 64 * KM * 16 + (16 * h + 4 * q) * 4);
+                        cn[4 * q + 0] = t.x; cn[4 * q + 1] = t.y; cn[4 * q + 2] = t.z; cn[4 * q + 3] = t.w;
+                    }
+                }
+#pragma unroll
+                for (int vt = 0; vt < VT; ++vt) {
+                    f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], b[vt][0], cn, 0, 0, 0);
+#pragma unroll
+                    for (int mi = 1; mi < KM; ++mi)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mi], b[vt][mi], acc, 0, 0, 0);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) m[vt] = __builtin_fminf(__builtin_fminf(m[vt], acc[2 * q]), acc[2 * q + 1]);
+                }
+            }
+            const uint32_t gid = (s * ST + tt) / GT;
+#pragma unroll
+            for (int vt = 0; vt < VT; ++vt) {
+                second[vt] = __builtin_amdgcn_fmed3f(best[vt], second[vt], m[vt]);
+                grp[vt] = m[vt] < best[vt] ? gid : grp[vt];
+                best[vt] = __builtin_fminf(best[vt], m[vt]);
+            }
+        }
+
+#pragma unroll
+        for (int p = 0; p < NPF; ++p) {
+            const uint32_t j = threadIdx.x + p * kThreads;
+            if (NPF * kThreads == STAGE_F4 || j < STAGE_F4) lds[cur ^ 1][j] = pf[p];
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: index recovery in direct form, merge of the two half-waves, guard-band test.
+    // Scores are in sigma-scaled units; the band is scaled to match.
+    const float sigma = __builtin_ldexpf(1.0f, centroid_scale_log2(hdr->cmax_bits, D));
+#pragma unroll
+    for (int vt = 0; vt < VT; ++vt) {
+        const uint32_t i_raw = vbase + vt * 32 + n;
+        const uint32_t i = min(i_raw, N - 1);
+        float x[D];
+        load_row<D>(X + size_t(i) * D, x);
+        float bd = INFINITY;
+        uint32_t bk = 0;
+        for (int g = 0; g < GT; ++g) {
+            const uint32_t k0 = 32 * (grp[vt] * GT + g) + 16 * h;
+            for (int r = 0; r < 16; ++r) {
+                const uint32_t k = k0 + r;
+                if (k < K) {
+                    float c[D];
+                    load_row<D>(C + size_t(k) * D, c);
+                    const float dk = direct_sqdist<D>(x, c);
+                    if (dk < bd) {
+                        bd = dk;
+                        bk = k;
+                    }
+                }
+            }
+        }
+        const float od = __shfl_xor(bd, 32, 64);
+        const uint32_t ok = uint32_t(__shfl_xor(int(bk), 32, 64));
+        const float ob = __shfl_xor(best[vt], 32, 64);
+        const float os = __shfl_xor(second[vt], 32, 64);
+        const bool take = od < bd || (od == bd && ok < bk);
+        const float dstar = take ? od : bd;
+        const uint32_t kstar = take ? ok : bk;
+        const float bstar = __builtin_fminf(best[vt], ob);
+        const float sstar = __builtin_fminf(second[vt], os);
+        float xn = 0.0f, x1 = 0.0f;
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            xn = __builtin_fmaf(x[j], x[j], xn);
+            x1 += __builtin_fabsf(x[j]);
+        }
+        // accumulation rounding of winner + true nearest (||c||^2 <= 2||x||^2 + 2D for both), then the
+        // split residuals: 2^-25 per component against |2 x_j|, twice, and the norm residual
+        const float delta = sigma * kGuardSafety * 2.0f * kAccumUlps * kUnit * (5.0f * xn + 4.0f * dstar) +
+                            kGuardSafety * (2.0f * kUnit * x1 + 1e-11f) + 1e-36f;
+        const bool safe = (sstar - bstar) > delta;  // false for NaN as well
+        if (h == 0 && i_raw < N) {
+            idx[i] = kstar;
+            dmin[i] = dstar;
+            if (!safe) {
+                const uint32_t pos = atomicAdd(&hdr->refine_count, 1u);
+                if (pos < refine_cap) {
+                    refine_list[pos] = i;
+                    refine_best[pos] = ~0ull;
+                }
+            }
+        }
+    }
+}
+
+template <int D, int VT, int ST>
+static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, const Workspace& w,
+                           int gate, hipStream_t s)
+{
+    constexpr int GT = int(kGroupTiles);
+    hipLaunchKernelGGL(codebook_absmax_kernel, dim3(1), dim3(1024), 0, s, C, size_t(K) * D, w.hdr, gate);
+    hipLaunchKernelGGL(pack_codebook_f16_kernel<D>, dim3((w.packed_tiles * 64 + kThreads - 1) / kThreads),
+                       dim3(kThreads), 0, s, C, K, w.packed_tiles, reinterpret_cast<char*>(w.packed), w.hdr, gate);
+    const uint32_t per_block = 4 * 32 * VT;
+    hipLaunchKernelGGL((assign_mfma_f16_kernel<D, VT, ST, GT>), dim3((N + per_block - 1) / per_block), dim3(kThreads),
+                       0, s, X, N, C, K, reinterpret_cast<const char*>(w.packed), w.packed_tiles, idx, w.dmin, w.hdr,
+                       w.refine_list, w.refine_best, w.refine_cap, gate);
+    return hipGetLastError();
+}
+
+hipError_t launch_assign_mfma_f16(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
+                                  const Workspace& w, int gate, hipStream_t s)
+{
+    switch (d) {
+        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, gate, s);
+        case 8: return launch_t<8, 4, 4>(X, N, C, K, idx, w, gate, s);
+        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, gate, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace cc

@@ -12,6 +12,8 @@ constexpr uint32_t kMaxK = 1u << 24;
 struct WsHeader {
     uint32_t absmax_bits;      // max over all inputs of the fp32 bit pattern of |x|
     uint32_t refine_count;     // length of the refine list written by the last matrix-core assign
+    uint32_t x_not_f16;        // != 0: some input is not exactly representable in fp16 (or |x| >= 2^15)
+    uint32_t cmax_bits;        // max over the current codebook of the fp32 bit pattern of |c|
     unsigned long long refined_vectors;
     unsigned long long skipped_vectors;
     unsigned long long assign_calls;
@@ -58,7 +60,8 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     w.dmin = reinterpret_cast<float*>(take(size_t(N) * 4));
     const uint32_t stage = kTileCentroids * kStageTilesMax;
     w.packed_tiles = uint32_t((uint64_t(K) + stage - 1) / stage) * kStageTilesMax;
-    w.packed = reinterpret_cast<float*>(take(size_t(w.packed_tiles) * kTileCentroids * (d + 1) * 4));
+    // per centroid: fp32 operands + norm take 4(d+1) bytes; the fp16-split operands take up to 6d+4 bytes
+    w.packed = reinterpret_cast<float*>(take(size_t(w.packed_tiles) * kTileCentroids * (6 * d + 16)));
     w.refine_cap = uint32_t(N / 8 + 4096);
     w.refine_list = reinterpret_cast<uint32_t*>(take(size_t(w.refine_cap) * 4));
     w.refine_best = reinterpret_cast<unsigned long long*>(take(size_t(w.refine_cap) * 8));
@@ -74,10 +77,30 @@ hipError_t launch_assign_direct(const float* X, uint32_t N, uint32_t d, const fl
                                 uint32_t* idx, float* dmin, const uint32_t* gate, uint32_t gate_limit,
                                 hipStream_t s);
 
-// Matrix-core E-step: packs the codebook, runs the fp32 MFMA kernel with min/second tracking, then
-// re-decides the guard-band vectors in direct form. Writes idx and w.dmin.
-hipError_t launch_assign_mfma(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K,
-                              uint32_t* idx, const Workspace& w, hipStream_t s);
+// Which inputs a gated kernel runs for (decided on the device from WsHeader::x_not_f16).
+enum Gate : int { kGateIfF16 = 0, kGateIfNotF16 = 1, kGateAlways = 2 };
+__device__ __forceinline__ bool gate_open(const WsHeader* hdr, int gate)
+{
+    return gate == kGateAlways || (gate == kGateIfF16) == (hdr->x_not_f16 == 0);
+}
+
+// Matrix-core E-step, fp32 MFMA: packs the codebook and runs the scoring kernel (provisional idx,
+// w.dmin and the refine list). Must be followed by launch_refine.
+hipError_t launch_assign_mfma_f32(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K,
+                                  uint32_t* idx, const Workspace& w, int gate, hipStream_t s);
+
+// Matrix-core E-step for fp16-representable inputs: centroids split into three fp16 parts so that
+// every product is exact, scored with the fp16 MFMA. Same outputs as the fp32 variant.
+hipError_t launch_assign_mfma_f16(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K,
+                                  uint32_t* idx, const Workspace& w, int gate, hipStream_t s);
+
+// Re-decides the listed guard-band vectors over all K centroids in direct form; if the list
+// overflowed, re-decides everything in direct form.
+hipError_t launch_refine(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
+                         const Workspace& w, hipStream_t s);
+
+// Scans the inputs: max |x| and whether every x is exactly representable in fp16.
+hipError_t launch_scan_inputs(const float* X, uint64_t n_floats, WsHeader* hdr, hipStream_t s);
 
 // *out = sum_i dmin[i] in fp64 with a fixed reduction shape.
 hipError_t launch_reduce_dmin(const float* dmin, uint32_t N, double* partials, uint32_t partial_slots,
@@ -85,7 +108,6 @@ hipError_t launch_reduce_dmin(const float* dmin, uint32_t N, double* partials, u
 
 // Header bookkeeping.
 hipError_t launch_reset_header(WsHeader* hdr, hipStream_t s);
-hipError_t launch_absmax(const float* X, uint64_t n_floats, WsHeader* hdr, hipStream_t s);
 hipError_t launch_bump_assign_calls(WsHeader* hdr, hipStream_t s);
 
 // M-step.

@@ -20,6 +20,8 @@ __global__ void reset_header_kernel(WsHeader* hdr)
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         hdr->absmax_bits = 0;
         hdr->refine_count = 0;
+        hdr->x_not_f16 = 0;
+        hdr->cmax_bits = 0;
         hdr->refined_vectors = 0;
         hdr->skipped_vectors = 0;
         hdr->assign_calls = 0;
@@ -45,27 +47,49 @@ hipError_t launch_bump_assign_calls(WsHeader* hdr, hipStream_t s)
     return hipGetLastError();
 }
 
-// max |x| over the whole input, as the maximum of the (sign-cleared) fp32 bit patterns: for finite
-// floats the integer order of the patterns is the order of the magnitudes.
-__global__ __launch_bounds__(kThreads) void absmax_kernel(const float4* __restrict__ X4, uint64_t n4, WsHeader* hdr)
+// One pass over the inputs: max |x| as the maximum of the (sign-cleared) fp32 bit patterns (for finite
+// floats the integer order of the patterns is the order of the magnitudes), and whether every value
+// survives a round trip through fp16 with |x| < 2^15 (then -2x is also an fp16 number).
+__global__ __launch_bounds__(kThreads) void scan_inputs_kernel(const float4* __restrict__ X4, uint64_t n4, WsHeader* hdr)
 {
-    uint32_t m = 0;
+    __shared__ uint32_t red_m[kThreads / 64], red_f[kThreads / 64];
+    uint32_t m = 0, bad = 0;
     for (uint64_t i = uint64_t(blockIdx.x) * kThreads + threadIdx.x; i < n4; i += uint64_t(gridDim.x) * kThreads) {
-        float4 t = X4[i];
-        m = max(m, __float_as_uint(t.x) & 0x7fffffffu);
-        m = max(m, __float_as_uint(t.y) & 0x7fffffffu);
-        m = max(m, __float_as_uint(t.z) & 0x7fffffffu);
-        m = max(m, __float_as_uint(t.w) & 0x7fffffffu);
+        const float4 t = X4[i];
+        const float v[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t a = __float_as_uint(v[j]) & 0x7fffffffu;
+            m = max(m, a);
+            const float back = float(_Float16(v[j]));
+            bad |= (back != v[j]) || (a >= 0x47000000u /* 2^15 */);
+        }
     }
-    for (int off = 32; off > 0; off >>= 1) m = max(m, uint32_t(__shfl_xor(int(m), off, 64)));
-    if ((threadIdx.x & 63) == 0) atomicMax(&hdr->absmax_bits, m);
+    for (int off = 32; off > 0; off >>= 1) {
+        m = max(m, uint32_t(__shfl_xor(int(m), off, 64)));
+        bad |= uint32_t(__shfl_xor(int(bad), off, 64));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        red_m[threadIdx.x >> 6] = m;
+        red_f[threadIdx.x >> 6] = bad;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kThreads / 64; ++w) {
+            m = max(m, red_m[w]);
+            bad |= red_f[w];
+        }
+        atomicMax(&hdr->absmax_bits, m);
+        if (bad) atomicOr(&hdr->x_not_f16, 1u);
+    }
 }
 
-hipError_t launch_absmax(const float* X, uint64_t n_floats, WsHeader* hdr, hipStream_t s)
+hipError_t launch_scan_inputs(const float* X, uint64_t n_floats, WsHeader* hdr, hipStream_t s)
 {
     const uint64_t n4 = n_floats / 4;  // d is a multiple of 4
-    const uint32_t blocks = uint32_t(std::min<uint64_t>((n4 + kThreads - 1) / kThreads, 256 * 16));
-    hipLaunchKernelGGL(absmax_kernel, dim3(blocks), dim3(kThreads), 0, s, reinterpret_cast<const float4*>(X), n4, hdr);
+    const uint32_t blocks = uint32_t(std::min<uint64_t>((n4 + kThreads - 1) / kThreads, 2048));
+    hipLaunchKernelGGL(scan_inputs_kernel, dim3(blocks), dim3(kThreads), 0, s, reinterpret_cast<const float4*>(X), n4,
+                       hdr);
     return hipGetLastError();
 }
 
