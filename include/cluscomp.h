@@ -78,6 +78,18 @@ int cc_assign(const float *vectors, uint64_t N, uint32_t d, const float *centroi
               uint32_t *idx, double *inertia, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * One Lloyd iteration (Section 3.1: an E-step followed by an M-step), the unit the fit repeats:
+ *   idx_i      = argmin_k ||w_i - c_k||^2 over the centroids as passed in,
+ *   centroids <- per-cluster means of those assignments, in place (empty clusters keep their value),
+ *   inertia    (fp64, device, may be NULL) = sum_i ||w_i - c_{idx_i}||^2 against the centroids as passed in,
+ *   counts [K] (uint32, may be NULL) = cluster sizes.
+ * The result is bit-identical to cc_assign followed by cc_update; it is faster because the cluster
+ * sums are accumulated by the assignment kernel while the vectors are on chip.
+ */
+int cc_lloyd_iter(const float *vectors, uint64_t N, uint32_t d, float *centroids, uint32_t K, uint32_t *idx,
+                  double *inertia, uint32_t *counts, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * M-step alone (Section 3.1): centroids_k = mean of the vectors with idx_i == k; a cluster without
  * members keeps prev_centroids_k. Every idx_i must be < K (checked on the device: offending vectors
  * are skipped and counted in the workspace statistics). `centroids` may alias `prev_centroids`.
@@ -110,8 +122,10 @@ typedef struct cc_stats {
 } cc_stats;
 int cc_read_stats(const void *workspace, size_t workspace_bytes, cc_stats *host_out, void *stream);
 
-/* Selects the E-step kernel: 0 = automatic (default), 1 = direct-form VALU kernel only,
- * 2 = matrix-core kernel with guard band + direct-form refinement. Process-wide; for tests and
+/* Selects the E-step kernel. 0 = automatic (default): for K >= 128 the matrix cores, with the fp16 MFMA
+ * (centroids split into three fp16 parts, exact products) when every input is an fp16 number and
+ * the fp32 MFMA otherwise, both with guard band + direct-form refinement; direct form for small K.
+ * 1 = direct-form vector-ALU kernel only. 2 = fp32 MFMA kernel always. Process-wide; for tests and
  * profiling. Returns the previous value, or CC_ERR_SHAPE for an unknown mode. */
 int cc_set_assign_mode(int mode);
 

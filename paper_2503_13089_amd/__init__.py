@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     kmeans_fit,
     last_error,
     lib_path,
+    lloyd_iter,
     load_library,
     read_stats,
     set_assign_mode,

@@ -13,7 +13,7 @@ _LIB_PATH = os.path.join(_HERE, "libcluscomp.so")
 _lib = None
 
 EXPORTS = (
-    "cc_workspace_bytes", "cc_kmeans_fit", "cc_assign", "cc_update", "cc_decode",
+    "cc_workspace_bytes", "cc_kmeans_fit", "cc_assign", "cc_lloyd_iter", "cc_update", "cc_decode",
     "cc_read_stats", "cc_set_assign_mode", "cc_last_error", "cc_version",
 )
 
@@ -59,6 +59,8 @@ def load_library():
     lib.cc_kmeans_fit.restype = ctypes.c_int
     lib.cc_assign.argtypes = [vp, u64, u32, vp, u32, vp, vp, vp, sz, vp]
     lib.cc_assign.restype = ctypes.c_int
+    lib.cc_lloyd_iter.argtypes = [vp, u64, u32, vp, u32, vp, vp, vp, vp, sz, vp]
+    lib.cc_lloyd_iter.restype = ctypes.c_int
     lib.cc_update.argtypes = [vp, u64, u32, vp, vp, u32, vp, vp, vp, sz, vp]
     lib.cc_update.restype = ctypes.c_int
     lib.cc_decode.argtypes = [vp, u32, u32, vp, u64, vp, vp]
@@ -140,6 +142,18 @@ def assign(vectors, centroids, idx, inertia, workspace) -> None:
                                     _ptr(centroids, torch.float32, "centroids"), K, _ptr(idx, _idx_dtype(), "idx"),
                                     _ptr(inertia, torch.float64, "inertia"), _ptr(workspace, torch.uint8, "workspace"),
                                     workspace.numel(), _stream()))
+
+
+def lloyd_iter(vectors, centroids, idx, inertia, counts, workspace) -> None:
+    """cc_lloyd_iter: one E-step + M-step; `centroids` is updated in place."""
+    import torch
+
+    N, d = vectors.shape
+    K = centroids.shape[0]
+    _check(load_library().cc_lloyd_iter(_ptr(vectors, torch.float32, "vectors"), N, d,
+                                        _ptr(centroids, torch.float32, "centroids"), K, _ptr(idx, _idx_dtype(), "idx"),
+                                        _ptr(inertia, torch.float64, "inertia"), _ptr(counts, _idx_dtype(), "counts"),
+                                        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
 
 
 def update(vectors, idx, prev_centroids, centroids, counts, workspace) -> None:

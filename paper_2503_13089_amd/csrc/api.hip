@@ -54,26 +54,59 @@ int check_workspace(void* ws, size_t ws_bytes, uint64_t N, uint32_t d, uint32_t 
         if (e_ != hipSuccess) return hip_fail(e_, what); \
     } while (0)
 
+bool use_matrix_cores(uint32_t K)
+{
+    const int mode = g_assign_mode.load();
+    return mode == 2 || (mode == 0 && K >= 128);
+}
+
+// Scoring + refinement on the matrix cores. The input scan (WsHeader::x_not_f16) must have run on this
+// workspace since the last header reset.
+int run_assign_matrix(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
+                      const cc::Workspace& w, bool accumulate, hipStream_t s)
+{
+    if (g_assign_mode.load() == 0) {
+        // both variants are enqueued; the device-side gate lets exactly one of them run
+        CC_TRY_HIP(cc::launch_assign_mfma_f16(X, N, d, C, K, idx, w, cc::kGateIfF16, accumulate, s),
+                   "assign (fp16 matrix cores)");
+        CC_TRY_HIP(cc::launch_assign_mfma_f32(X, N, d, C, K, idx, w, cc::kGateIfNotF16, accumulate, s),
+                   "assign (fp32 matrix cores)");
+    } else {
+        CC_TRY_HIP(cc::launch_assign_mfma_f32(X, N, d, C, K, idx, w, cc::kGateAlways, accumulate, s),
+                   "assign (fp32 matrix cores)");
+    }
+    CC_TRY_HIP(cc::launch_refine(X, N, d, C, K, idx, w, accumulate, s), "assign (refinement)");
+    return CC_OK;
+}
+
 // One E-step pass: idx (and, if inertia != NULL, the objective) for the given centroids.
-// The input scan (WsHeader::x_not_f16) must have run on this workspace since the last header reset.
 int run_assign(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx, double* inertia,
                const cc::Workspace& w, hipStream_t s)
 {
-    const int mode = g_assign_mode.load();
-    const bool matrix_cores = mode == 2 || (mode == 0 && K >= 128);
-    if (matrix_cores) {
-        if (mode == 0) {
-            // both variants are enqueued; the device-side gate lets exactly one of them run
-            CC_TRY_HIP(cc::launch_assign_mfma_f16(X, N, d, C, K, idx, w, cc::kGateIfF16, s), "assign (fp16 matrix cores)");
-            CC_TRY_HIP(cc::launch_assign_mfma_f32(X, N, d, C, K, idx, w, cc::kGateIfNotF16, s),
-                       "assign (fp32 matrix cores)");
-        } else {
-            CC_TRY_HIP(cc::launch_assign_mfma_f32(X, N, d, C, K, idx, w, cc::kGateAlways, s), "assign (fp32 matrix cores)");
-        }
-        CC_TRY_HIP(cc::launch_refine(X, N, d, C, K, idx, w, s), "assign (refinement)");
+    if (use_matrix_cores(K)) {
+        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, false, s)) return rc;
     } else {
         CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s), "assign (direct form)");
         CC_TRY_HIP(cc::launch_bump_assign_calls(w.hdr, s), "bookkeeping");
+    }
+    if (inertia)
+        CC_TRY_HIP(cc::launch_reduce_dmin(w.dmin, N, w.partials, w.partial_slots, inertia, s), "objective reduction");
+    return CC_OK;
+}
+
+// One Lloyd iteration: idx = E-step against C, then C <- M-step(idx) in place. On the matrix-core path
+// the cluster sums are accumulated by the scoring kernel itself (no second pass over the vectors).
+int run_lloyd_iter(const float* X, uint32_t N, uint32_t d, float* C, uint32_t K, uint32_t* idx, double* inertia,
+                   uint32_t* counts, const cc::Workspace& w, hipStream_t s)
+{
+    if (use_matrix_cores(K)) {
+        CC_TRY_HIP(cc::launch_zero_accumulators(w, K, d, nullptr, 0, s), "update (clear)");
+        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, true, s)) return rc;
+        CC_TRY_HIP(cc::launch_finalize(C, C, counts, K, d, N, w, s), "update (means)");
+    } else {
+        CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s), "assign (direct form)");
+        CC_TRY_HIP(cc::launch_bump_assign_calls(w.hdr, s), "bookkeeping");
+        CC_TRY_HIP(cc::launch_update(X, N, d, idx, C, K, C, counts, w, s), "update");
     }
     if (inertia)
         CC_TRY_HIP(cc::launch_reduce_dmin(w.dmin, N, w.partials, w.partial_slots, inertia, s), "objective reduction");
@@ -110,10 +143,8 @@ int cc_kmeans_fit(const float* vectors, uint64_t N, uint32_t d, uint32_t K, int3
     CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
     if (centroids != init_centroids)
         CC_TRY_HIP(cc::launch_copy_f32(init_centroids, centroids, size_t(K) * d, s), "centroid copy");
-    for (int32_t t = 0; t < iters; ++t) {
-        if (int rc = run_assign(vectors, n, d, centroids, K, idx, nullptr, w, s)) return rc;
-        CC_TRY_HIP(cc::launch_update(vectors, n, d, idx, centroids, K, centroids, nullptr, w, s), "update");
-    }
+    for (int32_t t = 0; t < iters; ++t)
+        if (int rc = run_lloyd_iter(vectors, n, d, centroids, K, idx, nullptr, nullptr, w, s)) return rc;
     return run_assign(vectors, n, d, centroids, K, idx, inertia, w, s);
 }
 
@@ -130,6 +161,22 @@ int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroi
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
     CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
     return run_assign(vectors, uint32_t(N), d, centroids, K, idx, inertia, w, s);
+}
+
+int cc_lloyd_iter(const float* vectors, uint64_t N, uint32_t d, float* centroids, uint32_t K, uint32_t* idx,
+                  double* inertia, uint32_t* counts, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!vectors || !centroids || !idx) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (int rc = check_shape(N, d, K)) return rc;
+    if (!aligned(vectors, 16) || !aligned(centroids, 16) || !aligned(idx, 4) || (inertia && !aligned(inertia, 8)) ||
+        (counts && !aligned(counts, 4)))
+        return fail(CC_ERR_ALIGN, "vectors/centroids need 16-byte alignment, idx and counts 4, inertia 8");
+    if (int rc = check_workspace(workspace, workspace_bytes, N, d, K)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const cc::Workspace w = cc::carve(workspace, N, d, K);
+    CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
+    CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
+    return run_lloyd_iter(vectors, uint32_t(N), d, centroids, K, idx, inertia, counts, w, s);
 }
 
 int cc_update(const float* vectors, uint64_t N, uint32_t d, const uint32_t* idx, const float* prev_centroids,

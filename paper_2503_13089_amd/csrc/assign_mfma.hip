@@ -82,7 +82,8 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
                                                                uint32_t* __restrict__ idx, float* __restrict__ dmin,
                                                                WsHeader* hdr, uint32_t* __restrict__ refine_list,
                                                                unsigned long long* __restrict__ refine_best,
-                                                               uint32_t refine_cap, int gate)
+                                                               uint32_t refine_cap, int gate, long long* sums,
+                                                               uint32_t* counts)
 {
     constexpr int KS = D / 2;                 // MFMA k-steps per tile
     if (!gate_open(hdr, gate)) return;        // uniform over the grid
@@ -177,7 +178,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
             for (int vt = 0; vt < VT; ++vt) {
                 second[vt] = __builtin_amdgcn_fmed3f(best[vt], second[vt], m[vt]);
                 grp[vt] = m[vt] < best[vt] ? gid : grp[vt];
-                best[vt] = __builtin_fminf(best[vt], m[vt]);
+                best[vt] = __builtin_amdgcn_fmed3f(best[vt], m[vt], -INFINITY);  // = min(best, m)
             }
         }
 
@@ -230,6 +231,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
         if (h == 0 && i_raw < N) {
             idx[i] = kstar;
             dmin[i] = dstar;
+            if (sums != nullptr) accumulate_vector<D>(x, kstar, sums, counts, fixed_point_exp(hdr->absmax_bits, N), +1);
             if (!safe) {
                 const uint32_t pos = atomicAdd(&hdr->refine_count, 1u);
                 if (pos < refine_cap) {
@@ -243,7 +245,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
 
 template <int D, int VT, int ST>
 static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, const Workspace& w,
-                           int gate, hipStream_t s)
+                           int gate, bool accumulate, hipStream_t s)
 {
     constexpr int GT = int(kGroupTiles);
     constexpr uint32_t TF = 64 * (D / 2) + 32;
@@ -253,17 +255,17 @@ static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t 
     const uint32_t per_block = 4 * 32 * VT;
     hipLaunchKernelGGL((assign_mfma_kernel<D, VT, ST, GT>), dim3((N + per_block - 1) / per_block), dim3(kThreads), 0, s,
                        X, N, C, K, w.packed, w.packed_tiles, idx, w.dmin, w.hdr, w.refine_list, w.refine_best,
-                       w.refine_cap, gate);
+                       w.refine_cap, gate, accumulate ? w.sums : nullptr, accumulate ? w.counts : nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_assign_mfma_f32(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                                  const Workspace& w, int gate, hipStream_t s)
+                                  const Workspace& w, int gate, bool accumulate, hipStream_t s)
 {
     switch (d) {
-        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, gate, s);
-        case 8: return launch_t<8, 4, 8>(X, N, C, K, idx, w, gate, s);
-        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, gate, s);
+        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, gate, accumulate, s);
+        case 8: return launch_t<8, 4, 8>(X, N, C, K, idx, w, gate, accumulate, s);
+        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, gate, accumulate, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -20,6 +20,8 @@
 // ~3 * 2^-24 * (sum of |terms|); the band assumes kAccumUlps = 8 times that unit, plus the split
 // residual. A vector whose best and second-best group scores are closer than the band is re-decided
 // in direct form over all K (refine.hip), exactly as for the fp32 kernel.
+#include <algorithm>
+
 #include "common.h"
 
 namespace cc {
@@ -70,21 +72,19 @@ __device__ __forceinline__ void split_norm(float v, _Float16 (&g)[3])
     g[2] = _Float16(r2 * 16384.0f);
 }
 
-__global__ __launch_bounds__(1024) void codebook_absmax_kernel(const float* __restrict__ C, size_t n, WsHeader* hdr,
-                                                               int gate)
+__global__ __launch_bounds__(kThreads) void codebook_absmax_kernel(const float4* __restrict__ C4, size_t n4,
+                                                                   WsHeader* hdr, int gate)
 {
     if (!gate_open(hdr, gate)) return;
-    __shared__ uint32_t red[16];
     uint32_t m = 0;
-    for (size_t i = threadIdx.x; i < n; i += 1024) m = max(m, __float_as_uint(C[i]) & 0x7fffffffu);
-    for (int off = 32; off > 0; off >>= 1) m = max(m, uint32_t(__shfl_xor(int(m), off, 64)));
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int w = 1; w < 16; ++w) m = max(m, red[w]);
-        hdr->cmax_bits = m;
-        hdr->refine_count = 0;
+    for (size_t i = size_t(blockIdx.x) * kThreads + threadIdx.x; i < n4; i += size_t(gridDim.x) * kThreads) {
+        const float4 t = C4[i];
+        m = max(max(m, __float_as_uint(t.x) & 0x7fffffffu), __float_as_uint(t.y) & 0x7fffffffu);
+        m = max(max(m, __float_as_uint(t.z) & 0x7fffffffu), __float_as_uint(t.w) & 0x7fffffffu);
     }
+    for (int off = 32; off > 0; off >>= 1) m = max(m, uint32_t(__shfl_xor(int(m), off, 64)));
+    if ((threadIdx.x & 63) == 0) atomicMax(&hdr->cmax_bits, m);
+    if (blockIdx.x == 0 && threadIdx.x == 0) hdr->refine_count = 0;
 }
 
 // Packed codebook: per 32-centroid tile, [64 lanes][KM] x 8 fp16 A-operand values (lane (m, h) holds
@@ -158,7 +158,8 @@ template <int D, int VT, int ST, int GT>
 __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
     const float* __restrict__ X, uint32_t N, const float* __restrict__ C, uint32_t K, const char* __restrict__ packed,
     uint32_t ntiles, uint32_t* __restrict__ idx, float* __restrict__ dmin, WsHeader* hdr,
-    uint32_t* __restrict__ refine_list, unsigned long long* __restrict__ refine_best, uint32_t refine_cap, int gate)
+    uint32_t* __restrict__ refine_list, unsigned long long* __restrict__ refine_best, uint32_t refine_cap, int gate,
+    long long* sums, uint32_t* counts)
 {
     using S = F16Shape<D>;
     constexpr int KM = S::KM;
@@ -266,7 +267,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
             for (int vt = 0; vt < VT; ++vt) {
                 second[vt] = __builtin_amdgcn_fmed3f(best[vt], second[vt], m[vt]);
                 grp[vt] = m[vt] < best[vt] ? gid : grp[vt];
-                best[vt] = __builtin_fminf(best[vt], m[vt]);
+                best[vt] = __builtin_amdgcn_fmed3f(best[vt], m[vt], -INFINITY);  // = min(best, m)
             }
         }
 
@@ -327,6 +328,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
         if (h == 0 && i_raw < N) {
             idx[i] = kstar;
             dmin[i] = dstar;
+            if (sums != nullptr) accumulate_vector<D>(x, kstar, sums, counts, fixed_point_exp(hdr->absmax_bits, N), +1);
             if (!safe) {
                 const uint32_t pos = atomicAdd(&hdr->refine_count, 1u);
                 if (pos < refine_cap) {
@@ -340,26 +342,28 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
 
 template <int D, int VT, int ST>
 static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, const Workspace& w,
-                           int gate, hipStream_t s)
+                           int gate, bool accumulate, hipStream_t s)
 {
     constexpr int GT = int(kGroupTiles);
-    hipLaunchKernelGGL(codebook_absmax_kernel, dim3(1), dim3(1024), 0, s, C, size_t(K) * D, w.hdr, gate);
+    const size_t n4 = size_t(K) * D / 4;
+    hipLaunchKernelGGL(codebook_absmax_kernel, dim3(uint32_t(std::min<size_t>((n4 + kThreads - 1) / kThreads, 64))),
+                       dim3(kThreads), 0, s, reinterpret_cast<const float4*>(C), n4, w.hdr, gate);
     hipLaunchKernelGGL(pack_codebook_f16_kernel<D>, dim3((w.packed_tiles * 64 + kThreads - 1) / kThreads),
                        dim3(kThreads), 0, s, C, K, w.packed_tiles, reinterpret_cast<char*>(w.packed), w.hdr, gate);
     const uint32_t per_block = 4 * 32 * VT;
     hipLaunchKernelGGL((assign_mfma_f16_kernel<D, VT, ST, GT>), dim3((N + per_block - 1) / per_block), dim3(kThreads),
                        0, s, X, N, C, K, reinterpret_cast<const char*>(w.packed), w.packed_tiles, idx, w.dmin, w.hdr,
-                       w.refine_list, w.refine_best, w.refine_cap, gate);
+                       w.refine_list, w.refine_best, w.refine_cap, gate, accumulate ? w.sums : nullptr, accumulate ? w.counts : nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_assign_mfma_f16(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                                  const Workspace& w, int gate, hipStream_t s)
+                                  const Workspace& w, int gate, bool accumulate, hipStream_t s)
 {
     switch (d) {
-        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, gate, s);
-        case 8: return launch_t<8, 4, 4>(X, N, C, K, idx, w, gate, s);
-        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, gate, s);
+        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, gate, accumulate, s);
+        case 8: return launch_t<8, 4, 4>(X, N, C, K, idx, w, gate, accumulate, s);
+        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, gate, accumulate, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -86,18 +86,22 @@ __device__ __forceinline__ bool gate_open(const WsHeader* hdr, int gate)
 
 // Matrix-core E-step, fp32 MFMA: packs the codebook and runs the scoring kernel (provisional idx,
 // w.dmin and the refine list). Must be followed by launch_refine.
+// With accumulate = true the kernel also adds every vector into the cluster sums/counts of its
+// provisional code (the M-step accumulation, hidden under the scoring work).
 hipError_t launch_assign_mfma_f32(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K,
-                                  uint32_t* idx, const Workspace& w, int gate, hipStream_t s);
+                                  uint32_t* idx, const Workspace& w, int gate, bool accumulate, hipStream_t s);
 
 // Matrix-core E-step for fp16-representable inputs: centroids split into three fp16 parts so that
 // every product is exact, scored with the fp16 MFMA. Same outputs as the fp32 variant.
 hipError_t launch_assign_mfma_f16(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K,
-                                  uint32_t* idx, const Workspace& w, int gate, hipStream_t s);
+                                  uint32_t* idx, const Workspace& w, int gate, bool accumulate, hipStream_t s);
 
 // Re-decides the listed guard-band vectors over all K centroids in direct form; if the list
-// overflowed, re-decides everything in direct form.
+// overflowed, re-decides everything in direct form. With fix_sums = true the cluster sums/counts that
+// the scoring kernel accumulated are corrected for every vector whose code changed (or rebuilt from
+// scratch on overflow).
 hipError_t launch_refine(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                         const Workspace& w, hipStream_t s);
+                         const Workspace& w, bool fix_sums, hipStream_t s);
 
 // Scans the inputs: max |x| and whether every x is exactly representable in fp16.
 hipError_t launch_scan_inputs(const float* X, uint64_t n_floats, WsHeader* hdr, hipStream_t s);
@@ -110,7 +114,14 @@ hipError_t launch_reduce_dmin(const float* dmin, uint32_t N, double* partials, u
 hipError_t launch_reset_header(WsHeader* hdr, hipStream_t s);
 hipError_t launch_bump_assign_calls(WsHeader* hdr, hipStream_t s);
 
-// M-step.
+// M-step = zero the accumulators, accumulate, finalize. With gate != NULL a gated launch does nothing
+// unless *gate > gate_limit (the refine-overflow path).
+hipError_t launch_zero_accumulators(const Workspace& w, uint32_t K, uint32_t d, const uint32_t* gate,
+                                    uint32_t gate_limit, hipStream_t s);
+hipError_t launch_accumulate(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, uint32_t K,
+                             const Workspace& w, const uint32_t* gate, uint32_t gate_limit, hipStream_t s);
+hipError_t launch_finalize(const float* prev, float* out, uint32_t* counts_out, uint32_t K, uint32_t d, uint32_t N,
+                           const Workspace& w, hipStream_t s);
 hipError_t launch_update(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,
                          uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, hipStream_t s);
 
@@ -119,6 +130,31 @@ hipError_t launch_decode(const float* C, uint32_t K, uint32_t d, const uint32_t*
                          hipStream_t s);
 
 hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s);
+
+// Fixed-point exponent e of the cluster sums: inputs satisfy |x| < 2^(EM+1) with EM the unbiased
+// exponent of the largest magnitude M, and N < 2^LN, so |sum of N terms| < 2^(EM+1+e+LN) <= 2^62.
+__device__ __forceinline__ int fixed_point_exp(uint32_t absmax_bits, uint32_t N)
+{
+    const int em = int(absmax_bits >> 23) - 127;   // -127 for zero/subnormal M: fine, just a large e
+    const int ln = 32 - __clz(N);                  // N < 2^ln
+    const int e = 62 - ln - (em + 1);
+    return e < 100 ? e : 100;                      // keep ldexp away from fp64 overflow for tiny inputs
+}
+
+// Adds (sign = +1) or removes (sign = -1) one vector to/from cluster k's fixed-point sums and count.
+// Integer adds commute, so the totals do not depend on the order in which these atomics land.
+template <int D>
+__device__ __forceinline__ void accumulate_vector(const float (&x)[D], uint32_t k, long long* sums, uint32_t* counts,
+                                                  int e, int sign)
+{
+    unsigned long long* dst = reinterpret_cast<unsigned long long*>(sums + size_t(k) * D);
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+        const long long f = __double2ll_rn(ldexp(double(x[j]), e));
+        if (f != 0) atomicAdd(dst + j, static_cast<unsigned long long>(sign > 0 ? f : -f));
+    }
+    atomicAdd(counts + k, sign > 0 ? 1u : 0xffffffffu);
+}
 
 // ||x - c||^2 in fp32, direct form: first square, then one fused multiply-add per further component.
 // Every kernel that needs a distance uses this exact operation order, so that a vector decided by

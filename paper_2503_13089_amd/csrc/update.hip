@@ -93,19 +93,11 @@ hipError_t launch_scan_inputs(const float* X, uint64_t n_floats, WsHeader* hdr, 
     return hipGetLastError();
 }
 
-// Fixed-point exponent e: inputs satisfy |x| < 2^(EM+1) with EM the unbiased exponent of M, and
-// N < 2^LN, so |sum| < 2^(EM+1+e+LN) <= 2^62.
-__device__ inline int fixed_point_exp(uint32_t absmax_bits, uint32_t N)
-{
-    const int em = int(absmax_bits >> 23) - 127;   // -127 for zero/subnormal M: fine, just a large e
-    const int ln = 32 - __clz(N);                  // N < 2^ln
-    int e = 62 - ln - (em + 1);
-    return min(e, 100);                            // keep ldexp away from fp64 overflow for tiny inputs
-}
-
 __global__ __launch_bounds__(kThreads) void zero_accumulators_kernel(long long* sums, uint32_t* counts, uint32_t K,
-                                                                      uint32_t d)
+                                                                      uint32_t d, const uint32_t* __restrict__ gate,
+                                                                      uint32_t gate_limit)
 {
+    if (gate != nullptr && *gate <= gate_limit) return;
     const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
     if (i < K * d) sums[i] = 0;
     if (i < K) counts[i] = 0;
@@ -114,8 +106,10 @@ __global__ __launch_bounds__(kThreads) void zero_accumulators_kernel(long long* 
 template <int D>
 __global__ __launch_bounds__(kThreads) void accumulate_kernel(const float* __restrict__ X, uint32_t N,
                                                               const uint32_t* __restrict__ idx, uint32_t K,
-                                                              long long* sums, uint32_t* counts, WsHeader* hdr)
+                                                              long long* sums, uint32_t* counts, WsHeader* hdr,
+                                                              const uint32_t* __restrict__ gate, uint32_t gate_limit)
 {
+    if (gate != nullptr && *gate <= gate_limit) return;
     const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
     if (i >= N) return;
     const int e = fixed_point_exp(hdr->absmax_bits, N);
@@ -124,19 +118,9 @@ __global__ __launch_bounds__(kThreads) void accumulate_kernel(const float* __res
         atomicAdd(&hdr->skipped_vectors, 1ull);
         return;
     }
-    const float4* src = reinterpret_cast<const float4*>(X + size_t(i) * D);
-    unsigned long long* dst = reinterpret_cast<unsigned long long*>(sums + size_t(k) * D);
-#pragma unroll
-    for (int q = 0; q < D / 4; ++q) {
-        const float4 t = src[q];
-        const float v[4] = {t.x, t.y, t.z, t.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const long long f = __double2ll_rn(ldexp(double(v[j]), e));
-            if (f != 0) atomicAdd(dst + 4 * q + j, static_cast<unsigned long long>(f));
-        }
-    }
-    atomicAdd(counts + k, 1u);
+    float x[D];
+    load_row<D>(X + size_t(i) * D, x);
+    accumulate_vector<D>(x, k, sums, counts, e, +1);
 }
 
 __global__ __launch_bounds__(kThreads) void finalize_kernel(const long long* __restrict__ sums,
@@ -160,22 +144,43 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const long long* __r
     if (counts_out != nullptr && t % d == 0) counts_out[k] = n;
 }
 
+hipError_t launch_zero_accumulators(const Workspace& w, uint32_t K, uint32_t d, const uint32_t* gate,
+                                    uint32_t gate_limit, hipStream_t s)
+{
+    hipLaunchKernelGGL(zero_accumulators_kernel, dim3((K * d + kThreads - 1) / kThreads), dim3(kThreads), 0, s, w.sums,
+                       w.counts, K, d, gate, gate_limit);
+    return hipGetLastError();
+}
+
+hipError_t launch_accumulate(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, uint32_t K,
+                             const Workspace& w, const uint32_t* gate, uint32_t gate_limit, hipStream_t s)
+{
+    const dim3 grid((N + kThreads - 1) / kThreads);
+    switch (d) {
+        case 4: hipLaunchKernelGGL(accumulate_kernel<4>, grid, dim3(kThreads), 0, s, X, N, idx, K, w.sums, w.counts, w.hdr, gate, gate_limit); break;
+        case 8: hipLaunchKernelGGL(accumulate_kernel<8>, grid, dim3(kThreads), 0, s, X, N, idx, K, w.sums, w.counts, w.hdr, gate, gate_limit); break;
+        case 16: hipLaunchKernelGGL(accumulate_kernel<16>, grid, dim3(kThreads), 0, s, X, N, idx, K, w.sums, w.counts, w.hdr, gate, gate_limit); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize(const float* prev, float* out, uint32_t* counts_out, uint32_t K, uint32_t d, uint32_t N,
+                           const Workspace& w, hipStream_t s)
+{
+    hipLaunchKernelGGL(finalize_kernel, dim3((K * d + kThreads - 1) / kThreads), dim3(kThreads), 0, s, w.sums, w.counts,
+                       prev, out, counts_out, K, d, N, w.hdr);
+    return hipGetLastError();
+}
+
 hipError_t launch_update(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev, uint32_t K,
                          float* out, uint32_t* counts_out, const Workspace& w, hipStream_t s)
 {
-    const uint32_t kd = K * d;
-    hipLaunchKernelGGL(zero_accumulators_kernel, dim3((kd + kThreads - 1) / kThreads), dim3(kThreads), 0, s, w.sums,
-                       w.counts, K, d);
-    const dim3 grid((N + kThreads - 1) / kThreads);
-    switch (d) {
-        case 4: hipLaunchKernelGGL(accumulate_kernel<4>, grid, dim3(kThreads), 0, s, X, N, idx, K, w.sums, w.counts, w.hdr); break;
-        case 8: hipLaunchKernelGGL(accumulate_kernel<8>, grid, dim3(kThreads), 0, s, X, N, idx, K, w.sums, w.counts, w.hdr); break;
-        case 16: hipLaunchKernelGGL(accumulate_kernel<16>, grid, dim3(kThreads), 0, s, X, N, idx, K, w.sums, w.counts, w.hdr); break;
-        default: return hipErrorInvalidValue;
-    }
-    hipLaunchKernelGGL(finalize_kernel, dim3((kd + kThreads - 1) / kThreads), dim3(kThreads), 0, s, w.sums, w.counts,
-                       prev, out, counts_out, K, d, N, w.hdr);
-    return hipGetLastError();
+    hipError_t e = launch_zero_accumulators(w, K, d, nullptr, 0, s);
+    if (e != hipSuccess) return e;
+    e = launch_accumulate(X, N, d, idx, K, w, nullptr, 0, s);
+    if (e != hipSuccess) return e;
+    return launch_finalize(prev, out, counts_out, K, d, N, w, s);
 }
 
 }  // namespace cc

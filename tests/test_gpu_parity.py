@@ -24,9 +24,10 @@ def g():
     return gpu_helpers
 
 
-@pytest.fixture(params=[1, 2], ids=["direct", "matrix-core"])
+@pytest.fixture(params=[0, 1, 2], ids=["auto", "direct", "fp32-mfma"])
 def mode(request, g):
-    """Runs a test once per E-step kernel: 1 = direct form only, 2 = matrix cores + guard band + refinement."""
+    """Runs a test once per E-step selection: 0 = automatic (fp16 MFMA for these fp16-representable inputs when
+    K >= 128), 1 = direct form only, 2 = fp32 MFMA + guard band + refinement."""
     import paper_2503_13089_amd as cc
 
     cc.set_assign_mode(request.param)
@@ -77,6 +78,42 @@ def test_assign_lockstep(g, mode, N, d, K):
         parity.check_inertia(J, float(D1.sum()))
         idx2, none = g.gpu_assign(X, cents, want_inertia=False)
         assert none is None and np.array_equal(idx, idx2)
+
+
+def test_assign_general_fp32_inputs(g, mode):
+    """Inputs that are not fp16 numbers: the automatic selection must fall back to the fp32 kernels."""
+    X, C0 = workloads.make_small(60001, 8, 1300, seed=4242, fp16_round=False)
+    k0, _, _, _ = oracle.assign_top2(X, C0)
+    C, _ = oracle.update(X, k0, C0)
+    k1, D1, _, D2 = oracle.assign_top2(X, C)
+    idx, J = g.gpu_assign(X, C)
+    parity.check_assignment(X, C, idx, k1, D1, D2)
+    parity.check_inertia(J, float(D1.sum()))
+
+
+@pytest.mark.parametrize("N,d,K", SHAPES)
+def test_lloyd_iter_equals_assign_then_update(g, mode, N, d, K):
+    import paper_2503_13089_amd as cc
+
+    X, C0 = workloads.make_small(N, d, K, seed=7000 + N)
+    Xd = g.dev(X)
+    ws = g.workspace(N, d, K)
+    idx_a, J_a = g.gpu_assign(Xd, C0, ws=ws)
+    C_a, counts_a, _ = g.gpu_update(Xd, idx_a, C0, ws=ws)
+    Cd = g.dev(C0)
+    idx_d = torch.empty(N, dtype=torch.uint32, device="cuda")
+    counts_d = torch.empty(K, dtype=torch.uint32, device="cuda")
+    J_d = torch.zeros(1, dtype=torch.float64, device="cuda")
+    print(f"lloyd_iter N={N} d={d} K={K}", flush=True)
+    cc.lloyd_iter(Xd, Cd, idx_d, J_d, counts_d, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx_d.cpu().numpy(), idx_a)
+    assert np.array_equal(counts_d.cpu().numpy(), counts_a)
+    assert Cd.cpu().numpy().tobytes() == C_a.tobytes()
+    assert float(J_d.item()) == J_a
+    # and against the oracle's M-step on those codes
+    want, counts = oracle.update(X, idx_a, C0)
+    assert C_a.tobytes() == want.tobytes() and np.array_equal(counts_a, counts)
 
 
 def test_assign_exact_ties_take_the_lowest_index(g, mode):
