@@ -178,7 +178,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
             for (int vt = 0; vt < VT; ++vt) {
                 second[vt] = __builtin_amdgcn_fmed3f(best[vt], second[vt], m[vt]);
                 grp[vt] = m[vt] < best[vt] ? gid : grp[vt];
-                best[vt] = __builtin_amdgcn_fmed3f(best[vt], m[vt], -INFINITY);  // = min(best, m)
+                asm("v_min_f32 %0, %1, %2" : "=v"(best[vt]) : "v"(best[vt]), "v"(m[vt]));  // operands are canonical
             }
         }
 

@@ -267,7 +267,9 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
             for (int vt = 0; vt < VT; ++vt) {
                 second[vt] = __builtin_amdgcn_fmed3f(best[vt], second[vt], m[vt]);
                 grp[vt] = m[vt] < best[vt] ? gid : grp[vt];
-                best[vt] = __builtin_amdgcn_fmed3f(best[vt], m[vt], -INFINITY);  // = min(best, m)
+                // plain v_min_f32: both operands come from v_min3/v_med3 results, which are already canonical,
+                // so the canonicalising v_max the compiler would put in front of fminf is not needed
+                asm("v_min_f32 %0, %1, %2" : "=v"(best[vt]) : "v"(best[vt]), "v"(m[vt]));
             }
         }
 
@@ -344,7 +346,7 @@ template <int D, int VT, int ST>
 static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, const Workspace& w,
                            int gate, bool accumulate, hipStream_t s)
 {
-    constexpr int GT = int(kGroupTiles);
+    constexpr int GT = 4;  // tiles per tracking group: 64 centroids per lane are re-evaluated in the epilogue
     const size_t n4 = size_t(K) * D / 4;
     hipLaunchKernelGGL(codebook_absmax_kernel, dim3(uint32_t(std::min<size_t>((n4 + kThreads - 1) / kThreads, 64))),
                        dim3(kThreads), 0, s, reinterpret_cast<const float4*>(C), n4, w.hdr, gate);

@@ -11,34 +11,49 @@ namespace cc {
 constexpr int kThreads = 256;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <int D>
+// Each block moves kThreads * U consecutive 16-byte pieces. Measured on MI355X at d = 4, K = 65536: a plain
+// fill of the output runs at 6.7 TB/s and fill + code read at 7.1 TB/s, but the 16-byte gathers hit 64
+// different cache lines per wave instruction and the L1 looks up about one line per clock, which adds
+// ~20 us per 11.3M vectors whatever the unroll factor or cache policy; U = 1 was the fastest variant.
+template <int D, int U>
 __global__ __launch_bounds__(kThreads) void decode_kernel(const f32x4* __restrict__ C4, uint32_t K,
                                                           const uint32_t* __restrict__ idx, uint64_t n_chunks,
                                                           f32x4* __restrict__ out4)
 {
     constexpr int Q = D / 4;  // 16-byte pieces per vector
-    const uint64_t stride = uint64_t(gridDim.x) * kThreads;
-    for (uint64_t t = uint64_t(blockIdx.x) * kThreads + threadIdx.x; t < n_chunks; t += stride) {
-        const uint64_t i = t / Q;
-        const uint32_t q = uint32_t(t % Q);
-        uint32_t k = idx[i];
-        k = k < K ? k : K - 1;  // never read outside the codebook
-        const f32x4 v = C4[size_t(k) * Q + q];
-        __builtin_nontemporal_store(v, &out4[t]);
+    const uint64_t base = uint64_t(blockIdx.x) * (kThreads * U) + threadIdx.x;
+    uint32_t k[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t t = min(base + uint64_t(u) * kThreads, n_chunks - 1);
+        const uint32_t kk = idx[t / Q];
+        k[u] = kk < K ? kk : K - 1;  // never read outside the codebook
+    }
+    f32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t t = min(base + uint64_t(u) * kThreads, n_chunks - 1);
+        v[u] = C4[size_t(k[u]) * Q + uint32_t(t % Q)];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t t = base + uint64_t(u) * kThreads;
+        if (t < n_chunks) __builtin_nontemporal_store(v[u], &out4[t]);
     }
 }
 
 hipError_t launch_decode(const float* C, uint32_t K, uint32_t d, const uint32_t* idx, uint64_t N, float* out,
                          hipStream_t s)
 {
+    constexpr int U = 1;
     const uint64_t n_chunks = N * (d / 4);
-    const uint32_t blocks = uint32_t(std::min<uint64_t>((n_chunks + kThreads - 1) / kThreads, 256u * 32u));
+    const uint32_t blocks = uint32_t((n_chunks + kThreads * U - 1) / (kThreads * U));
     const f32x4* C4 = reinterpret_cast<const f32x4*>(C);
     f32x4* out4 = reinterpret_cast<f32x4*>(out);
     switch (d) {
-        case 4: hipLaunchKernelGGL(decode_kernel<4>, dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
-        case 8: hipLaunchKernelGGL(decode_kernel<8>, dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
-        case 16: hipLaunchKernelGGL(decode_kernel<16>, dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
+        case 4: hipLaunchKernelGGL((decode_kernel<4, U>), dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
+        case 8: hipLaunchKernelGGL((decode_kernel<8, U>), dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
+        case 16: hipLaunchKernelGGL((decode_kernel<16, U>), dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
