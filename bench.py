@@ -23,9 +23,14 @@ if ROOT not in sys.path:
 
 FP32_PEAK_TFLOPS = 157.3   # MI355X fp32 vector = fp32 matrix peak
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
+VALU_ISSUE_PEAK = 1024 * 2.4e9 / 4   # wave-instructions/s: 1024 SIMDs, one 64-lane VALU instruction per 4 cycles
+
+# HBM bytes per launch of the E-step kernel from rocprofv3 counters (profiles/pmc_bench_cfg3.md):
+# FETCH_SIZE 290,816 KiB x 2.000 + WRITE_SIZE 88,406 KiB x 1.000, scale factors from a device copy of known size.
+MEASURED_TRAFFIC_BYTES = {("cfg3_4096x11008_d4_k65536", 0): (290816 * 2.0 + 88406 * 1.0) * 1024}
 
 
-def cpu_baseline(w, X, C0, sample_log2=17):
+def cpu_baseline(w, X, C0, sample_log2=20):
     """The oracle as it stands, timed on this host: one E-step over the first 2^sample_log2 vectors against
     all K centroids, scaled linearly in N (its cost is exactly proportional to N), plus one full-N M-step."""
     import numpy as np
@@ -56,6 +61,9 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--assign-mode", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of the input matrix (known size) so that a counter run "
+                         "can scale FETCH_SIZE / WRITE_SIZE against it")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (matrices are independent, so "
@@ -120,6 +128,10 @@ def main():
     Cn = torch.empty_like(Cd)
     update_ms = timed(lambda: cc.update(Xd, idx, Cd, Cn, None, ws))
 
+    if args.calibrate_copy:
+        out.copy_(Xd)  # N*d*4 bytes read and as many written
+        torch.cuda.synchronize()
+
     assign_flop = 2.0 * d * N * K
     update_bytes = 4.0 * d * N + 4.0 * N + 4.0 * K * (d + 1)
     decode_bytes = 4.0 * N + 4.0 * K * d + 4.0 * d * N
@@ -128,14 +140,20 @@ def main():
         "metric": "Lloyd iter/s (assign+update) at 4096x11008,d=4,K=65536; % FP32 peak",
         "value": args.steps / wall, "unit": "Lloyd iter/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32" if args.assign_mode != 0 else "f32 (scores from exact fp16x3 products on the fp16 MFMA, fp32 accumulate)",
+        "data": "synthetic",
         "config": {"workload": w.name, "rows": w.rows, "cols": w.cols, "d": d, "N": N, "K": K,
                    "step": "cc_lloyd_iter (E-step + objective + fused M-step) + cc_decode, centroids chained",
                    "assign_mode": args.assign_mode, "final_objective": final_objective},
         "roofline": {"bound": "mfma" if args.assign_mode != 1 else "alu", "kernel": "assign (E-step)",
                      "achieved": achieved, "peak": FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / FP32_PEAK_TFLOPS, "traffic": None,
+                     "frac": achieved / FP32_PEAK_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.assign_mode)),
                      "flop_per_launch": assign_flop, "avg_ms": assign_ms},
+        # the same kernel against the unit that actually bounds the fp16-MFMA variant: one v_min3_f32 per two scores
+        "roofline_alu": {"bound": "alu", "kernel": "assign (E-step)", "achieved": N * K / 128.0 / (assign_ms * 1e-3) / 1e9,
+                         "peak": VALU_ISSUE_PEAK / 1e9, "unit": "G wave-instr/s",
+                         "frac": N * K / 128.0 / (assign_ms * 1e-3) / VALU_ISSUE_PEAK, "traffic": None},
         "lloyd_iter_ms": iter_ms,
         "other_kernels": {
             "update": {"bound": "hbm", "achieved": update_bytes / (update_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
