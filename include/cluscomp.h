@@ -124,9 +124,14 @@ int cc_read_stats(const void *workspace, size_t workspace_bytes, cc_stats *host_
 
 /* Selects the E-step kernel. 0 = automatic (default): for K >= 128 the matrix cores, with the fp16 MFMA
  * (centroids split into three fp16 parts, exact products) when every input is an fp16 number and
- * the fp32 MFMA otherwise, both with guard band + direct-form refinement; direct form for small K.
- * 1 = direct-form vector-ALU kernel only. 2 = fp32 MFMA kernel always. Process-wide; for tests and
- * profiling. Returns the previous value, or CC_ERR_SHAPE for an unknown mode. */
+ * the fp32 MFMA otherwise, both with guard band + direct-form refinement; direct form for small K;
+ * for K >= 8192 vectors and centroids are additionally visited in norm order and a workgroup skips
+ * the part of the codebook that the triangle inequality rules out (an exact shortcut: a centroid
+ * whose norm differs from a vector's by more than a known upper bound of its nearest distance
+ * cannot be the nearest; the previous call's codes on the same workspace provide that bound).
+ * 1 = direct-form vector-ALU kernel only. 2 = fp32 MFMA kernel always, whole codebook.
+ * 3 = as 0 but always the whole codebook. Process-wide; for tests and profiling.
+ * Returns the previous value, or CC_ERR_SHAPE for an unknown mode. */
 int cc_set_assign_mode(int mode);
 
 /* Thread-local description of the last error returned on this thread (host pointer, static storage). */

@@ -57,34 +57,43 @@ int check_workspace(void* ws, size_t ws_bytes, uint64_t N, uint32_t d, uint32_t 
 bool use_matrix_cores(uint32_t K)
 {
     const int mode = g_assign_mode.load();
-    return mode == 2 || (mode == 0 && K >= 128);
+    return mode == 2 || ((mode == 0 || mode == 3) && K >= 128);
 }
 
+// Norm-window pruning: only in the automatic mode and only where the ordering overhead can pay off.
+bool use_pruning(uint32_t K) { return g_assign_mode.load() == 0 && K >= 8192; }
+
 // Scoring + refinement on the matrix cores. The input scan (WsHeader::x_not_f16) must have run on this
-// workspace since the last header reset.
+// workspace since the last header reset; with pruned = true the vectors must have been norm-ordered
+// (launch_sort_vectors) and the codes are left in norm order in w.idx_sorted.
 int run_assign_matrix(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                      const cc::Workspace& w, bool accumulate, hipStream_t s)
+                      const cc::Workspace& w, bool accumulate, bool pruned, hipStream_t s)
 {
-    if (g_assign_mode.load() == 0) {
+    const float* Xe = pruned ? w.xsorted : X;
+    uint32_t* idxe = pruned ? w.idx_sorted : idx;
+    if (pruned) CC_TRY_HIP(cc::launch_sort_centroids_and_windows(C, N, d, K, w, s), "assign (norm windows)");
+    if (g_assign_mode.load() != 2) {
         // both variants are enqueued; the device-side gate lets exactly one of them run
-        CC_TRY_HIP(cc::launch_assign_mfma_f16(X, N, d, C, K, idx, w, cc::kGateIfF16, accumulate, s),
+        CC_TRY_HIP(cc::launch_assign_mfma_f16(Xe, N, d, C, K, idxe, w, cc::kGateIfF16, accumulate, pruned, s),
                    "assign (fp16 matrix cores)");
-        CC_TRY_HIP(cc::launch_assign_mfma_f32(X, N, d, C, K, idx, w, cc::kGateIfNotF16, accumulate, s),
+        CC_TRY_HIP(cc::launch_assign_mfma_f32(Xe, N, d, C, K, idxe, w, cc::kGateIfNotF16, accumulate, pruned, s),
                    "assign (fp32 matrix cores)");
     } else {
-        CC_TRY_HIP(cc::launch_assign_mfma_f32(X, N, d, C, K, idx, w, cc::kGateAlways, accumulate, s),
+        CC_TRY_HIP(cc::launch_assign_mfma_f32(Xe, N, d, C, K, idxe, w, cc::kGateAlways, accumulate, false, s),
                    "assign (fp32 matrix cores)");
     }
-    CC_TRY_HIP(cc::launch_refine(X, N, d, C, K, idx, w, accumulate, s), "assign (refinement)");
+    CC_TRY_HIP(cc::launch_refine(Xe, N, d, C, K, idxe, w, accumulate, pruned, s), "assign (refinement)");
     return CC_OK;
 }
 
 // One E-step pass: idx (and, if inertia != NULL, the objective) for the given centroids.
+// to_user = false leaves norm-ordered codes in the workspace only (intermediate fit iterations).
 int run_assign(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx, double* inertia,
-               const cc::Workspace& w, hipStream_t s)
+               const cc::Workspace& w, bool pruned, hipStream_t s)
 {
     if (use_matrix_cores(K)) {
-        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, false, s)) return rc;
+        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, false, pruned, s)) return rc;
+        if (pruned) CC_TRY_HIP(cc::launch_unpermute(N, idx, w, s), "assign (codes to input order)");
     } else {
         CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s), "assign (direct form)");
         CC_TRY_HIP(cc::launch_bump_assign_calls(w.hdr, s), "bookkeeping");
@@ -96,13 +105,15 @@ int run_assign(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t 
 
 // One Lloyd iteration: idx = E-step against C, then C <- M-step(idx) in place. On the matrix-core path
 // the cluster sums are accumulated by the scoring kernel itself (no second pass over the vectors).
+// idx == NULL (only inside the fit loop, pruned path) skips the copy of the codes to input order.
 int run_lloyd_iter(const float* X, uint32_t N, uint32_t d, float* C, uint32_t K, uint32_t* idx, double* inertia,
-                   uint32_t* counts, const cc::Workspace& w, hipStream_t s)
+                   uint32_t* counts, const cc::Workspace& w, bool pruned, hipStream_t s)
 {
     if (use_matrix_cores(K)) {
         CC_TRY_HIP(cc::launch_zero_accumulators(w, K, d, nullptr, 0, s), "update (clear)");
-        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, true, s)) return rc;
+        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, true, pruned, s)) return rc;
         CC_TRY_HIP(cc::launch_finalize(C, C, counts, K, d, N, w, s), "update (means)");
+        if (pruned && idx != nullptr) CC_TRY_HIP(cc::launch_unpermute(N, idx, w, s), "assign (codes to input order)");
     } else {
         CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s), "assign (direct form)");
         CC_TRY_HIP(cc::launch_bump_assign_calls(w.hdr, s), "bookkeeping");
@@ -143,9 +154,14 @@ int cc_kmeans_fit(const float* vectors, uint64_t N, uint32_t d, uint32_t K, int3
     CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
     if (centroids != init_centroids)
         CC_TRY_HIP(cc::launch_copy_f32(init_centroids, centroids, size_t(K) * d, s), "centroid copy");
-    for (int32_t t = 0; t < iters; ++t)
-        if (int rc = run_lloyd_iter(vectors, n, d, centroids, K, idx, nullptr, nullptr, w, s)) return rc;
-    return run_assign(vectors, n, d, centroids, K, idx, inertia, w, s);
+    const bool pruned = use_matrix_cores(K) && use_pruning(K);
+    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, n, d, K, w, s), "norm ordering");
+    for (int32_t t = 0; t < iters; ++t) {
+        // only the matrix-core path can leave its codes in the workspace; the others write idx directly
+        uint32_t* step_idx = pruned ? nullptr : idx;
+        if (int rc = run_lloyd_iter(vectors, n, d, centroids, K, step_idx, nullptr, nullptr, w, pruned, s)) return rc;
+    }
+    return run_assign(vectors, n, d, centroids, K, idx, inertia, w, pruned, s);
 }
 
 int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroids, uint32_t K, uint32_t* idx,
@@ -160,7 +176,9 @@ int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroi
     const cc::Workspace w = cc::carve(workspace, N, d, K);
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
     CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
-    return run_assign(vectors, uint32_t(N), d, centroids, K, idx, inertia, w, s);
+    const bool pruned = use_matrix_cores(K) && use_pruning(K);
+    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, uint32_t(N), d, K, w, s), "norm ordering");
+    return run_assign(vectors, uint32_t(N), d, centroids, K, idx, inertia, w, pruned, s);
 }
 
 int cc_lloyd_iter(const float* vectors, uint64_t N, uint32_t d, float* centroids, uint32_t K, uint32_t* idx,
@@ -176,7 +194,9 @@ int cc_lloyd_iter(const float* vectors, uint64_t N, uint32_t d, float* centroids
     const cc::Workspace w = cc::carve(workspace, N, d, K);
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
     CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
-    return run_lloyd_iter(vectors, uint32_t(N), d, centroids, K, idx, inertia, counts, w, s);
+    const bool pruned = use_matrix_cores(K) && use_pruning(K);
+    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, uint32_t(N), d, K, w, s), "norm ordering");
+    return run_lloyd_iter(vectors, uint32_t(N), d, centroids, K, idx, inertia, counts, w, pruned, s);
 }
 
 int cc_update(const float* vectors, uint64_t N, uint32_t d, const uint32_t* idx, const float* prev_centroids,
@@ -226,7 +246,7 @@ int cc_read_stats(const void* workspace, size_t workspace_bytes, cc_stats* host_
 
 int cc_set_assign_mode(int mode)
 {
-    if (mode < 0 || mode > 2) return fail(CC_ERR_SHAPE, "unknown assign mode %d", mode);
+    if (mode < 0 || mode > 3) return fail(CC_ERR_SHAPE, "unknown assign mode %d", mode);
     return g_assign_mode.exchange(mode);
 }
 

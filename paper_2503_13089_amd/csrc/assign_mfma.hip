@@ -44,7 +44,8 @@ constexpr float kGuardSafety = 1.5f;
 template <int D>
 __global__ __launch_bounds__(kThreads) void pack_codebook_kernel(const float* __restrict__ C, uint32_t K,
                                                                  uint32_t ntiles, float* __restrict__ packed,
-                                                                 WsHeader* hdr, int gate)
+                                                                 WsHeader* hdr, int gate,
+                                                                 const uint32_t* __restrict__ cperm)
 {
     constexpr uint32_t KS = D / 2, TF = 64 * KS + 32;
     if (!gate_open(hdr, gate)) return;
@@ -56,11 +57,13 @@ __global__ __launch_bounds__(kThreads) void pack_codebook_kernel(const float* __
     if (r < 64 * KS) {
         const uint32_t lane = r / KS, ks = r % KS, h = lane >> 5, m = lane & 31;
         // MFMA output row m lives in half (m/4)%2, register (m%4) + 4*(m/8): give it centroid 16*half + register
-        const uint32_t k = 32 * tile + 16 * ((m >> 2) & 1) + (m & 3) + 4 * (m >> 3);
-        val = k < K ? C[size_t(k) * D + 2 * ks + h] : 0.0f;
+        const uint32_t pos = 32 * tile + 16 * ((m >> 2) & 1) + (m & 3) + 4 * (m >> 3);
+        const uint32_t k = (cperm != nullptr && pos < K) ? cperm[pos] : pos;  // norm order when pruning
+        val = pos < K ? C[size_t(k) * D + 2 * ks + h] : 0.0f;
     } else {
-        const uint32_t k = 32 * tile + (r - 64 * KS);
-        if (k < K) {
+        const uint32_t pos = 32 * tile + (r - 64 * KS);
+        const uint32_t k = (cperm != nullptr && pos < K) ? cperm[pos] : pos;
+        if (pos < K) {
             double s = 0.0;
             for (int j = 0; j < D; ++j) {
                 const double c = double(C[size_t(k) * D + j]);
@@ -83,7 +86,8 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
                                                                WsHeader* hdr, uint32_t* __restrict__ refine_list,
                                                                unsigned long long* __restrict__ refine_best,
                                                                uint32_t refine_cap, int gate, long long* sums,
-                                                               uint32_t* counts)
+                                                               uint32_t* counts, const uint2* __restrict__ windows,
+                                                               const uint32_t* __restrict__ cperm)
 {
     constexpr int KS = D / 2;                 // MFMA k-steps per tile
     if (!gate_open(hdr, gate)) return;        // uniform over the grid
@@ -117,19 +121,26 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
 
     // ntiles is a multiple of ST (padding rows carry ||c||^2 = +inf), so every stage is whole
     const float4* P4 = reinterpret_cast<const float4*>(packed);
-    const uint32_t nstages = ntiles / ST;
+    // stage range of this workgroup: everything, or the window of its 512-vector tile (in units of
+    // kStageTilesMax tiles, norm-ordered codebook)
+    uint32_t s_begin = 0, s_end = ntiles / ST;
+    if (windows != nullptr) {
+        const uint2 wdw = windows[(blockIdx.x * (4 * 32 * VT)) / 512];
+        s_begin = wdw.x * (kStageTilesMax / ST);
+        s_end = wdw.y * (kStageTilesMax / ST);
+    }
 #pragma unroll
     for (int p = 0; p < NPF; ++p) {
         const uint32_t j = threadIdx.x + p * kThreads;
-        if (NPF * kThreads == STAGE_F4 || j < STAGE_F4) lds[0][j] = P4[j];
+        if (NPF * kThreads == STAGE_F4 || j < STAGE_F4) lds[s_begin & 1][j] = P4[size_t(s_begin) * STAGE_F4 + j];
     }
     __syncthreads();
 
-    for (uint32_t s = 0; s < nstages; ++s) {
+    for (uint32_t s = s_begin; s < s_end; ++s) {
         const int cur = s & 1;
         // prefetch the next stage into registers while this one is consumed (the last iteration
         // re-reads its own stage; the copy is never used)
-        const uint32_t sn = min(s + 1, nstages - 1);
+        const uint32_t sn = min(s + 1, s_end - 1);
         float4 pf[NPF];
 #pragma unroll
         for (int p = 0; p < NPF; ++p) {
@@ -202,12 +213,13 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
         for (int g = 0; g < GT; ++g) {
             const uint32_t k0 = 32 * (grp[vt] * GT + g) + 16 * h;
             for (int r = 0; r < 16; ++r) {
-                const uint32_t k = k0 + r;
-                if (k < K) {
+                const uint32_t pos = k0 + r;  // position in the packed (possibly norm-ordered) codebook
+                if (pos < K) {
+                    const uint32_t k = cperm != nullptr ? cperm[pos] : pos;
                     float c[D];
                     load_row<D>(C + size_t(k) * D, c);
                     const float dk = direct_sqdist<D>(x, c);
-                    if (dk < bd) {
+                    if (dk < bd || (dk == bd && k < bk)) {
                         bd = dk;
                         bk = k;
                     }
@@ -245,27 +257,28 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
 
 template <int D, int VT, int ST>
 static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, const Workspace& w,
-                           int gate, bool accumulate, hipStream_t s)
+                           int gate, bool accumulate, bool pruned, hipStream_t s)
 {
     constexpr int GT = int(kGroupTiles);
     constexpr uint32_t TF = 64 * (D / 2) + 32;
     const size_t packed_floats = size_t(w.packed_tiles) * TF;
     hipLaunchKernelGGL(pack_codebook_kernel<D>, dim3(uint32_t((packed_floats + kThreads - 1) / kThreads)),
-                       dim3(kThreads), 0, s, C, K, w.packed_tiles, w.packed, w.hdr, gate);
+                       dim3(kThreads), 0, s, C, K, w.packed_tiles, w.packed, w.hdr, gate, pruned ? w.cperm : nullptr);
     const uint32_t per_block = 4 * 32 * VT;
     hipLaunchKernelGGL((assign_mfma_kernel<D, VT, ST, GT>), dim3((N + per_block - 1) / per_block), dim3(kThreads), 0, s,
                        X, N, C, K, w.packed, w.packed_tiles, idx, w.dmin, w.hdr, w.refine_list, w.refine_best,
-                       w.refine_cap, gate, accumulate ? w.sums : nullptr, accumulate ? w.counts : nullptr);
+                       w.refine_cap, gate, accumulate ? w.sums : nullptr, accumulate ? w.counts : nullptr,
+                       pruned ? w.windows : nullptr, pruned ? w.cperm : nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_assign_mfma_f32(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                                  const Workspace& w, int gate, bool accumulate, hipStream_t s)
+                                  const Workspace& w, int gate, bool accumulate, bool pruned, hipStream_t s)
 {
     switch (d) {
-        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, gate, accumulate, s);
-        case 8: return launch_t<8, 4, 8>(X, N, C, K, idx, w, gate, accumulate, s);
-        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, gate, accumulate, s);
+        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, gate, accumulate, pruned, s);
+        case 8: return launch_t<8, 4, 8>(X, N, C, K, idx, w, gate, accumulate, pruned, s);
+        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, gate, accumulate, pruned, s);
         default: return hipErrorInvalidValue;
     }
 }

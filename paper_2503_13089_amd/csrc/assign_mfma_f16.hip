@@ -94,7 +94,8 @@ __global__ __launch_bounds__(kThreads) void codebook_absmax_kernel(const float4*
 template <int D>
 __global__ __launch_bounds__(kThreads) void pack_codebook_f16_kernel(const float* __restrict__ C, uint32_t K,
                                                                      uint32_t ntiles, char* __restrict__ packed,
-                                                                     const WsHeader* __restrict__ hdr, int gate)
+                                                                     const WsHeader* __restrict__ hdr, int gate,
+                                                                     const uint32_t* __restrict__ cperm)
 {
     using S = F16Shape<D>;
     if (!gate_open(hdr, gate)) return;
@@ -103,8 +104,9 @@ __global__ __launch_bounds__(kThreads) void pack_codebook_f16_kernel(const float
     if (tile >= ntiles) return;
     const float sigma = __builtin_ldexpf(1.0f, centroid_scale_log2(hdr->cmax_bits, D));
     const uint32_t h = lane >> 5, m = lane & 31;
-    const uint32_t k = 32 * tile + 16 * ((m >> 2) & 1) + (m & 3) + 4 * (m >> 3);
-    const bool valid = k < K;
+    const uint32_t pos = 32 * tile + 16 * ((m >> 2) & 1) + (m & 3) + 4 * (m >> 3);
+    const bool valid = pos < K;
+    const uint32_t k = (cperm != nullptr && valid) ? cperm[pos] : pos;  // norm order when pruning
     _Float16 parts[D][3];
     double norm = 0.0;
 #pragma unroll
@@ -140,9 +142,10 @@ __global__ __launch_bounds__(kThreads) void pack_codebook_f16_kernel(const float
     }
     if (!S::kNormInK && lane < 32) {
         // norms in centroid order 32*tile + lane (this thread's own k is a permuted row, so recompute)
-        const uint32_t kc = 32 * tile + lane;
+        const uint32_t pc = 32 * tile + lane;
+        const uint32_t kc = (cperm != nullptr && pc < K) ? cperm[pc] : pc;
         float v = INFINITY;
-        if (kc < K) {
+        if (pc < K) {
             double s = 0.0;
             for (int j = 0; j < D; ++j) {
                 const double c = double(C[size_t(kc) * D + j]);
@@ -159,7 +162,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
     const float* __restrict__ X, uint32_t N, const float* __restrict__ C, uint32_t K, const char* __restrict__ packed,
     uint32_t ntiles, uint32_t* __restrict__ idx, float* __restrict__ dmin, WsHeader* hdr,
     uint32_t* __restrict__ refine_list, unsigned long long* __restrict__ refine_best, uint32_t refine_cap, int gate,
-    long long* sums, uint32_t* counts)
+    long long* sums, uint32_t* counts, const uint2* __restrict__ windows, const uint32_t* __restrict__ cperm)
 {
     using S = F16Shape<D>;
     constexpr int KM = S::KM;
@@ -211,17 +214,24 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
     }
 
     const float4* P4 = reinterpret_cast<const float4*>(packed);
-    const uint32_t nstages = ntiles / ST;
+    // stage range of this workgroup: everything, or the window of its 512-vector tile (in units of
+    // kStageTilesMax tiles, norm-ordered codebook)
+    uint32_t s_begin = 0, s_end = ntiles / ST;
+    if (windows != nullptr) {
+        const uint2 wdw = windows[(blockIdx.x * (4 * 32 * VT)) / 512];
+        s_begin = wdw.x * (kStageTilesMax / ST);
+        s_end = wdw.y * (kStageTilesMax / ST);
+    }
 #pragma unroll
     for (int p = 0; p < NPF; ++p) {
         const uint32_t j = threadIdx.x + p * kThreads;
-        if (NPF * kThreads == STAGE_F4 || j < STAGE_F4) lds[0][j] = P4[j];
+        if (NPF * kThreads == STAGE_F4 || j < STAGE_F4) lds[s_begin & 1][j] = P4[size_t(s_begin) * STAGE_F4 + j];
     }
     __syncthreads();
 
-    for (uint32_t s = 0; s < nstages; ++s) {
+    for (uint32_t s = s_begin; s < s_end; ++s) {
         const int cur = s & 1;
-        const uint32_t sn = min(s + 1, nstages - 1);  // the last iteration re-reads its own stage; never used
+        const uint32_t sn = min(s + 1, s_end - 1);  // the last iteration re-reads its own stage; never used
         float4 pf[NPF];
 #pragma unroll
         for (int p = 0; p < NPF; ++p) {
@@ -295,12 +305,13 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
         for (int g = 0; g < GT; ++g) {
             const uint32_t k0 = 32 * (grp[vt] * GT + g) + 16 * h;
             for (int r = 0; r < 16; ++r) {
-                const uint32_t k = k0 + r;
-                if (k < K) {
+                const uint32_t pos = k0 + r;  // position in the packed (possibly norm-ordered) codebook
+                if (pos < K) {
+                    const uint32_t k = cperm != nullptr ? cperm[pos] : pos;
                     float c[D];
                     load_row<D>(C + size_t(k) * D, c);
                     const float dk = direct_sqdist<D>(x, c);
-                    if (dk < bd) {
+                    if (dk < bd || (dk == bd && k < bk)) {
                         bd = dk;
                         bk = k;
                     }
@@ -344,28 +355,30 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
 
 template <int D, int VT, int ST>
 static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, const Workspace& w,
-                           int gate, bool accumulate, hipStream_t s)
+                           int gate, bool accumulate, bool pruned, hipStream_t s)
 {
     constexpr int GT = 4;  // tiles per tracking group: 64 centroids per lane are re-evaluated in the epilogue
     const size_t n4 = size_t(K) * D / 4;
     hipLaunchKernelGGL(codebook_absmax_kernel, dim3(uint32_t(std::min<size_t>((n4 + kThreads - 1) / kThreads, 64))),
                        dim3(kThreads), 0, s, reinterpret_cast<const float4*>(C), n4, w.hdr, gate);
     hipLaunchKernelGGL(pack_codebook_f16_kernel<D>, dim3((w.packed_tiles * 64 + kThreads - 1) / kThreads),
-                       dim3(kThreads), 0, s, C, K, w.packed_tiles, reinterpret_cast<char*>(w.packed), w.hdr, gate);
+                       dim3(kThreads), 0, s, C, K, w.packed_tiles, reinterpret_cast<char*>(w.packed), w.hdr, gate,
+                       pruned ? w.cperm : nullptr);
     const uint32_t per_block = 4 * 32 * VT;
     hipLaunchKernelGGL((assign_mfma_f16_kernel<D, VT, ST, GT>), dim3((N + per_block - 1) / per_block), dim3(kThreads),
                        0, s, X, N, C, K, reinterpret_cast<const char*>(w.packed), w.packed_tiles, idx, w.dmin, w.hdr,
-                       w.refine_list, w.refine_best, w.refine_cap, gate, accumulate ? w.sums : nullptr, accumulate ? w.counts : nullptr);
+                       w.refine_list, w.refine_best, w.refine_cap, gate, accumulate ? w.sums : nullptr, accumulate ? w.counts : nullptr,
+                       pruned ? w.windows : nullptr, pruned ? w.cperm : nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_assign_mfma_f16(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                                  const Workspace& w, int gate, bool accumulate, hipStream_t s)
+                                  const Workspace& w, int gate, bool accumulate, bool pruned, hipStream_t s)
 {
     switch (d) {
-        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, gate, accumulate, s);
-        case 8: return launch_t<8, 4, 4>(X, N, C, K, idx, w, gate, accumulate, s);
-        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, gate, accumulate, s);
+        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, gate, accumulate, pruned, s);
+        case 8: return launch_t<8, 4, 4>(X, N, C, K, idx, w, gate, accumulate, pruned, s);
+        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, gate, accumulate, pruned, s);
         default: return hipErrorInvalidValue;
     }
 }

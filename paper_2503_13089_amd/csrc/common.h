@@ -21,6 +21,15 @@ struct WsHeader {
     uint32_t reserved;
 };
 
+// Survives between calls on the same workspace (not touched by the per-call header reset): whether the
+// norm-ordered codes of the previous E-step may serve as a hint. A hint never affects results, only
+// how much of the codebook has to be scored.
+struct WsPersist {
+    unsigned long long magic;
+    uint32_t N, d, K;
+    uint32_t hint_valid;
+};
+
 // Carved view of the caller's workspace.
 struct Workspace {
     WsHeader* hdr;
@@ -32,6 +41,20 @@ struct Workspace {
     float* packed;             // codebook re-laid out as matrix-core operand tiles (+ ||c||^2)
     uint32_t* refine_list;     // [refine_cap] ids of vectors to re-decide in direct form
     unsigned long long* refine_best;  // [refine_cap] (distance bits << 32 | index), reduced with atomicMin
+    // norm ordering for the pruned E-step
+    WsPersist* persist;
+    float* xsorted;            // [N*d]  the vectors in ascending-norm order
+    uint32_t* idx_sorted;      // [N]    codes in that order (also the next call's hint)
+    uint32_t* vperm;           // [N]    input position of the p-th vector in norm order
+    uint32_t* vperm_tmp;       // [N]
+    uint16_t* vkeys;           // [N]    norm keys (sorted after the sort)
+    uint16_t* vkeys_tmp;       // [N]
+    uint32_t* cperm;           // [K]    centroid index of the p-th centroid in norm order
+    uint32_t* cperm_tmp;       // [K]
+    uint16_t* ckeys;           // [K]
+    uint16_t* ckeys_tmp;       // [K]
+    uint32_t* sort_hist;       // [256 * sort blocks]
+    uint2* windows;            // [ceil(N/512)] codebook stage range per 512-vector tile
     uint32_t refine_cap;
     uint32_t partial_slots;
     uint32_t packed_tiles;     // number of 32-centroid tiles in `packed` (K rounded up, padded)
@@ -51,7 +74,10 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     char* p = static_cast<char*>(base);
     size_t off = 0;
     auto take = [&](size_t bytes) { char* q = p ? p + off : nullptr; off += align256(bytes); return q; };
-    w.hdr = reinterpret_cast<WsHeader*>(take(sizeof(WsHeader)));
+    static_assert(sizeof(WsHeader) <= 128 && sizeof(WsPersist) <= 128, "header slot layout");
+    char* slot = take(256);
+    w.hdr = reinterpret_cast<WsHeader*>(slot);
+    w.persist = reinterpret_cast<WsPersist*>(slot ? slot + 128 : nullptr);
     w.cnorm = reinterpret_cast<float*>(take(size_t(K) * 4));
     w.sums = reinterpret_cast<long long*>(take(size_t(K) * d * 8));
     w.counts = reinterpret_cast<uint32_t*>(take(size_t(K) * 4));
@@ -65,6 +91,18 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     w.refine_cap = uint32_t(N / 8 + 4096);
     w.refine_list = reinterpret_cast<uint32_t*>(take(size_t(w.refine_cap) * 4));
     w.refine_best = reinterpret_cast<unsigned long long*>(take(size_t(w.refine_cap) * 8));
+    w.xsorted = reinterpret_cast<float*>(take(size_t(N) * d * 4));
+    w.idx_sorted = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
+    w.vperm = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
+    w.vperm_tmp = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
+    w.vkeys = reinterpret_cast<uint16_t*>(take(size_t(N) * 2));
+    w.vkeys_tmp = reinterpret_cast<uint16_t*>(take(size_t(N) * 2));
+    w.cperm = reinterpret_cast<uint32_t*>(take(size_t(K) * 4));
+    w.cperm_tmp = reinterpret_cast<uint32_t*>(take(size_t(K) * 4));
+    w.ckeys = reinterpret_cast<uint16_t*>(take(size_t(K) * 2));
+    w.ckeys_tmp = reinterpret_cast<uint16_t*>(take(size_t(K) * 2));
+    w.sort_hist = reinterpret_cast<uint32_t*>(take((size_t(N) / 4096 + 3) * 256 * 4));  // histogram + 256 totals
+    w.windows = reinterpret_cast<uint2*>(take((size_t(N) / 512 + 1) * 8));
     w.bytes = off;
     return w;
 }
@@ -87,21 +125,32 @@ __device__ __forceinline__ bool gate_open(const WsHeader* hdr, int gate)
 // Matrix-core E-step, fp32 MFMA: packs the codebook and runs the scoring kernel (provisional idx,
 // w.dmin and the refine list). Must be followed by launch_refine.
 // With accumulate = true the kernel also adds every vector into the cluster sums/counts of its
-// provisional code (the M-step accumulation, hidden under the scoring work).
+// provisional code (the M-step accumulation, hidden under the scoring work). With pruned = true the
+// codebook is packed in norm order (w.cperm) and each workgroup scores only its window (w.windows).
 hipError_t launch_assign_mfma_f32(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K,
-                                  uint32_t* idx, const Workspace& w, int gate, bool accumulate, hipStream_t s);
+                                  uint32_t* idx, const Workspace& w, int gate, bool accumulate, bool pruned,
+                                  hipStream_t s);
 
 // Matrix-core E-step for fp16-representable inputs: centroids split into three fp16 parts so that
 // every product is exact, scored with the fp16 MFMA. Same outputs as the fp32 variant.
 hipError_t launch_assign_mfma_f16(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K,
-                                  uint32_t* idx, const Workspace& w, int gate, bool accumulate, hipStream_t s);
+                                  uint32_t* idx, const Workspace& w, int gate, bool accumulate, bool pruned,
+                                  hipStream_t s);
+
+// Norm ordering (pruned E-step): vectors once per call, centroids + per-tile windows once per E-step,
+// and the codes back to input order afterwards.
+hipError_t launch_sort_vectors(const float* X, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, hipStream_t s);
+hipError_t launch_sort_centroids_and_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w,
+                                             hipStream_t s);
+hipError_t launch_unpermute(uint32_t N, uint32_t* idx, const Workspace& w, hipStream_t s);
 
 // Re-decides the listed guard-band vectors over all K centroids in direct form; if the list
 // overflowed, re-decides everything in direct form. With fix_sums = true the cluster sums/counts that
 // the scoring kernel accumulated are corrected for every vector whose code changed (or rebuilt from
 // scratch on overflow).
+// With mark_hint = true (norm-ordered run) the codes are flagged as a usable hint for the next call.
 hipError_t launch_refine(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                         const Workspace& w, bool fix_sums, hipStream_t s);
+                         const Workspace& w, bool fix_sums, bool mark_hint, hipStream_t s);
 
 // Scans the inputs: max |x| and whether every x is exactly representable in fp16.
 hipError_t launch_scan_inputs(const float* X, uint64_t n_floats, WsHeader* hdr, hipStream_t s);

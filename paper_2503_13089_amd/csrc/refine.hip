@@ -68,11 +68,13 @@ __global__ __launch_bounds__(kThreads) void refine_finish_kernel(WsHeader* hdr, 
                                                                  const unsigned long long* __restrict__ refine_best,
                                                                  uint32_t refine_cap, uint32_t* __restrict__ idx,
                                                                  float* __restrict__ dmin, const float* __restrict__ X,
-                                                                 uint32_t N, long long* sums, uint32_t* counts)
+                                                                 uint32_t N, long long* sums, uint32_t* counts,
+                                                                 WsPersist* persist)
 {
     const uint32_t count = hdr->refine_count;
     const uint32_t e = blockIdx.x * kThreads + threadIdx.x;
     if (e == 0) {
+        if (persist != nullptr) persist->hint_valid = 1;  // idx (norm-ordered) is a usable hint from now on
         hdr->refined_vectors += count;
         hdr->assign_calls += 1;
         hdr->cmax_bits = 0;  // the next E-step scans its own codebook
@@ -97,22 +99,23 @@ __global__ __launch_bounds__(kThreads) void refine_finish_kernel(WsHeader* hdr, 
 
 template <int D>
 static void launch_refine_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, const Workspace& w,
-                            bool fix_sums, uint32_t slices, hipStream_t s)
+                            bool fix_sums, bool mark_hint, uint32_t slices, hipStream_t s)
 {
     hipLaunchKernelGGL(refine_kernel<D>, dim3(4096), dim3(64), 0, s, X, C, K, w.hdr, w.refine_list, w.refine_best,
                        w.refine_cap, slices);
     hipLaunchKernelGGL(refine_finish_kernel<D>, dim3(256), dim3(kThreads), 0, s, w.hdr, w.refine_list, w.refine_best,
-                       w.refine_cap, idx, w.dmin, X, N, fix_sums ? w.sums : nullptr, fix_sums ? w.counts : nullptr);
+                       w.refine_cap, idx, w.dmin, X, N, fix_sums ? w.sums : nullptr, fix_sums ? w.counts : nullptr,
+                       mark_hint ? w.persist : nullptr);
 }
 
 hipError_t launch_refine(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                         const Workspace& w, bool fix_sums, hipStream_t s)
+                         const Workspace& w, bool fix_sums, bool mark_hint, hipStream_t s)
 {
     const uint32_t slices = std::max(1u, std::min(128u, K / 512));
     switch (d) {
-        case 4: launch_refine_t<4>(X, N, C, K, idx, w, fix_sums, slices, s); break;
-        case 8: launch_refine_t<8>(X, N, C, K, idx, w, fix_sums, slices, s); break;
-        case 16: launch_refine_t<16>(X, N, C, K, idx, w, fix_sums, slices, s); break;
+        case 4: launch_refine_t<4>(X, N, C, K, idx, w, fix_sums, mark_hint, slices, s); break;
+        case 8: launch_refine_t<8>(X, N, C, K, idx, w, fix_sums, mark_hint, slices, s); break;
+        case 16: launch_refine_t<16>(X, N, C, K, idx, w, fix_sums, mark_hint, slices, s); break;
         default: return hipErrorInvalidValue;
     }
     // overflow path: more guard-band vectors than the list holds -> decide everything in direct form

@@ -1,0 +1,334 @@
+// Norm ordering for the pruned E-step (Section 3.1: the codes are the argmin over ALL centroids; a
+// centroid can be skipped for a vector only if it provably cannot be that argmin).
+//
+// Triangle inequality: ||x - c|| >= | ||x|| - ||c|| |. If some centroid is known to lie within
+// distance u of x (any centroid will do - the previous iteration's code is a good one), then every
+// centroid with | ||c|| - ||x|| | > u is farther than that and cannot be the nearest. With the
+// centroids ordered by norm this is a contiguous window of the codebook, and with the vectors ordered
+// by norm too, the 512 vectors a workgroup scores share almost the same window.
+//
+// This file holds the ordering machinery: 16-bit norm keys (the top half of the fp32 pattern of the
+// norm: monotone, 2^-7 relative resolution), a stable two-pass LSD radix sort of (key, id) pairs whose
+// output does not depend on scheduling, the row gather that builds the norm-ordered copy of the
+// vectors, the per-workgroup window computation, and the scatter of the codes back to input order.
+#include <algorithm>
+
+#include "common.h"
+
+namespace cc {
+
+constexpr int kThreads = 256;
+constexpr int kSortThreads = 512;          // 8 waves
+constexpr uint32_t kSortChunk = 4096;      // elements per block and pass
+
+__device__ __forceinline__ uint32_t norm_key(float norm) { return __float_as_uint(norm) >> 16; }
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void vector_keys_kernel(const float* __restrict__ X, uint32_t N,
+                                                               uint16_t* __restrict__ keys, uint32_t* __restrict__ ids)
+{
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= N) return;
+    float x[D];
+    load_row<D>(X + size_t(i) * D, x);
+    float s = 0.0f;
+#pragma unroll
+    for (int j = 0; j < D; ++j) s = __builtin_fmaf(x[j], x[j], s);
+    keys[i] = uint16_t(norm_key(__builtin_sqrtf(s)));
+    ids[i] = i;
+}
+
+// One radix pass over 8 bits of the key. hist is digit-major: hist[digit * blocks + block].
+__global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const uint16_t* __restrict__ keys, uint32_t n,
+                                                                  int shift, uint32_t* __restrict__ hist)
+{
+    __shared__ uint32_t h[256];
+    if (threadIdx.x < 256) h[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t lo = blockIdx.x * kSortChunk, hi = min(lo + kSortChunk, n);
+    for (uint32_t i = lo + threadIdx.x; i < hi; i += kSortThreads) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
+    __syncthreads();
+    if (threadIdx.x < 256) hist[threadIdx.x * gridDim.x + blockIdx.x] = h[threadIdx.x];
+}
+
+// Row scan of the digit-major histogram: block `digit` replaces hist[digit][0..blocks) by its exclusive
+// prefix sum and writes the row total to totals[digit]. The scatter adds the prefix of the totals itself.
+__global__ __launch_bounds__(1024) void radix_rowscan_kernel(uint32_t* __restrict__ hist, uint32_t blocks,
+                                                             uint32_t* __restrict__ totals)
+{
+    __shared__ uint32_t part[1024];
+    uint32_t* row = hist + size_t(blockIdx.x) * blocks;
+    uint32_t carry = 0;
+    for (uint32_t base = 0; base < blocks; base += 1024) {
+        const uint32_t i = base + threadIdx.x;
+        const uint32_t v = i < blocks ? row[i] : 0;
+        part[threadIdx.x] = v;
+        __syncthreads();
+        for (uint32_t off = 1; off < 1024; off <<= 1) {  // Hillis-Steele inclusive scan
+            const uint32_t t = threadIdx.x >= off ? part[threadIdx.x - off] : 0;
+            __syncthreads();
+            part[threadIdx.x] += t;
+            __syncthreads();
+        }
+        if (i < blocks) row[i] = carry + part[threadIdx.x] - v;
+        carry += part[1023];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) totals[blockIdx.x] = carry;
+}
+
+// Stable scatter of one pass: an element goes to (start of its digit for this block, from the scanned
+// histogram) + (number of earlier elements of this block with the same digit). "Earlier" is by
+// position, so the result is the same whatever the scheduling.
+__global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uint16_t* __restrict__ keys_in,
+                                                                     const uint32_t* __restrict__ ids_in, uint32_t n,
+                                                                     int shift, const uint32_t* __restrict__ hist,
+                                                                     const uint32_t* __restrict__ totals,
+                                                                     uint16_t* __restrict__ keys_out,
+                                                                     uint32_t* __restrict__ ids_out)
+{
+    constexpr int kWaves = kSortThreads / 64;
+    __shared__ uint32_t base[256];            // next free slot per digit
+    __shared__ uint32_t cnt[kWaves][256];     // per round: elements of each digit in each wave
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // start of (digit, this block) = sum of the totals of all smaller digits + this block's row prefix
+    if (threadIdx.x < 256) cnt[0][threadIdx.x] = totals[threadIdx.x];
+    __syncthreads();
+    if (threadIdx.x < 256) {
+        uint32_t before = 0;
+        for (uint32_t dg = 0; dg < threadIdx.x; ++dg) before += cnt[0][dg];
+        base[threadIdx.x] = before + hist[threadIdx.x * gridDim.x + blockIdx.x];
+    }
+    __syncthreads();
+    const uint32_t lo = blockIdx.x * kSortChunk, hi = min(lo + kSortChunk, n);
+    for (uint32_t r0 = lo; r0 < hi; r0 += kSortThreads) {
+        for (int t = threadIdx.x; t < kWaves * 256; t += kSortThreads) (&cnt[0][0])[t] = 0;
+        __syncthreads();
+        const uint32_t i = r0 + threadIdx.x;
+        const bool live = i < hi;
+        const uint32_t key = live ? keys_in[i] : 0;
+        const uint32_t id = live ? ids_in[i] : 0;
+        const uint32_t digit = (key >> shift) & 255u;
+        // lanes of this wave holding the same digit
+        unsigned long long same = __ballot(live);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const unsigned long long set = __ballot(live && ((digit >> b) & 1u));
+            same &= ((digit >> b) & 1u) ? set : ~set;
+        }
+        const uint32_t below = __popcll(same & ((1ull << lane) - 1ull));
+        if (live && below == 0) cnt[wave][digit] = uint32_t(__popcll(same));  // one writer per (wave, digit)
+        __syncthreads();
+        uint32_t pos = 0;
+        if (live) {
+            pos = base[digit] + below;
+            for (int w = 0; w < wave; ++w) pos += cnt[w][digit];
+        }
+        __syncthreads();
+        if (threadIdx.x < 256) {
+            uint32_t t = 0;
+            for (int w = 0; w < kWaves; ++w) t += cnt[w][threadIdx.x];
+            base[threadIdx.x] += t;
+        }
+        if (live) {
+            keys_out[pos] = uint16_t(key);
+            ids_out[pos] = id;
+        }
+        __syncthreads();
+    }
+}
+
+// out_row[p] = in_row[ids[p]]
+template <int D>
+__global__ __launch_bounds__(kThreads) void gather_rows_kernel(const float* __restrict__ in,
+                                                               const uint32_t* __restrict__ ids, uint32_t n,
+                                                               float* __restrict__ out)
+{
+    constexpr int Q = D / 4;
+    const uint64_t t = uint64_t(blockIdx.x) * kThreads + threadIdx.x;
+    if (t >= uint64_t(n) * Q) return;
+    const uint32_t p = uint32_t(t / Q), q = uint32_t(t % Q);
+    reinterpret_cast<float4*>(out)[t] = reinterpret_cast<const float4*>(in)[size_t(ids[p]) * Q + q];
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void centroid_keys_kernel(const float* __restrict__ C, uint32_t K,
+                                                                 uint16_t* __restrict__ keys, uint32_t* __restrict__ ids)
+{
+    const uint32_t k = blockIdx.x * kThreads + threadIdx.x;
+    if (k >= K) return;
+    double s = 0.0;
+    for (int j = 0; j < D; ++j) {
+        const double c = double(C[size_t(k) * D + j]);
+        s += c * c;
+    }
+    keys[k] = uint16_t(norm_key(__builtin_sqrtf(float(s))));
+    ids[k] = k;
+}
+
+// Window of codebook stages (256 norm-ordered centroids each) that the 512 norm-ordered vectors of one
+// workgroup tile have to score: every centroid whose norm key lies in [min_i key(||x_i|| - u_i) - 1,
+// max_i key(||x_i|| + u_i) + 1], u_i = the distance from x_i to its hinted centroid, slightly enlarged.
+// Keys are monotone in the norm and 2^-7 wide, so the +-1 key absorbs every rounding of the norms and of u.
+// Without a hint the window is the whole codebook.
+template <int D>
+__global__ __launch_bounds__(kThreads) void window_kernel(const float* __restrict__ Xs, uint32_t N,
+                                                          const float* __restrict__ C, uint32_t K,
+                                                          const uint32_t* __restrict__ hint, const WsPersist* persist,
+                                                          const uint16_t* __restrict__ ckeys, uint32_t nstages,
+                                                          uint2* __restrict__ win)
+{
+    __shared__ uint32_t red_lo[kThreads / 64], red_hi[kThreads / 64];
+    const bool have_hint = persist->hint_valid != 0;
+    uint32_t klo = 0xffffu, khi = 0;
+    if (have_hint) {
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            const uint32_t p = blockIdx.x * 512 + v * kThreads + threadIdx.x;
+            if (p < N) {
+                float x[D], c[D];
+                load_row<D>(Xs + size_t(p) * D, x);
+                load_row<D>(C + size_t(min(hint[p], K - 1)) * D, c);
+                const float u = __builtin_sqrtf(direct_sqdist<D>(x, c)) * 1.001f + 1e-30f;
+                float s = 0.0f;
+#pragma unroll
+                for (int j = 0; j < D; ++j) s = __builtin_fmaf(x[j], x[j], s);
+                const float nrm = __builtin_sqrtf(s);
+                const float lo = nrm - u, hi = nrm + u;
+                const uint32_t a = lo > 0.0f ? norm_key(lo) : 0u;
+                const uint32_t b = hi < 3.0e38f ? norm_key(hi) : 0xffffu;
+                klo = min(klo, a > 0 ? a - 1 : 0u);
+                khi = max(khi, min(b + 1, 0xffffu));
+            }
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        klo = min(klo, uint32_t(__shfl_xor(int(klo), off, 64)));
+        khi = max(khi, uint32_t(__shfl_xor(int(khi), off, 64)));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        red_lo[threadIdx.x >> 6] = klo;
+        red_hi[threadIdx.x >> 6] = khi;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    for (int w = 1; w < kThreads / 64; ++w) {
+        klo = min(klo, red_lo[w]);
+        khi = max(khi, red_hi[w]);
+    }
+    // stage s holds norm-ordered positions [256 s, 256 s + 255]; stages past K hold padding only
+    const uint32_t real = (K + 255) / 256;
+    uint32_t s0 = 0, s1 = real;
+    if (have_hint && klo <= khi) {
+        uint32_t a = 0, b = real;  // first stage whose largest key >= klo
+        while (a < b) {
+            const uint32_t m = (a + b) / 2;
+            if (ckeys[min(256 * m + 255, K - 1)] >= klo) b = m; else a = m + 1;
+        }
+        s0 = a;
+        a = 0, b = real;           // first stage whose smallest key > khi
+        while (a < b) {
+            const uint32_t m = (a + b) / 2;
+            if (ckeys[256 * m] > khi) b = m; else a = m + 1;
+        }
+        s1 = a;
+        if (s0 >= s1) { s0 = 0; s1 = real; }
+    }
+    (void)nstages;
+    win[blockIdx.x] = make_uint2(s0, s1);
+}
+
+// Codes back to input order: idx[ids[p]] = idx_sorted[p]; also records that the sorted codes are a usable hint.
+__global__ __launch_bounds__(kThreads) void unpermute_kernel(const uint32_t* __restrict__ idx_sorted,
+                                                             const uint32_t* __restrict__ ids, uint32_t n,
+                                                             uint32_t* __restrict__ idx, WsPersist* persist)
+{
+    const uint32_t p = blockIdx.x * kThreads + threadIdx.x;
+    if (p == 0) persist->hint_valid = 1;
+    if (p < n) idx[ids[p]] = idx_sorted[p];
+}
+
+// The hint survives between calls only for the same problem shape.
+__global__ void persist_check_kernel(WsPersist* persist, uint32_t N, uint32_t d, uint32_t K)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    constexpr unsigned long long kMagic = 0x636c7573636f6d70ull;  // "cluscomp"
+    if (persist->magic != kMagic || persist->N != N || persist->d != d || persist->K != K) {
+        persist->magic = kMagic;
+        persist->N = N;
+        persist->d = d;
+        persist->K = K;
+        persist->hint_valid = 0;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+static void radix_sort16(uint16_t* keys_a, uint32_t* ids_a, uint16_t* keys_b, uint32_t* ids_b, uint32_t n,
+                         uint32_t* hist, hipStream_t s)
+{
+    const uint32_t blocks = (n + kSortChunk - 1) / kSortChunk;
+    // pass 1: low byte a -> b; pass 2: high byte b -> a
+    uint32_t* totals = hist + size_t(256) * blocks;
+    hipLaunchKernelGGL(radix_hist_kernel, dim3(blocks), dim3(kSortThreads), 0, s, keys_a, n, 0, hist);
+    hipLaunchKernelGGL(radix_rowscan_kernel, dim3(256), dim3(1024), 0, s, hist, blocks, totals);
+    hipLaunchKernelGGL(radix_scatter_kernel, dim3(blocks), dim3(kSortThreads), 0, s, keys_a, ids_a, n, 0, hist, totals,
+                       keys_b, ids_b);
+    hipLaunchKernelGGL(radix_hist_kernel, dim3(blocks), dim3(kSortThreads), 0, s, keys_b, n, 8, hist);
+    hipLaunchKernelGGL(radix_rowscan_kernel, dim3(256), dim3(1024), 0, s, hist, blocks, totals);
+    hipLaunchKernelGGL(radix_scatter_kernel, dim3(blocks), dim3(kSortThreads), 0, s, keys_b, ids_b, n, 8, hist, totals,
+                       keys_a, ids_a);
+}
+
+template <int D>
+static void sort_vectors_t(const float* X, uint32_t N, const Workspace& w, hipStream_t s)
+{
+    hipLaunchKernelGGL(vector_keys_kernel<D>, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, s, X, N, w.vkeys,
+                       w.vperm);
+    radix_sort16(w.vkeys, w.vperm, w.vkeys_tmp, w.vperm_tmp, N, w.sort_hist, s);
+    const uint64_t pieces = uint64_t(N) * (D / 4);
+    hipLaunchKernelGGL(gather_rows_kernel<D>, dim3(uint32_t((pieces + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, X,
+                       w.vperm, N, w.xsorted);
+}
+
+hipError_t launch_sort_vectors(const float* X, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, hipStream_t s)
+{
+    hipLaunchKernelGGL(persist_check_kernel, dim3(1), dim3(64), 0, s, w.persist, N, d, K);
+    switch (d) {
+        case 4: sort_vectors_t<4>(X, N, w, s); break;
+        case 8: sort_vectors_t<8>(X, N, w, s); break;
+        case 16: sort_vectors_t<16>(X, N, w, s); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+template <int D>
+static void sort_centroids_t(const float* C, uint32_t N, uint32_t K, const Workspace& w, hipStream_t s)
+{
+    hipLaunchKernelGGL(centroid_keys_kernel<D>, dim3((K + kThreads - 1) / kThreads), dim3(kThreads), 0, s, C, K, w.ckeys,
+                       w.cperm);
+    radix_sort16(w.ckeys, w.cperm, w.ckeys_tmp, w.cperm_tmp, K, w.sort_hist, s);
+    hipLaunchKernelGGL(window_kernel<D>, dim3((N + 511) / 512), dim3(kThreads), 0, s, w.xsorted, N, C, K, w.idx_sorted,
+                       w.persist, w.ckeys, w.packed_tiles / kStageTilesMax, w.windows);
+}
+
+hipError_t launch_sort_centroids_and_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w,
+                                             hipStream_t s)
+{
+    switch (d) {
+        case 4: sort_centroids_t<4>(C, N, K, w, s); break;
+        case 8: sort_centroids_t<8>(C, N, K, w, s); break;
+        case 16: sort_centroids_t<16>(C, N, K, w, s); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_unpermute(uint32_t N, uint32_t* idx, const Workspace& w, hipStream_t s)
+{
+    hipLaunchKernelGGL(unpermute_kernel, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, s, w.idx_sorted, w.vperm, N,
+                       idx, w.persist);
+    return hipGetLastError();
+}
+
+}  // namespace cc

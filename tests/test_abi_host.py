@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 def test_workspace_query():
     assert cc.workspace_bytes(65536, 4, 256) > 0
     big = cc.workspace_bytes(11272192, 4, 65536)
-    assert 11272192 * 4 <= big < 200e6  # at least the per-vector distance array
+    assert 11272192 * 4 <= big < 1e9  # at least the per-vector distance array
     assert cc.workspace_bytes(65536, 4, 256) % 256 == 0
     for N, d, K in [(0, 4, 1), (10, 5, 2), (10, 4, 0), (10, 4, 11), (1 << 32, 4, 8), (1 << 26, 4, (1 << 24) + 1)]:
         assert cc.workspace_bytes(N, d, K) == 0
@@ -76,7 +76,7 @@ def test_other_entry_points_reject_bad_arguments():
     assert lib.cc_decode(A16, 0, 4, A4, 10, A16, None) == -2
     assert lib.cc_decode(A16, 2, 4, A4, 10, MISALIGNED, None) == -4
     assert lib.cc_read_stats(None, 0, None, None) == -1
-    assert lib.cc_set_assign_mode(7) == -2
+    assert lib.cc_set_assign_mode(7) == -2 and lib.cc_set_assign_mode(-1) == -2
     prev = lib.cc_set_assign_mode(1)
     assert lib.cc_set_assign_mode(prev) == 1
 

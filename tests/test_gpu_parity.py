@@ -24,10 +24,11 @@ def g():
     return gpu_helpers
 
 
-@pytest.fixture(params=[0, 1, 2], ids=["auto", "direct", "fp32-mfma"])
+@pytest.fixture(params=[0, 1, 2, 3], ids=["auto", "direct", "fp32-mfma", "auto-unpruned"])
 def mode(request, g):
     """Runs a test once per E-step selection: 0 = automatic (fp16 MFMA for these fp16-representable inputs when
-    K >= 128), 1 = direct form only, 2 = fp32 MFMA + guard band + refinement."""
+    K >= 128, norm-window pruning when K >= 8192), 1 = direct form only, 2 = fp32 MFMA + guard band + refinement,
+    3 = automatic without pruning."""
     import paper_2503_13089_amd as cc
 
     cc.set_assign_mode(request.param)
@@ -43,6 +44,8 @@ SHAPES = [  # (N, d, K): ragged in N (not a multiple of 256/512/1024) and in K (
     (513, 8, 1),       # a single centroid
     (1, 4, 1),         # the smallest legal problem
     (65536, 4, 256),   # cfg1's shape
+    (40003, 4, 9001),  # K large enough for the norm-window pruning of the automatic mode
+    (20011, 8, 8200),
 ]
 
 
@@ -165,7 +168,8 @@ def test_update_general_fp32_inputs_and_bad_codes(g):
     parity.check_centroids(got2, want2, X)
 
 
-@pytest.mark.parametrize("N,d,K,iters", [(65536, 4, 256, 10), (30011, 8, 777, 5), (20003, 16, 515, 4), (3000, 4, 3000, 2)])
+@pytest.mark.parametrize("N,d,K,iters", [(65536, 4, 256, 10), (30011, 8, 777, 5), (20003, 16, 515, 4), (3000, 4, 3000, 2),
+                                         (50021, 4, 8500, 4)])
 def test_fit_trajectory_following(g, mode, N, d, K, iters):
     """Free-running GPU fit, every step verified: the oracle checks each assignment against the GPU's
     own centroids, adopts the GPU's choice on near-ties, and recomputes the update."""
