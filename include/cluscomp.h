@@ -117,6 +117,9 @@ typedef struct cc_stats {
                                   re-decided with direct-form distances (summed over all assigns) */
     uint64_t skipped_vectors;  /* vectors with idx >= K seen by an update */
     uint64_t assign_calls;     /* assign passes run */
+    uint64_t scored_stages;    /* norm-window pruning: codebook stages (256 centroids) scored, summed over
+                                  the 512-vector tiles of all assigns; 0 when pruning did not run */
+    uint64_t total_stages;     /* the same sum if every tile had scored the whole codebook */
     int32_t  fixed_point_exp;  /* e: cluster sums are held as round(x * 2^e) in int64 */
     uint32_t reserved;
 } cc_stats;

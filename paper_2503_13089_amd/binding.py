@@ -26,7 +26,8 @@ class CCError(RuntimeError):
 
 class _CStats(ctypes.Structure):
     _fields_ = [("refined_vectors", ctypes.c_uint64), ("skipped_vectors", ctypes.c_uint64),
-                ("assign_calls", ctypes.c_uint64), ("fixed_point_exp", ctypes.c_int32),
+                ("assign_calls", ctypes.c_uint64), ("scored_stages", ctypes.c_uint64),
+                ("total_stages", ctypes.c_uint64), ("fixed_point_exp", ctypes.c_int32),
                 ("reserved", ctypes.c_uint32)]
 
 
@@ -35,6 +36,8 @@ class Stats:
     refined_vectors: int
     skipped_vectors: int
     assign_calls: int
+    scored_stages: int
+    total_stages: int
     fixed_point_exp: int
 
 
@@ -182,7 +185,8 @@ def read_stats(workspace) -> Stats:
     st = _CStats()
     _check(load_library().cc_read_stats(_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
                                         ctypes.byref(st), _stream()))
-    return Stats(int(st.refined_vectors), int(st.skipped_vectors), int(st.assign_calls), int(st.fixed_point_exp))
+    return Stats(int(st.refined_vectors), int(st.skipped_vectors), int(st.assign_calls), int(st.scored_stages),
+                 int(st.total_stages), int(st.fixed_point_exp))
 
 
 def set_assign_mode(mode: int) -> int:

@@ -239,6 +239,8 @@ int cc_read_stats(const void* workspace, size_t workspace_bytes, cc_stats* host_
     host_out->refined_vectors = h.refined_vectors;
     host_out->skipped_vectors = h.skipped_vectors;
     host_out->assign_calls = h.assign_calls;
+    host_out->scored_stages = h.window_stages;
+    host_out->total_stages = h.window_total;
     host_out->fixed_point_exp = h.fixed_point_exp;
     host_out->reserved = 0;
     return CC_OK;

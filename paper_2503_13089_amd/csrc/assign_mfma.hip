@@ -208,24 +208,9 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
         const uint32_t i = min(i_raw, N - 1);
         float x[D];
         load_row<D>(X + size_t(i) * D, x);
-        float bd = INFINITY;
-        uint32_t bk = 0;
-        for (int g = 0; g < GT; ++g) {
-            const uint32_t k0 = 32 * (grp[vt] * GT + g) + 16 * h;
-            for (int r = 0; r < 16; ++r) {
-                const uint32_t pos = k0 + r;  // position in the packed (possibly norm-ordered) codebook
-                if (pos < K) {
-                    const uint32_t k = cperm != nullptr ? cperm[pos] : pos;
-                    float c[D];
-                    load_row<D>(C + size_t(k) * D, c);
-                    const float dk = direct_sqdist<D>(x, c);
-                    if (dk < bd || (dk == bd && k < bk)) {
-                        bd = dk;
-                        bk = k;
-                    }
-                }
-            }
-        }
+        float bd;
+        uint32_t bk;
+        recover_group<D, GT>(x, C, cperm, K, grp[vt], h, bd, bk);
         const float od = __shfl_xor(bd, 32, 64);
         const uint32_t ok = uint32_t(__shfl_xor(int(bk), 32, 64));
         const float ob = __shfl_xor(best[vt], 32, 64);
@@ -266,7 +251,7 @@ static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t 
                        dim3(kThreads), 0, s, C, K, w.packed_tiles, w.packed, w.hdr, gate, pruned ? w.cperm : nullptr);
     const uint32_t per_block = 4 * 32 * VT;
     hipLaunchKernelGGL((assign_mfma_kernel<D, VT, ST, GT>), dim3((N + per_block - 1) / per_block), dim3(kThreads), 0, s,
-                       X, N, C, K, w.packed, w.packed_tiles, idx, w.dmin, w.hdr, w.refine_list, w.refine_best,
+                       X, N, pruned ? w.csorted : C, K, w.packed, w.packed_tiles, idx, w.dmin, w.hdr, w.refine_list, w.refine_best,
                        w.refine_cap, gate, accumulate ? w.sums : nullptr, accumulate ? w.counts : nullptr,
                        pruned ? w.windows : nullptr, pruned ? w.cperm : nullptr);
     return hipGetLastError();

@@ -17,6 +17,8 @@ struct WsHeader {
     unsigned long long refined_vectors;
     unsigned long long skipped_vectors;
     unsigned long long assign_calls;
+    unsigned long long window_stages;   // sum over 512-vector tiles of the codebook stages they had to score
+    unsigned long long window_total;    // what that sum would be without pruning
     int32_t fixed_point_exp;
     uint32_t reserved;
 };
@@ -49,6 +51,7 @@ struct Workspace {
     uint32_t* vperm_tmp;       // [N]
     uint16_t* vkeys;           // [N]    norm keys (sorted after the sort)
     uint16_t* vkeys_tmp;       // [N]
+    float* csorted;            // [K*d]  the centroids in ascending-norm order
     uint32_t* cperm;           // [K]    centroid index of the p-th centroid in norm order
     uint32_t* cperm_tmp;       // [K]
     uint16_t* ckeys;           // [K]
@@ -97,6 +100,7 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     w.vperm_tmp = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vkeys = reinterpret_cast<uint16_t*>(take(size_t(N) * 2));
     w.vkeys_tmp = reinterpret_cast<uint16_t*>(take(size_t(N) * 2));
+    w.csorted = reinterpret_cast<float*>(take(size_t(K) * d * 4));
     w.cperm = reinterpret_cast<uint32_t*>(take(size_t(K) * 4));
     w.cperm_tmp = reinterpret_cast<uint32_t*>(take(size_t(K) * 4));
     w.ckeys = reinterpret_cast<uint16_t*>(take(size_t(K) * 2));
@@ -219,6 +223,48 @@ __device__ __forceinline__ float direct_sqdist(const float (&x)[D], const float 
         acc = __builtin_fmaf(t, t, acc);
     }
     return acc;
+}
+
+template <int D>
+__device__ __forceinline__ void load_row(const float* __restrict__ p, float (&v)[D]);
+
+// Index recovery of the matrix-core E-step: direct-form argmin over the GT*16 codebook positions
+// 32*(group*GT+g) + 16*h + r that one lane's winning group covers. `rows` holds the centroids in packed
+// order (the codebook itself, or its norm-ordered copy together with `cperm`, which maps a position
+// to the centroid index). Among exactly equal distances the lowest centroid index wins.
+// Rows are fetched U at a time so that U independent loads are in flight.
+template <int D, int GT>
+__device__ __forceinline__ void recover_group(const float (&x)[D], const float* __restrict__ rows,
+                                              const uint32_t* __restrict__ cperm, uint32_t K, uint32_t group, int h,
+                                              float& best_d, uint32_t& best_k)
+{
+    constexpr int U = D <= 8 ? 8 : 4;
+    float bd = INFINITY;
+    uint32_t bpos = 0;
+    for (int g = 0; g < GT; ++g) {
+        const uint32_t k0 = 32 * (group * GT + g) + 16 * h;
+#pragma unroll
+        for (int r0 = 0; r0 < 16; r0 += U) {
+            float c[U][D];
+#pragma unroll
+            for (int u = 0; u < U; ++u) load_row<D>(rows + size_t(min(k0 + r0 + u, K - 1)) * D, c[u]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t pos = k0 + r0 + u;
+                const float dk = direct_sqdist<D>(x, c[u]);
+                if (pos < K) {
+                    if (dk < bd) {
+                        bd = dk;
+                        bpos = pos;
+                    } else if (dk == bd && cperm != nullptr && cperm[pos] < cperm[bpos]) {
+                        bpos = pos;  // exact tie in norm order: keep the lower centroid index
+                    }
+                }
+            }
+        }
+    }
+    best_d = bd;
+    best_k = cperm != nullptr ? cperm[bpos] : bpos;
 }
 
 template <int D>

@@ -175,7 +175,7 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restrict__ Xs, uint32_t N,
                                                           const float* __restrict__ C, uint32_t K,
                                                           const uint32_t* __restrict__ hint, const WsPersist* persist,
-                                                          const uint16_t* __restrict__ ckeys, uint32_t nstages,
+                                                          const uint16_t* __restrict__ ckeys, WsHeader* hdr,
                                                           uint2* __restrict__ win)
 {
     __shared__ uint32_t red_lo[kThreads / 64], red_hi[kThreads / 64];
@@ -234,7 +234,8 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
         s1 = a;
         if (s0 >= s1) { s0 = 0; s1 = real; }
     }
-    (void)nstages;
+    atomicAdd(&hdr->window_stages, static_cast<unsigned long long>(s1 - s0));
+    atomicAdd(&hdr->window_total, static_cast<unsigned long long>(real));
     win[blockIdx.x] = make_uint2(s0, s1);
 }
 
@@ -308,8 +309,11 @@ static void sort_centroids_t(const float* C, uint32_t N, uint32_t K, const Works
     hipLaunchKernelGGL(centroid_keys_kernel<D>, dim3((K + kThreads - 1) / kThreads), dim3(kThreads), 0, s, C, K, w.ckeys,
                        w.cperm);
     radix_sort16(w.ckeys, w.cperm, w.ckeys_tmp, w.cperm_tmp, K, w.sort_hist, s);
+    const uint64_t pieces = uint64_t(K) * (D / 4);
+    hipLaunchKernelGGL(gather_rows_kernel<D>, dim3(uint32_t((pieces + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, C,
+                       w.cperm, K, w.csorted);
     hipLaunchKernelGGL(window_kernel<D>, dim3((N + 511) / 512), dim3(kThreads), 0, s, w.xsorted, N, C, K, w.idx_sorted,
-                       w.persist, w.ckeys, w.packed_tiles / kStageTilesMax, w.windows);
+                       w.persist, w.ckeys, w.hdr, w.windows);
 }
 
 hipError_t launch_sort_centroids_and_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w,

@@ -25,6 +25,8 @@ __global__ void reset_header_kernel(WsHeader* hdr)
         hdr->refined_vectors = 0;
         hdr->skipped_vectors = 0;
         hdr->assign_calls = 0;
+        hdr->window_stages = 0;
+        hdr->window_total = 0;
         hdr->fixed_point_exp = 0;
         hdr->reserved = 0;
     }
