@@ -155,7 +155,7 @@ int cc_kmeans_fit(const float* vectors, uint64_t N, uint32_t d, uint32_t K, int3
     if (centroids != init_centroids)
         CC_TRY_HIP(cc::launch_copy_f32(init_centroids, centroids, size_t(K) * d, s), "centroid copy");
     const bool pruned = use_matrix_cores(K) && use_pruning(K);
-    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, n, d, K, w, s), "norm ordering");
+    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, n, d, K, w, true, s), "norm ordering");
     for (int32_t t = 0; t < iters; ++t) {
         // only the matrix-core path can leave its codes in the workspace; the others write idx directly
         uint32_t* step_idx = pruned ? nullptr : idx;
@@ -177,7 +177,7 @@ int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroi
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
     CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
     const bool pruned = use_matrix_cores(K) && use_pruning(K);
-    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, uint32_t(N), d, K, w, s), "norm ordering");
+    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, uint32_t(N), d, K, w, false, s), "norm ordering");
     return run_assign(vectors, uint32_t(N), d, centroids, K, idx, inertia, w, pruned, s);
 }
 
@@ -195,7 +195,7 @@ int cc_lloyd_iter(const float* vectors, uint64_t N, uint32_t d, float* centroids
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
     CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
     const bool pruned = use_matrix_cores(K) && use_pruning(K);
-    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, uint32_t(N), d, K, w, s), "norm ordering");
+    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, uint32_t(N), d, K, w, false, s), "norm ordering");
     return run_lloyd_iter(vectors, uint32_t(N), d, centroids, K, idx, inertia, counts, w, pruned, s);
 }
 

@@ -143,7 +143,9 @@ hipError_t launch_assign_mfma_f16(const float* X, uint32_t N, uint32_t d, const 
 
 // Norm ordering (pruned E-step): vectors once per call, centroids + per-tile windows once per E-step,
 // and the codes back to input order afterwards.
-hipError_t launch_sort_vectors(const float* X, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, hipStream_t s);
+// drop_hint = true forgets the codes a previous call left in the workspace (a fit starts cold).
+hipError_t launch_sort_vectors(const float* X, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, bool drop_hint,
+                               hipStream_t s);
 hipError_t launch_sort_centroids_and_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w,
                                              hipStream_t s);
 hipError_t launch_unpermute(uint32_t N, uint32_t* idx, const Workspace& w, hipStream_t s);

@@ -234,8 +234,7 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
         s1 = a;
         if (s0 >= s1) { s0 = 0; s1 = real; }
     }
-    atomicAdd(&hdr->window_stages, static_cast<unsigned long long>(s1 - s0));
-    atomicAdd(&hdr->window_total, static_cast<unsigned long long>(real));
+    (void)hdr;
     win[blockIdx.x] = make_uint2(s0, s1);
 }
 
@@ -249,12 +248,29 @@ __global__ __launch_bounds__(kThreads) void unpermute_kernel(const uint32_t* __r
     if (p < n) idx[ids[p]] = idx_sorted[p];
 }
 
+// Sum of the window sizes of the last E-step (one block; statistics only).
+__global__ __launch_bounds__(1024) void window_stats_kernel(const uint2* __restrict__ win, uint32_t tiles, uint32_t K,
+                                                            WsHeader* hdr)
+{
+    __shared__ unsigned long long red[16];
+    unsigned long long s = 0;
+    for (uint32_t t = threadIdx.x; t < tiles; t += 1024) s += win[t].y - win[t].x;
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w) s += red[w];
+        hdr->window_stages += s;
+        hdr->window_total += static_cast<unsigned long long>(tiles) * ((K + 255) / 256);
+    }
+}
+
 // The hint survives between calls only for the same problem shape.
-__global__ void persist_check_kernel(WsPersist* persist, uint32_t N, uint32_t d, uint32_t K)
+__global__ void persist_check_kernel(WsPersist* persist, uint32_t N, uint32_t d, uint32_t K, int drop_hint)
 {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     constexpr unsigned long long kMagic = 0x636c7573636f6d70ull;  // "cluscomp"
-    if (persist->magic != kMagic || persist->N != N || persist->d != d || persist->K != K) {
+    if (drop_hint || persist->magic != kMagic || persist->N != N || persist->d != d || persist->K != K) {
         persist->magic = kMagic;
         persist->N = N;
         persist->d = d;
@@ -291,9 +307,10 @@ static void sort_vectors_t(const float* X, uint32_t N, const Workspace& w, hipSt
                        w.vperm, N, w.xsorted);
 }
 
-hipError_t launch_sort_vectors(const float* X, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, hipStream_t s)
+hipError_t launch_sort_vectors(const float* X, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, bool drop_hint,
+                               hipStream_t s)
 {
-    hipLaunchKernelGGL(persist_check_kernel, dim3(1), dim3(64), 0, s, w.persist, N, d, K);
+    hipLaunchKernelGGL(persist_check_kernel, dim3(1), dim3(64), 0, s, w.persist, N, d, K, drop_hint ? 1 : 0);
     switch (d) {
         case 4: sort_vectors_t<4>(X, N, w, s); break;
         case 8: sort_vectors_t<8>(X, N, w, s); break;
@@ -314,6 +331,7 @@ static void sort_centroids_t(const float* C, uint32_t N, uint32_t K, const Works
                        w.cperm, K, w.csorted);
     hipLaunchKernelGGL(window_kernel<D>, dim3((N + 511) / 512), dim3(kThreads), 0, s, w.xsorted, N, C, K, w.idx_sorted,
                        w.persist, w.ckeys, w.hdr, w.windows);
+    hipLaunchKernelGGL(window_stats_kernel, dim3(1), dim3(1024), 0, s, w.windows, (N + 511) / 512, K, w.hdr);
 }
 
 hipError_t launch_sort_centroids_and_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w,

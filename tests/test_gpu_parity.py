@@ -250,3 +250,41 @@ def test_zero_inertia_when_every_distinct_vector_is_a_centroid(g, mode):
     C, idx, J, _ = g.gpu_fit(X, pool, 3)
     assert J == 0.0
     assert np.array_equal(g.gpu_decode(C, idx), X)
+
+
+@pytest.mark.parametrize("N,d,K", [(60013, 4, 9000), (30007, 8, 8192), (25013, 16, 8300)])
+def test_pruned_estep_is_bit_identical_whatever_the_hint(g, N, d, K):
+    """The automatic mode visits only a norm window of the codebook, sized from the codes a previous call left in
+    the workspace. The hint may be fresh, stale or absent: the codes must be the same bits as without pruning."""
+    import paper_2503_13089_amd as cc
+
+    X, C0 = workloads.make_small(N, d, K, seed=8800 + N)
+    k0, _, _, _ = oracle.assign_top2(X, C0)
+    C1, _ = oracle.update(X, k0, C0)
+    rng = np.random.default_rng(1)
+    C2 = (C1 * rng.uniform(0.5, 1.5, size=(K, 1))).astype(np.float32)  # very different norms: a useless hint for C1
+    Xd = g.dev(X)
+    try:
+        cc.set_assign_mode(3)
+        ref_idx, ref_J = g.gpu_assign(Xd, C1)
+        cc.set_assign_mode(0)
+        ws = g.workspace(N, d, K)
+        fresh_idx, fresh_J = g.gpu_assign(Xd, C1, ws=ws)      # no hint yet: whole codebook
+        hinted_idx, hinted_J = g.gpu_assign(Xd, C1, ws=ws)    # hint = the exact codes: tightest windows
+        st = cc.read_stats(ws)
+        assert 0 < st.scored_stages <= st.total_stages
+        g.gpu_assign(Xd, C2, ws=ws)                           # leaves codes for another codebook behind
+        stale_idx, stale_J = g.gpu_assign(Xd, C1, ws=ws)      # stale hint
+        Xs = g.dev(X[::-1].copy())                            # other vectors on the same workspace: misaligned hint
+        g.gpu_assign(Xs, C2, ws=ws)
+        mis_idx, mis_J = g.gpu_assign(Xd, C1, ws=ws)
+    finally:
+        cc.set_assign_mode(0)
+    for name, idx, J in (("fresh", fresh_idx, fresh_J), ("hinted", hinted_idx, hinted_J), ("stale", stale_idx, stale_J),
+                         ("misaligned", mis_idx, mis_J)):
+        assert np.array_equal(idx, ref_idx), name
+        assert J == pytest.approx(ref_J, rel=1e-12), name  # same terms, summed in norm order instead of input order
+    k1, D1, _, D2 = oracle.assign_top2(X, C1)
+    parity.check_assignment(X, C1, ref_idx, k1, D1, D2)
+    if d == 4:
+        assert st.scored_stages < 0.9 * st.total_stages  # at 4 dimensions the windows really are narrower
