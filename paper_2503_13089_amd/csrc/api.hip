@@ -69,20 +69,41 @@ bool use_pruning(uint32_t K) { return g_assign_mode.load() == 0 && K >= 8192; }
 int run_assign_matrix(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
                       const cc::Workspace& w, bool accumulate, bool pruned, hipStream_t s)
 {
-    const float* Xe = pruned ? w.xsorted : X;
-    uint32_t* idxe = pruned ? w.idx_sorted : idx;
-    if (pruned) CC_TRY_HIP(cc::launch_sort_centroids_and_windows(C, N, d, K, w, s), "assign (norm windows)");
-    if (g_assign_mode.load() != 2) {
-        // both variants are enqueued; the device-side gate lets exactly one of them run
-        CC_TRY_HIP(cc::launch_assign_mfma_f16(Xe, N, d, C, K, idxe, w, cc::kGateIfF16, accumulate, pruned, s),
-                   "assign (fp16 matrix cores)");
-        CC_TRY_HIP(cc::launch_assign_mfma_f32(Xe, N, d, C, K, idxe, w, cc::kGateIfNotF16, accumulate, pruned, s),
-                   "assign (fp32 matrix cores)");
-    } else {
-        CC_TRY_HIP(cc::launch_assign_mfma_f32(Xe, N, d, C, K, idxe, w, cc::kGateAlways, accumulate, false, s),
-                   "assign (fp32 matrix cores)");
+    const bool both = g_assign_mode.load() != 2;  // fp16 and fp32 variants enqueued, the device gate picks one
+    cc::EStep e{};
+    e.X = pruned ? w.xsorted : X;
+    e.N = N;
+    e.idx = pruned ? w.idx_sorted : idx;
+    if (pruned) {
+        CC_TRY_HIP(cc::launch_sort_centroids(C, d, K, w, s), "assign (centroid norm order)");
+        // Bootstrap (only runs on the device when the workspace holds no hint): nearest among every 16th
+        // centroid of the norm order; its codes are only the upper bounds that size the windows below.
+        CC_TRY_HIP(cc::launch_subsample_centroids(d, K, w, s), "assign (bootstrap codebook)");
+        cc::EStep b = e;
+        b.pack_rows = w.csub; b.pack_perm = nullptr; b.rows = w.csub; b.row_ids = w.csub_ids; b.K = w.ksub;
+        b.packed = w.packed_sub; b.packed_tiles = w.packed_sub_tiles; b.windows = nullptr;
+        b.accumulate = false; b.hint_only = true;
+        b.gate = cc::kGateIfF16 | cc::kGateNoHint;
+        CC_TRY_HIP(cc::launch_assign_mfma_f16(b, d, w, s), "assign (bootstrap, fp16 matrix cores)");
+        b.gate = cc::kGateIfNotF16 | cc::kGateNoHint;
+        CC_TRY_HIP(cc::launch_assign_mfma_f32(b, d, w, s), "assign (bootstrap, fp32 matrix cores)");
+        CC_TRY_HIP(cc::launch_windows(C, N, d, K, w, true, s), "assign (norm windows)");
     }
-    CC_TRY_HIP(cc::launch_refine(Xe, N, d, C, K, idxe, w, accumulate, pruned, s), "assign (refinement)");
+    e.pack_rows = C; e.pack_perm = pruned ? w.cperm : nullptr;
+    e.rows = pruned ? w.csorted : C; e.row_ids = pruned ? w.cperm : nullptr;
+    e.K = K; e.packed = w.packed; e.packed_tiles = w.packed_tiles;
+    e.windows = pruned ? w.windows : nullptr;
+    e.accumulate = accumulate; e.hint_only = false;
+    if (both) {
+        e.gate = cc::kGateIfF16;
+        CC_TRY_HIP(cc::launch_assign_mfma_f16(e, d, w, s), "assign (fp16 matrix cores)");
+        e.gate = cc::kGateIfNotF16;
+        CC_TRY_HIP(cc::launch_assign_mfma_f32(e, d, w, s), "assign (fp32 matrix cores)");
+    } else {
+        e.gate = cc::kGateAlways;
+        CC_TRY_HIP(cc::launch_assign_mfma_f32(e, d, w, s), "assign (fp32 matrix cores)");
+    }
+    CC_TRY_HIP(cc::launch_refine(e.X, N, d, C, K, e.idx, w, accumulate, pruned, s), "assign (refinement)");
     return CC_OK;
 }
 

@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
                                                                unsigned long long* __restrict__ refine_best,
                                                                uint32_t refine_cap, int gate, long long* sums,
                                                                uint32_t* counts, const uint2* __restrict__ windows,
-                                                               const uint32_t* __restrict__ cperm)
+                                                               const uint32_t* __restrict__ cperm, int hint_only)
 {
     constexpr int KS = D / 2;                 // MFMA k-steps per tile
     if (!gate_open(hdr, gate)) return;        // uniform over the grid
@@ -218,6 +218,10 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
         const bool take = od < bd || (od == bd && ok < bk);
         const float dstar = take ? od : bd;
         const uint32_t kstar = take ? ok : bk;
+        if (hint_only) {  // bootstrap pass: the code is only an upper bound for the next pass's windows
+            if (h == 0 && i_raw < N) idx[i] = kstar;
+            continue;
+        }
         const float bstar = __builtin_fminf(best[vt], ob);
         const float sstar = __builtin_fminf(second[vt], os);
         float xn = 0.0f;
@@ -241,29 +245,28 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
 }
 
 template <int D, int VT, int ST>
-static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, const Workspace& w,
-                           int gate, bool accumulate, bool pruned, hipStream_t s)
+static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
 {
     constexpr int GT = int(kGroupTiles);
     constexpr uint32_t TF = 64 * (D / 2) + 32;
-    const size_t packed_floats = size_t(w.packed_tiles) * TF;
+    const size_t packed_floats = size_t(e.packed_tiles) * TF;
     hipLaunchKernelGGL(pack_codebook_kernel<D>, dim3(uint32_t((packed_floats + kThreads - 1) / kThreads)),
-                       dim3(kThreads), 0, s, C, K, w.packed_tiles, w.packed, w.hdr, gate, pruned ? w.cperm : nullptr);
+                       dim3(kThreads), 0, s, e.pack_rows, e.K, e.packed_tiles, static_cast<float*>(e.packed), w.hdr, e.gate,
+                       e.pack_perm);
     const uint32_t per_block = 4 * 32 * VT;
-    hipLaunchKernelGGL((assign_mfma_kernel<D, VT, ST, GT>), dim3((N + per_block - 1) / per_block), dim3(kThreads), 0, s,
-                       X, N, pruned ? w.csorted : C, K, w.packed, w.packed_tiles, idx, w.dmin, w.hdr, w.refine_list, w.refine_best,
-                       w.refine_cap, gate, accumulate ? w.sums : nullptr, accumulate ? w.counts : nullptr,
-                       pruned ? w.windows : nullptr, pruned ? w.cperm : nullptr);
+    hipLaunchKernelGGL((assign_mfma_kernel<D, VT, ST, GT>), dim3((e.N + per_block - 1) / per_block), dim3(kThreads), 0, s,
+                       e.X, e.N, e.rows, e.K, static_cast<const float*>(e.packed), e.packed_tiles, e.idx, w.dmin, w.hdr,
+                       w.refine_list, w.refine_best, w.refine_cap, e.gate, e.accumulate ? w.sums : nullptr,
+                       e.accumulate ? w.counts : nullptr, e.windows, e.row_ids, e.hint_only ? 1 : 0);
     return hipGetLastError();
 }
 
-hipError_t launch_assign_mfma_f32(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                                  const Workspace& w, int gate, bool accumulate, bool pruned, hipStream_t s)
+hipError_t launch_assign_mfma_f32(const EStep& e, uint32_t d, const Workspace& w, hipStream_t s)
 {
     switch (d) {
-        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, gate, accumulate, pruned, s);
-        case 8: return launch_t<8, 4, 8>(X, N, C, K, idx, w, gate, accumulate, pruned, s);
-        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, gate, accumulate, pruned, s);
+        case 4: return launch_t<4, 4, 8>(e, w, s);
+        case 8: return launch_t<8, 4, 8>(e, w, s);
+        case 16: return launch_t<16, 2, 4>(e, w, s);
         default: return hipErrorInvalidValue;
     }
 }

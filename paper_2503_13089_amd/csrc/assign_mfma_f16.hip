@@ -162,7 +162,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
     const float* __restrict__ X, uint32_t N, const float* __restrict__ C, uint32_t K, const char* __restrict__ packed,
     uint32_t ntiles, uint32_t* __restrict__ idx, float* __restrict__ dmin, WsHeader* hdr,
     uint32_t* __restrict__ refine_list, unsigned long long* __restrict__ refine_best, uint32_t refine_cap, int gate,
-    long long* sums, uint32_t* counts, const uint2* __restrict__ windows, const uint32_t* __restrict__ cperm)
+    long long* sums, uint32_t* counts, const uint2* __restrict__ windows, const uint32_t* __restrict__ cperm, int hint_only)
 {
     using S = F16Shape<D>;
     constexpr int KM = S::KM;
@@ -310,6 +310,10 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
         const bool take = od < bd || (od == bd && ok < bk);
         const float dstar = take ? od : bd;
         const uint32_t kstar = take ? ok : bk;
+        if (hint_only) {  // bootstrap pass: the code is only an upper bound for the next pass's windows
+            if (h == 0 && i_raw < N) idx[i] = kstar;
+            continue;
+        }
         const float bstar = __builtin_fminf(best[vt], ob);
         const float sstar = __builtin_fminf(second[vt], os);
         float xn = 0.0f, x1 = 0.0f;
@@ -339,31 +343,29 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
 }
 
 template <int D, int VT, int ST>
-static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, const Workspace& w,
-                           int gate, bool accumulate, bool pruned, hipStream_t s)
+static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
 {
     constexpr int GT = 4;  // tiles per tracking group: 64 centroids per lane are re-evaluated in the epilogue
-    const size_t n4 = size_t(K) * D / 4;
+    const size_t n4 = size_t(e.K) * D / 4;
     hipLaunchKernelGGL(codebook_absmax_kernel, dim3(uint32_t(std::min<size_t>((n4 + kThreads - 1) / kThreads, 64))),
-                       dim3(kThreads), 0, s, reinterpret_cast<const float4*>(C), n4, w.hdr, gate);
-    hipLaunchKernelGGL(pack_codebook_f16_kernel<D>, dim3((w.packed_tiles * 64 + kThreads - 1) / kThreads),
-                       dim3(kThreads), 0, s, C, K, w.packed_tiles, reinterpret_cast<char*>(w.packed), w.hdr, gate,
-                       pruned ? w.cperm : nullptr);
+                       dim3(kThreads), 0, s, reinterpret_cast<const float4*>(e.pack_rows), n4, w.hdr, e.gate);
+    hipLaunchKernelGGL(pack_codebook_f16_kernel<D>, dim3((e.packed_tiles * 64 + kThreads - 1) / kThreads),
+                       dim3(kThreads), 0, s, e.pack_rows, e.K, e.packed_tiles, static_cast<char*>(e.packed), w.hdr, e.gate,
+                       e.pack_perm);
     const uint32_t per_block = 4 * 32 * VT;
-    hipLaunchKernelGGL((assign_mfma_f16_kernel<D, VT, ST, GT>), dim3((N + per_block - 1) / per_block), dim3(kThreads),
-                       0, s, X, N, pruned ? w.csorted : C, K, reinterpret_cast<const char*>(w.packed), w.packed_tiles, idx, w.dmin, w.hdr,
-                       w.refine_list, w.refine_best, w.refine_cap, gate, accumulate ? w.sums : nullptr, accumulate ? w.counts : nullptr,
-                       pruned ? w.windows : nullptr, pruned ? w.cperm : nullptr);
+    hipLaunchKernelGGL((assign_mfma_f16_kernel<D, VT, ST, GT>), dim3((e.N + per_block - 1) / per_block), dim3(kThreads),
+                       0, s, e.X, e.N, e.rows, e.K, static_cast<const char*>(e.packed), e.packed_tiles, e.idx, w.dmin, w.hdr,
+                       w.refine_list, w.refine_best, w.refine_cap, e.gate, e.accumulate ? w.sums : nullptr,
+                       e.accumulate ? w.counts : nullptr, e.windows, e.row_ids, e.hint_only ? 1 : 0);
     return hipGetLastError();
 }
 
-hipError_t launch_assign_mfma_f16(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                                  const Workspace& w, int gate, bool accumulate, bool pruned, hipStream_t s)
+hipError_t launch_assign_mfma_f16(const EStep& e, uint32_t d, const Workspace& w, hipStream_t s)
 {
     switch (d) {
-        case 4: return launch_t<4, 4, 8>(X, N, C, K, idx, w, gate, accumulate, pruned, s);
-        case 8: return launch_t<8, 4, 4>(X, N, C, K, idx, w, gate, accumulate, pruned, s);
-        case 16: return launch_t<16, 2, 4>(X, N, C, K, idx, w, gate, accumulate, pruned, s);
+        case 4: return launch_t<4, 4, 8>(e, w, s);
+        case 8: return launch_t<8, 4, 4>(e, w, s);
+        case 16: return launch_t<16, 2, 4>(e, w, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -58,6 +58,10 @@ struct Workspace {
     uint16_t* ckeys_tmp;       // [K]
     uint32_t* sort_hist;       // [256 * sort blocks]
     uint2* windows;            // [ceil(N/512)] codebook stage range per 512-vector tile
+    float* csub;               // [Ksub*d] every kBootstrapStride-th centroid in norm order
+    uint32_t* csub_ids;        // [Ksub]   their centroid indices
+    void* packed_sub;          // operand tiles of that sub-codebook
+    uint32_t ksub, packed_sub_tiles;
     uint32_t refine_cap;
     uint32_t partial_slots;
     uint32_t packed_tiles;     // number of 32-centroid tiles in `packed` (K rounded up, padded)
@@ -67,6 +71,7 @@ struct Workspace {
 constexpr uint32_t kTileCentroids = 32;   // centroids per matrix-core tile
 constexpr uint32_t kGroupTiles = 2;       // tiles per tracking group of the matrix-core E-step
 constexpr uint32_t kStageTilesMax = 8;    // the packed codebook is padded to whole LDS stages of this many tiles
+constexpr uint32_t kBootstrapStride = 16; // the bootstrap hint pass scores every 16th centroid (in norm order)
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -107,6 +112,11 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     w.ckeys_tmp = reinterpret_cast<uint16_t*>(take(size_t(K) * 2));
     w.sort_hist = reinterpret_cast<uint32_t*>(take((size_t(N) / 4096 + 3) * 256 * 4));  // histogram + 256 totals
     w.windows = reinterpret_cast<uint2*>(take((size_t(N) / 512 + 1) * 8));
+    w.ksub = (K + kBootstrapStride - 1) / kBootstrapStride;
+    w.packed_sub_tiles = uint32_t((uint64_t(w.ksub) + stage - 1) / stage) * kStageTilesMax;
+    w.csub = reinterpret_cast<float*>(take(size_t(w.ksub) * d * 4));
+    w.csub_ids = reinterpret_cast<uint32_t*>(take(size_t(w.ksub) * 4));
+    w.packed_sub = take(size_t(w.packed_sub_tiles) * kTileCentroids * (6 * d + 16));
     w.bytes = off;
     return w;
 }
@@ -120,34 +130,55 @@ hipError_t launch_assign_direct(const float* X, uint32_t N, uint32_t d, const fl
                                 hipStream_t s);
 
 // Which inputs a gated kernel runs for (decided on the device from WsHeader::x_not_f16).
-enum Gate : int { kGateIfF16 = 0, kGateIfNotF16 = 1, kGateAlways = 2 };
+// kGateNoHint (a flag on top of the three) additionally requires that the workspace holds no usable hint.
+enum Gate : int { kGateIfF16 = 0, kGateIfNotF16 = 1, kGateAlways = 2, kGateNoHint = 4 };
 __device__ __forceinline__ bool gate_open(const WsHeader* hdr, int gate)
 {
-    return gate == kGateAlways || (gate == kGateIfF16) == (hdr->x_not_f16 == 0);
+    if (gate & kGateNoHint) {
+        // the persistent state sits in the second half of the header's 256-byte slot
+        const WsPersist* persist = reinterpret_cast<const WsPersist*>(reinterpret_cast<const char*>(hdr) + 128);
+        if (persist->hint_valid != 0) return false;
+    }
+    const int base = gate & 3;
+    return base == kGateAlways || (base == kGateIfF16) == (hdr->x_not_f16 == 0);
 }
+
+// One scoring pass of a matrix-core E-step kernel.
+struct EStep {
+    const float* X;             // vectors to score (input order, or the norm-ordered copy)
+    uint32_t N;
+    const float* pack_rows;     // centroid rows the packed codebook is built from ...
+    const uint32_t* pack_perm;  // ... through this position -> row map (NULL = identity)
+    const float* rows;          // centroid rows in packed order, for the direct-form index recovery ...
+    const uint32_t* row_ids;    // ... and the centroid index of each packed position (NULL = identity)
+    uint32_t K;                 // rows in this codebook
+    void* packed;               // operand tiles
+    uint32_t packed_tiles;
+    const uint2* windows;       // per 512-vector tile stage range (NULL = whole codebook)
+    uint32_t* idx;              // codes out
+    bool accumulate;            // also add every vector to the cluster sums/counts of its provisional code
+    bool hint_only;             // only write codes: no guard band, no distances, no refine list
+    int gate;
+};
 
 // Matrix-core E-step, fp32 MFMA: packs the codebook and runs the scoring kernel (provisional idx,
 // w.dmin and the refine list). Must be followed by launch_refine.
-// With accumulate = true the kernel also adds every vector into the cluster sums/counts of its
-// provisional code (the M-step accumulation, hidden under the scoring work). With pruned = true the
-// codebook is packed in norm order (w.cperm) and each workgroup scores only its window (w.windows).
-hipError_t launch_assign_mfma_f32(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K,
-                                  uint32_t* idx, const Workspace& w, int gate, bool accumulate, bool pruned,
-                                  hipStream_t s);
+hipError_t launch_assign_mfma_f32(const EStep& e, uint32_t d, const Workspace& w, hipStream_t s);
 
 // Matrix-core E-step for fp16-representable inputs: centroids split into three fp16 parts so that
 // every product is exact, scored with the fp16 MFMA. Same outputs as the fp32 variant.
-hipError_t launch_assign_mfma_f16(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K,
-                                  uint32_t* idx, const Workspace& w, int gate, bool accumulate, bool pruned,
-                                  hipStream_t s);
+hipError_t launch_assign_mfma_f16(const EStep& e, uint32_t d, const Workspace& w, hipStream_t s);
 
 // Norm ordering (pruned E-step): vectors once per call, centroids + per-tile windows once per E-step,
 // and the codes back to input order afterwards.
 // drop_hint = true forgets the codes a previous call left in the workspace (a fit starts cold).
 hipError_t launch_sort_vectors(const float* X, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, bool drop_hint,
                                hipStream_t s);
-hipError_t launch_sort_centroids_and_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w,
-                                             hipStream_t s);
+hipError_t launch_sort_centroids(const float* C, uint32_t d, uint32_t K, const Workspace& w, hipStream_t s);
+// Every kBootstrapStride-th centroid in norm order (rows + indices), for the bootstrap hint pass.
+hipError_t launch_subsample_centroids(uint32_t d, uint32_t K, const Workspace& w, hipStream_t s);
+hipError_t launch_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, bool assume_hint,
+                          hipStream_t s);
 hipError_t launch_unpermute(uint32_t N, uint32_t* idx, const Workspace& w, hipStream_t s);
 
 // Re-decides the listed guard-band vectors over all K centroids in direct form; if the list

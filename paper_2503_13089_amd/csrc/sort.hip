@@ -175,11 +175,11 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restrict__ Xs, uint32_t N,
                                                           const float* __restrict__ C, uint32_t K,
                                                           const uint32_t* __restrict__ hint, const WsPersist* persist,
-                                                          const uint16_t* __restrict__ ckeys, WsHeader* hdr,
+                                                          const uint16_t* __restrict__ ckeys, int assume_hint,
                                                           uint2* __restrict__ win)
 {
     __shared__ uint32_t red_lo[kThreads / 64], red_hi[kThreads / 64];
-    const bool have_hint = persist->hint_valid != 0;
+    const bool have_hint = assume_hint || persist->hint_valid != 0;
     uint32_t klo = 0xffffu, khi = 0;
     if (have_hint) {
 #pragma unroll
@@ -234,7 +234,6 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
         s1 = a;
         if (s0 >= s1) { s0 = 0; s1 = real; }
     }
-    (void)hdr;
     win[blockIdx.x] = make_uint2(s0, s1);
 }
 
@@ -320,8 +319,24 @@ hipError_t launch_sort_vectors(const float* X, uint32_t N, uint32_t d, uint32_t 
     return hipGetLastError();
 }
 
+// Every kBootstrapStride-th centroid of the norm order: rows and centroid indices (only when no hint exists).
 template <int D>
-static void sort_centroids_t(const float* C, uint32_t N, uint32_t K, const Workspace& w, hipStream_t s)
+__global__ __launch_bounds__(kThreads) void subsample_centroids_kernel(const float* __restrict__ csorted,
+                                                                       const uint32_t* __restrict__ cperm, uint32_t K,
+                                                                       uint32_t ksub, float* __restrict__ csub,
+                                                                       uint32_t* __restrict__ csub_ids,
+                                                                       const WsHeader* __restrict__ hdr)
+{
+    if (!gate_open(hdr, kGateAlways | kGateNoHint)) return;
+    const uint32_t p = blockIdx.x * kThreads + threadIdx.x;
+    if (p >= ksub) return;
+    const uint32_t src = min(p * kBootstrapStride, K - 1);
+    for (int j = 0; j < D; ++j) csub[size_t(p) * D + j] = csorted[size_t(src) * D + j];
+    csub_ids[p] = cperm[src];
+}
+
+template <int D>
+static void sort_centroids_t(const float* C, uint32_t K, const Workspace& w, hipStream_t s)
 {
     hipLaunchKernelGGL(centroid_keys_kernel<D>, dim3((K + kThreads - 1) / kThreads), dim3(kThreads), 0, s, C, K, w.ckeys,
                        w.cperm);
@@ -329,18 +344,46 @@ static void sort_centroids_t(const float* C, uint32_t N, uint32_t K, const Works
     const uint64_t pieces = uint64_t(K) * (D / 4);
     hipLaunchKernelGGL(gather_rows_kernel<D>, dim3(uint32_t((pieces + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, C,
                        w.cperm, K, w.csorted);
+}
+
+hipError_t launch_sort_centroids(const float* C, uint32_t d, uint32_t K, const Workspace& w, hipStream_t s)
+{
+    switch (d) {
+        case 4: sort_centroids_t<4>(C, K, w, s); break;
+        case 8: sort_centroids_t<8>(C, K, w, s); break;
+        case 16: sort_centroids_t<16>(C, K, w, s); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_subsample_centroids(uint32_t d, uint32_t K, const Workspace& w, hipStream_t s)
+{
+    const dim3 grid((w.ksub + kThreads - 1) / kThreads);
+    switch (d) {
+        case 4: hipLaunchKernelGGL(subsample_centroids_kernel<4>, grid, dim3(kThreads), 0, s, w.csorted, w.cperm, K, w.ksub, w.csub, w.csub_ids, w.hdr); break;
+        case 8: hipLaunchKernelGGL(subsample_centroids_kernel<8>, grid, dim3(kThreads), 0, s, w.csorted, w.cperm, K, w.ksub, w.csub, w.csub_ids, w.hdr); break;
+        case 16: hipLaunchKernelGGL(subsample_centroids_kernel<16>, grid, dim3(kThreads), 0, s, w.csorted, w.cperm, K, w.ksub, w.csub, w.csub_ids, w.hdr); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+template <int D>
+static void windows_t(const float* C, uint32_t N, uint32_t K, const Workspace& w, bool assume_hint, hipStream_t s)
+{
     hipLaunchKernelGGL(window_kernel<D>, dim3((N + 511) / 512), dim3(kThreads), 0, s, w.xsorted, N, C, K, w.idx_sorted,
-                       w.persist, w.ckeys, w.hdr, w.windows);
+                       w.persist, w.ckeys, assume_hint ? 1 : 0, w.windows);
     hipLaunchKernelGGL(window_stats_kernel, dim3(1), dim3(1024), 0, s, w.windows, (N + 511) / 512, K, w.hdr);
 }
 
-hipError_t launch_sort_centroids_and_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w,
-                                             hipStream_t s)
+hipError_t launch_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, bool assume_hint,
+                          hipStream_t s)
 {
     switch (d) {
-        case 4: sort_centroids_t<4>(C, N, K, w, s); break;
-        case 8: sort_centroids_t<8>(C, N, K, w, s); break;
-        case 16: sort_centroids_t<16>(C, N, K, w, s); break;
+        case 4: windows_t<4>(C, N, K, w, assume_hint, s); break;
+        case 8: windows_t<8>(C, N, K, w, assume_hint, s); break;
+        case 16: windows_t<16>(C, N, K, w, assume_hint, s); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
