@@ -84,7 +84,6 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
                                                                const float* __restrict__ packed, uint32_t ntiles,
                                                                uint32_t* __restrict__ idx, float* __restrict__ dmin,
                                                                WsHeader* hdr, uint32_t* __restrict__ refine_list,
-                                                               unsigned long long* __restrict__ refine_best,
                                                                uint32_t refine_cap, int gate, long long* sums,
                                                                uint32_t* counts, const uint2* __restrict__ windows,
                                                                const uint32_t* __restrict__ cperm, int hint_only)
@@ -208,13 +207,22 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
         const uint32_t i = min(i_raw, N - 1);
         float x[D];
         load_row<D>(X + size_t(i) * D, x);
-        float bd;
-        uint32_t bk;
-        recover_group<D, GT>(x, C, cperm, K, grp[vt], h, bd, bk);
-        const float od = __shfl_xor(bd, 32, 64);
-        const uint32_t ok = uint32_t(__shfl_xor(int(bk), 32, 64));
+        // The overall best group sits in one of the two lanes that share this vector; both lanes split its
+        // tiles. The other lane's best group, like every other group, only matters through `second`.
+        static_assert(GT % 2 == 0, "the two lanes of a vector split the tiles of the winning group");
         const float ob = __shfl_xor(best[vt], 32, 64);
         const float os = __shfl_xor(second[vt], 32, 64);
+        const uint32_t og = uint32_t(__shfl_xor(int(grp[vt]), 32, 64));
+        const bool mine = best[vt] < ob || (best[vt] == ob && h == 0);
+        const int wh = mine ? h : 1 - h;
+        const uint32_t wgrp = mine ? grp[vt] : og;
+        const float bstar = __builtin_fminf(best[vt], ob);
+        const float sstar = __builtin_fminf(__builtin_fminf(second[vt], os), __builtin_fmaxf(best[vt], ob));
+        float bd;
+        uint32_t bk;
+        recover_group<D, GT>(x, C, cperm, K, wgrp, wh, h * (GT / 2), (h + 1) * (GT / 2), bd, bk);
+        const float od = __shfl_xor(bd, 32, 64);
+        const uint32_t ok = uint32_t(__shfl_xor(int(bk), 32, 64));
         const bool take = od < bd || (od == bd && ok < bk);
         const float dstar = take ? od : bd;
         const uint32_t kstar = take ? ok : bk;
@@ -222,8 +230,6 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
             if (h == 0 && i_raw < N) idx[i] = kstar;
             continue;
         }
-        const float bstar = __builtin_fminf(best[vt], ob);
-        const float sstar = __builtin_fminf(second[vt], os);
         float xn = 0.0f;
 #pragma unroll
         for (int j = 0; j < D; ++j) xn = __builtin_fmaf(x[j], x[j], xn);
@@ -235,10 +241,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
             if (sums != nullptr) accumulate_vector<D>(x, kstar, sums, counts, fixed_point_exp(hdr->absmax_bits, N), +1);
             if (!safe) {
                 const uint32_t pos = atomicAdd(&hdr->refine_count, 1u);
-                if (pos < refine_cap) {
-                    refine_list[pos] = i;
-                    refine_best[pos] = ~0ull;
-                }
+                if (pos < refine_cap) refine_list[pos] = i;
             }
         }
     }
@@ -256,7 +259,7 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
     const uint32_t per_block = 4 * 32 * VT;
     hipLaunchKernelGGL((assign_mfma_kernel<D, VT, ST, GT>), dim3((e.N + per_block - 1) / per_block), dim3(kThreads), 0, s,
                        e.X, e.N, e.rows, e.K, static_cast<const float*>(e.packed), e.packed_tiles, e.idx, w.dmin, w.hdr,
-                       w.refine_list, w.refine_best, w.refine_cap, e.gate, e.accumulate ? w.sums : nullptr,
+                       w.refine_list, w.refine_cap, e.gate, e.accumulate ? w.sums : nullptr,
                        e.accumulate ? w.counts : nullptr, e.windows, e.row_ids, e.hint_only ? 1 : 0);
     return hipGetLastError();
 }

@@ -42,7 +42,6 @@ struct Workspace {
     float* dmin;               // [N]    ||x_i - c_idx_i||^2 of the last assign (fp32, direct form)
     float* packed;             // codebook re-laid out as matrix-core operand tiles (+ ||c||^2)
     uint32_t* refine_list;     // [refine_cap] ids of vectors to re-decide in direct form
-    unsigned long long* refine_best;  // [refine_cap] (distance bits << 32 | index), reduced with atomicMin
     // norm ordering for the pruned E-step
     WsPersist* persist;
     float* xsorted;            // [N*d]  the vectors in ascending-norm order
@@ -98,7 +97,6 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     w.packed = reinterpret_cast<float*>(take(size_t(w.packed_tiles) * kTileCentroids * (6 * d + 16)));
     w.refine_cap = uint32_t(N / 8 + 4096);
     w.refine_list = reinterpret_cast<uint32_t*>(take(size_t(w.refine_cap) * 4));
-    w.refine_best = reinterpret_cast<unsigned long long*>(take(size_t(w.refine_cap) * 8));
     w.xsorted = reinterpret_cast<float*>(take(size_t(N) * d * 4));
     w.idx_sorted = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vperm = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
@@ -185,9 +183,10 @@ hipError_t launch_unpermute(uint32_t N, uint32_t* idx, const Workspace& w, hipSt
 // overflowed, re-decides everything in direct form. With fix_sums = true the cluster sums/counts that
 // the scoring kernel accumulated are corrected for every vector whose code changed (or rebuilt from
 // scratch on overflow).
-// With mark_hint = true (norm-ordered run) the codes are flagged as a usable hint for the next call.
+// With norm_ordered = true (X = w.xsorted, idx = w.idx_sorted) only each vector's window is searched and
+// the codes are flagged as a usable hint for the next call.
 hipError_t launch_refine(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                         const Workspace& w, bool fix_sums, bool mark_hint, hipStream_t s);
+                         const Workspace& w, bool fix_sums, bool norm_ordered, hipStream_t s);
 
 // Scans the inputs: max |x| and whether every x is exactly representable in fp16.
 hipError_t launch_scan_inputs(const float* X, uint64_t n_floats, WsHeader* hdr, hipStream_t s);
@@ -261,20 +260,21 @@ __device__ __forceinline__ float direct_sqdist(const float (&x)[D], const float 
 template <int D>
 __device__ __forceinline__ void load_row(const float* __restrict__ p, float (&v)[D]);
 
-// Index recovery of the matrix-core E-step: direct-form argmin over the GT*16 codebook positions
-// 32*(group*GT+g) + 16*h + r that one lane's winning group covers. `rows` holds the centroids in packed
+// Index recovery of the matrix-core E-step: direct-form argmin over the codebook positions
+// 32*(group*GT+g) + 16*h + r, g in [g_begin, g_end), r in [0, 16), of a winning group (the two lanes that
+// share a vector split the group's tiles between them). `rows` holds the centroids in packed
 // order (the codebook itself, or its norm-ordered copy together with `cperm`, which maps a position
 // to the centroid index). Among exactly equal distances the lowest centroid index wins.
 // Rows are fetched U at a time so that U independent loads are in flight.
 template <int D, int GT>
 __device__ __forceinline__ void recover_group(const float (&x)[D], const float* __restrict__ rows,
                                               const uint32_t* __restrict__ cperm, uint32_t K, uint32_t group, int h,
-                                              float& best_d, uint32_t& best_k)
+                                              int g_begin, int g_end, float& best_d, uint32_t& best_k)
 {
     constexpr int U = D <= 8 ? 8 : 4;
     float bd = INFINITY;
     uint32_t bpos = 0;
-    for (int g = 0; g < GT; ++g) {
+    for (int g = g_begin; g < g_end; ++g) {
         const uint32_t k0 = 32 * (group * GT + g) + 16 * h;
 #pragma unroll
         for (int r0 = 0; r0 < 16; r0 += U) {
@@ -297,7 +297,7 @@ __device__ __forceinline__ void recover_group(const float (&x)[D], const float* 
         }
     }
     best_d = bd;
-    best_k = cperm != nullptr ? cperm[bpos] : bpos;
+    best_k = (cperm != nullptr && bd < INFINITY) ? cperm[min(bpos, K - 1)] : bpos;
 }
 
 template <int D>
