@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
     constexpr int STAGE_F4 = ST * TILE_F4;
     constexpr int NPF = (STAGE_F4 + kThreads - 1) / kThreads;
     static_assert(ST % GT == 0, "a tracking group must not straddle LDS stages");
-    static_assert(int(kStageTilesMax) % ST == 0, "the packed codebook is padded to whole stages");
+    static_assert(ST == int(kStageTiles), "window lists count runs in stages of kStageTiles tiles");
     if (!gate_open(hdr, gate)) return;  // uniform over the grid
     __shared__ float4 lds[2][STAGE_F4];
 
@@ -214,24 +214,34 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
     }
 
     const float4* P4 = reinterpret_cast<const float4*>(packed);
-    // stage range of this workgroup: everything, or the window of its 512-vector tile (in units of
-    // kStageTilesMax tiles, norm-ordered codebook)
-    uint32_t s_begin = 0, s_end = ntiles / ST;
-    if (windows != nullptr) {
-        const uint2 wdw = windows[(blockIdx.x * (4 * 32 * VT)) / 512];
-        s_begin = wdw.x * (kStageTilesMax / ST);
-        s_end = wdw.y * (kStageTilesMax / ST);
-    }
+    // Stages to score: the whole packed codebook, or the runs of this workgroup's 512-vector tile.
+    const uint2* wl = windows != nullptr ? windows + size_t((blockIdx.x * (4 * 32 * VT)) / 512) * kWinStride : nullptr;
+    const uint32_t nruns = wl != nullptr ? wl[0].x : 1u;
+    uint32_t run = 0;
+    uint2 cur_run = wl != nullptr ? wl[1] : make_uint2(0, ntiles / ST);
+    uint32_t s = cur_run.x;
+    int cur = 0;
 #pragma unroll
     for (int p = 0; p < NPF; ++p) {
         const uint32_t j = threadIdx.x + p * kThreads;
-        if (NPF * kThreads == STAGE_F4 || j < STAGE_F4) lds[s_begin & 1][j] = P4[size_t(s_begin) * STAGE_F4 + j];
+        if (NPF * kThreads == STAGE_F4 || j < STAGE_F4) lds[0][j] = P4[size_t(s) * STAGE_F4 + j];
     }
     __syncthreads();
 
-    for (uint32_t s = s_begin; s < s_end; ++s) {
-        const int cur = s & 1;
-        const uint32_t sn = min(s + 1, s_end - 1);  // the last iteration re-reads its own stage; never used
+    while (true) {
+        // the stage after this one: next in the run, or the first of the next run, or none
+        uint32_t sn = s + 1, run_n = run;
+        uint2 next_run = cur_run;
+        if (sn >= cur_run.y) {
+            run_n = run + 1;
+            if (run_n < nruns) {
+                next_run = wl[1 + run_n];
+                sn = next_run.x;
+            }
+        }
+        const bool has_next = run_n < nruns;
+        if (!has_next) sn = s;  // the last iteration re-reads its own stage; the copy is never used
+
         float4 pf[NPF];
 #pragma unroll
         for (int p = 0; p < NPF; ++p) {
@@ -289,6 +299,11 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
             if (NPF * kThreads == STAGE_F4 || j < STAGE_F4) lds[cur ^ 1][j] = pf[p];
         }
         __syncthreads();
+        if (!has_next) break;
+        s = sn;
+        run = run_n;
+        cur_run = next_run;
+        cur ^= 1;
     }
 
     // ---- epilogue: index recovery in direct form, merge of the two half-waves, guard-band test.
@@ -367,7 +382,7 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
 hipError_t launch_assign_mfma_f16(const EStep& e, uint32_t d, const Workspace& w, hipStream_t s)
 {
     switch (d) {
-        case 4: return launch_t<4, 4, 8>(e, w, s);
+        case 4: return launch_t<4, 4, 4>(e, w, s);
         case 8: return launch_t<8, 4, 4>(e, w, s);
         case 16: return launch_t<16, 2, 4>(e, w, s);
         default: return hipErrorInvalidValue;

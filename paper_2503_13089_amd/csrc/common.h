@@ -56,7 +56,7 @@ struct Workspace {
     uint16_t* ckeys;           // [K]
     uint16_t* ckeys_tmp;       // [K]
     uint32_t* sort_hist;       // [256 * sort blocks]
-    uint2* windows;            // [ceil(N/512)] codebook stage range per 512-vector tile
+    uint2* windows;            // [ceil(N/512)][kWinStride] window list (runs of codebook stages) per 512-vector tile
     float* csub;               // [Ksub*d] every kBootstrapStride-th centroid in norm order
     uint32_t* csub_ids;        // [Ksub]   their centroid indices
     void* packed_sub;          // operand tiles of that sub-codebook
@@ -71,6 +71,10 @@ constexpr uint32_t kTileCentroids = 32;   // centroids per matrix-core tile
 constexpr uint32_t kGroupTiles = 2;       // tiles per tracking group of the matrix-core E-step
 constexpr uint32_t kStageTilesMax = 8;    // the packed codebook is padded to whole LDS stages of this many tiles
 constexpr uint32_t kBootstrapStride = 16; // the bootstrap hint pass scores every 16th centroid (in norm order)
+constexpr uint32_t kStageTiles = 4;       // tiles per LDS stage of the matrix-core E-step kernels
+constexpr uint32_t kWinQuad = kStageTiles * kTileCentroids;  // window lists count runs in stages = 128 positions
+constexpr int kWinSlots = 32;             // most runs a window list can hold (one per norm shell)
+constexpr int kWinStride = kWinSlots + 1; // uint2 entries per 512-vector tile: (count, -), then the runs
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -109,7 +113,7 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     w.ckeys = reinterpret_cast<uint16_t*>(take(size_t(K) * 2));
     w.ckeys_tmp = reinterpret_cast<uint16_t*>(take(size_t(K) * 2));
     w.sort_hist = reinterpret_cast<uint32_t*>(take((size_t(N) / 4096 + 3) * 256 * 4));  // histogram + 256 totals
-    w.windows = reinterpret_cast<uint2*>(take((size_t(N) / 512 + 1) * 8));
+    w.windows = reinterpret_cast<uint2*>(take((size_t(N) / 512 + 1) * kWinStride * 8));
     w.ksub = (K + kBootstrapStride - 1) / kBootstrapStride;
     w.packed_sub_tiles = uint32_t((uint64_t(w.ksub) + stage - 1) / stage) * kStageTilesMax;
     w.csub = reinterpret_cast<float*>(take(size_t(w.ksub) * d * 4));
@@ -152,7 +156,7 @@ struct EStep {
     uint32_t K;                 // rows in this codebook
     void* packed;               // operand tiles
     uint32_t packed_tiles;
-    const uint2* windows;       // per 512-vector tile stage range (NULL = whole codebook)
+    const uint2* windows;       // per 512-vector tile window list (NULL = whole codebook)
     uint32_t* idx;              // codes out
     bool accumulate;            // also add every vector to the cluster sums/counts of its provisional code
     bool hint_only;             // only write codes: no guard band, no distances, no refine list

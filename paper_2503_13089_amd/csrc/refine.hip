@@ -39,19 +39,31 @@ __global__ __launch_bounds__(kThreads) void refine_kernel(const float* __restric
         const uint32_t i = refine_list[e];
         float x[D];
         load_row<D>(X + size_t(i) * D, x);
-        uint32_t lo = 0, hi = K;
-        if (windows != nullptr) {
-            const uint2 wdw = windows[i / 512];
-            lo = min(256u * wdw.x, K);
-            hi = min(256u * wdw.y, K);
-        }
+        const uint2* wl = windows != nullptr ? windows + size_t(i / 512) * kWinStride : nullptr;
+        const uint32_t nruns = wl != nullptr ? wl[0].x : 1u;
         unsigned long long best = ~0ull;
-        for (uint32_t pos = lo + lane; pos < hi; pos += 64) {
-            float c[D];
-            load_row<D>(rows + size_t(pos) * D, c);
-            const uint32_t k = row_ids != nullptr ? row_ids[pos] : pos;
-            const unsigned long long v = (static_cast<unsigned long long>(__float_as_uint(direct_sqdist<D>(x, c))) << 32) | k;
-            best = v < best ? v : best;
+        for (uint32_t r = 0; r < nruns; ++r) {
+            uint32_t lo = 0, hi = K;
+            if (wl != nullptr) {
+                lo = min(kWinQuad * wl[1 + r].x, K);
+                hi = min(kWinQuad * wl[1 + r].y, K);
+            }
+            for (uint32_t p0 = lo + lane; p0 < hi; p0 += 4 * 64) {  // four independent row loads in flight per lane
+                float c[4][D];
+                uint32_t k[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t pos = min(p0 + u * 64, hi - 1);
+                    load_row<D>(rows + size_t(pos) * D, c[u]);
+                    k[u] = row_ids != nullptr ? row_ids[pos] : pos;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const unsigned long long v =
+                        (static_cast<unsigned long long>(__float_as_uint(direct_sqdist<D>(x, c[u]))) << 32) | k[u];
+                    if (p0 + u * 64 < hi) best = v < best ? v : best;
+                }
+            }
         }
         for (int off = 32; off > 0; off >>= 1) {
             const unsigned long long o = __shfl_xor(best, off, 64);

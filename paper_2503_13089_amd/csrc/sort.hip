@@ -7,10 +7,16 @@
 // centroids ordered by norm this is a contiguous window of the codebook, and with the vectors ordered
 // by norm too, the 512 vectors a workgroup scores share almost the same window.
 //
-// This file holds the ordering machinery: 16-bit norm keys (the top half of the fp32 pattern of the
-// norm: monotone, 2^-7 relative resolution), a stable two-pass LSD radix sort of (key, id) pairs whose
-// output does not depend on scheduling, the row gather that builds the norm-ordered copy of the
-// vectors, the per-workgroup window computation, and the scatter of the codes back to input order.
+// A second necessary condition comes from any fixed unit direction e: |e.c - e.x| <= ||c - x|| <= u.
+// Both are folded into one 16-bit ordering key: 9 bits of norm shell (about 3 % wide, 511 shells below
+// the largest possible norm, open-ended at both ends) and 7 bits of the cosine between the vector and
+// e = (1,..,1)/sqrt(d). In that order the candidates of a vector are, per shell inside its norm band,
+// one contiguous run of cosine buckets; the 512 neighbouring vectors a workgroup scores need almost
+// the same runs.
+//
+// This file holds the ordering machinery: the keys, a stable two-pass LSD radix sort of (key, id)
+// pairs whose output does not depend on scheduling, the row gather that builds the ordered copy of
+// the vectors, the per-workgroup window lists, and the scatter of the codes back to input order.
 #include <algorithm>
 
 #include "common.h"
@@ -21,20 +27,61 @@ constexpr int kThreads = 256;
 constexpr int kSortThreads = 512;          // 8 waves
 constexpr uint32_t kSortChunk = 4096;      // elements per block and pass
 
+// 16-bit norm key: the top half of the fp32 pattern of a non-negative float (monotone, 2^-7 relative steps)
 __device__ __forceinline__ uint32_t norm_key(float norm) { return __float_as_uint(norm) >> 16; }
+
+// Shells: 4 norm keys each. `base` places shell 511 at the largest norm any vector can have; everything
+// 511 shells (16 octaves) or more below that shares shell 0, anything above shares shell 511.
+__device__ __forceinline__ uint32_t shell_base(uint32_t absmax_bits, int d)
+{
+    const float top = __uint_as_float(absmax_bits) * __builtin_sqrtf(float(d)) * 1.0001f;
+    const uint32_t tk = norm_key(top) >> 2;
+    return tk > 511u ? tk - 511u : 0u;
+}
+__device__ __forceinline__ uint32_t shell_of_key(uint32_t nkey, uint32_t base)
+{
+    const uint32_t s = nkey >> 2;
+    return s <= base ? 0u : min(s - base, 511u);
+}
+// every norm whose key falls in shell s lies in [shell_rlo, shell_rhi)
+__device__ __forceinline__ float shell_rlo(uint32_t s, uint32_t base)
+{
+    return s == 0 ? 0.0f : __uint_as_float(((s + base) << 2) << 16);
+}
+__device__ __forceinline__ float shell_rhi(uint32_t s, uint32_t base)
+{
+    return s >= 511u ? INFINITY : __uint_as_float(((s + base + 1) << 2) << 16);
+}
+__device__ __forceinline__ uint32_t cos_bucket(float t)
+{
+    const int q = int((t + 1.0f) * 64.0f);
+    return uint32_t(max(0, min(q, 127)));
+}
+// norm, projection on e = (1,..,1)/sqrt(d), and the ordering key of one row
+template <int D>
+__device__ __forceinline__ uint32_t ordering_key(const float (&x)[D], float norm, uint32_t base, float& proj)
+{
+    float sum = 0.0f;
+#pragma unroll
+    for (int j = 0; j < D; ++j) sum += x[j];
+    proj = sum * (D == 4 ? 0.5f : (D == 16 ? 0.25f : 0.35355339059327373f));
+    const float t = norm > 0.0f ? proj / norm : 0.0f;
+    return (shell_of_key(norm_key(norm), base) << 7) | cos_bucket(t);
+}
 
 template <int D>
 __global__ __launch_bounds__(kThreads) void vector_keys_kernel(const float* __restrict__ X, uint32_t N,
-                                                               uint16_t* __restrict__ keys, uint32_t* __restrict__ ids)
+                                                               uint16_t* __restrict__ keys, uint32_t* __restrict__ ids,
+                                                               const WsHeader* __restrict__ hdr)
 {
     const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
     if (i >= N) return;
     float x[D];
     load_row<D>(X + size_t(i) * D, x);
-    float s = 0.0f;
+    float s = 0.0f, proj;
 #pragma unroll
     for (int j = 0; j < D; ++j) s = __builtin_fmaf(x[j], x[j], s);
-    keys[i] = uint16_t(norm_key(__builtin_sqrtf(s)));
+    keys[i] = uint16_t(ordering_key<D>(x, __builtin_sqrtf(s), shell_base(hdr->absmax_bits, D), proj));
     ids[i] = i;
 }
 
@@ -153,88 +200,178 @@ __global__ __launch_bounds__(kThreads) void gather_rows_kernel(const float* __re
 
 template <int D>
 __global__ __launch_bounds__(kThreads) void centroid_keys_kernel(const float* __restrict__ C, uint32_t K,
-                                                                 uint16_t* __restrict__ keys, uint32_t* __restrict__ ids)
+                                                                 uint16_t* __restrict__ keys, uint32_t* __restrict__ ids,
+                                                                 const WsHeader* __restrict__ hdr)
 {
     const uint32_t k = blockIdx.x * kThreads + threadIdx.x;
     if (k >= K) return;
-    double s = 0.0;
-    for (int j = 0; j < D; ++j) {
-        const double c = double(C[size_t(k) * D + j]);
-        s += c * c;
-    }
-    keys[k] = uint16_t(norm_key(__builtin_sqrtf(float(s))));
+    float c[D];
+    load_row<D>(C + size_t(k) * D, c);
+    float s = 0.0f, proj;
+#pragma unroll
+    for (int j = 0; j < D; ++j) s = __builtin_fmaf(c[j], c[j], s);
+    keys[k] = uint16_t(ordering_key<D>(c, __builtin_sqrtf(s), shell_base(hdr->absmax_bits, D), proj));
     ids[k] = k;
 }
 
-// Window of codebook stages (256 norm-ordered centroids each) that the 512 norm-ordered vectors of one
-// workgroup tile have to score: every centroid whose norm key lies in [min_i key(||x_i|| - u_i) - 1,
-// max_i key(||x_i|| + u_i) + 1], u_i = the distance from x_i to its hinted centroid, slightly enlarged.
-// Keys are monotone in the norm and 2^-7 wide, so the +-1 key absorbs every rounding of the norms and of u.
-// Without a hint the window is the whole codebook.
+// Window list of one 512-vector tile: the runs of the ordered codebook (in units of kWinQuad = 128
+// positions) that can hold the nearest centroid of any of its vectors. For vector x with bound u (the
+// distance to its hinted centroid, slightly enlarged), a candidate c has its norm within u of ||x|| and
+// its projection e.c within u of e.x; per shell s inside that norm band the cosine e.c/||c|| is
+// therefore confined to [t_lo, t_hi] computed from the shell's radius range, i.e. to a run of ordering
+// keys (s, q_lo..q_hi). Norm keys are widened by one step (0.8 %) and cosine buckets by one (1/64) on
+// each side, far more than any rounding in the norms, projections and u. Runs of neighbouring shells
+// that touch are merged. If the band spans more than kWinSlots shells the list degrades to the single
+// run of all keys inside the norm band.
+// Layout per tile: entry 0 = (number of runs, unused), entries 1.. = (first quad, end quad).
 template <int D>
 __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restrict__ Xs, uint32_t N,
                                                           const float* __restrict__ C, uint32_t K,
                                                           const uint32_t* __restrict__ hint, const WsPersist* persist,
                                                           const uint16_t* __restrict__ ckeys, int assume_hint,
-                                                          uint2* __restrict__ win)
+                                                          const WsHeader* __restrict__ hdr, uint2* __restrict__ win)
 {
-    __shared__ uint32_t red_lo[kThreads / 64], red_hi[kThreads / 64];
+    __shared__ uint32_t s_min, s_max, q_lo[kWinSlots], q_hi[kWinSlots];
+    __shared__ uint2 runs[kWinSlots];
+    const uint32_t quads = (K + kWinQuad - 1) / kWinQuad;
+    uint2* out = win + size_t(blockIdx.x) * kWinStride;
     const bool have_hint = assume_hint || persist->hint_valid != 0;
-    uint32_t klo = 0xffffu, khi = 0;
-    if (have_hint) {
+    if (!have_hint) {
+        if (threadIdx.x == 0) {
+            out[0] = make_uint2(1, 0);
+            out[1] = make_uint2(0, quads);
+        }
+        return;
+    }
+    const uint32_t base = shell_base(hdr->absmax_bits, D);
+    if (threadIdx.x == 0) {
+        s_min = 511;
+        s_max = 0;
+    }
+    if (threadIdx.x < kWinSlots) {
+        q_lo[threadIdx.x] = 127;
+        q_hi[threadIdx.x] = 0;
+    }
+    __syncthreads();
+    // phase 1: per vector the bound, the norm band and its shells
+    float u[2], nrm[2], prj[2];
+    uint32_t sl[2], sh[2];
+    bool live[2];
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+        const uint32_t p = blockIdx.x * 512 + v * kThreads + threadIdx.x;
+        live[v] = p < N;
+        if (live[v]) {
+            float x[D], c[D];
+            load_row<D>(Xs + size_t(p) * D, x);
+            load_row<D>(C + size_t(min(hint[p], K - 1)) * D, c);
+            u[v] = __builtin_sqrtf(direct_sqdist<D>(x, c)) * 1.001f + 1e-30f;
+            float s = 0.0f;
+#pragma unroll
+            for (int j = 0; j < D; ++j) s = __builtin_fmaf(x[j], x[j], s);
+            nrm[v] = __builtin_sqrtf(s);
+            (void)ordering_key<D>(x, nrm[v], base, prj[v]);
+            const float lo = nrm[v] - u[v], hi = nrm[v] + u[v];
+            const uint32_t a = lo > 0.0f ? norm_key(lo) : 0u;
+            const uint32_t b = hi < 3.0e38f ? norm_key(hi) : 0xffffu;
+            sl[v] = shell_of_key(a > 0 ? a - 1 : 0u, base);
+            sh[v] = shell_of_key(min(b + 1, 0xffffu), base);
+            atomicMin(&s_min, sl[v]);
+            atomicMax(&s_max, sh[v]);
+        }
+    }
+    __syncthreads();
+    const uint32_t smin = s_min, smax = s_max;
+    const bool wide = smax - smin + 1 > uint32_t(kWinSlots);
+    // phase 2: per shell the union of the cosine runs
+    if (!wide) {
 #pragma unroll
         for (int v = 0; v < 2; ++v) {
-            const uint32_t p = blockIdx.x * 512 + v * kThreads + threadIdx.x;
-            if (p < N) {
-                float x[D], c[D];
-                load_row<D>(Xs + size_t(p) * D, x);
-                load_row<D>(C + size_t(min(hint[p], K - 1)) * D, c);
-                const float u = __builtin_sqrtf(direct_sqdist<D>(x, c)) * 1.001f + 1e-30f;
-                float s = 0.0f;
-#pragma unroll
-                for (int j = 0; j < D; ++j) s = __builtin_fmaf(x[j], x[j], s);
-                const float nrm = __builtin_sqrtf(s);
-                const float lo = nrm - u, hi = nrm + u;
-                const uint32_t a = lo > 0.0f ? norm_key(lo) : 0u;
-                const uint32_t b = hi < 3.0e38f ? norm_key(hi) : 0xffffu;
-                klo = min(klo, a > 0 ? a - 1 : 0u);
-                khi = max(khi, min(b + 1, 0xffffu));
+            if (!live[v]) continue;
+            const float plo = prj[v] - u[v], phi = prj[v] + u[v];
+            for (uint32_t s = sl[v]; s <= sh[v]; ++s) {
+                const float rlo = shell_rlo(s, base), rhi = shell_rhi(s, base);
+                float tlo, thi;
+                if (plo >= 0.0f) tlo = rhi < INFINITY ? plo / rhi : 0.0f; else tlo = rlo > 0.0f ? plo / rlo : -1.0f;
+                if (phi >= 0.0f) thi = rlo > 0.0f ? phi / rlo : 1.0f; else thi = rhi < INFINITY ? phi / rhi : 0.0f;
+                tlo = __builtin_fmaxf(tlo, -1.0f);
+                thi = __builtin_fminf(thi, 1.0f);
+                const uint32_t a = cos_bucket(tlo), b = cos_bucket(thi);
+                atomicMin(&q_lo[s - smin], a > 0 ? a - 1 : 0u);
+                atomicMax(&q_hi[s - smin], min(b + 1, 127u));
             }
         }
     }
-    for (int off = 32; off > 0; off >>= 1) {
-        klo = min(klo, uint32_t(__shfl_xor(int(klo), off, 64)));
-        khi = max(khi, uint32_t(__shfl_xor(int(khi), off, 64)));
-    }
-    if ((threadIdx.x & 63) == 0) {
-        red_lo[threadIdx.x >> 6] = klo;
-        red_hi[threadIdx.x >> 6] = khi;
+    __syncthreads();
+    // phase 3: key runs -> position runs (the ordered keys are ascending), in quads
+    const uint32_t nslots = wide ? 1 : smax - smin + 1;
+    if (threadIdx.x < nslots) {
+        uint32_t klo, khi;
+        if (wide) {
+            klo = smin << 7;
+            khi = (smax << 7) | 127u;
+        } else {
+            klo = ((smin + threadIdx.x) << 7) | q_lo[threadIdx.x];
+            khi = ((smin + threadIdx.x) << 7) | q_hi[threadIdx.x];
+        }
+        uint2 r = make_uint2(0, 0);
+        if (klo <= khi) {
+            uint32_t a = 0, b = K;  // first position with key >= klo
+            while (a < b) {
+                const uint32_t m = (a + b) / 2;
+                if (ckeys[m] >= klo) b = m; else a = m + 1;
+            }
+            const uint32_t first = a;
+            a = first, b = K;       // first position with key > khi
+            while (a < b) {
+                const uint32_t m = (a + b) / 2;
+                if (ckeys[m] > khi) b = m; else a = m + 1;
+            }
+            if (first < a) r = make_uint2(first / kWinQuad, (a + kWinQuad - 1) / kWinQuad);
+        }
+        runs[threadIdx.x] = r;
     }
     __syncthreads();
     if (threadIdx.x != 0) return;
-    for (int w = 1; w < kThreads / 64; ++w) {
-        klo = min(klo, red_lo[w]);
-        khi = max(khi, red_hi[w]);
-    }
-    // stage s holds norm-ordered positions [256 s, 256 s + 255]; stages past K hold padding only
-    const uint32_t real = (K + 255) / 256;
-    uint32_t s0 = 0, s1 = real;
-    if (have_hint && klo <= khi) {
-        uint32_t a = 0, b = real;  // first stage whose largest key >= klo
-        while (a < b) {
-            const uint32_t m = (a + b) / 2;
-            if (ckeys[min(256 * m + 255, K - 1)] >= klo) b = m; else a = m + 1;
+    uint32_t n = 0;
+    uint2 last = make_uint2(0, 0);
+    for (uint32_t t = 0; t < nslots; ++t) {
+        const uint2 r = runs[t];
+        if (r.x >= r.y) continue;
+        if (n > 0 && r.x <= last.y) {  // touches or overlaps the previous run (positions ascend with the shell)
+            last.y = max(last.y, r.y);
+            out[n] = last;
+        } else {
+            ++n;
+            last = r;
+            out[n] = last;
         }
-        s0 = a;
-        a = 0, b = real;           // first stage whose smallest key > khi
-        while (a < b) {
-            const uint32_t m = (a + b) / 2;
-            if (ckeys[256 * m] > khi) b = m; else a = m + 1;
-        }
-        s1 = a;
-        if (s0 >= s1) { s0 = 0; s1 = real; }
     }
-    win[blockIdx.x] = make_uint2(s0, s1);
+    if (n == 0) {  // cannot happen (the hinted centroid itself lies inside its own runs); stay safe
+        n = 1;
+        out[1] = make_uint2(0, quads);
+    }
+    out[0] = make_uint2(n, 0);
+}
+
+// Sum of the window sizes of the last E-step (one block; statistics only).
+__global__ __launch_bounds__(1024) void window_stats_kernel(const uint2* __restrict__ win, uint32_t tiles, uint32_t K,
+                                                            WsHeader* hdr)
+{
+    __shared__ unsigned long long red[16];
+    unsigned long long s = 0;
+    for (uint32_t t = threadIdx.x; t < tiles; t += 1024) {
+        const uint2* w = win + size_t(t) * kWinStride;
+        for (uint32_t r = 1; r <= w[0].x; ++r) s += w[r].y - w[r].x;
+    }
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w) s += red[w];
+        hdr->window_stages += s;
+        hdr->window_total += static_cast<unsigned long long>(tiles) * ((K + kWinQuad - 1) / kWinQuad);
+    }
 }
 
 // Codes back to input order: idx[ids[p]] = idx_sorted[p]; also records that the sorted codes are a usable hint.
@@ -245,23 +382,6 @@ __global__ __launch_bounds__(kThreads) void unpermute_kernel(const uint32_t* __r
     const uint32_t p = blockIdx.x * kThreads + threadIdx.x;
     if (p == 0) persist->hint_valid = 1;
     if (p < n) idx[ids[p]] = idx_sorted[p];
-}
-
-// Sum of the window sizes of the last E-step (one block; statistics only).
-__global__ __launch_bounds__(1024) void window_stats_kernel(const uint2* __restrict__ win, uint32_t tiles, uint32_t K,
-                                                            WsHeader* hdr)
-{
-    __shared__ unsigned long long red[16];
-    unsigned long long s = 0;
-    for (uint32_t t = threadIdx.x; t < tiles; t += 1024) s += win[t].y - win[t].x;
-    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int w = 1; w < 16; ++w) s += red[w];
-        hdr->window_stages += s;
-        hdr->window_total += static_cast<unsigned long long>(tiles) * ((K + 255) / 256);
-    }
 }
 
 // The hint survives between calls only for the same problem shape.
@@ -299,7 +419,7 @@ template <int D>
 static void sort_vectors_t(const float* X, uint32_t N, const Workspace& w, hipStream_t s)
 {
     hipLaunchKernelGGL(vector_keys_kernel<D>, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, s, X, N, w.vkeys,
-                       w.vperm);
+                       w.vperm, w.hdr);
     radix_sort16(w.vkeys, w.vperm, w.vkeys_tmp, w.vperm_tmp, N, w.sort_hist, s);
     const uint64_t pieces = uint64_t(N) * (D / 4);
     hipLaunchKernelGGL(gather_rows_kernel<D>, dim3(uint32_t((pieces + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, X,
@@ -339,7 +459,7 @@ template <int D>
 static void sort_centroids_t(const float* C, uint32_t K, const Workspace& w, hipStream_t s)
 {
     hipLaunchKernelGGL(centroid_keys_kernel<D>, dim3((K + kThreads - 1) / kThreads), dim3(kThreads), 0, s, C, K, w.ckeys,
-                       w.cperm);
+                       w.cperm, w.hdr);
     radix_sort16(w.ckeys, w.cperm, w.ckeys_tmp, w.cperm_tmp, K, w.sort_hist, s);
     const uint64_t pieces = uint64_t(K) * (D / 4);
     hipLaunchKernelGGL(gather_rows_kernel<D>, dim3(uint32_t((pieces + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, C,
@@ -373,7 +493,7 @@ template <int D>
 static void windows_t(const float* C, uint32_t N, uint32_t K, const Workspace& w, bool assume_hint, hipStream_t s)
 {
     hipLaunchKernelGGL(window_kernel<D>, dim3((N + 511) / 512), dim3(kThreads), 0, s, w.xsorted, N, C, K, w.idx_sorted,
-                       w.persist, w.ckeys, assume_hint ? 1 : 0, w.windows);
+                       w.persist, w.ckeys, assume_hint ? 1 : 0, w.hdr, w.windows);
     hipLaunchKernelGGL(window_stats_kernel, dim3(1), dim3(1024), 0, s, w.windows, (N + 511) / 512, K, w.hdr);
 }
 
