@@ -223,7 +223,7 @@ __global__ __launch_bounds__(kThreads) void centroid_keys_kernel(const float* __
 // each side, far more than any rounding in the norms, projections and u. Runs of neighbouring shells
 // that touch are merged. If the band spans more than kWinSlots shells the list degrades to the single
 // run of all keys inside the norm band.
-// Layout per tile: entry 0 = (number of runs, unused), entries 1.. = (first quad, end quad).
+// Layout per tile: entry 0 = (number of runs, their total length), entries 1.. = (first quad, end quad).
 template <int D>
 __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restrict__ Xs, uint32_t N,
                                                           const float* __restrict__ C, uint32_t K,
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
     const bool have_hint = assume_hint || persist->hint_valid != 0;
     if (!have_hint) {
         if (threadIdx.x == 0) {
-            out[0] = make_uint2(1, 0);
+            out[0] = make_uint2(1, quads);
             out[1] = make_uint2(0, quads);
         }
         return;
@@ -276,29 +276,63 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
             const uint32_t b = hi < 3.0e38f ? norm_key(hi) : 0xffffu;
             sl[v] = shell_of_key(a > 0 ? a - 1 : 0u, base);
             sh[v] = shell_of_key(min(b + 1, 0xffffu), base);
-            atomicMin(&s_min, sl[v]);
-            atomicMax(&s_max, sh[v]);
+        }
+    }
+    {
+        uint32_t lo = 511u, hi = 0u;
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+            if (live[v]) {
+                lo = min(lo, sl[v]);
+                hi = max(hi, sh[v]);
+            }
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            lo = min(lo, uint32_t(__shfl_xor(int(lo), off, 64)));
+            hi = max(hi, uint32_t(__shfl_xor(int(hi), off, 64)));
+        }
+        if ((threadIdx.x & 63) == 0 && lo <= hi) {
+            atomicMin(&s_min, lo);
+            atomicMax(&s_max, hi);
         }
     }
     __syncthreads();
     const uint32_t smin = s_min, smax = s_max;
     const bool wide = smax - smin + 1 > uint32_t(kWinSlots);
-    // phase 2: per shell the union of the cosine runs
+    // phase 2: per shell the union of the cosine runs. The lanes of a wave hold neighbouring vectors with
+    // almost the same shells, so each shell is first reduced across the wave with shuffles and only one lane
+    // touches the shared slot.
     if (!wide) {
+        const int lane = threadIdx.x & 63;
 #pragma unroll
         for (int v = 0; v < 2; ++v) {
-            if (!live[v]) continue;
+            uint32_t wlo = live[v] ? sl[v] : 511u, whi = live[v] ? sh[v] : 0u;
+            for (int off = 32; off > 0; off >>= 1) {
+                wlo = min(wlo, uint32_t(__shfl_xor(int(wlo), off, 64)));
+                whi = max(whi, uint32_t(__shfl_xor(int(whi), off, 64)));
+            }
             const float plo = prj[v] - u[v], phi = prj[v] + u[v];
-            for (uint32_t s = sl[v]; s <= sh[v]; ++s) {
-                const float rlo = shell_rlo(s, base), rhi = shell_rhi(s, base);
-                float tlo, thi;
-                if (plo >= 0.0f) tlo = rhi < INFINITY ? plo / rhi : 0.0f; else tlo = rlo > 0.0f ? plo / rlo : -1.0f;
-                if (phi >= 0.0f) thi = rlo > 0.0f ? phi / rlo : 1.0f; else thi = rhi < INFINITY ? phi / rhi : 0.0f;
-                tlo = __builtin_fmaxf(tlo, -1.0f);
-                thi = __builtin_fminf(thi, 1.0f);
-                const uint32_t a = cos_bucket(tlo), b = cos_bucket(thi);
-                atomicMin(&q_lo[s - smin], a > 0 ? a - 1 : 0u);
-                atomicMax(&q_hi[s - smin], min(b + 1, 127u));
+            for (uint32_t s = wlo; s <= whi; ++s) {  // wave-uniform trip count
+                uint32_t a = 127, b = 0;
+                if (live[v] && s >= sl[v] && s <= sh[v]) {
+                    const float rlo = shell_rlo(s, base), rhi = shell_rhi(s, base);
+                    float tlo, thi;
+                    if (plo >= 0.0f) tlo = rhi < INFINITY ? plo / rhi : 0.0f; else tlo = rlo > 0.0f ? plo / rlo : -1.0f;
+                    if (phi >= 0.0f) thi = rlo > 0.0f ? phi / rlo : 1.0f; else thi = rhi < INFINITY ? phi / rhi : 0.0f;
+                    tlo = __builtin_fmaxf(tlo, -1.0f);
+                    thi = __builtin_fminf(thi, 1.0f);
+                    const uint32_t qa = cos_bucket(tlo), qb = cos_bucket(thi);
+                    a = qa > 0 ? qa - 1 : 0u;
+                    b = min(qb + 1, 127u);
+                }
+                for (int off = 32; off > 0; off >>= 1) {
+                    a = min(a, uint32_t(__shfl_xor(int(a), off, 64)));
+                    b = max(b, uint32_t(__shfl_xor(int(b), off, 64)));
+                }
+                if (lane == 0 && a <= b) {
+                    atomicMin(&q_lo[s - smin], a);
+                    atomicMax(&q_hi[s - smin], b);
+                }
             }
         }
     }
@@ -351,7 +385,9 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
         n = 1;
         out[1] = make_uint2(0, quads);
     }
-    out[0] = make_uint2(n, 0);
+    uint32_t total = 0;
+    for (uint32_t r = 1; r <= n; ++r) total += out[r].y - out[r].x;
+    out[0] = make_uint2(n, total);
 }
 
 // Sum of the window sizes of the last E-step (one block; statistics only).
@@ -360,10 +396,7 @@ __global__ __launch_bounds__(1024) void window_stats_kernel(const uint2* __restr
 {
     __shared__ unsigned long long red[16];
     unsigned long long s = 0;
-    for (uint32_t t = threadIdx.x; t < tiles; t += 1024) {
-        const uint2* w = win + size_t(t) * kWinStride;
-        for (uint32_t r = 1; r <= w[0].x; ++r) s += w[r].y - w[r].x;
-    }
+    for (uint32_t t = threadIdx.x; t < tiles; t += 1024) s += win[size_t(t) * kWinStride].y;
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
     __syncthreads();
