@@ -48,6 +48,7 @@ struct Workspace {
     uint32_t* idx_sorted;      // [N]    codes in that order (also the next call's hint)
     uint32_t* vperm;           // [N]    input position of the p-th vector in norm order
     uint32_t* vperm_tmp;       // [N]
+    uint32_t* mperm;           // [N]    positions ordered by code (M-step by sorting)
     uint16_t* vkeys;           // [N]    norm keys (sorted after the sort)
     uint16_t* vkeys_tmp;       // [N]
     float* csorted;            // [K*d]  the centroids in ascending-norm order
@@ -105,6 +106,7 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     w.idx_sorted = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vperm = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vperm_tmp = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
+    w.mperm = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vkeys = reinterpret_cast<uint16_t*>(take(size_t(N) * 2));
     w.vkeys_tmp = reinterpret_cast<uint16_t*>(take(size_t(N) * 2));
     w.csorted = reinterpret_cast<float*>(take(size_t(K) * d * 4));
@@ -182,6 +184,11 @@ hipError_t launch_subsample_centroids(uint32_t d, uint32_t K, const Workspace& w
 hipError_t launch_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, bool assume_hint,
                           hipStream_t s);
 hipError_t launch_unpermute(uint32_t N, uint32_t* idx, const Workspace& w, hipStream_t s);
+
+// Cluster sums/counts without atomics (K <= 65536): codes are radix-sorted, one wave sums each run.
+// Overwrites w.sums / w.counts for every cluster; uses the vector-sort scratch buffers (not w.vperm).
+hipError_t launch_accumulate_sorted(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, uint32_t K,
+                                    const Workspace& w, hipStream_t s);
 
 // Re-decides the listed guard-band vectors over all K centroids in direct form; if the list
 // overflowed, re-decides everything in direct form. With fix_sums = true the cluster sums/counts that

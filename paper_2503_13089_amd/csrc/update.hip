@@ -178,10 +178,17 @@ hipError_t launch_finalize(const float* prev, float* out, uint32_t* counts_out, 
 hipError_t launch_update(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev, uint32_t K,
                          float* out, uint32_t* counts_out, const Workspace& w, hipStream_t s)
 {
-    hipError_t e = launch_zero_accumulators(w, K, d, nullptr, 0, s);
-    if (e != hipSuccess) return e;
-    e = launch_accumulate(X, N, d, idx, K, w, nullptr, 0, s);
-    if (e != hipSuccess) return e;
+    hipError_t e;
+    if (K <= 65536 && N >= 32768) {
+        // memory-side atomics are the bottleneck of the scatter formulation: sort by code and sum runs instead
+        e = launch_accumulate_sorted(X, N, d, idx, K, w, s);
+        if (e != hipSuccess) return e;
+    } else {
+        e = launch_zero_accumulators(w, K, d, nullptr, 0, s);
+        if (e != hipSuccess) return e;
+        e = launch_accumulate(X, N, d, idx, K, w, nullptr, 0, s);
+        if (e != hipSuccess) return e;
+    }
     return launch_finalize(prev, out, counts_out, K, d, N, w, s);
 }
 
