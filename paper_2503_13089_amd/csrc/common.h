@@ -56,6 +56,8 @@ struct Workspace {
     uint32_t* cperm_tmp;       // [K]
     uint16_t* ckeys;           // [K]
     uint16_t* ckeys_tmp;       // [K]
+    uint32_t* key_starts;      // [65537] first norm-ordered centroid position with ordering key >= v
+    uint32_t* code_starts;     // [K+1]   first position of each code in the code-sorted order
     uint32_t* sort_hist;       // [256 * sort blocks]
     uint2* windows;            // [ceil(N/512)][kWinStride] window list (runs of codebook stages) per 512-vector tile
     float* csub;               // [Ksub*d] every kBootstrapStride-th centroid in norm order
@@ -114,6 +116,8 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     w.cperm_tmp = reinterpret_cast<uint32_t*>(take(size_t(K) * 4));
     w.ckeys = reinterpret_cast<uint16_t*>(take(size_t(K) * 2));
     w.ckeys_tmp = reinterpret_cast<uint16_t*>(take(size_t(K) * 2));
+    w.key_starts = reinterpret_cast<uint32_t*>(take(size_t(65537) * 4));
+    w.code_starts = reinterpret_cast<uint32_t*>(take((size_t(K) + 1) * 4));
     w.sort_hist = reinterpret_cast<uint32_t*>(take((size_t(N) / 4096 + 3) * 256 * 4));  // histogram + 256 totals
     w.windows = reinterpret_cast<uint2*>(take((size_t(N) / 512 + 1) * kWinStride * 8));
     w.ksub = (K + kBootstrapStride - 1) / kBootstrapStride;

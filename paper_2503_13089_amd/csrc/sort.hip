@@ -214,6 +214,21 @@ __global__ __launch_bounds__(kThreads) void centroid_keys_kernel(const float* __
     ids[k] = k;
 }
 
+// starts[v] = first position of the ascending 16-bit keys that holds a key >= v, for v = 0 .. nvals
+// (starts[nvals] = n): turns "the run of keys in [a, b]" into two table reads.
+__global__ __launch_bounds__(kThreads) void key_starts_kernel(const uint16_t* __restrict__ sorted_keys, uint32_t n,
+                                                              uint32_t nvals, uint32_t* __restrict__ starts)
+{
+    const uint32_t v = blockIdx.x * kThreads + threadIdx.x;
+    if (v > nvals) return;
+    uint32_t a = 0, b = n;
+    while (a < b) {
+        const uint32_t m = (a + b) / 2;
+        if (sorted_keys[m] >= v) b = m; else a = m + 1;
+    }
+    starts[v] = a;
+}
+
 // Window list of one 512-vector tile: the runs of the ordered codebook (in units of kWinQuad = 128
 // positions) that can hold the nearest centroid of any of its vectors. For vector x with bound u (the
 // distance to its hinted centroid, slightly enlarged), a candidate c has its norm within u of ||x|| and
@@ -228,7 +243,7 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restrict__ Xs, uint32_t N,
                                                           const float* __restrict__ C, uint32_t K,
                                                           const uint32_t* __restrict__ hint, const WsPersist* persist,
-                                                          const uint16_t* __restrict__ ckeys, int assume_hint,
+                                                          const uint32_t* __restrict__ ckey_starts, int assume_hint,
                                                           const WsHeader* __restrict__ hdr, uint2* __restrict__ win)
 {
     __shared__ uint32_t s_min, s_max, q_lo[kWinSlots], q_hi[kWinSlots];
@@ -350,18 +365,8 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
         }
         uint2 r = make_uint2(0, 0);
         if (klo <= khi) {
-            uint32_t a = 0, b = K;  // first position with key >= klo
-            while (a < b) {
-                const uint32_t m = (a + b) / 2;
-                if (ckeys[m] >= klo) b = m; else a = m + 1;
-            }
-            const uint32_t first = a;
-            a = first, b = K;       // first position with key > khi
-            while (a < b) {
-                const uint32_t m = (a + b) / 2;
-                if (ckeys[m] > khi) b = m; else a = m + 1;
-            }
-            if (first < a) r = make_uint2(first / kWinQuad, (a + kWinQuad - 1) / kWinQuad);
+            const uint32_t first = ckey_starts[klo], end = ckey_starts[khi + 1];  // keys are ascending
+            if (first < end) r = make_uint2(first / kWinQuad, (end + kWinQuad - 1) / kWinQuad);
         }
         runs[threadIdx.x] = r;
     }
@@ -424,7 +429,7 @@ __global__ __launch_bounds__(kThreads) void code_keys_kernel(const uint32_t* __r
 template <int D>
 __global__ __launch_bounds__(kThreads) void segment_sum_kernel(const float* __restrict__ X, uint32_t N,
                                                                const uint32_t* __restrict__ idx,
-                                                               const uint16_t* __restrict__ sorted_codes,
+                                                               const uint32_t* __restrict__ code_starts,
                                                                const uint32_t* __restrict__ sorted_ids, uint32_t K,
                                                                long long* __restrict__ sums, uint32_t* __restrict__ counts,
                                                                WsHeader* hdr)
@@ -432,19 +437,7 @@ __global__ __launch_bounds__(kThreads) void segment_sum_kernel(const float* __re
     const int lane = threadIdx.x & 63;
     const uint32_t k = (blockIdx.x * kThreads + threadIdx.x) >> 6;  // one wave per cluster
     if (k >= K) return;
-    // the run of code k in the sorted codes: [lower_bound(k), lower_bound(k + 1))
-    uint32_t a = 0, b = N;
-    while (a < b) {
-        const uint32_t m = (a + b) / 2;
-        if (sorted_codes[m] >= k) b = m; else a = m + 1;
-    }
-    const uint32_t first = a;
-    b = N;
-    while (a < b) {
-        const uint32_t m = (a + b) / 2;
-        if (sorted_codes[m] > k) b = m; else a = m + 1;
-    }
-    const uint32_t last = a;
+    const uint32_t first = code_starts[k], last = code_starts[k + 1];  // the run of code k in the sorted codes
     const int e = fixed_point_exp(hdr->absmax_bits, N);
     long long acc[D];
 #pragma unroll
@@ -563,6 +556,8 @@ static void sort_centroids_t(const float* C, uint32_t K, const Workspace& w, hip
     hipLaunchKernelGGL(centroid_keys_kernel<D>, dim3((K + kThreads - 1) / kThreads), dim3(kThreads), 0, s, C, K, w.ckeys,
                        w.cperm, w.hdr);
     radix_sort16(w.ckeys, w.cperm, w.ckeys_tmp, w.cperm_tmp, K, w.sort_hist, s);
+    hipLaunchKernelGGL(key_starts_kernel, dim3((65536 + kThreads) / kThreads), dim3(kThreads), 0, s, w.ckeys, K, 65536u,
+                       w.key_starts);
     const uint64_t pieces = uint64_t(K) * (D / 4);
     hipLaunchKernelGGL(gather_rows_kernel<D>, dim3(uint32_t((pieces + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, C,
                        w.cperm, K, w.csorted);
@@ -595,7 +590,7 @@ template <int D>
 static void windows_t(const float* C, uint32_t N, uint32_t K, const Workspace& w, bool assume_hint, hipStream_t s)
 {
     hipLaunchKernelGGL(window_kernel<D>, dim3((N + 511) / 512), dim3(kThreads), 0, s, w.xsorted, N, C, K, w.idx_sorted,
-                       w.persist, w.ckeys, assume_hint ? 1 : 0, w.hdr, w.windows);
+                       w.persist, w.key_starts, assume_hint ? 1 : 0, w.hdr, w.windows);
     hipLaunchKernelGGL(window_stats_kernel, dim3(1), dim3(1024), 0, s, w.windows, (N + 511) / 512, K, w.hdr);
 }
 
@@ -617,11 +612,13 @@ hipError_t launch_accumulate_sorted(const float* X, uint32_t N, uint32_t d, cons
     hipLaunchKernelGGL(code_keys_kernel, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, s, idx, N, K, w.vkeys,
                        w.mperm);
     radix_sort16(w.vkeys, w.mperm, w.vkeys_tmp, w.vperm_tmp, N, w.sort_hist, s);
+    hipLaunchKernelGGL(key_starts_kernel, dim3((K + kThreads) / kThreads), dim3(kThreads), 0, s, w.vkeys, N, K,
+                       w.code_starts);
     const dim3 grid(uint32_t((uint64_t(K) * 64 + kThreads - 1) / kThreads));
     switch (d) {
-        case 4: hipLaunchKernelGGL(segment_sum_kernel<4>, grid, dim3(kThreads), 0, s, X, N, idx, w.vkeys, w.mperm, K, w.sums, w.counts, w.hdr); break;
-        case 8: hipLaunchKernelGGL(segment_sum_kernel<8>, grid, dim3(kThreads), 0, s, X, N, idx, w.vkeys, w.mperm, K, w.sums, w.counts, w.hdr); break;
-        case 16: hipLaunchKernelGGL(segment_sum_kernel<16>, grid, dim3(kThreads), 0, s, X, N, idx, w.vkeys, w.mperm, K, w.sums, w.counts, w.hdr); break;
+        case 4: hipLaunchKernelGGL(segment_sum_kernel<4>, grid, dim3(kThreads), 0, s, X, N, idx, w.code_starts, w.mperm, K, w.sums, w.counts, w.hdr); break;
+        case 8: hipLaunchKernelGGL(segment_sum_kernel<8>, grid, dim3(kThreads), 0, s, X, N, idx, w.code_starts, w.mperm, K, w.sums, w.counts, w.hdr); break;
+        case 16: hipLaunchKernelGGL(segment_sum_kernel<16>, grid, dim3(kThreads), 0, s, X, N, idx, w.code_starts, w.mperm, K, w.sums, w.counts, w.hdr); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
