@@ -136,7 +136,7 @@ int run_lloyd_iter(const float* X, uint32_t N, uint32_t d, float* C, uint32_t K,
         const bool by_sorting = pruned && K <= 65536;
         if (!by_sorting) CC_TRY_HIP(cc::launch_zero_accumulators(w, K, d, nullptr, 0, s), "update (clear)");
         if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, !by_sorting, pruned, s)) return rc;
-        if (by_sorting) CC_TRY_HIP(cc::launch_accumulate_sorted(w.xsorted, N, d, w.idx_sorted, K, w, s), "update (sums)");
+        if (by_sorting) CC_TRY_HIP(cc::launch_accumulate_sorted(w.xsorted, N, d, w.idx_sorted, K, w, true, s), "update (sums)");
         CC_TRY_HIP(cc::launch_finalize(C, C, counts, K, d, N, w, s), "update (means)");
         if (pruned && idx != nullptr) CC_TRY_HIP(cc::launch_unpermute(N, idx, w, s), "assign (codes to input order)");
     } else {

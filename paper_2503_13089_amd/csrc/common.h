@@ -191,8 +191,9 @@ hipError_t launch_unpermute(uint32_t N, uint32_t* idx, const Workspace& w, hipSt
 
 // Cluster sums/counts without atomics (K <= 65536): codes are radix-sorted, one wave sums each run.
 // Overwrites w.sums / w.counts for every cluster; uses the vector-sort scratch buffers (not w.vperm).
+// codes_trusted = true (codes written by the library's own E-step) skips the per-member range check.
 hipError_t launch_accumulate_sorted(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, uint32_t K,
-                                    const Workspace& w, hipStream_t s);
+                                    const Workspace& w, bool codes_trusted, hipStream_t s);
 
 // Re-decides the listed guard-band vectors over all K centroids in direct form; if the list
 // overflowed, re-decides everything in direct form. With fix_sums = true the cluster sums/counts that

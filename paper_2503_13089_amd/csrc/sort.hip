@@ -232,9 +232,9 @@ __global__ __launch_bounds__(kThreads) void key_starts_kernel(const uint16_t* __
 // Window list of one 512-vector tile: the runs of the ordered codebook (in units of kWinQuad = 128
 // positions) that can hold the nearest centroid of any of its vectors. For vector x with bound u (the
 // distance to its hinted centroid, slightly enlarged), a candidate c has its norm within u of ||x|| and
-// its projection e.c within u of e.x; per shell s inside that norm band the cosine e.c/||c|| is
-// therefore confined to [t_lo, t_hi] computed from the shell's radius range, i.e. to a run of ordering
-// keys (s, q_lo..q_hi). Norm keys are widened by one step (0.8 %) and cosine buckets by one (1/64) on
+// its projection e.c within u of e.x. The tile takes the hull of those bands over its 512 (neighbouring,
+// hence similar) vectors; per shell s inside the norm band the cosine e.c/||c|| is then confined to
+// [t_lo, t_hi] computed from the shell's radius range, i.e. to a run of ordering keys (s, q_lo..q_hi). Norm keys are widened by one step (0.8 %) and cosine buckets by one (1/64) on
 // each side, far more than any rounding in the norms, projections and u. Runs of neighbouring shells
 // that touch are merged. If the band spans more than kWinSlots shells the list degrades to the single
 // run of all keys inside the norm band.
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
                                                           const uint32_t* __restrict__ ckey_starts, int assume_hint,
                                                           const WsHeader* __restrict__ hdr, uint2* __restrict__ win)
 {
-    __shared__ uint32_t s_min, s_max, q_lo[kWinSlots], q_hi[kWinSlots];
+    __shared__ float red[4][kThreads / 64];
     __shared__ uint2 runs[kWinSlots];
     const uint32_t quads = (K + kWinQuad - 1) / kWinQuad;
     uint2* out = win + size_t(blockIdx.x) * kWinStride;
@@ -259,99 +259,53 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
         return;
     }
     const uint32_t base = shell_base(hdr->absmax_bits, D);
-    if (threadIdx.x == 0) {
-        s_min = 511;
-        s_max = 0;
-    }
-    if (threadIdx.x < kWinSlots) {
-        q_lo[threadIdx.x] = 127;
-        q_hi[threadIdx.x] = 0;
-    }
-    __syncthreads();
-    // phase 1: per vector the bound, the norm band and its shells
-    float u[2], nrm[2], prj[2];
-    uint32_t sl[2], sh[2];
-    bool live[2];
+    // phase 1: hull over the tile's vectors of the norm band [||x|| - u, ||x|| + u] and of the projection band
+    // [e.x - u, e.x + u] (the hull of a union of intervals contains the union, so this only ever adds candidates)
+    float nlo = INFINITY, nhi = 0.0f, plo = INFINITY, phi = -INFINITY;
 #pragma unroll
     for (int v = 0; v < 2; ++v) {
         const uint32_t p = blockIdx.x * 512 + v * kThreads + threadIdx.x;
-        live[v] = p < N;
-        if (live[v]) {
+        if (p < N) {
             float x[D], c[D];
             load_row<D>(Xs + size_t(p) * D, x);
             load_row<D>(C + size_t(min(hint[p], K - 1)) * D, c);
-            u[v] = __builtin_sqrtf(direct_sqdist<D>(x, c)) * 1.001f + 1e-30f;
-            float s = 0.0f;
+            const float u = __builtin_sqrtf(direct_sqdist<D>(x, c)) * 1.001f + 1e-30f;
+            float s = 0.0f, prj;
 #pragma unroll
             for (int j = 0; j < D; ++j) s = __builtin_fmaf(x[j], x[j], s);
-            nrm[v] = __builtin_sqrtf(s);
-            (void)ordering_key<D>(x, nrm[v], base, prj[v]);
-            const float lo = nrm[v] - u[v], hi = nrm[v] + u[v];
-            const uint32_t a = lo > 0.0f ? norm_key(lo) : 0u;
-            const uint32_t b = hi < 3.0e38f ? norm_key(hi) : 0xffffu;
-            sl[v] = shell_of_key(a > 0 ? a - 1 : 0u, base);
-            sh[v] = shell_of_key(min(b + 1, 0xffffu), base);
+            const float nrm = __builtin_sqrtf(s);
+            (void)ordering_key<D>(x, nrm, base, prj);
+            nlo = __builtin_fminf(nlo, nrm - u);
+            nhi = __builtin_fmaxf(nhi, nrm + u);
+            plo = __builtin_fminf(plo, prj - u);
+            phi = __builtin_fmaxf(phi, prj + u);
         }
     }
-    {
-        uint32_t lo = 511u, hi = 0u;
-#pragma unroll
-        for (int v = 0; v < 2; ++v) {
-            if (live[v]) {
-                lo = min(lo, sl[v]);
-                hi = max(hi, sh[v]);
-            }
-        }
-        for (int off = 32; off > 0; off >>= 1) {
-            lo = min(lo, uint32_t(__shfl_xor(int(lo), off, 64)));
-            hi = max(hi, uint32_t(__shfl_xor(int(hi), off, 64)));
-        }
-        if ((threadIdx.x & 63) == 0 && lo <= hi) {
-            atomicMin(&s_min, lo);
-            atomicMax(&s_max, hi);
-        }
+    for (int off = 32; off > 0; off >>= 1) {
+        nlo = __builtin_fminf(nlo, __shfl_xor(nlo, off, 64));
+        nhi = __builtin_fmaxf(nhi, __shfl_xor(nhi, off, 64));
+        plo = __builtin_fminf(plo, __shfl_xor(plo, off, 64));
+        phi = __builtin_fmaxf(phi, __shfl_xor(phi, off, 64));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        red[0][threadIdx.x >> 6] = nlo;
+        red[1][threadIdx.x >> 6] = nhi;
+        red[2][threadIdx.x >> 6] = plo;
+        red[3][threadIdx.x >> 6] = phi;
     }
     __syncthreads();
-    const uint32_t smin = s_min, smax = s_max;
+    for (int w = 0; w < kThreads / 64; ++w) {
+        nlo = __builtin_fminf(nlo, red[0][w]);
+        nhi = __builtin_fmaxf(nhi, red[1][w]);
+        plo = __builtin_fminf(plo, red[2][w]);
+        phi = __builtin_fmaxf(phi, red[3][w]);
+    }
+    // shells of the norm band, widened by one norm key (0.8 %) on each side
+    const uint32_t ka = nlo > 0.0f ? norm_key(nlo) : 0u;
+    const uint32_t kb = nhi < 3.0e38f ? norm_key(nhi) : 0xffffu;
+    const uint32_t smin = shell_of_key(ka > 0 ? ka - 1 : 0u, base);
+    const uint32_t smax = shell_of_key(min(kb + 1, 0xffffu), base);
     const bool wide = smax - smin + 1 > uint32_t(kWinSlots);
-    // phase 2: per shell the union of the cosine runs. The lanes of a wave hold neighbouring vectors with
-    // almost the same shells, so each shell is first reduced across the wave with shuffles and only one lane
-    // touches the shared slot.
-    if (!wide) {
-        const int lane = threadIdx.x & 63;
-#pragma unroll
-        for (int v = 0; v < 2; ++v) {
-            uint32_t wlo = live[v] ? sl[v] : 511u, whi = live[v] ? sh[v] : 0u;
-            for (int off = 32; off > 0; off >>= 1) {
-                wlo = min(wlo, uint32_t(__shfl_xor(int(wlo), off, 64)));
-                whi = max(whi, uint32_t(__shfl_xor(int(whi), off, 64)));
-            }
-            const float plo = prj[v] - u[v], phi = prj[v] + u[v];
-            for (uint32_t s = wlo; s <= whi; ++s) {  // wave-uniform trip count
-                uint32_t a = 127, b = 0;
-                if (live[v] && s >= sl[v] && s <= sh[v]) {
-                    const float rlo = shell_rlo(s, base), rhi = shell_rhi(s, base);
-                    float tlo, thi;
-                    if (plo >= 0.0f) tlo = rhi < INFINITY ? plo / rhi : 0.0f; else tlo = rlo > 0.0f ? plo / rlo : -1.0f;
-                    if (phi >= 0.0f) thi = rlo > 0.0f ? phi / rlo : 1.0f; else thi = rhi < INFINITY ? phi / rhi : 0.0f;
-                    tlo = __builtin_fmaxf(tlo, -1.0f);
-                    thi = __builtin_fminf(thi, 1.0f);
-                    const uint32_t qa = cos_bucket(tlo), qb = cos_bucket(thi);
-                    a = qa > 0 ? qa - 1 : 0u;
-                    b = min(qb + 1, 127u);
-                }
-                for (int off = 32; off > 0; off >>= 1) {
-                    a = min(a, uint32_t(__shfl_xor(int(a), off, 64)));
-                    b = max(b, uint32_t(__shfl_xor(int(b), off, 64)));
-                }
-                if (lane == 0 && a <= b) {
-                    atomicMin(&q_lo[s - smin], a);
-                    atomicMax(&q_hi[s - smin], b);
-                }
-            }
-        }
-    }
-    __syncthreads();
     // phase 3: key runs -> position runs (the ordered keys are ascending), in quads
     const uint32_t nslots = wide ? 1 : smax - smin + 1;
     if (threadIdx.x < nslots) {
@@ -360,8 +314,15 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
             klo = smin << 7;
             khi = (smax << 7) | 127u;
         } else {
-            klo = ((smin + threadIdx.x) << 7) | q_lo[threadIdx.x];
-            khi = ((smin + threadIdx.x) << 7) | q_hi[threadIdx.x];
+            // cosine e.c/||c|| of a candidate in shell s: e.c in [plo, phi], ||c|| in [rlo, rhi); one bucket of slack
+            const uint32_t sh = smin + threadIdx.x;
+            const float rlo = shell_rlo(sh, base), rhi = shell_rhi(sh, base);
+            float tlo, thi;
+            if (plo >= 0.0f) tlo = rhi < INFINITY ? plo / rhi : 0.0f; else tlo = rlo > 0.0f ? plo / rlo : -1.0f;
+            if (phi >= 0.0f) thi = rlo > 0.0f ? phi / rlo : 1.0f; else thi = rhi < INFINITY ? phi / rhi : 0.0f;
+            const uint32_t qa = cos_bucket(__builtin_fmaxf(tlo, -1.0f)), qb = cos_bucket(__builtin_fminf(thi, 1.0f));
+            klo = (sh << 7) | (qa > 0 ? qa - 1 : 0u);
+            khi = (sh << 7) | min(qb + 1, 127u);
         }
         uint2 r = make_uint2(0, 0);
         if (klo <= khi) {
@@ -426,7 +387,8 @@ __global__ __launch_bounds__(kThreads) void code_keys_kernel(const uint32_t* __r
     ids[i] = i;
 }
 
-template <int D>
+// CHECK = true re-reads each member's code and skips (and counts) those that were out of range.
+template <int D, bool CHECK>
 __global__ __launch_bounds__(kThreads) void segment_sum_kernel(const float* __restrict__ X, uint32_t N,
                                                                const uint32_t* __restrict__ idx,
                                                                const uint32_t* __restrict__ code_starts,
@@ -445,7 +407,7 @@ __global__ __launch_bounds__(kThreads) void segment_sum_kernel(const float* __re
     uint32_t n = 0, bad = 0;
     for (uint32_t j = first + lane; j < last; j += 64) {
         const uint32_t i = sorted_ids[j];
-        if (idx[i] == k) {
+        if (!CHECK || idx[i] == k) {
             float x[D];
             load_row<D>(X + size_t(i) * D, x);
 #pragma unroll
@@ -606,22 +568,29 @@ hipError_t launch_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, co
     return hipGetLastError();
 }
 
+template <bool CHECK>
+static hipError_t launch_segment_sum(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, uint32_t K,
+                                     const Workspace& w, hipStream_t s)
+{
+    const dim3 grid(uint32_t((uint64_t(K) * 64 + kThreads - 1) / kThreads));
+    switch (d) {
+        case 4: hipLaunchKernelGGL((segment_sum_kernel<4, CHECK>), grid, dim3(kThreads), 0, s, X, N, idx, w.code_starts, w.mperm, K, w.sums, w.counts, w.hdr); break;
+        case 8: hipLaunchKernelGGL((segment_sum_kernel<8, CHECK>), grid, dim3(kThreads), 0, s, X, N, idx, w.code_starts, w.mperm, K, w.sums, w.counts, w.hdr); break;
+        case 16: hipLaunchKernelGGL((segment_sum_kernel<16, CHECK>), grid, dim3(kThreads), 0, s, X, N, idx, w.code_starts, w.mperm, K, w.sums, w.counts, w.hdr); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_accumulate_sorted(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, uint32_t K,
-                                    const Workspace& w, hipStream_t s)
+                                    const Workspace& w, bool codes_trusted, hipStream_t s)
 {
     hipLaunchKernelGGL(code_keys_kernel, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, s, idx, N, K, w.vkeys,
                        w.mperm);
     radix_sort16(w.vkeys, w.mperm, w.vkeys_tmp, w.vperm_tmp, N, w.sort_hist, s);
     hipLaunchKernelGGL(key_starts_kernel, dim3((K + kThreads) / kThreads), dim3(kThreads), 0, s, w.vkeys, N, K,
                        w.code_starts);
-    const dim3 grid(uint32_t((uint64_t(K) * 64 + kThreads - 1) / kThreads));
-    switch (d) {
-        case 4: hipLaunchKernelGGL(segment_sum_kernel<4>, grid, dim3(kThreads), 0, s, X, N, idx, w.code_starts, w.mperm, K, w.sums, w.counts, w.hdr); break;
-        case 8: hipLaunchKernelGGL(segment_sum_kernel<8>, grid, dim3(kThreads), 0, s, X, N, idx, w.code_starts, w.mperm, K, w.sums, w.counts, w.hdr); break;
-        case 16: hipLaunchKernelGGL(segment_sum_kernel<16>, grid, dim3(kThreads), 0, s, X, N, idx, w.code_starts, w.mperm, K, w.sums, w.counts, w.hdr); break;
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
+    return codes_trusted ? launch_segment_sum<false>(X, N, d, idx, K, w, s) : launch_segment_sum<true>(X, N, d, idx, K, w, s);
 }
 
 hipError_t launch_unpermute(uint32_t N, uint32_t* idx, const Workspace& w, hipStream_t s)

@@ -181,7 +181,7 @@ hipError_t launch_update(const float* X, uint32_t N, uint32_t d, const uint32_t*
     hipError_t e;
     if (K <= 65536 && N >= 32768) {
         // memory-side atomics are the bottleneck of the scatter formulation: sort by code and sum runs instead
-        e = launch_accumulate_sorted(X, N, d, idx, K, w, s);
+        e = launch_accumulate_sorted(X, N, d, idx, K, w, false, s);
         if (e != hipSuccess) return e;
     } else {
         e = launch_zero_accumulators(w, K, d, nullptr, 0, s);
