@@ -218,8 +218,8 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
     const uint2* wl = windows != nullptr ? windows + size_t((blockIdx.x * (4 * 32 * VT)) / 512) * kWinStride : nullptr;
     const uint32_t nruns = wl != nullptr ? wl[0].x : 1u;
     uint32_t run = 0;
-    uint2 cur_run = wl != nullptr ? wl[1] : make_uint2(0, ntiles / ST);
-    uint32_t s = cur_run.x;
+    uint2 cur_run = wl != nullptr ? wl[1] : make_uint2(0, ntiles);  // [first tile, end tile)
+    uint32_t s = cur_run.x / ST;
     int cur = 0;
 #pragma unroll
     for (int p = 0; p < NPF; ++p) {
@@ -232,13 +232,16 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
         // the stage after this one: next in the run, or the first of the next run, or none
         uint32_t sn = s + 1, run_n = run;
         uint2 next_run = cur_run;
-        if (sn >= cur_run.y) {
+        if (sn * ST >= cur_run.y) {
             run_n = run + 1;
             if (run_n < nruns) {
                 next_run = wl[1 + run_n];
-                sn = next_run.x;
+                sn = next_run.x / ST;
             }
         }
+        // tiles of this stage that belong to the run
+        const uint32_t g_lo = cur_run.x > s * ST ? cur_run.x - s * ST : 0u;
+        const uint32_t g_hi = min(cur_run.y - s * ST, uint32_t(ST));
         const bool has_next = run_n < nruns;
         if (!has_next) sn = s;  // the last iteration re-reads its own stage; the copy is never used
 
@@ -257,6 +260,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
             for (int vt = 0; vt < VT; ++vt) m[vt] = INFINITY;
 #pragma unroll
             for (int g = 0; g < GT; ++g) {
+                if (tt + g < g_lo || tt + g >= g_hi) continue;  // wave-uniform: tile outside the run
                 const char* T = L + (tt + g) * S::kTileBytes;
                 f16x8 a[KM];
 #pragma unroll

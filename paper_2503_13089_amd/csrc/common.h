@@ -75,7 +75,7 @@ constexpr uint32_t kGroupTiles = 2;       // tiles per tracking group of the mat
 constexpr uint32_t kStageTilesMax = 8;    // the packed codebook is padded to whole LDS stages of this many tiles
 constexpr uint32_t kBootstrapStride = 16; // the bootstrap hint pass scores every 16th centroid (in norm order)
 constexpr uint32_t kStageTiles = 4;       // tiles per LDS stage of the matrix-core E-step kernels
-constexpr uint32_t kWinQuad = kStageTiles * kTileCentroids;  // window lists count runs in stages = 128 positions
+constexpr uint32_t kWinQuad = kTileCentroids;  // window lists count runs in tiles = 32 positions; runs never share a stage
 constexpr int kWinSlots = 32;             // most runs a window list can hold (one per norm shell)
 constexpr int kWinStride = kWinSlots + 1; // uint2 entries per 512-vector tile: (count, -), then the runs
 

@@ -229,8 +229,8 @@ __global__ __launch_bounds__(kThreads) void key_starts_kernel(const uint16_t* __
     starts[v] = a;
 }
 
-// Window list of one 512-vector tile: the runs of the ordered codebook (in units of kWinQuad = 128
-// positions) that can hold the nearest centroid of any of its vectors. For vector x with bound u (the
+// Window list of one 512-vector tile: the runs of the ordered codebook (in units of kWinQuad = 32
+// positions, one operand tile) that can hold the nearest centroid of any of its vectors. For vector x with bound u (the
 // distance to its hinted centroid, slightly enlarged), a candidate c has its norm within u of ||x|| and
 // its projection e.c within u of e.x. The tile takes the hull of those bands over its 512 (neighbouring,
 // hence similar) vectors; per shell s inside the norm band the cosine e.c/||c|| is then confined to
@@ -338,7 +338,9 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
     for (uint32_t t = 0; t < nslots; ++t) {
         const uint2 r = runs[t];
         if (r.x >= r.y) continue;
-        if (n > 0 && r.x <= last.y) {  // touches or overlaps the previous run (positions ascend with the shell)
+        // touches or overlaps the previous run, or starts in the stage where it ended (positions ascend with
+        // the shell): merge, so that no stage - and no tracking group - is ever visited twice
+        if (n > 0 && r.x / kStageTiles <= (last.y - 1) / kStageTiles) {
             last.y = max(last.y, r.y);
             out[n] = last;
         } else {
