@@ -66,8 +66,10 @@ bool use_pruning(uint32_t K) { return g_assign_mode.load() == 0 && K >= 8192; }
 // Scoring + refinement on the matrix cores. The input scan (WsHeader::x_not_f16) must have run on this
 // workspace since the last header reset; with pruned = true the vectors must have been norm-ordered
 // (launch_sort_vectors) and the codes are left in norm order in w.idx_sorted.
+// have_hint = true: the caller knows that this workspace holds the codes of a previous E-step of the same
+// call (later iterations of a fit), so the bootstrap pass need not even be enqueued.
 int run_assign_matrix(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                      const cc::Workspace& w, bool accumulate, bool pruned, hipStream_t s)
+                      const cc::Workspace& w, bool accumulate, bool pruned, bool have_hint, hipStream_t s)
 {
     const bool both = g_assign_mode.load() != 2;  // fp16 and fp32 variants enqueued, the device gate picks one
     cc::EStep e{};
@@ -78,15 +80,17 @@ int run_assign_matrix(const float* X, uint32_t N, uint32_t d, const float* C, ui
         CC_TRY_HIP(cc::launch_sort_centroids(C, d, K, w, s), "assign (centroid norm order)");
         // Bootstrap (only runs on the device when the workspace holds no hint): nearest among every 16th
         // centroid of the norm order; its codes are only the upper bounds that size the windows below.
-        CC_TRY_HIP(cc::launch_subsample_centroids(d, K, w, s), "assign (bootstrap codebook)");
-        cc::EStep b = e;
-        b.pack_rows = w.csub; b.pack_perm = nullptr; b.rows = w.csub; b.row_ids = w.csub_ids; b.K = w.ksub;
-        b.packed = w.packed_sub; b.packed_tiles = w.packed_sub_tiles; b.windows = nullptr;
-        b.accumulate = false; b.hint_only = true;
-        b.gate = cc::kGateIfF16 | cc::kGateNoHint;
-        CC_TRY_HIP(cc::launch_assign_mfma_f16(b, d, w, s), "assign (bootstrap, fp16 matrix cores)");
-        b.gate = cc::kGateIfNotF16 | cc::kGateNoHint;
-        CC_TRY_HIP(cc::launch_assign_mfma_f32(b, d, w, s), "assign (bootstrap, fp32 matrix cores)");
+        if (!have_hint) {
+            CC_TRY_HIP(cc::launch_subsample_centroids(d, K, w, s), "assign (bootstrap codebook)");
+            cc::EStep b = e;
+            b.pack_rows = w.csub; b.pack_perm = nullptr; b.rows = w.csub; b.row_ids = w.csub_ids; b.K = w.ksub;
+            b.packed = w.packed_sub; b.packed_tiles = w.packed_sub_tiles; b.windows = nullptr;
+            b.accumulate = false; b.hint_only = true;
+            b.gate = cc::kGateIfF16 | cc::kGateNoHint;
+            CC_TRY_HIP(cc::launch_assign_mfma_f16(b, d, w, s), "assign (bootstrap, fp16 matrix cores)");
+            b.gate = cc::kGateIfNotF16 | cc::kGateNoHint;
+            CC_TRY_HIP(cc::launch_assign_mfma_f32(b, d, w, s), "assign (bootstrap, fp32 matrix cores)");
+        }
         CC_TRY_HIP(cc::launch_windows(C, N, d, K, w, true, s), "assign (norm windows)");
     }
     e.pack_rows = C; e.pack_perm = pruned ? w.cperm : nullptr;
@@ -110,10 +114,10 @@ int run_assign_matrix(const float* X, uint32_t N, uint32_t d, const float* C, ui
 // One E-step pass: idx (and, if inertia != NULL, the objective) for the given centroids.
 // to_user = false leaves norm-ordered codes in the workspace only (intermediate fit iterations).
 int run_assign(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx, double* inertia,
-               const cc::Workspace& w, bool pruned, hipStream_t s)
+               const cc::Workspace& w, bool pruned, bool have_hint, hipStream_t s)
 {
     if (use_matrix_cores(K)) {
-        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, false, pruned, s)) return rc;
+        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, false, pruned, have_hint, s)) return rc;
         if (pruned) CC_TRY_HIP(cc::launch_unpermute(N, idx, w, s), "assign (codes to input order)");
     } else {
         CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s), "assign (direct form)");
@@ -128,14 +132,14 @@ int run_assign(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t 
 // the cluster sums are accumulated by the scoring kernel itself (no second pass over the vectors).
 // idx == NULL (only inside the fit loop, pruned path) skips the copy of the codes to input order.
 int run_lloyd_iter(const float* X, uint32_t N, uint32_t d, float* C, uint32_t K, uint32_t* idx, double* inertia,
-                   uint32_t* counts, const cc::Workspace& w, bool pruned, hipStream_t s)
+                   uint32_t* counts, const cc::Workspace& w, bool pruned, bool have_hint, hipStream_t s)
 {
     if (use_matrix_cores(K)) {
         // A pruned E-step is shorter than the atomic traffic of the fused accumulation (which then becomes the
         // bottleneck), so there the M-step sums come from sorting the codes instead.
         const bool by_sorting = pruned && K <= 65536;
         if (!by_sorting) CC_TRY_HIP(cc::launch_zero_accumulators(w, K, d, nullptr, 0, s), "update (clear)");
-        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, !by_sorting, pruned, s)) return rc;
+        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, !by_sorting, pruned, have_hint, s)) return rc;
         if (by_sorting) CC_TRY_HIP(cc::launch_accumulate_sorted(w.xsorted, N, d, w.idx_sorted, K, w, true, s), "update (sums)");
         CC_TRY_HIP(cc::launch_finalize(C, C, counts, K, d, N, w, s), "update (means)");
         if (pruned && idx != nullptr) CC_TRY_HIP(cc::launch_unpermute(N, idx, w, s), "assign (codes to input order)");
@@ -184,9 +188,10 @@ int cc_kmeans_fit(const float* vectors, uint64_t N, uint32_t d, uint32_t K, int3
     for (int32_t t = 0; t < iters; ++t) {
         // only the matrix-core path can leave its codes in the workspace; the others write idx directly
         uint32_t* step_idx = pruned ? nullptr : idx;
-        if (int rc = run_lloyd_iter(vectors, n, d, centroids, K, step_idx, nullptr, nullptr, w, pruned, s)) return rc;
+        if (int rc = run_lloyd_iter(vectors, n, d, centroids, K, step_idx, nullptr, nullptr, w, pruned, t > 0, s))
+            return rc;
     }
-    return run_assign(vectors, n, d, centroids, K, idx, inertia, w, pruned, s);
+    return run_assign(vectors, n, d, centroids, K, idx, inertia, w, pruned, iters > 0, s);
 }
 
 int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroids, uint32_t K, uint32_t* idx,
@@ -203,7 +208,7 @@ int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroi
     CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
     const bool pruned = use_matrix_cores(K) && use_pruning(K);
     if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, uint32_t(N), d, K, w, false, s), "norm ordering");
-    return run_assign(vectors, uint32_t(N), d, centroids, K, idx, inertia, w, pruned, s);
+    return run_assign(vectors, uint32_t(N), d, centroids, K, idx, inertia, w, pruned, false, s);
 }
 
 int cc_lloyd_iter(const float* vectors, uint64_t N, uint32_t d, float* centroids, uint32_t K, uint32_t* idx,
@@ -221,7 +226,7 @@ int cc_lloyd_iter(const float* vectors, uint64_t N, uint32_t d, float* centroids
     CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
     const bool pruned = use_matrix_cores(K) && use_pruning(K);
     if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, uint32_t(N), d, K, w, false, s), "norm ordering");
-    return run_lloyd_iter(vectors, uint32_t(N), d, centroids, K, idx, inertia, counts, w, pruned, s);
+    return run_lloyd_iter(vectors, uint32_t(N), d, centroids, K, idx, inertia, counts, w, pruned, false, s);
 }
 
 int cc_update(const float* vectors, uint64_t N, uint32_t d, const uint32_t* idx, const float* prev_centroids,

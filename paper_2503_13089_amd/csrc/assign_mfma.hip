@@ -78,7 +78,9 @@ __global__ __launch_bounds__(kThreads) void pack_codebook_kernel(const float* __
 }
 
 // ---------------------------------------------------------------------------------------------
-template <int D, int VT, int ST, int GT>
+// WINDOWED = false: the whole packed codebook in stages of ST tiles. WINDOWED = true: the runs of the
+// workgroup's window list (stages of kStageTiles tiles, tiles outside a run skipped).
+template <int D, int VT, int ST, int GT, bool WINDOWED>
 __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* __restrict__ X, uint32_t N,
                                                                const float* __restrict__ C, uint32_t K,
                                                                const float* __restrict__ packed, uint32_t ntiles,
@@ -94,7 +96,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
     constexpr int STAGE_F4 = ST * TF / 4;     // float4 per LDS stage
     constexpr int NPF = (STAGE_F4 + kThreads - 1) / kThreads;
     static_assert(ST % GT == 0, "a tracking group must not straddle LDS stages");
-    static_assert(ST == int(kStageTiles), "window lists count runs in stages of kStageTiles tiles");
+    static_assert(!WINDOWED || ST == int(kStageTiles), "window runs never share a stage of kStageTiles tiles");
     __shared__ float4 lds[2][STAGE_F4];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -121,10 +123,10 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
     // ntiles is a multiple of ST (padding rows carry ||c||^2 = +inf), so every stage is whole
     const float4* P4 = reinterpret_cast<const float4*>(packed);
     // Stages to score: the whole packed codebook, or the runs of this workgroup's 512-vector tile.
-    const uint2* wl = windows != nullptr ? windows + size_t((blockIdx.x * (4 * 32 * VT)) / 512) * kWinStride : nullptr;
-    const uint32_t nruns = wl != nullptr ? wl[0].x : 1u;
+    const uint2* wl = WINDOWED ? windows + size_t((blockIdx.x * (4 * 32 * VT)) / 512) * kWinStride : nullptr;
+    const uint32_t nruns = WINDOWED ? wl[0].x : 1u;
     uint32_t run = 0;
-    uint2 cur_run = wl != nullptr ? wl[1] : make_uint2(0, ntiles);  // [first tile, end tile)
+    uint2 cur_run = WINDOWED ? wl[1] : make_uint2(0, ntiles);  // [first tile, end tile)
     uint32_t s = cur_run.x / ST;
     int cur = 0;
 #pragma unroll
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
         uint2 next_run = cur_run;
         if (sn * ST >= cur_run.y) {
             run_n = run + 1;
-            if (run_n < nruns) {
+            if (WINDOWED && run_n < nruns) {
                 next_run = wl[1 + run_n];
                 sn = next_run.x / ST;
             }
@@ -167,7 +169,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
             for (int vt = 0; vt < VT; ++vt) m[vt] = INFINITY;
 #pragma unroll
             for (int g = 0; g < GT; ++g) {
-                if (tt + g < g_lo || tt + g >= g_hi) continue;  // wave-uniform: tile outside the run
+                if (WINDOWED && (tt + g < g_lo || tt + g >= g_hi)) continue;  // wave-uniform: tile outside the run
                 const float* T = L + (tt + g) * TF;
                 float a[KS];
                 if constexpr (KS == 2) {
@@ -275,7 +277,9 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
                        dim3(kThreads), 0, s, e.pack_rows, e.K, e.packed_tiles, static_cast<float*>(e.packed), w.hdr, e.gate,
                        e.pack_perm);
     const uint32_t per_block = 4 * 32 * VT;
-    hipLaunchKernelGGL((assign_mfma_kernel<D, VT, ST, GT>), dim3((e.N + per_block - 1) / per_block), dim3(kThreads), 0, s,
+    const auto kernel = e.windows != nullptr ? assign_mfma_kernel<D, VT, int(kStageTiles), GT, true>
+                                             : assign_mfma_kernel<D, VT, ST, GT, false>;
+    hipLaunchKernelGGL(kernel, dim3((e.N + per_block - 1) / per_block), dim3(kThreads), 0, s,
                        e.X, e.N, e.rows, e.K, static_cast<const float*>(e.packed), e.packed_tiles, e.idx, w.dmin, w.hdr,
                        w.refine_list, w.refine_cap, e.gate, e.accumulate ? w.sums : nullptr,
                        e.accumulate ? w.counts : nullptr, e.windows, e.row_ids, e.hint_only ? 1 : 0);
@@ -285,8 +289,8 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
 hipError_t launch_assign_mfma_f32(const EStep& e, uint32_t d, const Workspace& w, hipStream_t s)
 {
     switch (d) {
-        case 4: return launch_t<4, 4, 4>(e, w, s);
-        case 8: return launch_t<8, 4, 4>(e, w, s);
+        case 4: return launch_t<4, 4, 8>(e, w, s);
+        case 8: return launch_t<8, 4, 8>(e, w, s);
         case 16: return launch_t<16, 2, 4>(e, w, s);
         default: return hipErrorInvalidValue;
     }

@@ -358,20 +358,21 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
     out[0] = make_uint2(n, total);
 }
 
-// Sum of the window sizes of the last E-step (one block; statistics only).
+// Sum of the window sizes of the last E-step (statistics only).
 __global__ __launch_bounds__(1024) void window_stats_kernel(const uint2* __restrict__ win, uint32_t tiles, uint32_t K,
                                                             WsHeader* hdr)
 {
     __shared__ unsigned long long red[16];
     unsigned long long s = 0;
-    for (uint32_t t = threadIdx.x; t < tiles; t += 1024) s += win[size_t(t) * kWinStride].y;
+    for (uint32_t t = blockIdx.x * 1024 + threadIdx.x; t < tiles; t += gridDim.x * 1024) s += win[size_t(t) * kWinStride].y;
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int w = 1; w < 16; ++w) s += red[w];
-        hdr->window_stages += s;
-        hdr->window_total += static_cast<unsigned long long>(tiles) * ((K + kWinQuad - 1) / kWinQuad);
+        atomicAdd(&hdr->window_stages, s);
+        if (blockIdx.x == 0)
+            atomicAdd(&hdr->window_total, static_cast<unsigned long long>(tiles) * ((K + kWinQuad - 1) / kWinQuad));
     }
 }
 
@@ -555,7 +556,7 @@ static void windows_t(const float* C, uint32_t N, uint32_t K, const Workspace& w
 {
     hipLaunchKernelGGL(window_kernel<D>, dim3((N + 511) / 512), dim3(kThreads), 0, s, w.xsorted, N, C, K, w.idx_sorted,
                        w.persist, w.key_starts, assume_hint ? 1 : 0, w.hdr, w.windows);
-    hipLaunchKernelGGL(window_stats_kernel, dim3(1), dim3(1024), 0, s, w.windows, (N + 511) / 512, K, w.hdr);
+    hipLaunchKernelGGL(window_stats_kernel, dim3(32), dim3(1024), 0, s, w.windows, (N + 511) / 512, K, w.hdr);
 }
 
 hipError_t launch_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, bool assume_hint,
