@@ -52,8 +52,11 @@ typedef enum cc_status {
     CC_ERR_HIP = -6        /* the HIP runtime reported an error at launch */
 } cc_status;
 
-/* Host-only query: bytes of device workspace that cc_kmeans_fit / cc_assign / cc_update need for this
- * problem size. Returns 0 for an unsupported shape. */
+/* Host-only query: bytes of device workspace that cc_kmeans_fit / cc_assign / cc_lloyd_iter / cc_update
+ * need for this problem size (about 4*N*d + 26*N bytes: an ordered copy of the vectors, permutations
+ * and sort buffers). Returns 0 for an unsupported shape. The first 256 bytes keep a little state between
+ * calls (problem shape, "codes of the previous E-step are present"): a workspace that held something
+ * else in between is still safe to reuse - stale state can only make a call slower, not wrong. */
 size_t cc_workspace_bytes(uint64_t N, uint32_t d, uint32_t K);
 
 /*
@@ -117,8 +120,8 @@ typedef struct cc_stats {
                                   re-decided with direct-form distances (summed over all assigns) */
     uint64_t skipped_vectors;  /* vectors with idx >= K seen by an update */
     uint64_t assign_calls;     /* assign passes run */
-    uint64_t scored_stages;    /* norm-window pruning: codebook stages (256 centroids) scored, summed over
-                                  the 512-vector tiles of all assigns; 0 when pruning did not run */
+    uint64_t scored_stages;    /* window pruning: codebook tiles (32 centroids) scored, summed over the
+                                  512-vector tiles of all assigns; 0 when pruning did not run */
     uint64_t total_stages;     /* the same sum if every tile had scored the whole codebook */
     int32_t  fixed_point_exp;  /* e: cluster sums are held as round(x * 2^e) in int64 */
     uint32_t reserved;
@@ -128,10 +131,12 @@ int cc_read_stats(const void *workspace, size_t workspace_bytes, cc_stats *host_
 /* Selects the E-step kernel. 0 = automatic (default): for K >= 128 the matrix cores, with the fp16 MFMA
  * (centroids split into three fp16 parts, exact products) when every input is an fp16 number and
  * the fp32 MFMA otherwise, both with guard band + direct-form refinement; direct form for small K;
- * for K >= 8192 vectors and centroids are additionally visited in norm order and a workgroup skips
- * the part of the codebook that the triangle inequality rules out (an exact shortcut: a centroid
- * whose norm differs from a vector's by more than a known upper bound of its nearest distance
- * cannot be the nearest; the previous call's codes on the same workspace provide that bound).
+ * for K >= 8192 vectors and centroids are additionally visited in the order of a (norm, cosine to a
+ * fixed direction) key and a workgroup skips the parts of the codebook that the triangle inequality
+ * rules out (an exact shortcut: a centroid whose norm, or whose projection on the fixed direction,
+ * differs from a vector's by more than a known upper bound of its nearest distance cannot be the
+ * nearest; the previous call's codes on the same workspace - or a bootstrap pass over every 16th
+ * centroid - provide that bound, and a poor bound costs time, never correctness).
  * 1 = direct-form vector-ALU kernel only. 2 = fp32 MFMA kernel always, whole codebook.
  * 3 = as 0 but always the whole codebook. Process-wide; for tests and profiling.
  * Returns the previous value, or CC_ERR_SHAPE for an unknown mode. */
