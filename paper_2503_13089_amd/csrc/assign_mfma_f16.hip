@@ -17,9 +17,13 @@
 // MFMAs; d = 16: 48 slots in three MFMAs and sigma * ||c||^2 as the fp32 C operand instead).
 //
 // Guard band: measured on gfx950, the accumulated result differs from the exact sum by at most
-// ~3 * 2^-24 * (sum of |terms|); the band assumes kAccumUlps = 8 times that unit, plus the split
-// residual. A vector whose best and second-best group scores are closer than the band is re-decided
-// in direct form over all K (refine.hip), exactly as for the fp32 kernel.
+// ~3 * 2^-24 * (sum of |terms|), where the matrix core aligns a product by the exponent FIELDS of its
+// factors: an fp16 subnormal factor counts as 2^-14 however small it is, so a nonzero product a * b
+// weighs max(|a|, 2^-14) * max(|b|, 2^-14) in that sum (a subnormal norm part against the 2^8
+// multiplier costs an absolute 2^-6 * 2^-24, for instance). The band assumes kAccumUlps = 8 times
+// 2^-24 times that inflated sum, plus the split residual. A vector whose best and second-best group
+// scores are closer than the band is re-decided in direct form over all K (refine.hip), exactly as
+// for the fp32 kernel.
 #include <algorithm>
 
 #include "common.h"
@@ -350,9 +354,15 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
             xn = __builtin_fmaf(x[j], x[j], xn);
             x1 += __builtin_fabsf(x[j]);
         }
-        // accumulation rounding of winner + true nearest (||c||^2 <= 2||x||^2 + 2D for both), then the
-        // split residuals: 2^-25 per component against |2 x_j|, twice, and the norm residual
-        const float delta = sigma * kGuardSafety * 2.0f * kAccumUlps * kUnit * (5.0f * xn + 4.0f * dstar) +
+        // accumulation rounding of winner + true nearest (||c||^2 <= 2||x||^2 + 2D for both); what fp16
+        // subnormal factors add to the sum of |terms| (with a = 2^-14: each of the 3D product slots at most
+        // a |2 x_j| + a |part| + a^2, the parts of one centroid summing to <= 1.002 sigma ||c||_1, and the
+        // norm slots at most 2^-6 + 2^-17 + 2^-28); then the split residuals: 2^-25 per component against
+        // |2 x_j|, twice, and the norm residual
+        constexpr float kA = 6.103515625e-05f;  // 2^-14
+        const float inflation = 6.0f * kA * x1 + 1.002f * kA * sigma * __builtin_sqrtf(float(D) * (2.0f * xn + 2.0f * dstar)) +
+                                3.0f * float(D) * kA * kA + (S::kNormInK ? 0.015634f : 0.0f);
+        const float delta = kGuardSafety * 2.0f * kAccumUlps * kUnit * (sigma * (5.0f * xn + 4.0f * dstar) + inflation) +
                             kGuardSafety * (2.0f * kUnit * x1 + 1e-11f) + 1e-36f;
         const bool safe = (sstar - bstar) > delta;  // false for NaN as well
         if (h == 0 && i_raw < N) {

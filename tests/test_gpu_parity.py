@@ -288,3 +288,56 @@ def test_pruned_estep_is_bit_identical_whatever_the_hint(g, N, d, K):
     parity.check_assignment(X, C1, ref_idx, k1, D1, D2)
     if d == 4:
         assert st.scored_stages < 0.9 * st.total_stages  # at 4 dimensions the windows really are narrower
+
+
+def _awkward_vectors(N, d, rng):
+    """fp16-representable vectors built to stress the window logic: seven orders of magnitude in norm, exact zeros,
+    vectors along +-e = (1,..,1)/sqrt(d) (cosine +-1), duplicates, and one huge outlier."""
+    scale = 10.0 ** rng.uniform(-6, 0, size=(N, 1))
+    X = (rng.standard_normal((N, d)) * scale).astype(np.float16).astype(np.float32)
+    X[::97] = 0.0
+    X[5::101] = np.float32(0.03125)        # exactly along e
+    X[7::103] = np.float32(-0.0078125)     # exactly along -e
+    X[11::107] = X[3]                      # duplicates
+    X[13] = np.float32(2048.0)
+    return np.ascontiguousarray(X)
+
+
+@pytest.mark.parametrize("d,fp16", [(4, True), (8, True), (4, False)])
+def test_pruned_estep_on_awkward_data(g, d, fp16):
+    """Pruned (automatic) and unpruned runs must agree bit for bit, and with the oracle, on data with extreme norm
+    ranges, zero vectors, vectors exactly along the projection direction, duplicates and an outlier; with fp16 = False
+    the values are perturbed off the fp16 grid so that the fp32 MFMA variant runs under the same windows."""
+    import paper_2503_13089_amd as cc
+
+    rng = np.random.default_rng(31 + d)
+    N, K = 70003, 8704
+    X = _awkward_vectors(N, d, rng)
+    if not fp16:
+        X = (X * np.float32(1.0001)).astype(np.float32)
+    C0 = np.ascontiguousarray(X[rng.choice(N, K, replace=False)])
+    k0, _, _, _ = oracle.assign_top2(X, C0)
+    C1, _ = oracle.update(X, k0, C0)
+    Xd = g.dev(X)
+    try:
+        cc.set_assign_mode(3)
+        ref = {}
+        for name, C in (("init", C0), ("step", C1)):
+            ref[name] = g.gpu_assign(Xd, C)
+        cc.set_assign_mode(0)
+        ws = g.workspace(N, d, K)
+        for name, C in (("init", C0), ("step", C1), ("init", C0), ("step", C1), ("step", C1)):
+            idx, J = g.gpu_assign(Xd, C, ws=ws)
+            assert np.array_equal(idx, ref[name][0]), name
+            assert J == pytest.approx(ref[name][1], rel=1e-12)
+        # a whole fit: pruned (bootstrap, hints, M-step by sorting) against unpruned (fused atomics), bit for bit
+        Cp, ip, Jp, stp = g.gpu_fit(X, C0, 4, ws=ws, Xd=Xd)
+        cc.set_assign_mode(3)
+        Cu, iu, Ju, _ = g.gpu_fit(X, C0, 4, Xd=Xd)
+    finally:
+        cc.set_assign_mode(0)
+    assert Cp.tobytes() == Cu.tobytes() and np.array_equal(ip, iu) and Jp == pytest.approx(Ju, rel=1e-12)
+    assert 0 < stp.scored_stages <= stp.total_stages
+    for name, C in (("init", C0), ("step", C1)):
+        k1, D1, _, D2 = oracle.assign_top2(X, C)
+        parity.check_assignment(X, C, ref[name][0], k1, D1, D2)
