@@ -53,10 +53,11 @@ typedef enum cc_status {
 } cc_status;
 
 /* Host-only query: bytes of device workspace that cc_kmeans_fit / cc_assign / cc_lloyd_iter / cc_update
- * need for this problem size (about 4*N*d + 26*N bytes: an ordered copy of the vectors, permutations
- * and sort buffers). Returns 0 for an unsupported shape. The first 256 bytes keep a little state between
- * calls (problem shape, "codes of the previous E-step are present"): a workspace that held something
- * else in between is still safe to reuse - stale state can only make a call slower, not wrong. */
+ * need for this problem size (about 8*N*d + 38*N bytes: an ordered copy of the vectors, a copy grouped
+ * by cluster for the M-step, permutations and sort buffers). Returns 0 for an unsupported shape. The
+ * first 256 bytes keep a little state between calls (problem shape, "codes of the previous E-step are
+ * present"): a workspace that held something else in between is still safe to reuse - stale state can
+ * only make a call slower, not wrong. */
 size_t cc_workspace_bytes(uint64_t N, uint32_t d, uint32_t K);
 
 /*

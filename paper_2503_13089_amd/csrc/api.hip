@@ -136,12 +136,14 @@ int run_lloyd_iter(const float* X, uint32_t N, uint32_t d, float* C, uint32_t K,
 {
     if (use_matrix_cores(K)) {
         // A pruned E-step is shorter than the atomic traffic of the fused accumulation (which then becomes the
-        // bottleneck), so there the M-step sums come from sorting the codes instead.
-        const bool by_sorting = pruned && K <= 65536;
-        if (!by_sorting) CC_TRY_HIP(cc::launch_zero_accumulators(w, K, d, nullptr, 0, s), "update (clear)");
-        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, !by_sorting, pruned, have_hint, s)) return rc;
-        if (by_sorting) CC_TRY_HIP(cc::launch_accumulate_sorted(w.xsorted, N, d, w.idx_sorted, K, w, true, s), "update (sums)");
-        CC_TRY_HIP(cc::launch_finalize(C, C, counts, K, d, N, w, s), "update (means)");
+        // bottleneck), so there the M-step groups the vectors by bucket of clusters and sums in LDS instead.
+        const bool by_buckets = pruned && w.bucket_ok;
+        if (!by_buckets) CC_TRY_HIP(cc::launch_zero_accumulators(w, K, d, nullptr, 0, s), "update (clear)");
+        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, !by_buckets, pruned, have_hint, s)) return rc;
+        if (by_buckets)
+            CC_TRY_HIP(cc::launch_update_buckets(w.xsorted, N, d, w.idx_sorted, C, K, C, counts, w, true, s), "update (buckets)");
+        else
+            CC_TRY_HIP(cc::launch_finalize(C, C, counts, K, d, N, w, s), "update (means)");
         if (pruned && idx != nullptr) CC_TRY_HIP(cc::launch_unpermute(N, idx, w, s), "assign (codes to input order)");
     } else {
         CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s), "assign (direct form)");

@@ -48,21 +48,27 @@ struct Workspace {
     uint32_t* idx_sorted;      // [N]    codes in that order (also the next call's hint)
     uint32_t* vperm;           // [N]    input position of the p-th vector in norm order
     uint32_t* vperm_tmp;       // [N]
-    uint32_t* mperm;           // [N]    positions ordered by code (M-step by sorting)
     uint16_t* vkeys;           // [N]    norm keys (sorted after the sort)
     uint16_t* vkeys_tmp;       // [N]
     float* csorted;            // [K*d]  the centroids in ascending-norm order
     uint32_t* cperm;           // [K]    centroid index of the p-th centroid in norm order
     uint32_t* cperm_tmp;       // [K]
+    uint32_t* cinv;            // [K]    position of centroid k in norm order (inverse of cperm)
     uint16_t* ckeys;           // [K]
     uint16_t* ckeys_tmp;       // [K]
     uint32_t* key_starts;      // [65537] first norm-ordered centroid position with ordering key >= v
-    uint32_t* code_starts;     // [K+1]   first position of each code in the code-sorted order
     uint32_t* sort_hist;       // [256 * sort blocks]
     uint2* windows;            // [ceil(N/512)][kWinStride] window list (runs of codebook stages) per 512-vector tile
     float* csub;               // [Ksub*d] every kBootstrapStride-th centroid in norm order
     uint32_t* csub_ids;        // [Ksub]   their centroid indices
     void* packed_sub;          // operand tiles of that sub-codebook
+    // M-step by buckets (K <= kMaxBuckets * kBucketClusters)
+    char* records;             // [N] x (4d + 16) bytes: the vectors, each with its code, grouped by bucket
+    uint32_t* bucket_hist;     // [blocks][buckets] members of each bucket in each block of kBucketChunk vectors
+    uint32_t* bucket_gtot;     // [groups of kBucketGroup blocks][buckets]
+    uint32_t* bucket_totals;   // [buckets]
+    uint32_t* bucket_base;     // [buckets + 1] first record of each bucket
+    bool bucket_ok;
     uint32_t ksub, packed_sub_tiles;
     uint32_t refine_cap;
     uint32_t partial_slots;
@@ -78,6 +84,10 @@ constexpr uint32_t kStageTiles = 4;       // tiles per LDS stage of the matrix-c
 constexpr uint32_t kWinQuad = kTileCentroids;  // window lists count runs in tiles = 32 positions; runs never share a stage
 constexpr int kWinSlots = 32;             // most runs a window list can hold (one per norm shell)
 constexpr int kWinStride = kWinSlots + 1; // uint2 entries per 512-vector tile: (count, -), then the runs
+constexpr uint32_t kBucketClusters = 64;  // M-step by buckets: consecutive clusters summed by one workgroup
+constexpr uint32_t kMaxBuckets = 1024;    // so K <= 65536 for that path
+constexpr uint32_t kBucketGroup = 64;     // blocks per group in the two-level scan of the bucket histogram
+constexpr uint32_t kBucketChunk = 4096;   // vectors per workgroup in its counting and scatter passes
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -108,16 +118,15 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     w.idx_sorted = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vperm = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vperm_tmp = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
-    w.mperm = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vkeys = reinterpret_cast<uint16_t*>(take(size_t(N) * 2));
     w.vkeys_tmp = reinterpret_cast<uint16_t*>(take(size_t(N) * 2));
     w.csorted = reinterpret_cast<float*>(take(size_t(K) * d * 4));
     w.cperm = reinterpret_cast<uint32_t*>(take(size_t(K) * 4));
     w.cperm_tmp = reinterpret_cast<uint32_t*>(take(size_t(K) * 4));
+    w.cinv = reinterpret_cast<uint32_t*>(take(size_t(K) * 4));
     w.ckeys = reinterpret_cast<uint16_t*>(take(size_t(K) * 2));
     w.ckeys_tmp = reinterpret_cast<uint16_t*>(take(size_t(K) * 2));
     w.key_starts = reinterpret_cast<uint32_t*>(take(size_t(65537) * 4));
-    w.code_starts = reinterpret_cast<uint32_t*>(take((size_t(K) + 1) * 4));
     w.sort_hist = reinterpret_cast<uint32_t*>(take((size_t(N) / 4096 + 3) * 256 * 4));  // histogram + 256 totals
     w.windows = reinterpret_cast<uint2*>(take((size_t(N) / 512 + 1) * kWinStride * 8));
     w.ksub = (K + kBootstrapStride - 1) / kBootstrapStride;
@@ -125,6 +134,15 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     w.csub = reinterpret_cast<float*>(take(size_t(w.ksub) * d * 4));
     w.csub_ids = reinterpret_cast<uint32_t*>(take(size_t(w.ksub) * 4));
     w.packed_sub = take(size_t(w.packed_sub_tiles) * kTileCentroids * (6 * d + 16));
+    w.bucket_ok = K <= kMaxBuckets * kBucketClusters;
+    if (w.bucket_ok) {
+        const size_t buckets = (size_t(K) + kBucketClusters - 1) / kBucketClusters;
+        w.records = take(size_t(N) * (4 * d + 16));
+        w.bucket_hist = reinterpret_cast<uint32_t*>(take(buckets * (size_t(N) / kBucketChunk + 1) * 4));
+        w.bucket_gtot = reinterpret_cast<uint32_t*>(take(buckets * (size_t(N) / kBucketChunk / kBucketGroup + 1) * 4));
+        w.bucket_totals = reinterpret_cast<uint32_t*>(take(buckets * 4));
+        w.bucket_base = reinterpret_cast<uint32_t*>(take((buckets + 1) * 4));
+    }
     w.bytes = off;
     return w;
 }
@@ -189,12 +207,6 @@ hipError_t launch_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, co
                           hipStream_t s);
 hipError_t launch_unpermute(uint32_t N, uint32_t* idx, const Workspace& w, hipStream_t s);
 
-// Cluster sums/counts without atomics (K <= 65536): codes are radix-sorted, one wave sums each run.
-// Overwrites w.sums / w.counts for every cluster; uses the vector-sort scratch buffers (not w.vperm).
-// codes_trusted = true (codes written by the library's own E-step) skips the per-member range check.
-hipError_t launch_accumulate_sorted(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, uint32_t K,
-                                    const Workspace& w, bool codes_trusted, hipStream_t s);
-
 // Re-decides the listed guard-band vectors over all K centroids in direct form; if the list
 // overflowed, re-decides everything in direct form. With fix_sums = true the cluster sums/counts that
 // the scoring kernel accumulated are corrected for every vector whose code changed (or rebuilt from
@@ -221,6 +233,12 @@ hipError_t launch_zero_accumulators(const Workspace& w, uint32_t K, uint32_t d, 
                                     uint32_t gate_limit, hipStream_t s);
 hipError_t launch_accumulate(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, uint32_t K,
                              const Workspace& w, const uint32_t* gate, uint32_t gate_limit, hipStream_t s);
+// M-step by buckets (K <= 65536): counts, scatter into per-bucket records, LDS sums, means (and counts_out if
+// not NULL) in one go. Codes >= K are skipped and counted in WsHeader::skipped_vectors. norm_order = true
+// buckets the clusters by their position in the norm order left by launch_sort_centroids (w.cinv, w.cperm).
+hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,
+                                 uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order,
+                                 hipStream_t s);
 hipError_t launch_finalize(const float* prev, float* out, uint32_t* counts_out, uint32_t K, uint32_t d, uint32_t N,
                            const Workspace& w, hipStream_t s);
 hipError_t launch_update(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,

@@ -376,64 +376,6 @@ __global__ __launch_bounds__(1024) void window_stats_kernel(const uint2* __restr
     }
 }
 
-// ---------------------------------------------------------------------------------------------------
-// M-step by sorting (for K <= 65536): the memory-side atomics of the accumulate kernel cost ~2.4 ms per
-// 11 M vectors at d = 4, more than a pruned E-step. Instead the (code, position) pairs are radix-sorted by
-// code, which makes every cluster a contiguous run, and one wave per cluster sums its members' rows in
-// the same 64-bit fixed point (so the result is bit-identical to the atomic path, and needs no atomics).
-__global__ __launch_bounds__(kThreads) void code_keys_kernel(const uint32_t* __restrict__ idx, uint32_t N, uint32_t K,
-                                                             uint16_t* __restrict__ keys, uint32_t* __restrict__ ids)
-{
-    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
-    if (i >= N) return;
-    keys[i] = uint16_t(min(idx[i], K - 1));  // an out-of-range code is parked in the last run and skipped there
-    ids[i] = i;
-}
-
-// CHECK = true re-reads each member's code and skips (and counts) those that were out of range.
-template <int D, bool CHECK>
-__global__ __launch_bounds__(kThreads) void segment_sum_kernel(const float* __restrict__ X, uint32_t N,
-                                                               const uint32_t* __restrict__ idx,
-                                                               const uint32_t* __restrict__ code_starts,
-                                                               const uint32_t* __restrict__ sorted_ids, uint32_t K,
-                                                               long long* __restrict__ sums, uint32_t* __restrict__ counts,
-                                                               WsHeader* hdr)
-{
-    const int lane = threadIdx.x & 63;
-    const uint32_t k = (blockIdx.x * kThreads + threadIdx.x) >> 6;  // one wave per cluster
-    if (k >= K) return;
-    const uint32_t first = code_starts[k], last = code_starts[k + 1];  // the run of code k in the sorted codes
-    const int e = fixed_point_exp(hdr->absmax_bits, N);
-    long long acc[D];
-#pragma unroll
-    for (int j = 0; j < D; ++j) acc[j] = 0;
-    uint32_t n = 0, bad = 0;
-    for (uint32_t j = first + lane; j < last; j += 64) {
-        const uint32_t i = sorted_ids[j];
-        if (!CHECK || idx[i] == k) {
-            float x[D];
-            load_row<D>(X + size_t(i) * D, x);
-#pragma unroll
-            for (int c = 0; c < D; ++c) acc[c] += __double2ll_rn(ldexp(double(x[c]), e));
-            ++n;
-        } else {
-            ++bad;  // its code was >= K
-        }
-    }
-    for (int off = 32; off > 0; off >>= 1) {
-#pragma unroll
-        for (int c = 0; c < D; ++c) acc[c] += __shfl_xor(acc[c], off, 64);
-        n += uint32_t(__shfl_xor(int(n), off, 64));
-        bad += uint32_t(__shfl_xor(int(bad), off, 64));
-    }
-    if (lane == 0) {
-#pragma unroll
-        for (int c = 0; c < D; ++c) sums[size_t(k) * D + c] = acc[c];
-        counts[k] = n;
-        if (bad) atomicAdd(&hdr->skipped_vectors, static_cast<unsigned long long>(bad));
-    }
-}
-
 // Codes back to input order: idx[ids[p]] = idx_sorted[p]; also records that the sorted codes are a usable hint.
 __global__ __launch_bounds__(kThreads) void unpermute_kernel(const uint32_t* __restrict__ idx_sorted,
                                                              const uint32_t* __restrict__ ids, uint32_t n,
@@ -515,6 +457,14 @@ __global__ __launch_bounds__(kThreads) void subsample_centroids_kernel(const flo
     csub_ids[p] = cperm[src];
 }
 
+// cinv[cperm[p]] = p
+__global__ __launch_bounds__(kThreads) void invert_perm_kernel(const uint32_t* __restrict__ perm, uint32_t n,
+                                                               uint32_t* __restrict__ inv)
+{
+    const uint32_t p = blockIdx.x * kThreads + threadIdx.x;
+    if (p < n) inv[perm[p]] = p;
+}
+
 template <int D>
 static void sort_centroids_t(const float* C, uint32_t K, const Workspace& w, hipStream_t s)
 {
@@ -523,6 +473,7 @@ static void sort_centroids_t(const float* C, uint32_t K, const Workspace& w, hip
     radix_sort16(w.ckeys, w.cperm, w.ckeys_tmp, w.cperm_tmp, K, w.sort_hist, s);
     hipLaunchKernelGGL(key_starts_kernel, dim3((65536 + kThreads) / kThreads), dim3(kThreads), 0, s, w.ckeys, K, 65536u,
                        w.key_starts);
+    hipLaunchKernelGGL(invert_perm_kernel, dim3((K + kThreads - 1) / kThreads), dim3(kThreads), 0, s, w.cperm, K, w.cinv);
     const uint64_t pieces = uint64_t(K) * (D / 4);
     hipLaunchKernelGGL(gather_rows_kernel<D>, dim3(uint32_t((pieces + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, C,
                        w.cperm, K, w.csorted);
@@ -569,31 +520,6 @@ hipError_t launch_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, co
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
-}
-
-template <bool CHECK>
-static hipError_t launch_segment_sum(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, uint32_t K,
-                                     const Workspace& w, hipStream_t s)
-{
-    const dim3 grid(uint32_t((uint64_t(K) * 64 + kThreads - 1) / kThreads));
-    switch (d) {
-        case 4: hipLaunchKernelGGL((segment_sum_kernel<4, CHECK>), grid, dim3(kThreads), 0, s, X, N, idx, w.code_starts, w.mperm, K, w.sums, w.counts, w.hdr); break;
-        case 8: hipLaunchKernelGGL((segment_sum_kernel<8, CHECK>), grid, dim3(kThreads), 0, s, X, N, idx, w.code_starts, w.mperm, K, w.sums, w.counts, w.hdr); break;
-        case 16: hipLaunchKernelGGL((segment_sum_kernel<16, CHECK>), grid, dim3(kThreads), 0, s, X, N, idx, w.code_starts, w.mperm, K, w.sums, w.counts, w.hdr); break;
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
-}
-
-hipError_t launch_accumulate_sorted(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, uint32_t K,
-                                    const Workspace& w, bool codes_trusted, hipStream_t s)
-{
-    hipLaunchKernelGGL(code_keys_kernel, dim3((N + kThreads - 1) / kThreads), dim3(kThreads), 0, s, idx, N, K, w.vkeys,
-                       w.mperm);
-    radix_sort16(w.vkeys, w.mperm, w.vkeys_tmp, w.vperm_tmp, N, w.sort_hist, s);
-    hipLaunchKernelGGL(key_starts_kernel, dim3((K + kThreads) / kThreads), dim3(kThreads), 0, s, w.vkeys, N, K,
-                       w.code_starts);
-    return codes_trusted ? launch_segment_sum<false>(X, N, d, idx, K, w, s) : launch_segment_sum<true>(X, N, d, idx, K, w, s);
 }
 
 hipError_t launch_unpermute(uint32_t N, uint32_t* idx, const Workspace& w, hipStream_t s)

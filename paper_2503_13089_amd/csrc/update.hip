@@ -179,10 +179,9 @@ hipError_t launch_update(const float* X, uint32_t N, uint32_t d, const uint32_t*
                          float* out, uint32_t* counts_out, const Workspace& w, hipStream_t s)
 {
     hipError_t e;
-    if (K <= 65536 && N >= 32768) {
-        // memory-side atomics are the bottleneck of the scatter formulation: sort by code and sum runs instead
-        e = launch_accumulate_sorted(X, N, d, idx, K, w, false, s);
-        if (e != hipSuccess) return e;
+    if (w.bucket_ok && N >= 32768) {
+        // memory-side atomics are the bottleneck of the scatter formulation: group by bucket, sum in LDS
+        return launch_update_buckets(X, N, d, idx, prev, K, out, counts_out, w, false, s);
     } else {
         e = launch_zero_accumulators(w, K, d, nullptr, 0, s);
         if (e != hipSuccess) return e;

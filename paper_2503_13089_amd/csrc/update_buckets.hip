@@ -1,0 +1,303 @@
+// M-step by buckets (Section 3.1: c_k <- mean of the vectors assigned to cluster k), for K <= 65536.
+//
+// Summing straight into K accumulators needs one memory-side atomic per vector component, and those run
+// at ~23 G/s on this chip: 2.4 ms for 11 M vectors of d = 4. Instead the vectors are first moved next to
+// the other members of their bucket of 64 consecutive clusters, and one workgroup per bucket then adds
+// its members up in LDS:
+//   1. count:   per block of 4096 vectors, an LDS histogram of the buckets (one row of a blocks x buckets matrix),
+//   2. scan:    two-level column scan of that matrix, prefix of the bucket totals = first record of every bucket,
+//   3. scatter: every vector is copied, with its code, into a record of its bucket's range,
+//   4. sum:     workgroup b adds the records of bucket b into 64 x (d sums + count) LDS accumulators
+//               and writes the 64 means (an empty cluster keeps its previous centroid).
+// The sums are the same 64-bit fixed-point integers as in the atomic formulation, so the order in which
+// records land inside a bucket - the only thing here that depends on scheduling - cannot change a bit
+// of the result.
+#include <algorithm>
+
+#include "common.h"
+
+namespace cc {
+
+constexpr int kThreads = 256;
+
+// Exclusive prefix sum over the workgroup of one value per thread; `total` receives the sum.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* wave_sum, uint32_t& total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = v;
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = uint32_t(__shfl_up(int(incl), off, 64));
+        if (lane >= off) incl += t;
+    }
+    __syncthreads();  // wave_sum may still be read from an earlier call
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    uint32_t before = incl - v;
+    total = 0;
+    for (int w = 0; w < kThreads / 64; ++w) {
+        if (w < wave) before += wave_sum[w];
+        total += wave_sum[w];
+    }
+    return before;
+}
+
+// The bucket of a code: by cluster index, or - with `cinv` (position of each centroid in the norm order of
+// the E-step that produced the codes) - by that position, which neighbouring vectors of the ordered copy
+// share, so that their records land next to each other.
+__device__ __forceinline__ uint32_t slot_of_code(uint32_t k, const uint32_t* __restrict__ cinv)
+{
+    return cinv != nullptr ? cinv[k] : k;
+}
+
+// ---- 1. bucket histogram of one block of vectors: row `block` of hist[blocks][nbuckets]
+__global__ __launch_bounds__(kThreads) void bucket_count_kernel(const uint32_t* __restrict__ idx, uint32_t N, uint32_t K,
+                                                                const uint32_t* __restrict__ cinv, uint32_t nbuckets,
+                                                                uint32_t* __restrict__ hist, WsHeader* hdr)
+{
+    __shared__ uint32_t h[kMaxBuckets];
+    __shared__ uint32_t bad_total;
+    for (uint32_t b = threadIdx.x; b < nbuckets; b += kThreads) h[b] = 0;
+    if (threadIdx.x == 0) bad_total = 0;
+    __syncthreads();
+    const uint32_t lo = blockIdx.x * kBucketChunk, hi = min(lo + kBucketChunk, N);
+    uint32_t bad = 0;
+    for (uint32_t i = lo + threadIdx.x; i < hi; i += kThreads) {
+        const uint32_t k = idx[i];
+        if (k < K) atomicAdd(&h[slot_of_code(k, cinv) / kBucketClusters], 1u);
+        else ++bad;
+    }
+    if (bad) atomicAdd(&bad_total, bad);
+    __syncthreads();
+    for (uint32_t b = threadIdx.x; b < nbuckets; b += kThreads) hist[size_t(blockIdx.x) * nbuckets + b] = h[b];
+    if (threadIdx.x == 0 && bad_total) atomicAdd(&hdr->skipped_vectors, static_cast<unsigned long long>(bad_total));
+}
+
+// ---- 2a. column scan, first level: within each group of kBucketGroup blocks, every column (bucket) of hist
+// becomes its exclusive prefix over the group's blocks; the group's column sums go to gtot[group][bucket].
+// One thread per (group, bucket); neighbouring threads read neighbouring buckets.
+__global__ __launch_bounds__(kThreads) void bucket_groupscan_kernel(uint32_t* __restrict__ hist, uint32_t blocks,
+                                                                    uint32_t nbuckets, uint32_t* __restrict__ gtot)
+{
+    const uint32_t b = blockIdx.x * kThreads + threadIdx.x;
+    if (b >= nbuckets) return;
+    const uint32_t first = blockIdx.y * kBucketGroup, last = min(first + kBucketGroup, blocks);
+    uint32_t run = 0;
+#pragma unroll 16
+    for (uint32_t blk = first; blk < last; ++blk) {
+        const size_t o = size_t(blk) * nbuckets + b;
+        const uint32_t v = hist[o];
+        hist[o] = run;
+        run += v;
+    }
+    gtot[size_t(blockIdx.y) * nbuckets + b] = run;
+}
+
+// ---- 2b. second level: every column of gtot becomes its exclusive prefix over the groups; totals[bucket]
+__global__ __launch_bounds__(kThreads) void bucket_totals_kernel(uint32_t* __restrict__ gtot, uint32_t groups,
+                                                                 uint32_t nbuckets, uint32_t* __restrict__ totals)
+{
+    const uint32_t b = blockIdx.x * kThreads + threadIdx.x;
+    if (b >= nbuckets) return;
+    uint32_t run = 0;
+#pragma unroll 16
+    for (uint32_t g = 0; g < groups; ++g) {
+        const size_t o = size_t(g) * nbuckets + b;
+        const uint32_t v = gtot[o];
+        gtot[o] = run;
+        run += v;
+    }
+    totals[b] = run;
+}
+
+// ---- 2c. first record of every bucket: exclusive prefix of the totals (one workgroup), base[nbuckets] = all
+__global__ __launch_bounds__(kThreads) void bucket_base_kernel(const uint32_t* __restrict__ totals, uint32_t nbuckets,
+                                                               uint32_t* __restrict__ base)
+{
+    __shared__ uint32_t wave_sum[kThreads / 64];
+    const uint32_t per = (nbuckets + kThreads - 1) / kThreads;
+    const uint32_t first = min(threadIdx.x * per, nbuckets), last = min(first + per, nbuckets);
+    uint32_t s = 0;
+    for (uint32_t i = first; i < last; ++i) s += totals[i];
+    uint32_t total;
+    uint32_t before = block_exclusive_scan(s, wave_sum, total);
+    for (uint32_t i = first; i < last; ++i) {
+        base[i] = before;
+        before += totals[i];
+    }
+    if (threadIdx.x == 0) base[nbuckets] = total;
+}
+
+// A record: the d floats of the vector, then 16 bytes whose first word is the code's slot.
+template <int D>
+struct Record {
+    static constexpr int kBytes = D * 4 + 16;
+};
+
+// ---- 3. copy every vector into its bucket's range. The block first orders its (vector, record position)
+// pairs by bucket in LDS, then writes the records in that order, so that the records of one bucket leave
+// as one contiguous run (isolated 32-byte writes reach only a fraction of the streaming bandwidth).
+template <int D>
+__global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(const float* __restrict__ X, uint32_t N,
+                                                                  const uint32_t* __restrict__ idx, uint32_t K,
+                                                                  const uint32_t* __restrict__ cinv, uint32_t nbuckets,
+                                                                  const uint32_t* __restrict__ hist,
+                                                                  const uint32_t* __restrict__ gtot,
+                                                                  const uint32_t* __restrict__ base,
+                                                                  char* __restrict__ records)
+{
+    constexpr int kPer = kBucketChunk / kThreads;  // vectors per thread
+    static_assert(kBucketChunk <= 8192 && kMaxBuckets * kBucketClusters <= (1u << 19), "packing of the stage entries");
+    __shared__ uint32_t h[kMaxBuckets];            // members of each bucket in this block, then their first stage slot
+    __shared__ uint32_t first_rec[kMaxBuckets];    // first record of (bucket, this block)
+    __shared__ uint2 stage[kBucketChunk];          // (vector, record) in bucket order
+    __shared__ uint32_t wave_sum[kThreads / 64];
+    for (uint32_t b = threadIdx.x; b < nbuckets; b += kThreads) {
+        h[b] = 0;
+        first_rec[b] = base[b] + gtot[size_t(blockIdx.x / kBucketGroup) * nbuckets + b] +
+                       hist[size_t(blockIdx.x) * nbuckets + b];
+    }
+    __syncthreads();
+    const uint32_t lo = blockIdx.x * kBucketChunk;
+    uint32_t slot[kPer], rank[kPer];
+#pragma unroll
+    for (int r = 0; r < kPer; ++r) {
+        const uint32_t i = lo + r * kThreads + threadIdx.x;
+        const uint32_t k = i < N ? idx[i] : 0xffffffffu;
+        slot[r] = 0xffffffffu;
+        rank[r] = 0;
+        if (k < K) {  // codes >= K were counted by the histogram pass and are left out
+            slot[r] = slot_of_code(k, cinv);
+            rank[r] = atomicAdd(&h[slot[r] / kBucketClusters], 1u);
+        }
+    }
+    __syncthreads();
+    // exclusive prefix of h over the buckets: contiguous entries per thread, then the workgroup scan
+    {
+        const uint32_t per = (nbuckets + kThreads - 1) / kThreads;
+        const uint32_t first = min(threadIdx.x * per, nbuckets), last = min(first + per, nbuckets);
+        uint32_t s = 0;
+        for (uint32_t b = first; b < last; ++b) s += h[b];
+        uint32_t total;
+        uint32_t before = block_exclusive_scan(s, wave_sum, total);
+        for (uint32_t b = first; b < last; ++b) {
+            const uint32_t v = h[b];
+            h[b] = before;
+            before += v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < kPer; ++r) {
+            if (slot[r] == 0xffffffffu) continue;
+            const uint32_t b = slot[r] / kBucketClusters;
+            // (position in the chunk | slot << 13, record): the write loop then needs nothing but the row
+            stage[h[b] + rank[r]] = make_uint2(uint32_t(r * kThreads + threadIdx.x) | (slot[r] << 13), first_rec[b] + rank[r]);
+        }
+        __syncthreads();
+        // One 16-byte piece per thread and step (the d/4 pieces of the row, then the trailer), so that a wave
+        // writes whole records side by side wherever a bucket's run is contiguous.
+        constexpr int P = D / 4 + 1, U = 4;
+        const uint32_t pieces = total * P;
+        for (uint32_t g0 = 0; g0 < pieces; g0 += U * kThreads) {
+            uint2 t[U];
+            float4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) t[u] = stage[min(g0 + u * kThreads + threadIdx.x, pieces - 1) / P];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t q = min(g0 + u * kThreads + threadIdx.x, pieces - 1) % P;
+                const uint32_t i = lo + (t[u].x & 8191u);
+                if (q < D / 4) {
+                    v[u] = reinterpret_cast<const float4*>(X + size_t(i) * D)[q];
+                } else {
+                    v[u] = make_float4(__uint_as_float(t[u].x >> 13), __uint_as_float(i), 0.0f, 0.0f);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t g = g0 + u * kThreads + threadIdx.x;
+                if (g < pieces) reinterpret_cast<float4*>(records + size_t(t[u].y) * Record<D>::kBytes)[g % P] = v[u];
+            }
+        }
+    }
+}
+
+// ---- 4. one workgroup per bucket: sums in LDS (component-major, so that the clusters of a bucket spread over
+// all banks), then the means
+template <int D>
+__global__ __launch_bounds__(kThreads) void bucket_sum_kernel(const char* __restrict__ records,
+                                                              const uint32_t* __restrict__ base, uint32_t N, uint32_t K,
+                                                              const uint32_t* __restrict__ cperm, const float* prev,
+                                                              float* out, uint32_t* counts_out, WsHeader* hdr)
+{
+    __shared__ unsigned long long sum[D][kBucketClusters];
+    __shared__ uint32_t cnt[kBucketClusters];
+    for (uint32_t t = threadIdx.x; t < kBucketClusters * D; t += kThreads) (&sum[0][0])[t] = 0;
+    if (threadIdx.x < kBucketClusters) cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const int e = fixed_point_exp(hdr->absmax_bits, N);
+    const uint32_t p0 = blockIdx.x * kBucketClusters;
+    const uint32_t first = base[blockIdx.x], last = base[blockIdx.x + 1];
+    for (uint32_t p = first + threadIdx.x; p < last; p += kThreads) {
+        const char* rec = records + size_t(p) * Record<D>::kBytes;
+        const uint32_t local = (*reinterpret_cast<const uint32_t*>(rec + D * 4) - p0) & (kBucketClusters - 1);
+        float x[D];
+        load_row<D>(reinterpret_cast<const float*>(rec), x);
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            const long long v = __double2ll_rn(ldexp(double(x[j]), e));
+            atomicAdd(&sum[j][local], static_cast<unsigned long long>(v));  // two's complement: wraps like int64
+        }
+        atomicAdd(&cnt[local], 1u);
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && threadIdx.x == 0) hdr->fixed_point_exp = e;
+    for (uint32_t t = threadIdx.x; t < kBucketClusters * D; t += kThreads) {
+        const uint32_t local = t / D, j = t % D;
+        if (p0 + local >= K) continue;
+        const uint32_t k = cperm != nullptr ? cperm[p0 + local] : p0 + local;
+        const uint32_t n = cnt[local];
+        const size_t o = size_t(k) * D + j;
+        // one fp64 division, one rounding to fp32; an empty cluster keeps its previous centroid
+        out[o] = n > 0 ? float(ldexp(double(static_cast<long long>(sum[j][local])), -e) / double(n)) : prev[o];
+        if (counts_out != nullptr && j == 0) counts_out[k] = n;
+    }
+}
+
+template <int D>
+static void update_buckets_t(const float* X, uint32_t N, const uint32_t* idx, const float* prev, uint32_t K, float* out,
+                             uint32_t* counts_out, const Workspace& w, bool norm_order, hipStream_t s)
+{
+    const uint32_t nbuckets = (K + kBucketClusters - 1) / kBucketClusters;
+    const uint32_t blocks = (N + kBucketChunk - 1) / kBucketChunk;
+    const uint32_t* cinv = norm_order ? w.cinv : nullptr;
+    const uint32_t* cperm = norm_order ? w.cperm : nullptr;
+    hipLaunchKernelGGL(bucket_count_kernel, dim3(blocks), dim3(kThreads), 0, s, idx, N, K, cinv, nbuckets, w.bucket_hist,
+                       w.hdr);
+    const uint32_t groups = (blocks + kBucketGroup - 1) / kBucketGroup;
+    const uint32_t bwg = (nbuckets + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL(bucket_groupscan_kernel, dim3(bwg, groups), dim3(kThreads), 0, s, w.bucket_hist, blocks, nbuckets,
+                       w.bucket_gtot);
+    hipLaunchKernelGGL(bucket_totals_kernel, dim3(bwg), dim3(kThreads), 0, s, w.bucket_gtot, groups, nbuckets,
+                       w.bucket_totals);
+    hipLaunchKernelGGL(bucket_base_kernel, dim3(1), dim3(kThreads), 0, s, w.bucket_totals, nbuckets, w.bucket_base);
+    hipLaunchKernelGGL(bucket_scatter_kernel<D>, dim3(blocks), dim3(kThreads), 0, s, X, N, idx, K, cinv, nbuckets,
+                       w.bucket_hist, w.bucket_gtot, w.bucket_base, w.records);
+    hipLaunchKernelGGL(bucket_sum_kernel<D>, dim3(nbuckets), dim3(kThreads), 0, s, w.records, w.bucket_base, N, K, cperm,
+                       prev, out, counts_out, w.hdr);
+}
+
+hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,
+                                 uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order,
+                                 hipStream_t s)
+{
+    if (K > kMaxBuckets * kBucketClusters || w.records == nullptr) return hipErrorInvalidValue;
+    switch (d) {
+        case 4: update_buckets_t<4>(X, N, idx, prev, K, out, counts_out, w, norm_order, s); break;
+        case 8: update_buckets_t<8>(X, N, idx, prev, K, out, counts_out, w, norm_order, s); break;
+        case 16: update_buckets_t<16>(X, N, idx, prev, K, out, counts_out, w, norm_order, s); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace cc
