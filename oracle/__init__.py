@@ -15,3 +15,4 @@ from .cpu import (  # noqa: F401
     threads,
     update,
 )
+from . import layer  # noqa: F401,E402  (the linear layer's data path: plain numpy)

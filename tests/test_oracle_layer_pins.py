@@ -1,0 +1,118 @@
+"""Pins of the layer oracle (oracle/layer.py) against things other than itself: element-by-element brute force on tiny
+inputs, torch's CPU library routines (embedding, matmul, bfloat16 conversion, autograd), the constructor arithmetic of
+the paper's layer listing, and round trips."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer
+
+
+@pytest.mark.parametrize("out_features,g,expect", [(4096, 4, 0), (4096, 6, 2), (4096, 9, 8), (11008, 7, 3), (10, 4, 2), (7, 7, 0)])
+def test_deficiency_and_code_count_follow_the_listing_constructor(out_features, g, expect):
+    assert layer.deficiency(out_features, g) == expect
+    assert (out_features + expect) % g == 0 and 0 <= expect < g
+    assert layer.num_codes(5, out_features, g) == 5 * (out_features + expect) // g
+
+
+def test_code_counts_of_table_1():
+    # Table 1 (4096 x 4096): 4.19 M, 2.80 M and 1.86 M codes for g = 4, 6, 9
+    assert round(layer.num_codes(4096, 4096, 4) / 1e6, 2) == 4.19
+    assert round(layer.num_codes(4096, 4096, 6) / 1e6, 2) == 2.80
+    assert round(layer.num_codes(4096, 4096, 9) / 1e6, 2) == 1.87  # with padding; the table's 1.86 is 4096*4096/9
+    assert round(4096 * 4096 / 9 / 1e6, 2) == 1.86
+
+
+@pytest.mark.parametrize("out_features,in_features,g", [(10, 3, 4), (12, 5, 4), (7, 2, 3), (9, 4, 9), (5, 1, 8)])
+def test_prepare_matrix_elementwise(out_features, in_features, g):
+    rng = np.random.default_rng(out_features * 31 + g)
+    W = rng.standard_normal((out_features, in_features)).astype(np.float32)
+    X = layer.prepare_matrix(W, g)
+    width = out_features + layer.deficiency(out_features, g)
+    assert X.shape == (in_features * width // g, g) and X.dtype == np.float32
+    flat = X.reshape(-1)
+    for r in range(in_features):
+        for c in range(width):
+            want = W[c, r] if c < out_features else 0.0
+            assert flat[r * width + c] == want
+
+
+@pytest.mark.parametrize("out_features,in_features,g", [(10, 3, 4), (12, 5, 4), (7, 6, 3), (64, 9, 9)])
+def test_identity_codebook_round_trip(out_features, in_features, g):
+    """Every vector its own centroid: reconstruction returns the transposed weight exactly."""
+    rng = np.random.default_rng(7)
+    W = rng.standard_normal((out_features, in_features)).astype(np.float32)
+    X = layer.prepare_matrix(W, g)
+    codes = np.arange(X.shape[0], dtype=np.uint32)
+    back = layer.layer_weight(X, codes, in_features, out_features)
+    assert back.tobytes() == np.ascontiguousarray(W.T).tobytes()
+
+
+def test_layer_weight_matches_torch_embedding_view_slice():
+    rng = np.random.default_rng(11)
+    K, g, in_features, out_features = 50, 6, 9, 20
+    C = rng.standard_normal((K, g)).astype(np.float32)
+    codes = rng.integers(0, K, size=layer.num_codes(in_features, out_features, g)).astype(np.uint32)
+    vectors = torch.nn.functional.embedding(torch.from_numpy(codes.astype(np.int64)), torch.from_numpy(C))
+    want = vectors.view(in_features, -1)[:, :out_features].contiguous().numpy()
+    assert layer.layer_weight(C, codes, in_features, out_features).tobytes() == want.tobytes()
+
+
+def test_bf16_round_matches_torch_and_known_cases():
+    rng = np.random.default_rng(3)
+    a = np.concatenate([
+        rng.standard_normal(20000).astype(np.float32) * np.float32(10.0) ** rng.integers(-30, 30, 20000).astype(np.float32),
+        np.array([0.0, -0.0, 1.0, np.inf, -np.inf, 1e-45, -1e-40, 3.3895314e38, 65504.0], np.float32),
+        # exact ties: 1 + 2^-8 (rounds to even: 1.0), 1 + 3*2^-8 (rounds to 1 + 2^-6), largest finite (overflows to inf)
+        np.array([1.00390625, 1.01171875, 3.4028235e38], np.float32),
+    ])
+    got = layer.bf16_round(a)
+    want = torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
+    assert got.tobytes() == want.tobytes()
+    assert got[-3] == 1.0 and got[-2] == np.float32(1.015625) and np.isinf(got[-1])
+    assert np.isnan(layer.bf16_round(np.array([np.nan], np.float32))[0])
+    # 8 significant bits: every bf16 value survives, and the error is at most half a unit in the last place
+    assert np.array_equal(layer.bf16_round(got), got)
+    finite = np.isfinite(got) & (np.abs(a) > 1e-30)
+    assert np.all(np.abs(got[finite] - a[finite]) <= np.abs(a[finite]) * 2.0 ** -8)
+
+
+def test_layer_forward_matches_torch_fp64_matmul():
+    rng = np.random.default_rng(5)
+    K, g, in_features, out_features, M = 40, 4, 12, 18, 7
+    C = rng.standard_normal((K, g)).astype(np.float32)
+    codes = rng.integers(0, K, size=layer.num_codes(in_features, out_features, g)).astype(np.uint32)
+    x = rng.standard_normal((M, in_features)).astype(np.float32)
+    b = rng.standard_normal(out_features).astype(np.float32)
+    W = torch.from_numpy(C).double()[torch.from_numpy(codes.astype(np.int64))].view(in_features, -1)[:, :out_features]
+    want = torch.matmul(torch.from_numpy(x).double(), W) + torch.from_numpy(b).double()
+    got = layer.layer_forward(x, C, codes, in_features, out_features, b)
+    np.testing.assert_allclose(got, want.numpy(), rtol=1e-13, atol=1e-13)
+    # one-hot inputs read out single rows of the reconstructed weight
+    eye = np.eye(in_features, dtype=np.float32)
+    assert np.array_equal(layer.layer_forward(eye, C, codes, in_features, out_features),
+                          layer.layer_weight(C.astype(np.float64), codes, in_features, out_features))
+
+
+@pytest.mark.parametrize("g,out_features", [(4, 16), (6, 20), (9, 30)])
+def test_gather_backward_matches_autograd_and_bruteforce(g, out_features):
+    rng = np.random.default_rng(13 + g)
+    K, in_features = 23, 8
+    C = torch.from_numpy(rng.standard_normal((K, g))).requires_grad_(True)  # fp64
+    codes = rng.integers(0, K, size=layer.num_codes(in_features, out_features, g)).astype(np.uint32)
+    G = rng.standard_normal((in_features, out_features))
+    W = C[torch.from_numpy(codes.astype(np.int64))].view(in_features, -1)[:, :out_features]
+    (W * torch.from_numpy(G)).sum().backward()
+    got = layer.gather_backward(G, codes, K, g)
+    np.testing.assert_allclose(got, C.grad.numpy(), rtol=1e-13, atol=1e-14)
+    # element by element
+    width = out_features + layer.deficiency(out_features, g)
+    brute = np.zeros((K, g))
+    for r in range(in_features):
+        for c in range(out_features):
+            brute[int(codes[(r * width + c) // g]), (r * width + c) % g] += G[r, c]
+    np.testing.assert_allclose(got, brute, rtol=1e-13, atol=1e-14)
+    # total mass is preserved, unused clusters get exactly zero
+    assert got.sum() == pytest.approx(G.sum(), rel=1e-12)
+    unused = np.setdiff1d(np.arange(K), codes)
+    assert np.all(got[unused] == 0.0)

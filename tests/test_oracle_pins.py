@@ -30,7 +30,7 @@ def _exact_top2(X, C):
     return out
 
 
-@pytest.mark.parametrize("d", [4, 8, 16])
+@pytest.mark.parametrize("d", [4, 8, 16, 3, 5, 6, 7, 9])  # the paper's g runs over 4..9 (Table 1 and its ablations)
 @pytest.mark.parametrize("seed", [0, 1])
 def test_assign_top2_equals_exact_rational_bruteforce(d, seed):
     X, C = workloads.make_small(N=40, d=d, K=7, seed=100 + seed)
@@ -58,7 +58,7 @@ def test_assign_single_centroid_has_no_runner_up():
 
 # ------------------------------------------------------------------ E-step: kd-tree library query
 
-@pytest.mark.parametrize("d,N,K", [(4, 30000, 1024), (8, 8000, 512), (16, 3000, 300)])
+@pytest.mark.parametrize("d,N,K", [(4, 30000, 1024), (8, 8000, 512), (16, 3000, 300), (6, 9000, 500), (9, 5000, 400)])
 def test_assign_top2_matches_kdtree(d, N, K):
     from scipy.spatial import cKDTree
 
@@ -132,7 +132,7 @@ def test_fit_equals_manual_composition_and_history_is_the_objective():
     assert J == hist[6] == pytest.approx(float(D1.sum()), rel=1e-13)
 
 
-@pytest.mark.parametrize("d,K", [(4, 256), (8, 100), (16, 33)])
+@pytest.mark.parametrize("d,K", [(4, 256), (8, 100), (16, 33), (6, 77), (9, 50)])
 def test_inertia_never_increases(d, K):
     X, C0 = workloads.make_small(N=20000, d=d, K=K, seed=31 + d)
     C0[1] = C0[0]  # a duplicate seed: cluster 1 is empty at the first E-step and must keep its value
