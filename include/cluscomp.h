@@ -14,8 +14,10 @@
  *     row-major, and owned by the caller; the library never frees or keeps them.
  *   - `vectors` is the weight matrix itself: an R x C row-major fp32 matrix viewed as N = R*C/d rows of
  *     d floats (the reshape of Section 3.1; a caller who wants the paper's transposed orientation
- *     transposes before the call). Supported d: 4, 8, 16. `vectors`, `centroids` and `out` must be
- *     16-byte aligned, `workspace` 256-byte aligned.
+ *     transposes before the call; cc_layer_vectors does it). Supported d: 1..16 (the paper's g runs
+ *     over 4..9). The kernels are built for d = 4, 8, 16; any other length runs on zero-padded copies
+ *     of the vectors and centroids kept in the workspace, which changes no distance and no mean.
+ *     `vectors`, `centroids` and `out` must be 16-byte aligned, `workspace` 256-byte aligned.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream) and is
  *     asynchronous: results are valid once the caller has synchronised that stream. No call
  *     synchronises, allocates, or copies to the host. Concurrent calls must not share a workspace.
@@ -45,7 +47,7 @@ extern "C" {
 typedef enum cc_status {
     CC_OK = 0,
     CC_ERR_NULL = -1,      /* a required pointer is NULL */
-    CC_ERR_SHAPE = -2,     /* N == 0, N >= 2^32, d not in {4,8,16}, K == 0, K > N, K > 2^24 */
+    CC_ERR_SHAPE = -2,     /* N == 0, N >= 2^32, d not in 1..16, K == 0, K > N, K > 2^24 */
     CC_ERR_ITERS = -3,     /* iters < 0 */
     CC_ERR_ALIGN = -4,     /* a pointer violates the alignment stated above */
     CC_ERR_WORKSPACE = -5, /* workspace_bytes < cc_workspace_bytes(N, d, K) */
@@ -54,7 +56,8 @@ typedef enum cc_status {
 
 /* Host-only query: bytes of device workspace that cc_kmeans_fit / cc_assign / cc_lloyd_iter / cc_update
  * need for this problem size (about 8*N*d + 38*N bytes: an ordered copy of the vectors, a copy grouped
- * by cluster for the M-step, permutations and sort buffers). Returns 0 for an unsupported shape. The
+ * by cluster for the M-step, permutations and sort buffers, with d rounded up to 4, 8 or 16; plus one
+ * more padded copy of the vectors if d is not one of those). Returns 0 for an unsupported shape. The
  * first 256 bytes keep a little state between calls (problem shape, "codes of the previous E-step are
  * present"): a workspace that held something else in between is still safe to reuse - stale state can
  * only make a call slower, not wrong. */

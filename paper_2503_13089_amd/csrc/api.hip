@@ -30,7 +30,7 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 
 int check_shape(uint64_t N, uint32_t d, uint32_t K)
 {
-    if (d != 4 && d != 8 && d != 16) return fail(CC_ERR_SHAPE, "d = %u is not supported (4, 8, 16)", d);
+    if (d == 0 || d > 16) return fail(CC_ERR_SHAPE, "d = %u is not supported (1..16)", d);
     if (N == 0) return fail(CC_ERR_SHAPE, "N == 0");
     if (N >= (1ull << 32)) return fail(CC_ERR_SHAPE, "N = %llu does not fit 32-bit vector ids", (unsigned long long)N);
     if (K == 0) return fail(CC_ERR_SHAPE, "K == 0");
@@ -155,6 +155,33 @@ int run_lloyd_iter(const float* X, uint32_t N, uint32_t d, float* C, uint32_t K,
     return CC_OK;
 }
 
+// Sub-vector lengths other than 4, 8, 16 run on zero-padded copies (length 4, 8 or 16): padding both the
+// vectors and the centroids with zeros changes no distance and no mean. Views of one call's operands:
+struct Operands {
+    const float* X;       // vectors, rows of w.d floats
+    const float* C_in;    // centroids entering the call (NULL if the call has none)
+    float* C_work;        // where the kernels read/write centroids
+};
+
+int enter(const float* vectors, const float* centroids_in, float* centroids_out, uint32_t N, uint32_t d, uint32_t K,
+          const cc::Workspace& w, hipStream_t s, Operands& o)
+{
+    if (!w.padded) {
+        o = {vectors, centroids_in, centroids_out};
+        return CC_OK;
+    }
+    CC_TRY_HIP(cc::launch_pad_rows(vectors, N, d, w.d, w.xpad, s), "padding (vectors)");
+    if (centroids_in) CC_TRY_HIP(cc::launch_pad_rows(centroids_in, K, d, w.d, w.cpad, s), "padding (centroids)");
+    o = {w.xpad, centroids_in ? w.cpad : nullptr, w.cpad};
+    return CC_OK;
+}
+
+int leave(float* centroids_out, uint32_t d, uint32_t K, const cc::Workspace& w, hipStream_t s)
+{
+    if (w.padded && centroids_out) CC_TRY_HIP(cc::launch_unpad_rows(w.cpad, K, w.d, d, centroids_out, s), "padding (result)");
+    return CC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -179,21 +206,24 @@ int cc_kmeans_fit(const float* vectors, uint64_t N, uint32_t d, uint32_t K, int3
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const cc::Workspace w = cc::carve(workspace, N, d, K);
-    const uint32_t n = uint32_t(N);
+    const uint32_t n = uint32_t(N), D = w.d;
 
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
-    CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
-    if (centroids != init_centroids)
-        CC_TRY_HIP(cc::launch_copy_f32(init_centroids, centroids, size_t(K) * d, s), "centroid copy");
+    Operands o;
+    if (int rc = enter(vectors, init_centroids, centroids, n, d, K, w, s, o)) return rc;
+    CC_TRY_HIP(cc::launch_scan_inputs(o.X, N * D, w.hdr, s), "input scan");
+    if (o.C_work != o.C_in)
+        CC_TRY_HIP(cc::launch_copy_f32(o.C_in, o.C_work, size_t(K) * D, s), "centroid copy");
     const bool pruned = use_matrix_cores(K) && use_pruning(K);
-    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, n, d, K, w, true, s), "norm ordering");
+    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(o.X, n, D, K, w, true, s), "norm ordering");
     for (int32_t t = 0; t < iters; ++t) {
         // only the matrix-core path can leave its codes in the workspace; the others write idx directly
         uint32_t* step_idx = pruned ? nullptr : idx;
-        if (int rc = run_lloyd_iter(vectors, n, d, centroids, K, step_idx, nullptr, nullptr, w, pruned, t > 0, s))
+        if (int rc = run_lloyd_iter(o.X, n, D, o.C_work, K, step_idx, nullptr, nullptr, w, pruned, t > 0, s))
             return rc;
     }
-    return run_assign(vectors, n, d, centroids, K, idx, inertia, w, pruned, iters > 0, s);
+    if (int rc = run_assign(o.X, n, D, o.C_work, K, idx, inertia, w, pruned, iters > 0, s)) return rc;
+    return leave(centroids, d, K, w, s);
 }
 
 int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroids, uint32_t K, uint32_t* idx,
@@ -207,10 +237,12 @@ int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroi
     hipStream_t s = static_cast<hipStream_t>(stream);
     const cc::Workspace w = cc::carve(workspace, N, d, K);
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
-    CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
+    Operands o;
+    if (int rc = enter(vectors, centroids, nullptr, uint32_t(N), d, K, w, s, o)) return rc;
+    CC_TRY_HIP(cc::launch_scan_inputs(o.X, N * w.d, w.hdr, s), "input scan");
     const bool pruned = use_matrix_cores(K) && use_pruning(K);
-    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, uint32_t(N), d, K, w, false, s), "norm ordering");
-    return run_assign(vectors, uint32_t(N), d, centroids, K, idx, inertia, w, pruned, false, s);
+    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(o.X, uint32_t(N), w.d, K, w, false, s), "norm ordering");
+    return run_assign(o.X, uint32_t(N), w.d, o.C_in, K, idx, inertia, w, pruned, false, s);
 }
 
 int cc_lloyd_iter(const float* vectors, uint64_t N, uint32_t d, float* centroids, uint32_t K, uint32_t* idx,
@@ -225,10 +257,13 @@ int cc_lloyd_iter(const float* vectors, uint64_t N, uint32_t d, float* centroids
     hipStream_t s = static_cast<hipStream_t>(stream);
     const cc::Workspace w = cc::carve(workspace, N, d, K);
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
-    CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
+    Operands o;
+    if (int rc = enter(vectors, centroids, centroids, uint32_t(N), d, K, w, s, o)) return rc;
+    CC_TRY_HIP(cc::launch_scan_inputs(o.X, N * w.d, w.hdr, s), "input scan");
     const bool pruned = use_matrix_cores(K) && use_pruning(K);
-    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(vectors, uint32_t(N), d, K, w, false, s), "norm ordering");
-    return run_lloyd_iter(vectors, uint32_t(N), d, centroids, K, idx, inertia, counts, w, pruned, false, s);
+    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(o.X, uint32_t(N), w.d, K, w, false, s), "norm ordering");
+    if (int rc = run_lloyd_iter(o.X, uint32_t(N), w.d, o.C_work, K, idx, inertia, counts, w, pruned, false, s)) return rc;
+    return leave(centroids, d, K, w, s);
 }
 
 int cc_update(const float* vectors, uint64_t N, uint32_t d, const uint32_t* idx, const float* prev_centroids,
@@ -243,16 +278,18 @@ int cc_update(const float* vectors, uint64_t N, uint32_t d, const uint32_t* idx,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const cc::Workspace w = cc::carve(workspace, N, d, K);
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
-    CC_TRY_HIP(cc::launch_scan_inputs(vectors, N * d, w.hdr, s), "input scan");
-    CC_TRY_HIP(cc::launch_update(vectors, uint32_t(N), d, idx, prev_centroids, K, centroids, counts, w, s), "update");
-    return CC_OK;
+    Operands o;
+    if (int rc = enter(vectors, prev_centroids, centroids, uint32_t(N), d, K, w, s, o)) return rc;
+    CC_TRY_HIP(cc::launch_scan_inputs(o.X, N * w.d, w.hdr, s), "input scan");
+    CC_TRY_HIP(cc::launch_update(o.X, uint32_t(N), w.d, idx, o.C_in, K, o.C_work, counts, w, s), "update");
+    return leave(centroids, d, K, w, s);
 }
 
 int cc_decode(const float* centroids, uint32_t K, uint32_t d, const uint32_t* idx, uint64_t N, float* out,
               void* stream)
 {
     if (!centroids || !idx || !out) return fail(CC_ERR_NULL, "a required pointer is NULL");
-    if (d != 4 && d != 8 && d != 16) return fail(CC_ERR_SHAPE, "d = %u is not supported (4, 8, 16)", d);
+    if (d == 0 || d > 16) return fail(CC_ERR_SHAPE, "d = %u is not supported (1..16)", d);
     if (N == 0 || K == 0) return fail(CC_ERR_SHAPE, "N == 0 or K == 0");
     if (N >= (1ull << 32)) return fail(CC_ERR_SHAPE, "N = %llu does not fit 32-bit vector ids", (unsigned long long)N);
     if (!aligned(centroids, 16) || !aligned(out, 16) || !aligned(idx, 4))

@@ -34,6 +34,10 @@ struct WsPersist {
 
 // Carved view of the caller's workspace.
 struct Workspace {
+    uint32_t d;                // sub-vector length the kernels run at: the caller's, rounded up to 4, 8 or 16
+    bool padded;               // the caller's length differs: the kernels see zero-padded copies
+    float* xpad;               // [N*d]  padded vectors   (only if padded)
+    float* cpad;               // [K*d]  padded centroids (only if padded)
     WsHeader* hdr;
     float* cnorm;              // [K]    ||c_k||^2
     long long* sums;           // [K*d]  fixed-point cluster sums
@@ -92,9 +96,12 @@ constexpr uint32_t kBucketChunk = 4096;   // vectors per workgroup in its counti
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
 // Lays the arrays out behind `base` (which may be NULL for a pure size query).
-inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
+inline Workspace carve(void* base, uint64_t N, uint32_t d_caller, uint32_t K)
 {
     Workspace w{};
+    const uint32_t d = d_caller <= 4 ? 4u : (d_caller <= 8 ? 8u : 16u);
+    w.d = d;
+    w.padded = d != d_caller;
     char* p = static_cast<char*>(base);
     size_t off = 0;
     auto take = [&](size_t bytes) { char* q = p ? p + off : nullptr; off += align256(bytes); return q; };
@@ -134,6 +141,10 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d, uint32_t K)
     w.csub = reinterpret_cast<float*>(take(size_t(w.ksub) * d * 4));
     w.csub_ids = reinterpret_cast<uint32_t*>(take(size_t(w.ksub) * 4));
     w.packed_sub = take(size_t(w.packed_sub_tiles) * kTileCentroids * (6 * d + 16));
+    if (w.padded) {
+        w.xpad = reinterpret_cast<float*>(take(size_t(N) * d * 4));
+        w.cpad = reinterpret_cast<float*>(take(size_t(K) * d * 4));
+    }
     w.bucket_ok = K <= kMaxBuckets * kBucketClusters;
     if (w.bucket_ok) {
         const size_t buckets = (size_t(K) + kBucketClusters - 1) / kBucketClusters;
@@ -239,6 +250,9 @@ hipError_t launch_accumulate(const float* X, uint32_t N, uint32_t d, const uint3
 hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,
                                  uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order,
                                  hipStream_t s);
+// out[i][j] = j < d_in ? in[i][j] : 0 for rows of d_out >= d_in floats, and the reverse (drop the tail).
+hipError_t launch_pad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s);
+hipError_t launch_unpad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s);
 hipError_t launch_finalize(const float* prev, float* out, uint32_t* counts_out, uint32_t K, uint32_t d, uint32_t N,
                            const Workspace& w, hipStream_t s);
 hipError_t launch_update(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,

@@ -42,6 +42,17 @@ __global__ __launch_bounds__(kThreads) void decode_kernel(const f32x4* __restric
     }
 }
 
+__global__ __launch_bounds__(kThreads) void decode_scalar_kernel(const float* __restrict__ C, uint32_t K, uint32_t d,
+                                                                 const uint32_t* __restrict__ idx, uint64_t n,
+                                                                 float* __restrict__ out)
+{
+    const uint64_t t = uint64_t(blockIdx.x) * kThreads + threadIdx.x;
+    if (t >= n) return;
+    const uint32_t kk = idx[t / d];
+    const uint32_t k = kk < K ? kk : K - 1;  // never read outside the codebook
+    __builtin_nontemporal_store(C[size_t(k) * d + uint32_t(t % d)], &out[t]);
+}
+
 hipError_t launch_decode(const float* C, uint32_t K, uint32_t d, const uint32_t* idx, uint64_t N, float* out,
                          hipStream_t s)
 {
@@ -53,9 +64,49 @@ hipError_t launch_decode(const float* C, uint32_t K, uint32_t d, const uint32_t*
     switch (d) {
         case 4: hipLaunchKernelGGL((decode_kernel<4, U>), dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
         case 8: hipLaunchKernelGGL((decode_kernel<8, U>), dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
+        case 12: hipLaunchKernelGGL((decode_kernel<12, U>), dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
         case 16: hipLaunchKernelGGL((decode_kernel<16, U>), dim3(blocks), dim3(kThreads), 0, s, C4, K, idx, n_chunks, out4); break;
-        default: return hipErrorInvalidValue;
+        default: {
+            // rows that are not whole 16-byte pieces: one float per lane
+            const uint64_t n = N * d;
+            hipLaunchKernelGGL(decode_scalar_kernel, dim3(uint32_t((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, C, K,
+                               d, idx, n, out);
+        }
     }
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(kThreads) void pad_rows_kernel(const float* __restrict__ in, uint64_t n_out, uint32_t d_in,
+                                                            uint32_t d_out, float* __restrict__ out)
+{
+    const uint64_t t = uint64_t(blockIdx.x) * kThreads + threadIdx.x;
+    if (t >= n_out) return;
+    const uint64_t i = t / d_out;
+    const uint32_t j = uint32_t(t % d_out);
+    out[t] = j < d_in ? in[i * d_in + j] : 0.0f;
+}
+
+__global__ __launch_bounds__(kThreads) void unpad_rows_kernel(const float* __restrict__ in, uint64_t n_out, uint32_t d_in,
+                                                              uint32_t d_out, float* __restrict__ out)
+{
+    const uint64_t t = uint64_t(blockIdx.x) * kThreads + threadIdx.x;
+    if (t >= n_out) return;
+    out[t] = in[(t / d_out) * d_in + t % d_out];
+}
+
+hipError_t launch_pad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s)
+{
+    const uint64_t n_out = uint64_t(n) * d_out;
+    hipLaunchKernelGGL(pad_rows_kernel, dim3(uint32_t((n_out + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, in, n_out,
+                       d_in, d_out, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s)
+{
+    const uint64_t n_out = uint64_t(n) * d_out;
+    hipLaunchKernelGGL(unpad_rows_kernel, dim3(uint32_t((n_out + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, in, n_out,
+                       d_in, d_out, out);
     return hipGetLastError();
 }
 

@@ -32,7 +32,7 @@ def test_workspace_query():
     big = cc.workspace_bytes(11272192, 4, 65536)
     assert 11272192 * 4 <= big < 1e9  # at least the per-vector distance array
     assert cc.workspace_bytes(65536, 4, 256) % 256 == 0
-    for N, d, K in [(0, 4, 1), (10, 5, 2), (10, 4, 0), (10, 4, 11), (1 << 32, 4, 8), (1 << 26, 4, (1 << 24) + 1)]:
+    for N, d, K in [(0, 4, 1), (10, 17, 2), (10, 0, 2), (10, 4, 0), (10, 4, 11), (1 << 32, 4, 8), (1 << 26, 4, (1 << 24) + 1)]:
         assert cc.workspace_bytes(N, d, K) == 0
 
 
@@ -49,7 +49,7 @@ def test_fit_rejects_bad_arguments_without_launching():
     lib = cc.load_library()
     assert _fit(lib, vectors=None) == -1 and "NULL" in cc.last_error()
     assert _fit(lib, idx=None) == -1
-    assert _fit(lib, d=5) == -2 and "d = 5" in cc.last_error()
+    assert _fit(lib, d=17) == -2 and "d = 17" in cc.last_error()
     assert _fit(lib, N=0) == -2
     assert _fit(lib, K=0) == -2
     assert _fit(lib, K=1001) == -2 and "exceeds N" in cc.last_error()
@@ -69,10 +69,10 @@ def test_other_entry_points_reject_bad_arguments():
     assert lib.cc_assign(A16, 10, 4, MISALIGNED, 2, A4, None, A16, 0, None) == -4
     assert lib.cc_assign(A16, 10, 4, A16, 2, A4, None, ctypes.c_void_p(0x1100), 16, None) == -5
     assert lib.cc_update(A16, 10, 4, None, A16, 2, A16, None, A16, 0, None) == -1
-    assert lib.cc_update(A16, 10, 12, A4, A16, 2, A16, None, A16, 0, None) == -2
+    assert lib.cc_update(A16, 10, 24, A4, A16, 2, A16, None, A16, 0, None) == -2
     assert lib.cc_update(A16, 10, 4, A4, A16, 2, A16, None, ctypes.c_void_p(0x1100), 16, None) == -5
     assert lib.cc_decode(None, 2, 4, A4, 10, A16, None) == -1
-    assert lib.cc_decode(A16, 2, 7, A4, 10, A16, None) == -2
+    assert lib.cc_decode(A16, 2, 17, A4, 10, A16, None) == -2
     assert lib.cc_decode(A16, 0, 4, A4, 10, A16, None) == -2
     assert lib.cc_decode(A16, 2, 4, A4, 10, MISALIGNED, None) == -4
     assert lib.cc_read_stats(None, 0, None, None) == -1

@@ -46,6 +46,13 @@ SHAPES = [  # (N, d, K): ragged in N (not a multiple of 256/512/1024) and in K (
     (65536, 4, 256),   # cfg1's shape
     (40003, 4, 9001),  # K large enough for the norm-window pruning of the automatic mode
     (20011, 8, 8200),
+    # sub-vector lengths other than 4, 8, 16 (the paper's g runs over 4..9): zero-padded inside the library
+    (30007, 6, 700),
+    (20011, 5, 8300),
+    (9001, 9, 300),
+    (5003, 7, 129),
+    (777, 3, 50),
+    (6007, 12, 200),
 ]
 
 
@@ -169,7 +176,7 @@ def test_update_general_fp32_inputs_and_bad_codes(g):
 
 
 @pytest.mark.parametrize("N,d,K,iters", [(65536, 4, 256, 10), (30011, 8, 777, 5), (20003, 16, 515, 4), (3000, 4, 3000, 2),
-                                         (50021, 4, 8500, 4)])
+                                         (50021, 4, 8500, 4), (30011, 6, 500, 4), (20003, 9, 8200, 3)])
 def test_fit_trajectory_following(g, mode, N, d, K, iters):
     """Free-running GPU fit, every step verified: the oracle checks each assignment against the GPU's
     own centroids, adopts the GPU's choice on near-ties, and recomputes the update."""
