@@ -132,6 +132,59 @@ typedef struct cc_stats {
 } cc_stats;
 int cc_read_stats(const void *workspace, size_t workspace_bytes, cc_stats *host_out, void *stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * The compressed linear layer (Section 3.1 footnote, Section 3.2, and the paper's layer listing).
+ *
+ * A linear layer's weight is stored [out_features, in_features] by the framework. What is clustered is
+ * its transpose, W[in_features, out_features] row-major, each row zero-padded by
+ * deficiency = (g - out_features % g) % g columns and cut into vectors of length g; the layer keeps a
+ * codebook [K, g] in a 16-bit float format and num_codes = in_features * (out_features + deficiency) / g
+ * unsigned 16-bit codes (hence K <= 65536), and rebuilds W by gathering codebook rows and cutting the
+ * padding columns off again. Element types are given as a cc_dtype.
+ */
+typedef enum cc_dtype { CC_F32 = 0, CC_F16 = 1, CC_BF16 = 2 } cc_dtype;
+
+/* Host-only arithmetic of the layer's constructor. */
+uint32_t cc_layer_deficiency(uint32_t out_features, uint32_t g);
+uint64_t cc_layer_num_codes(uint64_t in_features, uint64_t out_features, uint32_t g);
+
+/*
+ * The vectors to cluster (Section 3.1 footnote): weight [out_features * in_features] (weight_dtype) is
+ * transposed, every row of the transpose is zero-padded to out_features + deficiency columns, and the
+ * result is written as fp32: vectors [num_codes * g], ready for cc_kmeans_fit with N = num_codes, d = g.
+ */
+int cc_layer_vectors(const void *weight, int weight_dtype, uint32_t out_features, uint32_t in_features,
+                     uint32_t g, float *vectors, void *stream);
+
+/*
+ * Storage formats (Section 3.2): centroids [K * g] fp32 -> codebook [K * g] in codebook_dtype (CC_F16 or
+ * CC_BF16, round to nearest even); idx [num_codes] uint32 -> codes [num_codes] uint16. K <= 65536; an idx
+ * value >= K is clamped to K - 1. Either half may be skipped by passing NULL for both of its pointers.
+ */
+int cc_layer_pack(const float *centroids, uint32_t K, uint32_t g, void *codebook, int codebook_dtype,
+                  const uint32_t *idx, uint64_t num_codes, uint16_t *codes, void *stream);
+
+/*
+ * Reconstruction (layer listing, forward: gather, view as in_features rows, cut the padding):
+ * weight [in_features * out_features] in the codebook's dtype, weight[r][c] = codebook[codes[(r * width + c) / g]]
+ * [(r * width + c) % g] with width = out_features + deficiency. Pure data movement, bit-exact.
+ * A code >= K is clamped to K - 1. `dtype` may be CC_F32, CC_F16 or CC_BF16.
+ */
+int cc_layer_weight(const void *codebook, int dtype, uint32_t K, uint32_t g, const uint16_t *codes,
+                    uint32_t in_features, uint32_t out_features, void *weight, void *stream);
+
+/*
+ * Gradient of the codebook (the only trainable tensor of the layer, Sections 3.2-3.3): every weight entry
+ * is a copy of one codebook entry, so grad_codebook [K * g] (fp32) [k][j] is the sum of grad_weight
+ * [in_features * out_features] (grad_dtype) over the entries rebuilt from codebook[k][j]. Sums are
+ * accumulated in 64-bit fixed point scaled from max |grad|: deterministic, exact for 16-bit gradients, and
+ * within 2^-38 * max |grad| per term otherwise. Gradients must be finite.
+ * Workspace: cc_workspace_bytes(num_codes, g, K) bytes.
+ */
+int cc_layer_codebook_grad(const void *grad_weight, int grad_dtype, uint32_t in_features, uint32_t out_features,
+                           const uint16_t *codes, uint32_t K, uint32_t g, float *grad_codebook,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 /* Selects the E-step kernel. 0 = automatic (default): for K >= 128 the matrix cores, with the fp16 MFMA
  * (centroids split into three fp16 parts, exact products) when every input is an fp16 number and
  * the fp32 MFMA otherwise, both with guard band + direct-form refinement; direct form for small K;

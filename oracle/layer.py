@@ -55,7 +55,8 @@ def bf16_round(a):
 
 def fp16_round(a):
     """fp32 -> IEEE half (round to nearest even), returned as fp32."""
-    return np.asarray(a, dtype=np.float32).astype(np.float16).astype(np.float32)
+    with np.errstate(over="ignore"):  # values beyond the half range round to infinity, as the format prescribes
+        return np.asarray(a, dtype=np.float32).astype(np.float16).astype(np.float32)
 
 
 def layer_weight(codebook, codes, in_features: int, out_features: int):

@@ -11,6 +11,12 @@ from .binding import (  # noqa: F401
     decode,
     kmeans_fit,
     last_error,
+    layer_codebook_grad,
+    layer_deficiency,
+    layer_num_codes,
+    layer_pack,
+    layer_vectors,
+    layer_weight,
     lib_path,
     lloyd_iter,
     load_library,

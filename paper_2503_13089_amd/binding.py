@@ -15,6 +15,8 @@ _lib = None
 EXPORTS = (
     "cc_workspace_bytes", "cc_kmeans_fit", "cc_assign", "cc_lloyd_iter", "cc_update", "cc_decode",
     "cc_read_stats", "cc_set_assign_mode", "cc_last_error", "cc_version",
+    "cc_layer_deficiency", "cc_layer_num_codes", "cc_layer_vectors", "cc_layer_pack", "cc_layer_weight",
+    "cc_layer_codebook_grad",
 )
 
 
@@ -72,6 +74,18 @@ def load_library():
     lib.cc_read_stats.restype = ctypes.c_int
     lib.cc_set_assign_mode.argtypes = [ctypes.c_int]
     lib.cc_set_assign_mode.restype = ctypes.c_int
+    lib.cc_layer_deficiency.argtypes = [u32, u32]
+    lib.cc_layer_deficiency.restype = u32
+    lib.cc_layer_num_codes.argtypes = [u64, u64, u32]
+    lib.cc_layer_num_codes.restype = u64
+    lib.cc_layer_vectors.argtypes = [vp, ctypes.c_int, u32, u32, u32, vp, vp]
+    lib.cc_layer_vectors.restype = ctypes.c_int
+    lib.cc_layer_pack.argtypes = [vp, u32, u32, vp, ctypes.c_int, vp, u64, vp, vp]
+    lib.cc_layer_pack.restype = ctypes.c_int
+    lib.cc_layer_weight.argtypes = [vp, ctypes.c_int, u32, u32, vp, u32, u32, vp, vp]
+    lib.cc_layer_weight.restype = ctypes.c_int
+    lib.cc_layer_codebook_grad.argtypes = [vp, ctypes.c_int, u32, u32, vp, u32, u32, vp, vp, sz, vp]
+    lib.cc_layer_codebook_grad.restype = ctypes.c_int
     lib.cc_last_error.restype = ctypes.c_char_p
     lib.cc_version.restype = ctypes.c_char_p
     _lib = lib
@@ -194,3 +208,67 @@ def set_assign_mode(mode: int) -> int:
     if rc < 0:
         raise CCError(rc, last_error())
     return rc
+
+
+# ---- the compressed linear layer ---------------------------------------------------------------------
+
+def _dtype_code(t) -> int:
+    """cc_dtype of a tensor's element type."""
+    import torch
+
+    codes = {torch.float32: 0, torch.float16: 1, torch.bfloat16: 2}
+    if t.dtype not in codes:
+        raise TypeError(f"unsupported element type {t.dtype}")
+    return codes[t.dtype]
+
+
+def _any_ptr(t, what):
+    return _ptr(t, t.dtype, what) if t is not None else None
+
+
+def layer_deficiency(out_features: int, g: int) -> int:
+    return load_library().cc_layer_deficiency(out_features, g)
+
+
+def layer_num_codes(in_features: int, out_features: int, g: int) -> int:
+    return load_library().cc_layer_num_codes(in_features, out_features, g)
+
+
+def layer_vectors(weight, g: int, vectors) -> None:
+    import torch
+
+    out_features, in_features = weight.shape
+    _check(load_library().cc_layer_vectors(_any_ptr(weight, "weight"), _dtype_code(weight), out_features, in_features, g,
+                                           _ptr(vectors, torch.float32, "vectors"), _stream()))
+
+
+def layer_pack(centroids, codebook, idx, codes, K: int | None = None) -> None:
+    """Either pair (centroids, codebook) / (idx, codes) may be None; K is needed when only codes are packed."""
+    import torch
+
+    K, g = (centroids.shape if centroids is not None else (K, 1))
+    _check(load_library().cc_layer_pack(_ptr(centroids, torch.float32, "centroids"), K, g, _any_ptr(codebook, "codebook"),
+                                        _dtype_code(codebook) if codebook is not None else 1,
+                                        _ptr(idx, _idx_dtype(), "idx"), idx.numel() if idx is not None else 0,
+                                        _ptr(codes, torch.uint16, "codes"), _stream()))
+
+
+def layer_weight(codebook, codes, in_features: int, out_features: int, weight) -> None:
+    import torch
+
+    K, g = codebook.shape
+    if weight.dtype != codebook.dtype:
+        raise TypeError("weight and codebook must share one element type")
+    _check(load_library().cc_layer_weight(_any_ptr(codebook, "codebook"), _dtype_code(codebook), K, g,
+                                          _ptr(codes, torch.uint16, "codes"), in_features, out_features,
+                                          _any_ptr(weight, "weight"), _stream()))
+
+
+def layer_codebook_grad(grad_weight, codes, K: int, g: int, grad_codebook, workspace) -> None:
+    import torch
+
+    in_features, out_features = grad_weight.shape
+    _check(load_library().cc_layer_codebook_grad(_any_ptr(grad_weight, "grad_weight"), _dtype_code(grad_weight), in_features,
+                                                 out_features, _ptr(codes, torch.uint16, "codes"), K, g,
+                                                 _ptr(grad_codebook, torch.float32, "grad_codebook"),
+                                                 _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))

@@ -39,6 +39,16 @@ int check_shape(uint64_t N, uint32_t d, uint32_t K)
     return CC_OK;
 }
 
+int check_layer(uint32_t in_features, uint32_t out_features, uint32_t g, uint32_t K, int dtype, bool allow_f32)
+{
+    if (in_features == 0 || out_features == 0) return fail(CC_ERR_SHAPE, "in_features == 0 or out_features == 0");
+    if (g == 0 || g > 16) return fail(CC_ERR_SHAPE, "g = %u is not supported (1..16)", g);
+    if (K == 0 || K > 65536) return fail(CC_ERR_SHAPE, "K = %u does not fit 16-bit codes", K);
+    if (!(dtype == CC_F16 || dtype == CC_BF16 || (allow_f32 && dtype == CC_F32)))
+        return fail(CC_ERR_SHAPE, "element type %d is not supported here", dtype);
+    return CC_OK;
+}
+
 int check_workspace(void* ws, size_t ws_bytes, uint64_t N, uint32_t d, uint32_t K)
 {
     if (ws == nullptr) return fail(CC_ERR_NULL, "workspace is NULL");
@@ -141,14 +151,14 @@ int run_lloyd_iter(const float* X, uint32_t N, uint32_t d, float* C, uint32_t K,
         if (!by_buckets) CC_TRY_HIP(cc::launch_zero_accumulators(w, K, d, nullptr, 0, s), "update (clear)");
         if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, !by_buckets, pruned, have_hint, s)) return rc;
         if (by_buckets)
-            CC_TRY_HIP(cc::launch_update_buckets(w.xsorted, N, d, w.idx_sorted, C, K, C, counts, w, true, s), "update (buckets)");
+            CC_TRY_HIP(cc::launch_update_buckets(w.xsorted, N, d, w.idx_sorted, C, K, C, counts, w, true, true, s), "update (buckets)");
         else
-            CC_TRY_HIP(cc::launch_finalize(C, C, counts, K, d, N, w, s), "update (means)");
+            CC_TRY_HIP(cc::launch_finalize(C, C, counts, K, d, N, w, true, s), "update (means)");
         if (pruned && idx != nullptr) CC_TRY_HIP(cc::launch_unpermute(N, idx, w, s), "assign (codes to input order)");
     } else {
         CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s), "assign (direct form)");
         CC_TRY_HIP(cc::launch_bump_assign_calls(w.hdr, s), "bookkeeping");
-        CC_TRY_HIP(cc::launch_update(X, N, d, idx, C, K, C, counts, w, s), "update");
+        CC_TRY_HIP(cc::launch_update(X, N, d, idx, C, K, C, counts, w, true, s), "update");
     }
     if (inertia)
         CC_TRY_HIP(cc::launch_reduce_dmin(w.dmin, N, w.partials, w.partial_slots, inertia, s), "objective reduction");
@@ -281,7 +291,7 @@ int cc_update(const float* vectors, uint64_t N, uint32_t d, const uint32_t* idx,
     Operands o;
     if (int rc = enter(vectors, prev_centroids, centroids, uint32_t(N), d, K, w, s, o)) return rc;
     CC_TRY_HIP(cc::launch_scan_inputs(o.X, N * w.d, w.hdr, s), "input scan");
-    CC_TRY_HIP(cc::launch_update(o.X, uint32_t(N), w.d, idx, o.C_in, K, o.C_work, counts, w, s), "update");
+    CC_TRY_HIP(cc::launch_update(o.X, uint32_t(N), w.d, idx, o.C_in, K, o.C_work, counts, w, true, s), "update");
     return leave(centroids, d, K, w, s);
 }
 
@@ -295,6 +305,97 @@ int cc_decode(const float* centroids, uint32_t K, uint32_t d, const uint32_t* id
     if (!aligned(centroids, 16) || !aligned(out, 16) || !aligned(idx, 4))
         return fail(CC_ERR_ALIGN, "centroids/out need 16-byte alignment, idx 4");
     CC_TRY_HIP(cc::launch_decode(centroids, K, d, idx, N, out, static_cast<hipStream_t>(stream)), "decode");
+    return CC_OK;
+}
+
+// ---- the compressed linear layer -----------------------------------------------------------------
+
+uint32_t cc_layer_deficiency(uint32_t out_features, uint32_t g)
+{
+    if (g == 0) return 0;
+    const uint32_t r = out_features % g;
+    return r == 0 ? 0 : g - r;
+}
+
+uint64_t cc_layer_num_codes(uint64_t in_features, uint64_t out_features, uint32_t g)
+{
+    if (g == 0) return 0;
+    return in_features * ((out_features + g - 1) / g);
+}
+
+int cc_layer_vectors(const void* weight, int weight_dtype, uint32_t out_features, uint32_t in_features, uint32_t g,
+                     float* vectors, void* stream)
+{
+    if (!weight || !vectors) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (int rc = check_layer(in_features, out_features, g, 1, weight_dtype, true)) return rc;
+    if (!aligned(weight, 4) || !aligned(vectors, 16)) return fail(CC_ERR_ALIGN, "vectors need 16-byte alignment");
+    CC_TRY_HIP(cc::launch_layer_vectors(weight, weight_dtype, out_features, in_features, g, vectors,
+                                        static_cast<hipStream_t>(stream)), "layer vectors");
+    return CC_OK;
+}
+
+int cc_layer_pack(const float* centroids, uint32_t K, uint32_t g, void* codebook, int codebook_dtype,
+                  const uint32_t* idx, uint64_t num_codes, uint16_t* codes, void* stream)
+{
+    if ((centroids == nullptr) != (codebook == nullptr) || (idx == nullptr) != (codes == nullptr) ||
+        (centroids == nullptr && idx == nullptr))
+        return fail(CC_ERR_NULL, "pass both pointers of at least one of the pairs (centroids, codebook), (idx, codes)");
+    if (K == 0 || K > 65536) return fail(CC_ERR_SHAPE, "K = %u does not fit 16-bit codes", K);
+    if (g == 0 || g > 16) return fail(CC_ERR_SHAPE, "g = %u is not supported (1..16)", g);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (centroids) {
+        if (codebook_dtype != CC_F16 && codebook_dtype != CC_BF16)
+            return fail(CC_ERR_SHAPE, "the stored codebook is CC_F16 or CC_BF16");
+        if (!aligned(centroids, 4) || !aligned(codebook, 2)) return fail(CC_ERR_ALIGN, "misaligned codebook");
+        CC_TRY_HIP(cc::launch_layer_pack_codebook(centroids, size_t(K) * g, codebook, codebook_dtype, s), "codebook format");
+    }
+    if (idx) {
+        if (num_codes == 0 || num_codes >= (1ull << 32)) return fail(CC_ERR_SHAPE, "num_codes = %llu", (unsigned long long)num_codes);
+        if (!aligned(idx, 4) || !aligned(codes, 2)) return fail(CC_ERR_ALIGN, "misaligned codes");
+        CC_TRY_HIP(cc::launch_layer_pack_codes(idx, num_codes, K, codes, s), "code format");
+    }
+    return CC_OK;
+}
+
+int cc_layer_weight(const void* codebook, int dtype, uint32_t K, uint32_t g, const uint16_t* codes,
+                    uint32_t in_features, uint32_t out_features, void* weight, void* stream)
+{
+    if (!codebook || !codes || !weight) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (int rc = check_layer(in_features, out_features, g, K, dtype, true)) return rc;
+    if (!aligned(codebook, 16) || !aligned(weight, 16) || !aligned(codes, 2))
+        return fail(CC_ERR_ALIGN, "codebook/weight need 16-byte alignment, codes 2");
+    CC_TRY_HIP(cc::launch_layer_weight(codebook, dtype, K, g, codes, in_features, out_features, weight,
+                                       static_cast<hipStream_t>(stream)), "layer weight");
+    return CC_OK;
+}
+
+int cc_layer_codebook_grad(const void* grad_weight, int grad_dtype, uint32_t in_features, uint32_t out_features,
+                           const uint16_t* codes, uint32_t K, uint32_t g, float* grad_codebook, void* workspace,
+                           size_t workspace_bytes, void* stream)
+{
+    if (!grad_weight || !codes || !grad_codebook) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (int rc = check_layer(in_features, out_features, g, K, grad_dtype, true)) return rc;
+    const uint64_t N = cc_layer_num_codes(in_features, out_features, g);
+    if (N >= (1ull << 32)) return fail(CC_ERR_SHAPE, "num_codes = %llu does not fit 32-bit vector ids", (unsigned long long)N);
+    if (!aligned(grad_weight, 4) || !aligned(grad_codebook, 16) || !aligned(codes, 2))
+        return fail(CC_ERR_ALIGN, "grad_codebook needs 16-byte alignment, grad_weight 4, codes 2");
+    if (workspace == nullptr) return fail(CC_ERR_NULL, "workspace is NULL");
+    if (!aligned(workspace, 256)) return fail(CC_ERR_ALIGN, "workspace must be 256-byte aligned");
+    // sized like a clustering problem with at least K vectors (a layer may have fewer codes than clusters)
+    const uint64_t n_ws = N > K ? N : K;
+    const size_t need = cc::carve(nullptr, n_ws, g, K).bytes;
+    if (workspace_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const cc::Workspace w = cc::carve(workspace, n_ws, g, K);
+    CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
+    // the ordered-copy buffers of the E-step are free here: vectors in w.xsorted, widened codes in w.idx_sorted
+    CC_TRY_HIP(cc::launch_layer_grad_vectors(grad_weight, grad_dtype, in_features, out_features, g, w.d, codes, N, w.xsorted,
+                                             w.idx_sorted, s), "gradient vectors");
+    CC_TRY_HIP(cc::launch_scan_inputs(w.xsorted, N * w.d, w.hdr, s), "input scan");
+    float* out = w.padded ? w.csorted : grad_codebook;
+    CC_TRY_HIP(cc::launch_update(w.xsorted, uint32_t(N), w.d, w.idx_sorted, nullptr, K, out, nullptr, w, false, s),
+               "codebook gradient");
+    if (w.padded) CC_TRY_HIP(cc::launch_unpad_rows(w.csorted, K, w.d, g, grad_codebook, s), "padding (result)");
     return CC_OK;
 }
 

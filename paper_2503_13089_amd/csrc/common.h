@@ -247,16 +247,30 @@ hipError_t launch_accumulate(const float* X, uint32_t N, uint32_t d, const uint3
 // M-step by buckets (K <= 65536): counts, scatter into per-bucket records, LDS sums, means (and counts_out if
 // not NULL) in one go. Codes >= K are skipped and counted in WsHeader::skipped_vectors. norm_order = true
 // buckets the clusters by their position in the norm order left by launch_sort_centroids (w.cinv, w.cperm).
+// mean = false writes the plain sums (0 for an empty cluster) instead of the means.
 hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,
                                  uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order,
-                                 hipStream_t s);
+                                 bool mean, hipStream_t s);
 // out[i][j] = j < d_in ? in[i][j] : 0 for rows of d_out >= d_in floats, and the reverse (drop the tail).
 hipError_t launch_pad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s);
 hipError_t launch_unpad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s);
 hipError_t launch_finalize(const float* prev, float* out, uint32_t* counts_out, uint32_t K, uint32_t d, uint32_t N,
-                           const Workspace& w, hipStream_t s);
+                           const Workspace& w, bool mean, hipStream_t s);
 hipError_t launch_update(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,
-                         uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, hipStream_t s);
+                         uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool mean, hipStream_t s);
+
+// ---- the compressed linear layer (layer.hip); dtype: 0 = fp32, 1 = fp16, 2 = bf16
+hipError_t launch_layer_vectors(const void* weight, int dtype, uint32_t out_features, uint32_t in_features, uint32_t g,
+                                float* vectors, hipStream_t s);
+hipError_t launch_layer_pack_codebook(const float* centroids, size_t n, void* codebook, int dtype, hipStream_t s);
+hipError_t launch_layer_pack_codes(const uint32_t* idx, uint64_t n, uint32_t K, uint16_t* codes, hipStream_t s);
+hipError_t launch_layer_weight(const void* codebook, int dtype, uint32_t K, uint32_t g, const uint16_t* codes,
+                               uint32_t in_features, uint32_t out_features, void* weight, hipStream_t s);
+// grad_weight [in, out] (dtype) -> fp32 vectors [num_codes][d_pad] (zero padding columns and components) and
+// codes widened to 32 bits
+hipError_t launch_layer_grad_vectors(const void* grad, int dtype, uint32_t in_features, uint32_t out_features,
+                                     uint32_t g, uint32_t d_pad, const uint16_t* codes, uint64_t num_codes, float* vectors,
+                                     uint32_t* idx, hipStream_t s);
 
 // Reconstruction.
 hipError_t launch_decode(const float* C, uint32_t K, uint32_t d, const uint32_t* idx, uint64_t N, float* out,

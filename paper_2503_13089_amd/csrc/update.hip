@@ -128,7 +128,7 @@ __global__ __launch_bounds__(kThreads) void accumulate_kernel(const float* __res
 __global__ __launch_bounds__(kThreads) void finalize_kernel(const long long* __restrict__ sums,
                                                             const uint32_t* __restrict__ counts,
                                                             const float* prev, float* out, uint32_t* counts_out,
-                                                            uint32_t K, uint32_t d, uint32_t N, WsHeader* hdr)
+                                                            uint32_t K, uint32_t d, uint32_t N, WsHeader* hdr, int mean)
 {
     const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
     const int e = fixed_point_exp(hdr->absmax_bits, N);
@@ -137,7 +137,9 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(const long long* __r
     const uint32_t k = t / d;
     const uint32_t n = counts[k];
     float c;
-    if (n > 0) {
+    if (!mean) {
+        c = float(ldexp(double(sums[t]), -e));              // the plain sum (codebook gradient)
+    } else if (n > 0) {
         c = float(ldexp(double(sums[t]), -e) / double(n));  // one fp64 division, one rounding to fp32
     } else {
         c = prev[t];
@@ -168,27 +170,27 @@ hipError_t launch_accumulate(const float* X, uint32_t N, uint32_t d, const uint3
 }
 
 hipError_t launch_finalize(const float* prev, float* out, uint32_t* counts_out, uint32_t K, uint32_t d, uint32_t N,
-                           const Workspace& w, hipStream_t s)
+                           const Workspace& w, bool mean, hipStream_t s)
 {
     hipLaunchKernelGGL(finalize_kernel, dim3((K * d + kThreads - 1) / kThreads), dim3(kThreads), 0, s, w.sums, w.counts,
-                       prev, out, counts_out, K, d, N, w.hdr);
+                       prev, out, counts_out, K, d, N, w.hdr, mean ? 1 : 0);
     return hipGetLastError();
 }
 
 hipError_t launch_update(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev, uint32_t K,
-                         float* out, uint32_t* counts_out, const Workspace& w, hipStream_t s)
+                         float* out, uint32_t* counts_out, const Workspace& w, bool mean, hipStream_t s)
 {
     hipError_t e;
     if (w.bucket_ok && N >= 32768) {
         // memory-side atomics are the bottleneck of the scatter formulation: group by bucket, sum in LDS
-        return launch_update_buckets(X, N, d, idx, prev, K, out, counts_out, w, false, s);
+        return launch_update_buckets(X, N, d, idx, prev, K, out, counts_out, w, false, mean, s);
     } else {
         e = launch_zero_accumulators(w, K, d, nullptr, 0, s);
         if (e != hipSuccess) return e;
         e = launch_accumulate(X, N, d, idx, K, w, nullptr, 0, s);
         if (e != hipSuccess) return e;
     }
-    return launch_finalize(prev, out, counts_out, K, d, N, w, s);
+    return launch_finalize(prev, out, counts_out, K, d, N, w, mean, s);
 }
 
 }  // namespace cc

@@ -227,7 +227,7 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void bucket_sum_kernel(const char* __restrict__ records,
                                                               const uint32_t* __restrict__ base, uint32_t N, uint32_t K,
                                                               const uint32_t* __restrict__ cperm, const float* prev,
-                                                              float* out, uint32_t* counts_out, WsHeader* hdr)
+                                                              float* out, uint32_t* counts_out, WsHeader* hdr, int mean)
 {
     __shared__ unsigned long long sum[D][kBucketClusters];
     __shared__ uint32_t cnt[kBucketClusters];
@@ -257,15 +257,16 @@ __global__ __launch_bounds__(kThreads) void bucket_sum_kernel(const char* __rest
         const uint32_t k = cperm != nullptr ? cperm[p0 + local] : p0 + local;
         const uint32_t n = cnt[local];
         const size_t o = size_t(k) * D + j;
-        // one fp64 division, one rounding to fp32; an empty cluster keeps its previous centroid
-        out[o] = n > 0 ? float(ldexp(double(static_cast<long long>(sum[j][local])), -e) / double(n)) : prev[o];
+        const double total = ldexp(double(static_cast<long long>(sum[j][local])), -e);
+        // mean: one fp64 division, one rounding to fp32; an empty cluster keeps its previous centroid
+        out[o] = !mean ? float(total) : (n > 0 ? float(total / double(n)) : prev[o]);
         if (counts_out != nullptr && j == 0) counts_out[k] = n;
     }
 }
 
 template <int D>
 static void update_buckets_t(const float* X, uint32_t N, const uint32_t* idx, const float* prev, uint32_t K, float* out,
-                             uint32_t* counts_out, const Workspace& w, bool norm_order, hipStream_t s)
+                             uint32_t* counts_out, const Workspace& w, bool norm_order, bool mean, hipStream_t s)
 {
     const uint32_t nbuckets = (K + kBucketClusters - 1) / kBucketClusters;
     const uint32_t blocks = (N + kBucketChunk - 1) / kBucketChunk;
@@ -283,18 +284,18 @@ static void update_buckets_t(const float* X, uint32_t N, const uint32_t* idx, co
     hipLaunchKernelGGL(bucket_scatter_kernel<D>, dim3(blocks), dim3(kThreads), 0, s, X, N, idx, K, cinv, nbuckets,
                        w.bucket_hist, w.bucket_gtot, w.bucket_base, w.records);
     hipLaunchKernelGGL(bucket_sum_kernel<D>, dim3(nbuckets), dim3(kThreads), 0, s, w.records, w.bucket_base, N, K, cperm,
-                       prev, out, counts_out, w.hdr);
+                       prev, out, counts_out, w.hdr, mean ? 1 : 0);
 }
 
 hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,
                                  uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order,
-                                 hipStream_t s)
+                                 bool mean, hipStream_t s)
 {
     if (K > kMaxBuckets * kBucketClusters || w.records == nullptr) return hipErrorInvalidValue;
     switch (d) {
-        case 4: update_buckets_t<4>(X, N, idx, prev, K, out, counts_out, w, norm_order, s); break;
-        case 8: update_buckets_t<8>(X, N, idx, prev, K, out, counts_out, w, norm_order, s); break;
-        case 16: update_buckets_t<16>(X, N, idx, prev, K, out, counts_out, w, norm_order, s); break;
+        case 4: update_buckets_t<4>(X, N, idx, prev, K, out, counts_out, w, norm_order, mean, s); break;
+        case 8: update_buckets_t<8>(X, N, idx, prev, K, out, counts_out, w, norm_order, mean, s); break;
+        case 16: update_buckets_t<16>(X, N, idx, prev, K, out, counts_out, w, norm_order, mean, s); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -81,6 +81,31 @@ def test_other_entry_points_reject_bad_arguments():
     assert lib.cc_set_assign_mode(prev) == 1
 
 
+def test_layer_entry_points_reject_bad_arguments():
+    lib = cc.load_library()
+    F32, F16, BF16 = 0, 1, 2
+    assert lib.cc_layer_deficiency(4096, 6) == 2 and lib.cc_layer_deficiency(4096, 4) == 0
+    assert lib.cc_layer_num_codes(4096, 4096, 9) == 4096 * 456
+    assert lib.cc_layer_vectors(None, F16, 8, 8, 4, A16, None) == -1
+    assert lib.cc_layer_vectors(A16, F16, 8, 8, 0, A16, None) == -2
+    assert lib.cc_layer_vectors(A16, F16, 8, 8, 17, A16, None) == -2
+    assert lib.cc_layer_vectors(A16, 5, 8, 8, 4, A16, None) == -2
+    assert lib.cc_layer_vectors(A16, F16, 8, 8, 4, MISALIGNED, None) == -4
+    assert lib.cc_layer_pack(None, 10, 4, None, F16, None, 0, None, None) == -1
+    assert lib.cc_layer_pack(A16, 10, 4, None, F16, None, 0, None, None) == -1  # half a pair
+    assert lib.cc_layer_pack(A16, 70000, 4, A16, F16, None, 0, None, None) == -2 and "16-bit codes" in cc.last_error()
+    assert lib.cc_layer_pack(A16, 10, 4, A16, F32, None, 0, None, None) == -2
+    assert lib.cc_layer_pack(None, 10, 4, None, F16, A4, 0, A16, None) == -2
+    assert lib.cc_layer_weight(A16, BF16, 10, 4, None, 8, 8, A16, None) == -1
+    assert lib.cc_layer_weight(A16, BF16, 0, 4, A16, 8, 8, A16, None) == -2
+    assert lib.cc_layer_weight(A16, BF16, 10, 4, A16, 0, 8, A16, None) == -2
+    assert lib.cc_layer_weight(A16, BF16, 10, 4, A16, 8, 8, MISALIGNED, None) == -4
+    assert lib.cc_layer_codebook_grad(A16, F32, 8, 8, A16, 10, 4, None, A16, 0, None) == -1
+    assert lib.cc_layer_codebook_grad(A16, F32, 8, 8, A16, 10, 4, A16, None, 0, None) == -1
+    assert lib.cc_layer_codebook_grad(A16, F32, 8, 8, A16, 10, 4, A16, ctypes.c_void_p(0x1100), 16, None) == -5
+    assert lib.cc_layer_codebook_grad(A16, F32, 8, 8, A16, 10, 4, A16, ctypes.c_void_p(0x1010), 1 << 30, None) == -4
+
+
 def test_binding_refuses_host_tensors():
     import torch
 

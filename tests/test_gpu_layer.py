@@ -1,0 +1,148 @@
+"""GPU parity of the layer data path (include/cluscomp.h, "compressed linear layer") against oracle/layer.py:
+bit-exact for data movement and format conversion, fp64-derived tolerances for sums."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import layer as L
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def cc():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2503_13089_amd as cc
+
+    return cc
+
+
+TORCH_DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def _dev(a, dt=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dt is not None:
+        t = t.to(dt)
+    return t.cuda()
+
+
+# (out_features, in_features, g): ragged against the 64 x 64 transpose tiles, with and without padding columns
+LAYER_SHAPES = [(256, 192, 4), (250, 131, 4), (129, 67, 6), (100, 300, 9), (64, 64, 8), (7, 5, 7), (1, 1, 3), (513, 70, 5)]
+
+
+def test_constructor_arithmetic(cc):
+    for out_features, g in [(4096, 4), (4096, 6), (4096, 9), (11008, 7), (10, 4), (7, 7)]:
+        assert cc.layer_deficiency(out_features, g) == L.deficiency(out_features, g)
+        assert cc.layer_num_codes(123, out_features, g) == L.num_codes(123, out_features, g)
+
+
+@pytest.mark.parametrize("dt", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("out_features,in_features,g", LAYER_SHAPES)
+def test_layer_vectors_bit_exact(cc, out_features, in_features, g, dt):
+    rng = np.random.default_rng(out_features * 7 + in_features + g)
+    W = _dev(rng.standard_normal((out_features, in_features)).astype(np.float32), TORCH_DT[dt])
+    n = L.num_codes(in_features, out_features, g)
+    X = torch.full((n, g), 7.0, dtype=torch.float32, device="cuda")  # padding must be overwritten with zeros
+    print(f"layer_vectors {out_features}x{in_features} g={g} {dt}", flush=True)
+    cc.layer_vectors(W, g, X)
+    want = L.prepare_matrix(W.float().cpu().numpy(), g)
+    assert X.cpu().numpy().tobytes() == want.tobytes()
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+def test_layer_pack_formats(cc, dt):
+    rng = np.random.default_rng(5)
+    K, g, n = 3001, 6, 50021
+    C = rng.standard_normal((K, g)).astype(np.float32) * np.float32(10.0) ** rng.integers(-12, 6, (K, g)).astype(np.float32)
+    C[0, :4] = [1.00390625, 1.01171875, 65520.0, 3.4e38]  # bf16 ties; fp16 overflow; bf16 overflow
+    C[1, :3] = [0.0, -0.0, 5.9e-8]
+    idx = rng.integers(0, K, size=n).astype(np.uint32)
+    idx[7] = K + 5  # clamped
+    book = torch.empty((K, g), dtype=TORCH_DT[dt], device="cuda")
+    codes = torch.empty(n, dtype=torch.uint16, device="cuda")
+    cc.layer_pack(_dev(C), book, _dev(idx.view(np.int32)).view(torch.uint32), codes)
+    want = L.bf16_round(C) if dt == "bf16" else L.fp16_round(C)
+    got = book.float().cpu().numpy()
+    assert got.tobytes() == want.tobytes()
+    want_codes = np.minimum(idx, K - 1).astype(np.uint16)
+    assert np.array_equal(codes.cpu().view(torch.int16).numpy().view(np.uint16), want_codes)
+    # either half alone
+    book2 = torch.empty_like(book)
+    cc.layer_pack(_dev(C), book2, None, None)
+    assert torch.equal(book2.view(torch.int16), book.view(torch.int16))
+    codes2 = torch.empty_like(codes)
+    cc.layer_pack(None, None, _dev(idx.view(np.int32)).view(torch.uint32), codes2, K=K)
+    assert torch.equal(codes2.view(torch.int16), codes.view(torch.int16))
+
+
+@pytest.mark.parametrize("dt", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("out_features,in_features,g", LAYER_SHAPES)
+def test_layer_weight_bit_exact(cc, out_features, in_features, g, dt):
+    rng = np.random.default_rng(out_features + 3 * in_features + g)
+    K = 977
+    book = _dev(rng.standard_normal((K, g)).astype(np.float32), TORCH_DT[dt])
+    n = L.num_codes(in_features, out_features, g)
+    codes_np = rng.integers(0, K, size=n).astype(np.uint16)
+    codes_np[0] = 60000  # >= K: clamped to K - 1
+    codes = _dev(codes_np.view(np.int16)).view(torch.uint16)
+    W = torch.zeros((in_features, out_features), dtype=TORCH_DT[dt], device="cuda")
+    print(f"layer_weight {out_features}x{in_features} g={g} {dt}", flush=True)
+    cc.layer_weight(book, codes, in_features, out_features, W)
+    ref_codes = np.minimum(codes_np, K - 1)
+    want = L.layer_weight(book.float().cpu().numpy(), ref_codes, in_features, out_features)
+    assert W.float().cpu().numpy().tobytes() == want.tobytes()
+
+
+def test_cluster_then_rebuild_round_trip(cc):
+    """vectors -> fit -> pack -> weight: the rebuilt weight equals the oracle's reconstruction from the same
+    (codebook, codes), and with K = N every vector is its own centroid, so the bf16 weight comes back exactly."""
+    from tests import gpu_helpers as g_
+
+    rng = np.random.default_rng(9)
+    out_features, in_features, g = 150, 64, 4
+    W = torch.from_numpy(rng.standard_normal((out_features, in_features)).astype(np.float32)).to(torch.bfloat16).cuda()
+    n = L.num_codes(in_features, out_features, g)
+    X = torch.empty((n, g), dtype=torch.float32, device="cuda")
+    cc.layer_vectors(W, g, X)
+    Xh = X.cpu().numpy()
+    C, idx, J, _ = g_.gpu_fit(Xh, Xh.copy(), 0)  # K = N, init = the vectors themselves
+    assert J == 0.0
+    book = torch.empty((n, g), dtype=torch.bfloat16, device="cuda")
+    codes = torch.empty(n, dtype=torch.uint16, device="cuda")
+    cc.layer_pack(_dev(C), book, _dev(idx.view(np.int32)).view(torch.uint32), codes)
+    back = torch.empty((in_features, out_features), dtype=torch.bfloat16, device="cuda")
+    cc.layer_weight(book, codes, in_features, out_features, back)
+    assert torch.equal(back, W.t().contiguous())
+
+
+@pytest.mark.parametrize("dt", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("out_features,in_features,g,K", [(256, 192, 4, 500), (250, 131, 4, 9000), (129, 67, 6, 300),
+                                                          (100, 300, 9, 64), (513, 300, 5, 8200), (7, 5, 7, 3),
+                                                          (600, 512, 8, 65536)])
+def test_codebook_grad(cc, out_features, in_features, g, K, dt):
+    rng = np.random.default_rng(out_features + in_features + g + K)
+    G = _dev(rng.standard_normal((in_features, out_features)).astype(np.float32) * 1e-3, TORCH_DT[dt])
+    n = L.num_codes(in_features, out_features, g)
+    codes_np = rng.integers(0, K, size=n).astype(np.uint16) if K < 65536 else rng.integers(0, K, size=n).astype(np.uint16)
+    codes = _dev(codes_np.view(np.int16)).view(torch.uint16)
+    out = torch.full((K, g), 3.0, dtype=torch.float32, device="cuda")
+    ws = torch.empty(cc.workspace_bytes(max(n, K), g, K), dtype=torch.uint8, device="cuda")
+    print(f"codebook_grad {out_features}x{in_features} g={g} K={K} {dt}", flush=True)
+    cc.layer_codebook_grad(G, codes, K, g, out, ws)
+    Gh = G.float().cpu().numpy()
+    want = L.gather_backward(Gh, codes_np, K, g)
+    got = out.cpu().numpy().astype(np.float64)
+    # per entry: fixed-point grid 2^-38 max|G| per term (exact for 16-bit inputs) + one fp32 rounding of the sum
+    absG = L.gather_backward(np.abs(Gh), codes_np, K, g)
+    counts = L.gather_backward(np.ones_like(Gh), codes_np, K, g)
+    tol = 2.0 ** -24 * absG + counts * 2.0 ** -38 * np.abs(Gh).max() + 1e-45
+    assert np.all(np.abs(got - want) <= tol), float(np.max(np.abs(got - want) / tol))
+    if dt != "f32":
+        assert np.array_equal(got, want.astype(np.float32).astype(np.float64))  # exact sums, one rounding
+    # deterministic
+    out2 = torch.empty_like(out)
+    cc.layer_codebook_grad(G, codes, K, g, out2, ws)
+    assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
