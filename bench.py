@@ -53,6 +53,46 @@ def cpu_baseline(w, X, C0, sample_log2=20):
     }
 
 
+def layer_kernels(cc, torch, timed, w, ws, idx, Cd):
+    """The layer's data path on the benchmark matrix taken as a linear weight [out = cols, in = rows] (so that its
+    transpose is the clustered matrix): reshape, storage formats, reconstruction, codebook gradient, forward."""
+    in_features, out_features, g, K = w.rows, w.cols, w.d, w.K
+    n = cc.layer_num_codes(in_features, out_features, g)
+    bf = torch.bfloat16
+    weight = (torch.randn(out_features, in_features, device="cuda") * 0.02).to(bf)
+    vectors = torch.empty(n, g, dtype=torch.float32, device="cuda")
+    book = torch.empty(K, g, dtype=bf, device="cuda")
+    codes = torch.empty(n, dtype=torch.uint16, device="cuda")
+    cc.layer_pack(Cd, book, idx, codes)
+    rebuilt = torch.empty(in_features, out_features, dtype=bf, device="cuda")
+    grad = torch.empty(K, g, dtype=torch.float32, device="cuda")
+    res = {}
+
+    def entry(name, ms, nbytes, bound="hbm"):
+        res[name] = {"bound": bound, "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "bytes_per_launch": nbytes, "avg_ms": ms}
+
+    entry("layer_vectors", timed(lambda: cc.layer_vectors(weight, g, vectors), reps=10), in_features * out_features * 6.0)
+    entry("layer_weight", timed(lambda: cc.layer_weight(book, codes, in_features, out_features, rebuilt), reps=10),
+          2.0 * n + 2.0 * K * g + 2.0 * in_features * out_features)
+    entry("layer_codebook_grad", timed(lambda: cc.layer_codebook_grad(rebuilt, codes, K, g, grad, ws)),
+          2.0 * in_features * out_features + 2.0 * n + 4.0 * K * g)
+    fwd = {}
+    for M in (1, 32):
+        x = torch.randn(M, in_features, device="cuda").to(bf)
+        y = torch.empty(M, out_features, dtype=bf, device="cuda")
+        fws = torch.empty(max(cc.layer_forward_workspace_bytes(M, in_features, out_features), 256), dtype=torch.uint8,
+                          device="cuda")
+        ms = timed(lambda: cc.layer_forward(x, book, codes, out_features, None, y, fws), reps=10)
+        dense_ms = timed(lambda: torch.matmul(x, rebuilt, out=y), reps=10)
+        # algorithmic traffic: the codes, the codebook once, x and y; the dense product reads the whole 16-bit weight
+        nbytes = 2.0 * n + 2.0 * K * g + 2.0 * M * (in_features + out_features)
+        fwd["M%d" % M] = {"avg_ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9, "bytes_per_launch": nbytes,
+                          "dense_matmul_on_rebuilt_weight_ms": dense_ms}
+    res["layer_forward"] = fwd
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -129,6 +169,8 @@ def main():
     update_ms = timed(lambda: cc.update(Xd, idx, Cd, Cn, None, ws))
     decode_ms = timed(lambda: cc.decode(Cd, idx, out), reps=10)
 
+    layer = layer_kernels(cc, torch, timed, w, ws, idx, Cd) if w.d == 4 and K <= 65536 else None
+
     if args.calibrate_copy:
         out.copy_(Xd)  # N*d*4 bytes read and as many written
         torch.cuda.synchronize()
@@ -170,6 +212,8 @@ def main():
         },
         "refined_vectors_per_assign": stats.refined_vectors / max(1, stats.assign_calls),
     }
+    if layer is not None:
+        line["layer_kernels"] = layer
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, X, C0)
     print(json.dumps(line))

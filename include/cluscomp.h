@@ -174,6 +174,21 @@ int cc_layer_weight(const void *codebook, int dtype, uint32_t K, uint32_t g, con
                     uint32_t in_features, uint32_t out_features, void *weight, void *stream);
 
 /*
+ * Forward pass of the layer (layer listing): y [M * out_features] = x [M * in_features] . W (+ bias), with W
+ * as rebuilt by cc_layer_weight but never written to memory: codebook rows are gathered straight into
+ * matrix-core operand tiles. x, codebook, bias (may be NULL) and y share one 16-bit dtype (CC_F16 or
+ * CC_BF16); products are exact, accumulation is fp32, y is rounded once (to nearest even). The summation
+ * order is fixed: same inputs, same bits. in_features must be a multiple of 8, M <= 2^22; x, y and codebook
+ * 16-byte aligned. Workspace (fp32 partial sums of the in-feature slices that fill the chip when M is small):
+ * cc_layer_forward_workspace_bytes(M, in_features, out_features) bytes, 256-byte aligned; may be NULL if
+ * that is 0.
+ */
+size_t cc_layer_forward_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features);
+int cc_layer_forward(const void *x, uint64_t M, const void *codebook, int dtype, uint32_t K, uint32_t g,
+                     const uint16_t *codes, uint32_t in_features, uint32_t out_features, const void *bias,
+                     void *y, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Gradient of the codebook (the only trainable tensor of the layer, Sections 3.2-3.3): every weight entry
  * is a copy of one codebook entry, so grad_codebook [K * g] (fp32) [k][j] is the sum of grad_weight
  * [in_features * out_features] (grad_dtype) over the entries rebuilt from codebook[k][j]. Sums are

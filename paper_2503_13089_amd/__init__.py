@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     last_error,
     layer_codebook_grad,
     layer_deficiency,
+    layer_forward,
+    layer_forward_workspace_bytes,
     layer_num_codes,
     layer_pack,
     layer_vectors,

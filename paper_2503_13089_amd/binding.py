@@ -16,7 +16,7 @@ EXPORTS = (
     "cc_workspace_bytes", "cc_kmeans_fit", "cc_assign", "cc_lloyd_iter", "cc_update", "cc_decode",
     "cc_read_stats", "cc_set_assign_mode", "cc_last_error", "cc_version",
     "cc_layer_deficiency", "cc_layer_num_codes", "cc_layer_vectors", "cc_layer_pack", "cc_layer_weight",
-    "cc_layer_codebook_grad",
+    "cc_layer_codebook_grad", "cc_layer_forward", "cc_layer_forward_workspace_bytes",
 )
 
 
@@ -84,6 +84,10 @@ def load_library():
     lib.cc_layer_pack.restype = ctypes.c_int
     lib.cc_layer_weight.argtypes = [vp, ctypes.c_int, u32, u32, vp, u32, u32, vp, vp]
     lib.cc_layer_weight.restype = ctypes.c_int
+    lib.cc_layer_forward_workspace_bytes.argtypes = [u64, u32, u32]
+    lib.cc_layer_forward_workspace_bytes.restype = sz
+    lib.cc_layer_forward.argtypes = [vp, u64, vp, ctypes.c_int, u32, u32, vp, u32, u32, vp, vp, vp, sz, vp]
+    lib.cc_layer_forward.restype = ctypes.c_int
     lib.cc_layer_codebook_grad.argtypes = [vp, ctypes.c_int, u32, u32, vp, u32, u32, vp, vp, sz, vp]
     lib.cc_layer_codebook_grad.restype = ctypes.c_int
     lib.cc_last_error.restype = ctypes.c_char_p
@@ -272,3 +276,21 @@ def layer_codebook_grad(grad_weight, codes, K: int, g: int, grad_codebook, works
                                                  out_features, _ptr(codes, torch.uint16, "codes"), K, g,
                                                  _ptr(grad_codebook, torch.float32, "grad_codebook"),
                                                  _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
+
+
+def layer_forward_workspace_bytes(M: int, in_features: int, out_features: int) -> int:
+    return load_library().cc_layer_forward_workspace_bytes(M, in_features, out_features)
+
+
+def layer_forward(x, codebook, codes, out_features: int, bias, y, workspace) -> None:
+    import torch
+
+    M, in_features = x.shape
+    K, g = codebook.shape
+    if x.dtype != codebook.dtype or y.dtype != codebook.dtype or (bias is not None and bias.dtype != codebook.dtype):
+        raise TypeError("x, codebook, bias and y must share one element type")
+    _check(load_library().cc_layer_forward(_any_ptr(x, "x"), M, _any_ptr(codebook, "codebook"), _dtype_code(codebook), K, g,
+                                           _ptr(codes, torch.uint16, "codes"), in_features, out_features,
+                                           _any_ptr(bias, "bias"), _any_ptr(y, "y"),
+                                           _ptr(workspace, torch.uint8, "workspace"),
+                                           workspace.numel() if workspace is not None else 0, _stream()))

@@ -369,6 +369,34 @@ int cc_layer_weight(const void* codebook, int dtype, uint32_t K, uint32_t g, con
     return CC_OK;
 }
 
+size_t cc_layer_forward_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features)
+{
+    if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;
+    const uint32_t splits = cc::layer_forward_splits(M, in_features, out_features);
+    return splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
+}
+
+int cc_layer_forward(const void* x, uint64_t M, const void* codebook, int dtype, uint32_t K, uint32_t g,
+                     const uint16_t* codes, uint32_t in_features, uint32_t out_features, const void* bias, void* y,
+                     void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !codebook || !codes || !y) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (int rc = check_layer(in_features, out_features, g, K, dtype, false)) return rc;
+    if (M == 0 || M > (1ull << 22)) return fail(CC_ERR_SHAPE, "M = %llu is not in 1..2^22", (unsigned long long)M);
+    if (in_features % 8 != 0) return fail(CC_ERR_SHAPE, "in_features = %u is not a multiple of 8", in_features);
+    if (!aligned(x, 16) || !aligned(y, 16) || !aligned(codebook, 16) || !aligned(codes, 2) || (bias && !aligned(bias, 2)))
+        return fail(CC_ERR_ALIGN, "x, y and codebook need 16-byte alignment");
+    const size_t need = cc_layer_forward_workspace_bytes(M, in_features, out_features);
+    if (need > 0) {
+        if (workspace == nullptr) return fail(CC_ERR_NULL, "workspace is NULL");
+        if (!aligned(workspace, 256)) return fail(CC_ERR_ALIGN, "workspace must be 256-byte aligned");
+        if (workspace_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    }
+    CC_TRY_HIP(cc::launch_layer_forward(x, uint32_t(M), codebook, dtype, K, g, codes, in_features, out_features, bias, y,
+                                        static_cast<float*>(workspace), static_cast<hipStream_t>(stream)), "layer forward");
+    return CC_OK;
+}
+
 int cc_layer_codebook_grad(const void* grad_weight, int grad_dtype, uint32_t in_features, uint32_t out_features,
                            const uint16_t* codes, uint32_t K, uint32_t g, float* grad_codebook, void* workspace,
                            size_t workspace_bytes, void* stream)

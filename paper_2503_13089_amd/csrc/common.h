@@ -266,6 +266,12 @@ hipError_t launch_layer_pack_codebook(const float* centroids, size_t n, void* co
 hipError_t launch_layer_pack_codes(const uint32_t* idx, uint64_t n, uint32_t K, uint16_t* codes, hipStream_t s);
 hipError_t launch_layer_weight(const void* codebook, int dtype, uint32_t K, uint32_t g, const uint16_t* codes,
                                uint32_t in_features, uint32_t out_features, void* weight, hipStream_t s);
+// y = x . W(codebook, codes) (+ bias); `partial` holds layer_forward_splits(...) * M * out_features floats if that
+// count is above 1
+uint32_t layer_forward_splits(uint64_t M, uint32_t in_features, uint32_t out_features);
+hipError_t launch_layer_forward(const void* x, uint32_t M, const void* codebook, int dtype, uint32_t K, uint32_t g,
+                                const uint16_t* codes, uint32_t in_features, uint32_t out_features, const void* bias,
+                                void* y, float* partial, hipStream_t s);
 // grad_weight [in, out] (dtype) -> fp32 vectors [num_codes][d_pad] (zero padding columns and components) and
 // codes widened to 32 bits
 hipError_t launch_layer_grad_vectors(const void* grad, int dtype, uint32_t in_features, uint32_t out_features,

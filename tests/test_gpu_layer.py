@@ -146,3 +146,66 @@ def test_codebook_grad(cc, out_features, in_features, g, K, dt):
     out2 = torch.empty_like(out)
     cc.layer_codebook_grad(G, codes, K, g, out2, ws)
     assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
+
+
+FORWARD_CASES = [  # (M, in_features, out_features, g, K, bias)
+    (1, 256, 192, 4, 500, False),
+    (7, 512, 250, 4, 9000, True),     # padding columns, ragged column tile
+    (33, 136, 129, 6, 300, True),     # in_features not a multiple of the 64-wide step; codes straddle column tiles
+    (64, 128, 100, 9, 64, False),
+    (130, 320, 513, 5, 8200, True),   # three row tiles of 128/2/...; odd g
+    (32, 1024, 1024, 8, 65536, True),
+    (5, 64, 70, 7, 3, False),
+    (200, 4096, 256, 4, 65536, False),
+]
+
+
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("M,in_features,out_features,g,K,with_bias", FORWARD_CASES)
+def test_layer_forward(cc, M, in_features, out_features, g, K, with_bias, dt):
+    rng = np.random.default_rng(M + in_features + out_features + g)
+    T = TORCH_DT[dt]
+    x = _dev(rng.standard_normal((M, in_features)).astype(np.float32), T)
+    book = _dev(rng.standard_normal((K, g)).astype(np.float32) * 0.05, T)
+    bias = _dev(rng.standard_normal(out_features).astype(np.float32), T) if with_bias else None
+    n = L.num_codes(in_features, out_features, g)
+    codes_np = rng.integers(0, K, size=n).astype(np.uint16)
+    codes = _dev(codes_np.view(np.int16)).view(torch.uint16)
+    y = torch.full((M, out_features), 9.0, dtype=T, device="cuda")
+    nbytes = cc.layer_forward_workspace_bytes(M, in_features, out_features)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    print(f"layer_forward M={M} {in_features}->{out_features} g={g} K={K} {dt} ws={nbytes}", flush=True)
+    cc.layer_forward(x, book, codes, out_features, bias, y, ws)
+    xh, bh = x.float().cpu().numpy(), book.float().cpu().numpy()
+    biash = bias.float().cpu().numpy() if with_bias else None
+    want = L.layer_forward(xh, bh, codes_np, in_features, out_features, biash)
+    # products of two 16-bit values are exact in fp32; the fp32 accumulation of in_features terms (in whatever
+    # order) is off by at most in_features * 2^-24 * sum|terms|; then one rounding to the 16-bit output format
+    mag = L.layer_forward(np.abs(xh), np.abs(bh), codes_np, in_features, out_features,
+                          np.abs(biash) if with_bias else None)
+    half_ulp = 2.0 ** -8 if dt == "bf16" else 2.0 ** -11
+    got = y.float().cpu().numpy().astype(np.float64)
+    tol = half_ulp * np.abs(want) + in_features * 2.0 ** -24 * mag + (2.0 ** -24 if dt == "f16" else 1e-38)
+    bad = np.abs(got - want) > tol
+    assert not bad.any(), (int(bad.sum()), float(np.max(np.abs(got - want) / tol)))
+    # same inputs, same bits
+    y2 = torch.empty_like(y)
+    cc.layer_forward(x, book, codes, out_features, bias, y2, ws)
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+
+
+def test_layer_forward_reads_out_single_weight_rows(cc):
+    """One-hot inputs: y must equal rows of the reconstructed weight exactly (no arithmetic error possible)."""
+    rng = np.random.default_rng(2)
+    in_features, out_features, g, K = 128, 200, 4, 1000
+    book = _dev(rng.standard_normal((K, g)).astype(np.float32), torch.bfloat16)
+    n = L.num_codes(in_features, out_features, g)
+    codes = _dev(rng.integers(0, K, size=n).astype(np.uint16).view(np.int16)).view(torch.uint16)
+    x = torch.eye(in_features, dtype=torch.bfloat16, device="cuda")
+    y = torch.empty((in_features, out_features), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(max(cc.layer_forward_workspace_bytes(in_features, in_features, out_features), 256), dtype=torch.uint8,
+                     device="cuda")
+    cc.layer_forward(x, book, codes, out_features, None, y, ws)
+    W = torch.empty_like(y)
+    cc.layer_weight(book, codes, in_features, out_features, W)
+    assert torch.equal(y.view(torch.int16), W.view(torch.int16))
