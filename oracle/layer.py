@@ -92,3 +92,46 @@ def gather_backward(grad_weight, codes, num_clusters: int, g: int):
     G = np.zeros((num_clusters, g), dtype=np.float64)
     np.add.at(G, np.asarray(codes, dtype=np.int64), padded.reshape(-1, g))  # unbuffered: repeated codes accumulate
     return G
+
+
+# ---- uniformly quantised codebook (the paper's inference-only variant: Section 2's symmetric uniform grid
+# applied to the codebook, Section 4.4 / the codebook-quantisation appendix) ------------------------------
+
+def quantize_codebook(codebook, bits: int):
+    """Symmetric uniform quantisation of a whole codebook with one scale: q = clamp(round(c / s), -2^(b-1),
+    2^(b-1) - 1), round = to nearest (ties to even), s = max|c| / (2^(b-1) - 1), so that the grid spans the
+    codebook's range. (The background formula prints 2^b - 1 under the scale, which together with its own
+    clamp would clip everything above half the range; the reading taken here is the one under which the
+    clamp is a safeguard only.) The paper does not fix the arithmetic: scale and quotient are taken in fp32,
+    the precision of the device code, because they decide integers. Returns (q as int8, s as float32)."""
+    c = np.ascontiguousarray(codebook, dtype=np.float32)
+    qmax = np.float32(2 ** (bits - 1) - 1)
+    s = np.float32(np.max(np.abs(c)) / qmax) if c.size else np.float32(0.0)
+    if s == 0.0 or not np.isfinite(s):
+        return np.zeros(c.shape, dtype=np.int8), np.float32(0.0)
+    q = np.rint(np.divide(c, s, dtype=np.float32))
+    q = np.clip(q, -(2 ** (bits - 1)), 2 ** (bits - 1) - 1)
+    return q.astype(np.int8), s
+
+
+def dequantize_codebook(q, scale, fmt: str = "bf16"):
+    """c_hat = q * s in fp32, then rounded to the 16-bit format the layer computes in (returned as fp32)."""
+    v = np.multiply(np.asarray(q, dtype=np.float32), np.float32(scale), dtype=np.float32)
+    return bf16_round(v) if fmt == "bf16" else fp16_round(v)
+
+
+def pack_int4(q):
+    """Two's-complement nibbles in element order: element e sits in byte e // 2, low nibble first."""
+    flat = (np.asarray(q, dtype=np.int8).reshape(-1).astype(np.int16) & 0xF).astype(np.uint8)
+    if flat.size % 2:
+        flat = np.concatenate([flat, np.zeros(1, np.uint8)])
+    return (flat[0::2] | (flat[1::2] << 4)).astype(np.uint8)
+
+
+def unpack_int4(packed, count: int):
+    p = np.asarray(packed, dtype=np.uint8)
+    nib = np.empty(p.size * 2, dtype=np.int16)
+    nib[0::2] = p & 0xF
+    nib[1::2] = p >> 4
+    nib = np.where(nib >= 8, nib - 16, nib)
+    return nib[:count].astype(np.int8)

@@ -116,3 +116,67 @@ def test_gather_backward_matches_autograd_and_bruteforce(g, out_features):
     assert got.sum() == pytest.approx(G.sum(), rel=1e-12)
     unused = np.setdiff1d(np.arange(K), codes)
     assert np.all(got[unused] == 0.0)
+
+
+# ------------------------------------------------------------------ uniformly quantised codebook
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_quantize_codebook_grid_properties(bits):
+    rng = np.random.default_rng(17 + bits)
+    C = (rng.standard_normal((500, 4)) * 0.02).astype(np.float32)
+    C[3, 1] = 0.31  # the extreme value
+    q, s = layer.quantize_codebook(C, bits)
+    qmax = 2 ** (bits - 1) - 1
+    assert q.dtype == np.int8 and q.min() >= -qmax and q.max() == qmax and q[3, 1] == qmax
+    assert s == np.float32(np.float32(0.31) / np.float32(qmax))
+    # nearest grid point: error at most half a step (plus the rounding of the fp32 quotient)
+    err = np.abs(q.astype(np.float64) * float(s) - C.astype(np.float64))
+    assert err.max() <= 0.5 * float(s) * (1 + 1e-6)
+    # odd symmetry, and grid points are fixed points
+    qn, sn = layer.quantize_codebook(-C, bits)
+    assert sn == s and np.array_equal(qn, -q)
+    grid = (np.arange(-qmax, qmax + 1, dtype=np.float32) * s).reshape(-1, 1)
+    qg, sg = layer.quantize_codebook(grid, bits)
+    assert sg == s and np.array_equal(qg.reshape(-1), np.arange(-qmax, qmax + 1))
+    # all-zero codebook: scale 0, codes 0, no division by zero
+    q0, s0 = layer.quantize_codebook(np.zeros((3, 4), np.float32), bits)
+    assert s0 == 0.0 and not q0.any()
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_quantize_codebook_matches_exact_rational_rounding(bits):
+    """Away from ties (where the fp32 quotient could round either way) the integer is the exact nearest one."""
+    from fractions import Fraction
+
+    rng = np.random.default_rng(23 + bits)
+    C = (rng.standard_normal((40, 3)) * 0.1).astype(np.float32)
+    q, s = layer.quantize_codebook(C, bits)
+    qmax = 2 ** (bits - 1) - 1
+    checked = 0
+    for c, got in zip(C.reshape(-1), q.reshape(-1)):
+        t = Fraction(float(c)) / Fraction(float(s))
+        lo = t.numerator // t.denominator
+        frac = t - lo
+        if abs(frac - Fraction(1, 2)) < Fraction(1, 10 ** 5):
+            continue
+        want = lo + (1 if frac > Fraction(1, 2) else 0)
+        want = max(-(qmax + 1), min(qmax, want))
+        assert got == want
+        checked += 1
+    assert checked > 100
+
+
+def test_dequantize_and_nibble_packing():
+    rng = np.random.default_rng(29)
+    q = rng.integers(-8, 8, size=(33, 5)).astype(np.int8)
+    packed = layer.pack_int4(q)
+    assert packed.size == (q.size + 1) // 2
+    assert np.array_equal(layer.unpack_int4(packed, q.size).reshape(q.shape), q)
+    # element 0 in the low nibble of byte 0, element 1 in its high nibble; -1 is 0xF
+    assert layer.pack_int4(np.array([-1, 2, 7, -8], np.int8)).tolist() == [0x2F, 0x87]
+    s = np.float32(0.0123)
+    d = layer.dequantize_codebook(q, s, "bf16")
+    want = torch.from_numpy(q.astype(np.float32) * s).to(torch.bfloat16).to(torch.float32).numpy()
+    assert d.tobytes() == want.tobytes()
+    d16 = layer.dequantize_codebook(q, s, "f16")
+    assert d16.tobytes() == (q.astype(np.float32) * s).astype(np.float16).astype(np.float32).tobytes()
