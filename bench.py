@@ -90,6 +90,23 @@ def layer_kernels(cc, torch, timed, w, ws, idx, Cd):
         fwd["M%d" % M] = {"avg_ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9, "bytes_per_launch": nbytes,
                           "dense_matmul_on_rebuilt_weight_ms": dense_ms}
     res["layer_forward"] = fwd
+    # the paper's inference variant: codebook quantised to 4 bits (128 KB: held in LDS by persistent workgroups)
+    qbook = torch.empty(K * g // 2, dtype=torch.uint8, device="cuda")
+    scale = torch.zeros(1, dtype=torch.float32, device="cuda")
+    scratch = torch.zeros(4, dtype=torch.uint8, device="cuda")
+    cc.codebook_quantize(Cd, 4, qbook, scale, scratch)
+    entry("layer_weight_q4", timed(lambda: cc.layer_weight_q(qbook, 4, scale, K, g, codes, in_features, out_features, rebuilt),
+                                   reps=10), 2.0 * n + 0.5 * K * g + 2.0 * in_features * out_features)
+    fq = {}
+    for M in (1, 8):
+        x = torch.randn(M, in_features, device="cuda").to(bf)
+        y = torch.empty(M, out_features, dtype=bf, device="cuda")
+        fws = torch.empty(max(cc.layer_forward_q_workspace_bytes(M, in_features, out_features), 256), dtype=torch.uint8,
+                          device="cuda")
+        ms = timed(lambda: cc.layer_forward_q(x, qbook, 4, scale, K, g, codes, out_features, None, y, fws), reps=10)
+        nbytes = 2.0 * n + 0.5 * K * g + 2.0 * M * (in_features + out_features)
+        fq["M%d" % M] = {"avg_ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9, "bytes_per_launch": nbytes}
+    res["layer_forward_q4"] = fq
     return res
 
 

@@ -200,6 +200,37 @@ int cc_layer_codebook_grad(const void *grad_weight, int grad_dtype, uint32_t in_
                            const uint16_t *codes, uint32_t K, uint32_t g, float *grad_codebook,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Uniformly quantised codebook (the paper's inference-only variant: "#Bits for Codebook" 8 and 4 in its
+ * throughput and perplexity tables; the grid is the symmetric uniform one of Section 2).
+ * One scale per codebook: s = max|c| / (2^(bits-1) - 1), q = clamp(round_to_nearest_even(c / s),
+ * -2^(bits-1), 2^(bits-1) - 1), both in fp32; the dequantised entry is q * s (fp32) rounded to the layer's
+ * 16-bit format. Storage: bits = 8: int8 [K * g]; bits = 4: two's-complement nibbles, element e in byte
+ * e / 2, low nibble first, ceil(K * g / 2) bytes. A codebook of at most 128 KB (K = 65536, g = 4 at 4 bits)
+ * is held in LDS by persistent workgroups, which lifts the one-cache-miss-per-code limit of the 16-bit path.
+ */
+
+/* centroids [K * g] fp32 -> qbook (layout above) and scale [1] (device, fp32). `scratch` is 4 bytes of
+ * device memory (4-byte aligned) used for the maximum. bits must be 8 or 4. */
+int cc_codebook_quantize(const float *centroids, uint32_t K, uint32_t g, int bits, void *qbook, float *scale,
+                         void *scratch, void *stream);
+
+/* cc_layer_weight with the quantised codebook: weight [in_features * out_features] in `dtype` (CC_F16 or
+ * CC_BF16), bit-exact with respect to the dequantisation rule above. */
+int cc_layer_weight_q(const void *qbook, int bits, const float *scale, uint32_t K, uint32_t g,
+                      const uint16_t *codes, uint32_t in_features, uint32_t out_features, int dtype, void *weight,
+                      void *stream);
+
+/* cc_layer_forward with the quantised codebook (x, bias, y in `dtype`): y = s * (x . Q) (+ bias), where Q is the
+ * weight rebuilt from the integers q themselves. The products x * q are exact, the sum is fp32, the scale
+ * multiplies the finished sum, and y is rounded once - so this is slightly more accurate than a product with
+ * the 16-bit weight of cc_layer_weight_q, whose entries are each rounded to 16 bits. Same contract otherwise.
+ * Workspace: cc_layer_forward_q_workspace_bytes(M, in_features, out_features). */
+size_t cc_layer_forward_q_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features);
+int cc_layer_forward_q(const void *x, uint64_t M, const void *qbook, int bits, const float *scale, uint32_t K,
+                       uint32_t g, const uint16_t *codes, uint32_t in_features, uint32_t out_features,
+                       const void *bias, void *y, int dtype, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Selects the E-step kernel. 0 = automatic (default): for K >= 128 the matrix cores, with the fp16 MFMA
  * (centroids split into three fp16 parts, exact products) when every input is an fp16 number and
  * the fp32 MFMA otherwise, both with guard band + direct-form refinement; direct form for small K;

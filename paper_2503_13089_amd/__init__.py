@@ -8,17 +8,21 @@ from .binding import (  # noqa: F401
     CCError,
     Stats,
     assign,
+    codebook_quantize,
     decode,
     kmeans_fit,
     last_error,
     layer_codebook_grad,
     layer_deficiency,
     layer_forward,
+    layer_forward_q,
+    layer_forward_q_workspace_bytes,
     layer_forward_workspace_bytes,
     layer_num_codes,
     layer_pack,
     layer_vectors,
     layer_weight,
+    layer_weight_q,
     lib_path,
     lloyd_iter,
     load_library,

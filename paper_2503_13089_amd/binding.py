@@ -17,6 +17,7 @@ EXPORTS = (
     "cc_read_stats", "cc_set_assign_mode", "cc_last_error", "cc_version",
     "cc_layer_deficiency", "cc_layer_num_codes", "cc_layer_vectors", "cc_layer_pack", "cc_layer_weight",
     "cc_layer_codebook_grad", "cc_layer_forward", "cc_layer_forward_workspace_bytes",
+    "cc_codebook_quantize", "cc_layer_weight_q", "cc_layer_forward_q", "cc_layer_forward_q_workspace_bytes",
 )
 
 
@@ -88,6 +89,14 @@ def load_library():
     lib.cc_layer_forward_workspace_bytes.restype = sz
     lib.cc_layer_forward.argtypes = [vp, u64, vp, ctypes.c_int, u32, u32, vp, u32, u32, vp, vp, vp, sz, vp]
     lib.cc_layer_forward.restype = ctypes.c_int
+    lib.cc_codebook_quantize.argtypes = [vp, u32, u32, ctypes.c_int, vp, vp, vp, vp]
+    lib.cc_codebook_quantize.restype = ctypes.c_int
+    lib.cc_layer_weight_q.argtypes = [vp, ctypes.c_int, vp, u32, u32, vp, u32, u32, ctypes.c_int, vp, vp]
+    lib.cc_layer_weight_q.restype = ctypes.c_int
+    lib.cc_layer_forward_q_workspace_bytes.argtypes = [u64, u32, u32]
+    lib.cc_layer_forward_q_workspace_bytes.restype = sz
+    lib.cc_layer_forward_q.argtypes = [vp, u64, vp, ctypes.c_int, vp, u32, u32, vp, u32, u32, vp, vp, ctypes.c_int, vp, sz, vp]
+    lib.cc_layer_forward_q.restype = ctypes.c_int
     lib.cc_layer_codebook_grad.argtypes = [vp, ctypes.c_int, u32, u32, vp, u32, u32, vp, vp, sz, vp]
     lib.cc_layer_codebook_grad.restype = ctypes.c_int
     lib.cc_last_error.restype = ctypes.c_char_p
@@ -294,3 +303,40 @@ def layer_forward(x, codebook, codes, out_features: int, bias, y, workspace) -> 
                                            _any_ptr(bias, "bias"), _any_ptr(y, "y"),
                                            _ptr(workspace, torch.uint8, "workspace"),
                                            workspace.numel() if workspace is not None else 0, _stream()))
+
+
+# ---- uniformly quantised codebook --------------------------------------------------------------------
+
+def codebook_quantize(centroids, bits: int, qbook, scale, scratch) -> None:
+    """qbook: uint8 tensor of K*g (8 bits) or ceil(K*g/2) (4 bits) bytes; scale: 1 float32; scratch: >= 4 bytes."""
+    import torch
+
+    K, g = centroids.shape
+    _check(load_library().cc_codebook_quantize(_ptr(centroids, torch.float32, "centroids"), K, g, bits,
+                                               _ptr(qbook, torch.uint8, "qbook"), _ptr(scale, torch.float32, "scale"),
+                                               _ptr(scratch, torch.uint8, "scratch"), _stream()))
+
+
+def layer_weight_q(qbook, bits: int, scale, K: int, g: int, codes, in_features: int, out_features: int, weight) -> None:
+    import torch
+
+    _check(load_library().cc_layer_weight_q(_ptr(qbook, torch.uint8, "qbook"), bits, _ptr(scale, torch.float32, "scale"), K, g,
+                                            _ptr(codes, torch.uint16, "codes"), in_features, out_features,
+                                            _dtype_code(weight), _any_ptr(weight, "weight"), _stream()))
+
+
+def layer_forward_q_workspace_bytes(M: int, in_features: int, out_features: int) -> int:
+    return load_library().cc_layer_forward_q_workspace_bytes(M, in_features, out_features)
+
+
+def layer_forward_q(x, qbook, bits: int, scale, K: int, g: int, codes, out_features: int, bias, y, workspace) -> None:
+    import torch
+
+    M, in_features = x.shape
+    if y.dtype != x.dtype or (bias is not None and bias.dtype != x.dtype):
+        raise TypeError("x, bias and y must share one element type")
+    _check(load_library().cc_layer_forward_q(_any_ptr(x, "x"), M, _ptr(qbook, torch.uint8, "qbook"), bits,
+                                             _ptr(scale, torch.float32, "scale"), K, g, _ptr(codes, torch.uint16, "codes"),
+                                             in_features, out_features, _any_ptr(bias, "bias"), _any_ptr(y, "y"),
+                                             _dtype_code(x), _ptr(workspace, torch.uint8, "workspace"),
+                                             workspace.numel() if workspace is not None else 0, _stream()))

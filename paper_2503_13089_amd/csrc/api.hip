@@ -427,6 +427,65 @@ int cc_layer_codebook_grad(const void* grad_weight, int grad_dtype, uint32_t in_
     return CC_OK;
 }
 
+// ---- uniformly quantised codebook ---------------------------------------------------------------
+
+int cc_codebook_quantize(const float* centroids, uint32_t K, uint32_t g, int bits, void* qbook, float* scale,
+                         void* scratch, void* stream)
+{
+    if (!centroids || !qbook || !scale || !scratch) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (K == 0 || K > 65536) return fail(CC_ERR_SHAPE, "K = %u does not fit 16-bit codes", K);
+    if (g == 0 || g > 16) return fail(CC_ERR_SHAPE, "g = %u is not supported (1..16)", g);
+    if (bits != 8 && bits != 4) return fail(CC_ERR_SHAPE, "bits = %d is not supported (8, 4)", bits);
+    if (!aligned(centroids, 4) || !aligned(scale, 4) || !aligned(scratch, 4)) return fail(CC_ERR_ALIGN, "misaligned pointer");
+    CC_TRY_HIP(cc::launch_codebook_quantize(centroids, size_t(K) * g, bits, qbook, scale, static_cast<uint32_t*>(scratch),
+                                            static_cast<hipStream_t>(stream)), "codebook quantisation");
+    return CC_OK;
+}
+
+int cc_layer_weight_q(const void* qbook, int bits, const float* scale, uint32_t K, uint32_t g, const uint16_t* codes,
+                      uint32_t in_features, uint32_t out_features, int dtype, void* weight, void* stream)
+{
+    if (!qbook || !scale || !codes || !weight) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (int rc = check_layer(in_features, out_features, g, K, dtype, false)) return rc;
+    if (bits != 8 && bits != 4) return fail(CC_ERR_SHAPE, "bits = %d is not supported (8, 4)", bits);
+    if (!aligned(qbook, 16) || !aligned(weight, 16) || !aligned(codes, 2) || !aligned(scale, 4))
+        return fail(CC_ERR_ALIGN, "qbook/weight need 16-byte alignment, codes 2, scale 4");
+    CC_TRY_HIP(cc::launch_layer_weight_q(qbook, bits, scale, K, g, codes, in_features, out_features, dtype, weight,
+                                         static_cast<hipStream_t>(stream)), "layer weight (quantised codebook)");
+    return CC_OK;
+}
+
+size_t cc_layer_forward_q_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features)
+{
+    if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;
+    const uint32_t splits = cc::layer_forward_q_max_splits(M, in_features, out_features);
+    return splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
+}
+
+int cc_layer_forward_q(const void* x, uint64_t M, const void* qbook, int bits, const float* scale, uint32_t K, uint32_t g,
+                       const uint16_t* codes, uint32_t in_features, uint32_t out_features, const void* bias, void* y,
+                       int dtype, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !qbook || !scale || !codes || !y) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (int rc = check_layer(in_features, out_features, g, K, dtype, false)) return rc;
+    if (bits != 8 && bits != 4) return fail(CC_ERR_SHAPE, "bits = %d is not supported (8, 4)", bits);
+    if (M == 0 || M > (1ull << 22)) return fail(CC_ERR_SHAPE, "M = %llu is not in 1..2^22", (unsigned long long)M);
+    if (in_features % 8 != 0) return fail(CC_ERR_SHAPE, "in_features = %u is not a multiple of 8", in_features);
+    if (!aligned(x, 16) || !aligned(y, 16) || !aligned(qbook, 16) || !aligned(codes, 2) || !aligned(scale, 4) ||
+        (bias && !aligned(bias, 2)))
+        return fail(CC_ERR_ALIGN, "x, y and qbook need 16-byte alignment");
+    const size_t need = cc_layer_forward_q_workspace_bytes(M, in_features, out_features);
+    if (need > 0) {
+        if (workspace == nullptr) return fail(CC_ERR_NULL, "workspace is NULL");
+        if (!aligned(workspace, 256)) return fail(CC_ERR_ALIGN, "workspace must be 256-byte aligned");
+        if (workspace_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    }
+    CC_TRY_HIP(cc::launch_layer_forward_q(x, uint32_t(M), qbook, bits, scale, K, g, codes, in_features, out_features, bias, y,
+                                          dtype, static_cast<float*>(workspace), static_cast<hipStream_t>(stream)),
+               "layer forward (quantised codebook)");
+    return CC_OK;
+}
+
 int cc_read_stats(const void* workspace, size_t workspace_bytes, cc_stats* host_out, void* stream)
 {
     if (!workspace || !host_out) return fail(CC_ERR_NULL, "a required pointer is NULL");

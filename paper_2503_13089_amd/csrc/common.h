@@ -272,6 +272,16 @@ uint32_t layer_forward_splits(uint64_t M, uint32_t in_features, uint32_t out_fea
 hipError_t launch_layer_forward(const void* x, uint32_t M, const void* codebook, int dtype, uint32_t K, uint32_t g,
                                 const uint16_t* codes, uint32_t in_features, uint32_t out_features, const void* bias,
                                 void* y, float* partial, hipStream_t s);
+// ---- uniformly quantised codebook (layer_quant.hip); bits = 8 or 4
+hipError_t launch_codebook_quantize(const float* centroids, size_t n, int bits, void* qbook, float* scale,
+                                    uint32_t* absmax_scratch, hipStream_t s);
+hipError_t launch_layer_weight_q(const void* qbook, int bits, const float* scale, uint32_t K, uint32_t g,
+                                 const uint16_t* codes, uint32_t in_features, uint32_t out_features, int dtype, void* weight,
+                                 hipStream_t s);
+uint32_t layer_forward_q_max_splits(uint64_t M, uint32_t in_features, uint32_t out_features);
+hipError_t launch_layer_forward_q(const void* x, uint32_t M, const void* qbook, int bits, const float* scale, uint32_t K,
+                                  uint32_t g, const uint16_t* codes, uint32_t in_features, uint32_t out_features,
+                                  const void* bias, void* y, int dtype, float* partial, hipStream_t s);
 // grad_weight [in, out] (dtype) -> fp32 vectors [num_codes][d_pad] (zero padding columns and components) and
 // codes widened to 32 bits
 hipError_t launch_layer_grad_vectors(const void* grad, int dtype, uint32_t in_features, uint32_t out_features,

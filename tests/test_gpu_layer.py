@@ -209,3 +209,91 @@ def test_layer_forward_reads_out_single_weight_rows(cc):
     W = torch.empty_like(y)
     cc.layer_weight(book, codes, in_features, out_features, W)
     assert torch.equal(y.view(torch.int16), W.view(torch.int16))
+
+
+# ------------------------------------------------------------------ uniformly quantised codebook
+
+def _quantize_on_gpu(cc, C, bits):
+    K, g = C.shape
+    nbytes = K * g if bits == 8 else (K * g + 1) // 2
+    qbook = torch.zeros(nbytes + 16, dtype=torch.uint8, device="cuda")[:nbytes]
+    scale = torch.zeros(1, dtype=torch.float32, device="cuda")
+    scratch = torch.zeros(4, dtype=torch.uint8, device="cuda")
+    cc.codebook_quantize(_dev(C), bits, qbook, scale, scratch)
+    return qbook, scale
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("K,g", [(65536, 4), (3001, 6), (500, 9), (7, 5), (1, 1), (4096, 8)])
+def test_codebook_quantize_bit_exact(cc, K, g, bits):
+    rng = np.random.default_rng(K + g + bits)
+    C = (rng.standard_normal((K, g)) * 0.02).astype(np.float32)
+    C[0, 0] = 0.25  # the extreme entry defines the scale
+    qbook, scale = _quantize_on_gpu(cc, C, bits)
+    q, s = L.quantize_codebook(C, bits)
+    assert scale.cpu().numpy()[0] == s
+    want = q.reshape(-1).view(np.uint8) if bits == 8 else L.pack_int4(q)
+    assert np.array_equal(qbook.cpu().numpy(), want)
+    # all-zero codebook
+    qz, sz = _quantize_on_gpu(cc, np.zeros((K, g), np.float32), bits)
+    assert sz.item() == 0.0 and not qz.any().item()
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("out_features,in_features,g,K", [(256, 192, 4, 65536), (250, 131, 4, 9000), (129, 67, 6, 300),
+                                                          (100, 300, 9, 64), (513, 70, 5, 8200), (64, 64, 8, 65536),
+                                                          (7, 5, 7, 3)])
+def test_layer_weight_q_bit_exact(cc, out_features, in_features, g, K, dt, bits):
+    """Covers codebooks that fit LDS (<= 128 KB) and ones that do not (65536 x 4 at 8 bits, 65536 x 8)."""
+    rng = np.random.default_rng(out_features + in_features + g + K + bits)
+    C = (rng.standard_normal((K, g)) * 0.02).astype(np.float32)
+    q, s = L.quantize_codebook(C, bits)
+    qbook, scale = _quantize_on_gpu(cc, C, bits)
+    n = L.num_codes(in_features, out_features, g)
+    codes_np = rng.integers(0, K, size=n).astype(np.uint16)
+    codes = _dev(codes_np.view(np.int16)).view(torch.uint16)
+    W = torch.zeros((in_features, out_features), dtype=TORCH_DT[dt], device="cuda")
+    print(f"layer_weight_q {out_features}x{in_features} g={g} K={K} {dt} bits={bits}", flush=True)
+    cc.layer_weight_q(qbook, bits, scale, K, g, codes, in_features, out_features, W)
+    want = L.layer_weight(L.dequantize_codebook(q, s, dt), codes_np, in_features, out_features)
+    assert W.float().cpu().numpy().tobytes() == want.tobytes()
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("dt", ["f16", "bf16"])
+@pytest.mark.parametrize("M,in_features,out_features,g,K,with_bias", FORWARD_CASES + [(3, 2048, 1024, 4, 65536, True)])
+def test_layer_forward_q(cc, M, in_features, out_features, g, K, with_bias, dt, bits):
+    rng = np.random.default_rng(M + in_features + out_features + g + bits)
+    T = TORCH_DT[dt]
+    x = _dev(rng.standard_normal((M, in_features)).astype(np.float32), T)
+    C = (rng.standard_normal((K, g)) * 0.05).astype(np.float32)
+    q, s = L.quantize_codebook(C, bits)
+    qbook, scale = _quantize_on_gpu(cc, C, bits)
+    bias = _dev(rng.standard_normal(out_features).astype(np.float32), T) if with_bias else None
+    n = L.num_codes(in_features, out_features, g)
+    codes_np = rng.integers(0, K, size=n).astype(np.uint16)
+    codes = _dev(codes_np.view(np.int16)).view(torch.uint16)
+    y = torch.full((M, out_features), 9.0, dtype=T, device="cuda")
+    nbytes = cc.layer_forward_q_workspace_bytes(M, in_features, out_features)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    print(f"layer_forward_q M={M} {in_features}->{out_features} g={g} K={K} {dt} bits={bits} ws={nbytes}", flush=True)
+    cc.layer_forward_q(x, qbook, bits, scale, K, g, codes, out_features, bias, y, ws)
+    # definition: y = s * (x . Q) + bias with Q rebuilt from the integers q; fp64 here
+    xh = x.float().cpu().numpy()
+    biash = bias.float().cpu().numpy() if with_bias else None
+    want = float(s) * L.layer_forward(xh, q.astype(np.float64), codes_np, in_features, out_features)
+    # fp32 accumulation of exact products, possibly taken with the storage offset 2^(bits-1) left in
+    mag = float(s) * L.layer_forward(np.abs(xh), np.abs(q.astype(np.float64)) + 2.0 ** (bits - 1), codes_np, in_features,
+                                     out_features)
+    if with_bias:
+        want = want + biash.astype(np.float64)[None, :]
+        mag = mag + np.abs(biash.astype(np.float64))[None, :]
+    half_ulp = 2.0 ** -8 if dt == "bf16" else 2.0 ** -11
+    got = y.float().cpu().numpy().astype(np.float64)
+    tol = half_ulp * np.abs(want) + in_features * 2.0 ** -24 * mag + (2.0 ** -24 if dt == "f16" else 1e-38)
+    bad = np.abs(got - want) > tol
+    assert not bad.any(), (int(bad.sum()), float(np.max(np.abs(got - want) / tol)))
+    y2 = torch.empty_like(y)
+    cc.layer_forward_q(x, qbook, bits, scale, K, g, codes, out_features, bias, y2, ws)
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
