@@ -106,6 +106,32 @@ def test_layer_entry_points_reject_bad_arguments():
     assert lib.cc_layer_codebook_grad(A16, F32, 8, 8, A16, 10, 4, A16, ctypes.c_void_p(0x1010), 1 << 30, None) == -4
 
 
+def test_forward_and_quantised_entry_points_reject_bad_arguments():
+    lib = cc.load_library()
+    F32, F16, BF16 = 0, 1, 2
+    WS = ctypes.c_void_p(0x1100)
+    assert lib.cc_layer_forward_workspace_bytes(0, 64, 64) == 0
+    assert lib.cc_layer_forward_workspace_bytes(1, 4096, 4096) % 256 == 0 and lib.cc_layer_forward_workspace_bytes(1, 4096, 4096) > 0
+    assert lib.cc_layer_forward(None, 1, A16, BF16, 10, 4, A16, 64, 64, None, A16, WS, 1 << 30, None) == -1
+    assert lib.cc_layer_forward(A16, 0, A16, BF16, 10, 4, A16, 64, 64, None, A16, WS, 1 << 30, None) == -2
+    assert lib.cc_layer_forward(A16, 1, A16, F32, 10, 4, A16, 64, 64, None, A16, WS, 1 << 30, None) == -2  # 16-bit only
+    assert lib.cc_layer_forward(A16, 1, A16, BF16, 10, 4, A16, 60, 64, None, A16, WS, 1 << 30, None) == -2
+    assert "multiple of 8" in cc.last_error()
+    assert lib.cc_layer_forward(A16, 1, A16, BF16, 10, 4, A16, 64, 64, None, MISALIGNED, WS, 1 << 30, None) == -4
+    assert lib.cc_layer_forward(A16, 1, A16, BF16, 10, 4, A16, 4096, 4096, None, A16, None, 0, None) == -1
+    assert lib.cc_layer_forward(A16, 1, A16, BF16, 10, 4, A16, 4096, 4096, None, A16, WS, 16, None) == -5
+    assert lib.cc_codebook_quantize(None, 10, 4, 4, A16, A16, A16, None) == -1
+    assert lib.cc_codebook_quantize(A16, 10, 4, 3, A16, A16, A16, None) == -2 and "bits = 3" in cc.last_error()
+    assert lib.cc_codebook_quantize(A16, 70000, 4, 4, A16, A16, A16, None) == -2
+    assert lib.cc_layer_weight_q(A16, 4, A16, 10, 4, A16, 8, 8, F32, A16, None) == -2
+    assert lib.cc_layer_weight_q(A16, 2, A16, 10, 4, A16, 8, 8, BF16, A16, None) == -2
+    assert lib.cc_layer_weight_q(A16, 4, None, 10, 4, A16, 8, 8, BF16, A16, None) == -1
+    assert lib.cc_layer_forward_q_workspace_bytes(1, 4096, 4096) >= lib.cc_layer_forward_workspace_bytes(1, 4096, 4096)
+    assert lib.cc_layer_forward_q(A16, 1, A16, 4, A16, 10, 4, A16, 64, 64, None, A16, BF16, None, 0, None) == -1
+    assert lib.cc_layer_forward_q(A16, 1, A16, 5, A16, 10, 4, A16, 64, 64, None, A16, BF16, WS, 1 << 30, None) == -2
+    assert lib.cc_layer_forward_q(A16, 1, A16, 4, A16, 10, 4, A16, 64, 64, None, A16, BF16, WS, 16, None) == -5
+
+
 def test_binding_refuses_host_tensors():
     import torch
 
