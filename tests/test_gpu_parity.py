@@ -348,3 +348,37 @@ def test_pruned_estep_on_awkward_data(g, d, fp16):
     for name, C in (("init", C0), ("step", C1)):
         k1, D1, _, D2 = oracle.assign_top2(X, C)
         parity.check_assignment(X, C, ref[name][0], k1, D1, D2)
+
+
+def test_more_than_65536_clusters(g, mode):
+    """K above the 16-bit code range: the M-step cannot use its bucket formulation there (the sums are accumulated
+    by the E-step kernel, or by atomics), with and without the window pruning of the automatic mode."""
+    import paper_2503_13089_amd as cc
+
+    N, d, K = 90001, 4, 66001
+    X, C0 = workloads.make_small(N, d, K, seed=4242)
+    Xd = g.dev(X)
+    ws = g.workspace(N, d, K)
+    print(f"large K N={N} d={d} K={K}", flush=True)
+    idx_a, J_a = g.gpu_assign(Xd, C0, ws=ws)
+    k1, D1, _, D2 = oracle.assign_top2(X, C0)
+    parity.check_assignment(X, C0, idx_a, k1, D1, D2)
+    parity.check_inertia(J_a, float(D1.sum()))
+    C_a, counts_a, _ = g.gpu_update(Xd, idx_a, C0, ws=ws)
+    want, counts = oracle.update(X, idx_a, C0)
+    assert C_a.tobytes() == want.tobytes() and np.array_equal(counts_a, counts)
+    Cd = g.dev(C0)
+    idx_d = torch.empty(N, dtype=torch.uint32, device="cuda")
+    counts_d = torch.empty(K, dtype=torch.uint32, device="cuda")
+    J_d = torch.zeros(1, dtype=torch.float64, device="cuda")
+    cc.lloyd_iter(Xd, Cd, idx_d, J_d, counts_d, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx_d.cpu().numpy(), idx_a)
+    assert np.array_equal(counts_d.cpu().numpy(), counts_a)
+    assert Cd.cpu().numpy().tobytes() == C_a.tobytes()
+    # two iterations in one call equal two chained single-iteration calls
+    C2, i2, J2, _ = g.gpu_fit(X, C0, 2, ws=ws, Xd=Xd)
+    C1, _, _, _ = g.gpu_fit(X, C0, 1, ws=ws, Xd=Xd)
+    C12, i12, J12, _ = g.gpu_fit(X, C1, 1, ws=ws, Xd=Xd)
+    assert C2.tobytes() == C12.tobytes() and np.array_equal(i2, i12) and J2 == J12
+    assert C1.tobytes() == C_a.tobytes()
