@@ -53,6 +53,47 @@ def cpu_baseline(w, X, C0, sample_log2=20):
     }
 
 
+# (blocks, [(name, out_features, in_features)]) of decoder-only models, linear layers of one block
+MODEL_SHAPES = {
+    "llama7b": (32, [("q", 4096, 4096), ("k", 4096, 4096), ("v", 4096, 4096), ("o", 4096, 4096),
+                     ("gate", 11008, 4096), ("up", 11008, 4096), ("down", 4096, 11008)]),
+    "llama70b": (80, [("q", 8192, 8192), ("k", 1024, 8192), ("v", 1024, 8192), ("o", 8192, 8192),
+                      ("gate", 28672, 8192), ("up", 28672, 8192), ("down", 8192, 28672)]),
+}
+
+
+def model_job(cc, torch, args):
+    """Clusters every linear layer of a model-shaped list of synthetic bf16 weights (one pinned host matrix per
+    distinct shape, reused for every block: the values do not matter for the time, the copies are real) with the
+    settings of the paper's Appendix B.1 (20 iterations) and prints one JSON line."""
+    blocks, shapes = MODEL_SHAPES[args.model]
+    gen = torch.Generator().manual_seed(20250313)
+    host = {}
+    for _, o, i in shapes:
+        if (o, i) not in host:
+            host[(o, i)] = (torch.randn((o, i), generator=gen) * 0.02).to(torch.bfloat16).pin_memory()
+    layers = [("block%d.%s" % (b, n), host[(o, i)]) for b in range(blocks) for n, o, i in shapes]
+    params = sum(o * i for _, o, i in shapes) * blocks
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    total_inertia = 0.0
+    count = 0
+    for r in cc.compress_model(layers, args.model_g, args.model_k, args.steps, seed=1, keep_outputs=True):
+        total_inertia += r.inertia
+        count += 1
+        if count % 56 == 0:
+            print("[model] %d / %d layers, %.1f s" % (count, len(layers), time.perf_counter() - t0), file=sys.stderr, flush=True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    print(json.dumps({
+        "metric": "whole-model clustering time (all linear layers, host weights in, codebooks + codes out)",
+        "value": wall, "unit": "s", "higher_is_better": False, "n_gpus": 1, "data": "synthetic",
+        "config": {"workload": args.model, "layers": len(layers), "parameters": params, "g": args.model_g,
+                   "K": args.model_k, "iters": args.steps, "weights": "bf16, pinned host memory"},
+        "layers_per_s": len(layers) / wall, "sum_of_objectives": total_inertia,
+    }))
+
+
 def layer_kernels(cc, torch, timed, w, ws, idx, Cd):
     """The layer's data path on the benchmark matrix taken as a linear weight [out = cols, in = rows] (so that its
     transpose is the clustered matrix): reshape, storage formats, reconstruction, codebook gradient, forward."""
@@ -118,6 +159,11 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--assign-mode", type=int, default=0)
+    ap.add_argument("--model", choices=sorted(MODEL_SHAPES), default=None,
+                    help="instead of the default benchmark: cluster every linear layer of a model of this shape "
+                         "(synthetic weights) through the streaming driver and report the whole-model time")
+    ap.add_argument("--model-g", type=int, default=4)
+    ap.add_argument("--model-k", type=int, default=65500)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of the input matrix (known size) so that a counter run "
                          "can scale FETCH_SIZE / WRITE_SIZE against it")
@@ -132,8 +178,11 @@ def main():
     import paper_2503_13089_amd as cc
     import workloads
 
-    w = next(v for k, v in workloads.WORKLOADS.items() if k.startswith(args.workload))
     cc.load_library()  # raises if the HIP library has not been built: there is no fallback
+    if args.model:
+        model_job(cc, torch, args)
+        return
+    w = next(v for k, v in workloads.WORKLOADS.items() if k.startswith(args.workload))
     cc.set_assign_mode(args.assign_mode)
     torch.cuda.set_device(0)
     X, C0 = workloads.make_inputs(w)

@@ -200,6 +200,20 @@ int cc_layer_codebook_grad(const void *grad_weight, int grad_dtype, uint32_t in_
                            const uint16_t *codes, uint32_t K, uint32_t g, float *grad_codebook,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * One layer in one call (Sections 3.1-3.2): cc_layer_vectors, then the centroids start from the vectors listed in
+ * init_ids [K] (indices < num_codes, e.g. a seeded sample without replacement drawn by the caller; an index past
+ * the end is clamped), `iters` Lloyd iterations (cc_kmeans_fit), then cc_layer_pack: codebook [K * g] in
+ * codebook_dtype and codes [num_codes] uint16 for the layer listing; inertia (fp64, device) may be NULL.
+ * Bit-identical to calling those entry points one after the other. K <= min(65536, num_codes).
+ * Workspace: cc_layer_compress_workspace_bytes(...) bytes (the fp32 vectors, centroids and codes of the
+ * intermediate steps plus the clustering workspace); 0 for an unsupported shape.
+ */
+size_t cc_layer_compress_workspace_bytes(uint32_t out_features, uint32_t in_features, uint32_t g, uint32_t K);
+int cc_layer_compress(const void *weight, int weight_dtype, uint32_t out_features, uint32_t in_features, uint32_t g,
+                      uint32_t K, int32_t iters, const uint32_t *init_ids, void *codebook, int codebook_dtype,
+                      uint16_t *codes, double *inertia, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Uniformly quantised codebook (the paper's inference-only variant: "#Bits for Codebook" 8 and 4 in its
  * throughput and perplexity tables; the grid is the symmetric uniform one of Section 2).

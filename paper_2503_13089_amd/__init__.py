@@ -4,6 +4,7 @@ codebook-gather decode, as hand-written gfx950 HIP kernels behind a C ABI (inclu
 This package is a thin binding: every step of the path runs in the HIP library. There is no CPU
 fallback; calling anything without the built library (or without a GPU) raises.
 """
+from .driver import CompressedLayer, compress_model  # noqa: F401
 from .binding import (  # noqa: F401
     CCError,
     Stats,
@@ -13,6 +14,8 @@ from .binding import (  # noqa: F401
     kmeans_fit,
     last_error,
     layer_codebook_grad,
+    layer_compress,
+    layer_compress_workspace_bytes,
     layer_deficiency,
     layer_forward,
     layer_forward_q,

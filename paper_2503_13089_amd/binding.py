@@ -17,7 +17,7 @@ EXPORTS = (
     "cc_read_stats", "cc_set_assign_mode", "cc_last_error", "cc_version",
     "cc_layer_deficiency", "cc_layer_num_codes", "cc_layer_vectors", "cc_layer_pack", "cc_layer_weight",
     "cc_layer_codebook_grad", "cc_layer_forward", "cc_layer_forward_workspace_bytes",
-    "cc_codebook_quantize", "cc_layer_weight_q", "cc_layer_forward_q", "cc_layer_forward_q_workspace_bytes",
+    "cc_layer_compress", "cc_layer_compress_workspace_bytes", "cc_codebook_quantize", "cc_layer_weight_q", "cc_layer_forward_q", "cc_layer_forward_q_workspace_bytes",
 )
 
 
@@ -89,6 +89,10 @@ def load_library():
     lib.cc_layer_forward_workspace_bytes.restype = sz
     lib.cc_layer_forward.argtypes = [vp, u64, vp, ctypes.c_int, u32, u32, vp, u32, u32, vp, vp, vp, sz, vp]
     lib.cc_layer_forward.restype = ctypes.c_int
+    lib.cc_layer_compress_workspace_bytes.argtypes = [u32, u32, u32, u32]
+    lib.cc_layer_compress_workspace_bytes.restype = sz
+    lib.cc_layer_compress.argtypes = [vp, ctypes.c_int, u32, u32, u32, u32, i32, vp, vp, ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.cc_layer_compress.restype = ctypes.c_int
     lib.cc_codebook_quantize.argtypes = [vp, u32, u32, ctypes.c_int, vp, vp, vp, vp]
     lib.cc_codebook_quantize.restype = ctypes.c_int
     lib.cc_layer_weight_q.argtypes = [vp, ctypes.c_int, vp, u32, u32, vp, u32, u32, ctypes.c_int, vp, vp]
@@ -303,6 +307,22 @@ def layer_forward(x, codebook, codes, out_features: int, bias, y, workspace) -> 
                                            _any_ptr(bias, "bias"), _any_ptr(y, "y"),
                                            _ptr(workspace, torch.uint8, "workspace"),
                                            workspace.numel() if workspace is not None else 0, _stream()))
+
+
+def layer_compress_workspace_bytes(out_features: int, in_features: int, g: int, K: int) -> int:
+    return load_library().cc_layer_compress_workspace_bytes(out_features, in_features, g, K)
+
+
+def layer_compress(weight, g: int, iters: int, init_ids, codebook, codes, inertia, workspace) -> None:
+    import torch
+
+    out_features, in_features = weight.shape
+    K = codebook.shape[0]
+    _check(load_library().cc_layer_compress(_any_ptr(weight, "weight"), _dtype_code(weight), out_features, in_features, g, K,
+                                            iters, _ptr(init_ids, _idx_dtype(), "init_ids"), _any_ptr(codebook, "codebook"),
+                                            _dtype_code(codebook), _ptr(codes, torch.uint16, "codes"),
+                                            _ptr(inertia, torch.float64, "inertia"),
+                                            _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
 
 
 # ---- uniformly quantised codebook --------------------------------------------------------------------

@@ -427,6 +427,61 @@ int cc_layer_codebook_grad(const void* grad_weight, int grad_dtype, uint32_t in_
     return CC_OK;
 }
 
+// One layer, one call: reshape, seeded start, Lloyd iterations, storage formats.
+namespace {
+struct CompressLayout {
+    size_t vectors, centroids, idx, fit, total;
+    uint64_t N;
+};
+CompressLayout compress_layout(uint32_t out_features, uint32_t in_features, uint32_t g, uint32_t K)
+{
+    CompressLayout l{};
+    l.N = cc_layer_num_codes(in_features, out_features, g);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off += cc::align256(bytes); return at; };
+    l.vectors = take(size_t(l.N) * g * 4);
+    l.centroids = take(size_t(K) * g * 4);
+    l.idx = take(size_t(l.N) * 4);
+    l.fit = take(cc::carve(nullptr, l.N, g, K).bytes);
+    l.total = off;
+    return l;
+}
+}  // namespace
+
+size_t cc_layer_compress_workspace_bytes(uint32_t out_features, uint32_t in_features, uint32_t g, uint32_t K)
+{
+    if (check_layer(in_features, out_features, g, K, CC_BF16, true) != CC_OK) return 0;
+    const CompressLayout l = compress_layout(out_features, in_features, g, K);
+    if (check_shape(l.N, g, K) != CC_OK) return 0;
+    return l.total;
+}
+
+int cc_layer_compress(const void* weight, int weight_dtype, uint32_t out_features, uint32_t in_features, uint32_t g,
+                      uint32_t K, int32_t iters, const uint32_t* init_ids, void* codebook, int codebook_dtype,
+                      uint16_t* codes, double* inertia, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!weight || !init_ids || !codebook || !codes) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (int rc = check_layer(in_features, out_features, g, K, weight_dtype, true)) return rc;
+    if (codebook_dtype != CC_F16 && codebook_dtype != CC_BF16) return fail(CC_ERR_SHAPE, "the stored codebook is CC_F16 or CC_BF16");
+    if (iters < 0) return fail(CC_ERR_ITERS, "iters = %d is negative", iters);
+    const CompressLayout l = compress_layout(out_features, in_features, g, K);
+    if (int rc = check_shape(l.N, g, K)) return rc;
+    if (workspace == nullptr) return fail(CC_ERR_NULL, "workspace is NULL");
+    if (!aligned(workspace, 256)) return fail(CC_ERR_ALIGN, "workspace must be 256-byte aligned");
+    if (workspace_bytes < l.total) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, l.total);
+    char* base = static_cast<char*>(workspace);
+    float* vectors = reinterpret_cast<float*>(base + l.vectors);
+    float* centroids = reinterpret_cast<float*>(base + l.centroids);
+    uint32_t* idx = reinterpret_cast<uint32_t*>(base + l.idx);
+    if (int rc = cc_layer_vectors(weight, weight_dtype, out_features, in_features, g, vectors, stream)) return rc;
+    // the starting centroids are the listed vectors: a gather of rows, i.e. a decode with the vectors as the table
+    if (int rc = cc_decode(vectors, uint32_t(l.N), g, init_ids, K, centroids, stream)) return rc;
+    if (int rc = cc_kmeans_fit(vectors, l.N, g, K, iters, centroids, centroids, idx, inertia, base + l.fit,
+                               workspace_bytes - l.fit, stream))
+        return rc;
+    return cc_layer_pack(centroids, K, g, codebook, codebook_dtype, idx, l.N, codes, stream);
+}
+
 // ---- uniformly quantised codebook ---------------------------------------------------------------
 
 int cc_codebook_quantize(const float* centroids, uint32_t K, uint32_t g, int bits, void* qbook, float* scale,

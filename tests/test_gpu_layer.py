@@ -297,3 +297,64 @@ def test_layer_forward_q(cc, M, in_features, out_features, g, K, with_bias, dt, 
     y2 = torch.empty_like(y)
     cc.layer_forward_q(x, qbook, bits, scale, K, g, codes, out_features, bias, y2, ws)
     assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+
+
+# ------------------------------------------------------------------ one layer in one call
+
+@pytest.mark.parametrize("out_features,in_features,g,K,iters,dt", [(256, 192, 4, 500, 3, "bf16"), (250, 131, 6, 300, 2, "f16"),
+                                                                   (700, 512, 4, 9000, 2, "bf16"), (64, 40, 9, 17, 0, "f32")])
+def test_layer_compress_equals_the_chain_of_calls(cc, out_features, in_features, g, K, iters, dt):
+    from tests import gpu_helpers as g_
+
+    rng = np.random.default_rng(out_features + in_features + g + K)
+    W = _dev((rng.standard_normal((out_features, in_features)) * 0.02).astype(np.float32), TORCH_DT[dt])
+    n = L.num_codes(in_features, out_features, g)
+    ids_np = rng.choice(n, size=K, replace=False).astype(np.uint32)
+    ids = _dev(ids_np.view(np.int32)).view(torch.uint32)
+    book = torch.empty((K, g), dtype=torch.bfloat16, device="cuda")
+    codes = torch.empty(n, dtype=torch.uint16, device="cuda")
+    J = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ws = torch.empty(cc.layer_compress_workspace_bytes(out_features, in_features, g, K), dtype=torch.uint8, device="cuda")
+    print(f"layer_compress {out_features}x{in_features} g={g} K={K} iters={iters} {dt}", flush=True)
+    cc.layer_compress(W, g, iters, ids, book, codes, J, ws)
+    # the same thing step by step
+    X = torch.empty((n, g), dtype=torch.float32, device="cuda")
+    cc.layer_vectors(W, g, X)
+    Xh = X.cpu().numpy()
+    C, idx, Jc, _ = g_.gpu_fit(Xh, np.ascontiguousarray(Xh[ids_np]), iters)
+    book2 = torch.empty_like(book)
+    codes2 = torch.empty_like(codes)
+    cc.layer_pack(_dev(C), book2, _dev(idx.view(np.int32)).view(torch.uint32), codes2)
+    assert torch.equal(book.view(torch.int16), book2.view(torch.int16))
+    assert torch.equal(codes.view(torch.int16), codes2.view(torch.int16))
+    assert J.item() == Jc
+    # and against the oracle end to end (free-running on both sides; these small problems have no near-ties)
+    Co, idxo, Jo, _ = oracle.kmeans_fit(L.prepare_matrix(W.float().cpu().numpy(), g), Xh[ids_np], iters)
+    assert Jc == pytest.approx(Jo, rel=1e-5)
+    assert np.array_equal(idx, idxo)
+
+
+def test_model_driver_matches_single_calls(cc):
+    """The streaming driver (copies overlapped with clustering, shared workspace) returns what separate
+    cc_layer_compress calls return, layer by layer."""
+    rng = np.random.default_rng(3)
+    shapes = [(192, 128), (250, 128), (128, 320), (192, 128)]
+    layers = [("layer%d" % i, torch.from_numpy((rng.standard_normal(s) * 0.02).astype(np.float32)).to(torch.bfloat16).pin_memory())
+              for i, s in enumerate(shapes)]
+    g, K, iters, seed = 4, 300, 3, 11
+    got = list(cc.compress_model(layers, g, K, iters, seed))
+    assert [r.name for r in got] == [n for n, _ in layers]
+    for pos, ((name, w), r) in enumerate(zip(layers, got)):
+        out_features, in_features = w.shape
+        n = L.num_codes(in_features, out_features, g)
+        from paper_2503_13089_amd.driver import init_ids
+
+        ids = init_ids(n, K, seed + pos).cuda().view(torch.uint32)
+        book = torch.empty((K, g), dtype=torch.bfloat16, device="cuda")
+        codes = torch.empty(n, dtype=torch.uint16, device="cuda")
+        J = torch.zeros(1, dtype=torch.float64, device="cuda")
+        ws = torch.empty(cc.layer_compress_workspace_bytes(out_features, in_features, g, K), dtype=torch.uint8, device="cuda")
+        cc.layer_compress(w.cuda(), g, iters, ids, book, codes, J, ws)
+        assert torch.equal(r.codebook.view(torch.int16), book.cpu().view(torch.int16))
+        assert torch.equal(r.codes.view(torch.int16), codes.cpu().view(torch.int16))
+        assert r.inertia == J.item() and (r.in_features, r.out_features) == (in_features, out_features)
