@@ -100,3 +100,68 @@ def test_cfg2_exhaustive_lloyd_step(g):
         C = got
     out = g.gpu_decode(C, idx)
     assert out.tobytes() == oracle.decode(C, idx).tobytes()
+
+
+def test_layer_path_at_full_size(g):
+    """The layer's data path at the benchmark matrix taken as a linear layer (in = 4096, out = 11008, g = 4,
+    K = 65536, bf16), in the configuration bench.py times. The numpy oracle handles these sizes for the pure data
+    movement (whole arrays compared bit for bit); sums and products are checked on sampled outputs in fp64."""
+    import paper_2503_13089_amd as cc
+    from oracle import layer as L
+
+    w = workloads.by_number(3)
+    in_features, out_features, gdim, K = w.rows, w.cols, w.d, w.K
+    rng = np.random.default_rng(77)
+    n = L.num_codes(in_features, out_features, gdim)
+    print("layer path full size: reshape", flush=True)
+    W = torch.from_numpy((rng.standard_normal((out_features, in_features)) * 0.02).astype(np.float32)).to(torch.bfloat16)
+    Wd = W.cuda()
+    X = torch.empty((n, gdim), dtype=torch.float32, device="cuda")
+    cc.layer_vectors(Wd, gdim, X)
+    assert X.cpu().numpy().tobytes() == L.prepare_matrix(W.float().numpy(), gdim).tobytes()
+    del X
+    print("layer path full size: reconstruction", flush=True)
+    book = torch.from_numpy((rng.standard_normal((K, gdim)) * 0.02).astype(np.float32)).to(torch.bfloat16).cuda()
+    codes_np = rng.integers(0, K, size=n).astype(np.uint16)
+    codes = torch.from_numpy(codes_np.view(np.int16)).cuda().view(torch.uint16)
+    rebuilt = torch.empty((in_features, out_features), dtype=torch.bfloat16, device="cuda")
+    cc.layer_weight(book, codes, in_features, out_features, rebuilt)
+    bookh = book.float().cpu().numpy()
+    want = L.layer_weight(bookh, codes_np, in_features, out_features)
+    assert rebuilt.float().cpu().numpy().tobytes() == want.tobytes()
+    print("layer path full size: 4-bit codebook", flush=True)
+    C32 = (rng.standard_normal((K, gdim)) * 0.02).astype(np.float32)
+    q, s = L.quantize_codebook(C32, 4)
+    qbook = torch.empty(K * gdim // 2, dtype=torch.uint8, device="cuda")
+    scale = torch.zeros(1, dtype=torch.float32, device="cuda")
+    cc.codebook_quantize(torch.from_numpy(C32).cuda(), 4, qbook, scale, torch.zeros(4, dtype=torch.uint8, device="cuda"))
+    assert scale.item() == s and np.array_equal(qbook.cpu().numpy(), L.pack_int4(q))
+    cc.layer_weight_q(qbook, 4, scale, K, gdim, codes, in_features, out_features, rebuilt)
+    want_q = L.layer_weight(L.dequantize_codebook(q, s, "bf16"), codes_np, in_features, out_features)
+    assert rebuilt.float().cpu().numpy().tobytes() == want_q.tobytes()
+    print("layer path full size: forward (sampled outputs)", flush=True)
+    M = 3
+    x = torch.from_numpy(rng.standard_normal((M, in_features)).astype(np.float32)).to(torch.bfloat16).cuda()
+    xh = x.float().cpu().numpy().astype(np.float64)
+    cols = np.sort(rng.choice(out_features, size=64, replace=False))
+    y = torch.empty((M, out_features), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(max(cc.layer_forward_workspace_bytes(M, in_features, out_features),
+                         cc.layer_forward_q_workspace_bytes(M, in_features, out_features), 256), dtype=torch.uint8, device="cuda")
+    cc.layer_forward(x, book, codes, out_features, None, y, ws)
+    got = y.float().cpu().numpy().astype(np.float64)[:, cols]
+    ref = xh @ want.astype(np.float64)[:, cols]
+    mag = np.abs(xh) @ np.abs(want.astype(np.float64))[:, cols]
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + in_features * 2.0 ** -24 * mag)
+    cc.layer_forward_q(x, qbook, 4, scale, K, gdim, codes, out_features, None, y, ws)
+    got = y.float().cpu().numpy().astype(np.float64)[:, cols]
+    Q = L.layer_weight(q.astype(np.float64), codes_np, in_features, out_features)[:, cols]
+    ref = float(s) * (xh @ Q)
+    mag = float(s) * (np.abs(xh) @ (np.abs(Q) + 8.0))
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + in_features * 2.0 ** -24 * mag)
+    print("layer path full size: codebook gradient", flush=True)
+    wsz = torch.empty(cc.workspace_bytes(n, gdim, K), dtype=torch.uint8, device="cuda")
+    grad = torch.empty((K, gdim), dtype=torch.float32, device="cuda")
+    cc.layer_codebook_grad(Wd.t().contiguous(), codes, K, gdim, grad, wsz)
+    Gh = W.float().numpy().T
+    wantg = L.gather_backward(Gh, codes_np, K, gdim)
+    assert np.array_equal(grad.cpu().numpy(), wantg.astype(np.float32))  # exact sums of bf16 values, one rounding
