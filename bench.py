@@ -267,6 +267,13 @@ def main():
         "roofline_alu": {"bound": "alu", "kernel": "assign (E-step)", "achieved": N * K / 128.0 / (assign_ms * 1e-3) / 1e9,
                          "peak": VALU_ISSUE_PEAK / 1e9, "unit": "G wave-instr/s",
                          "frac": N * K / 128.0 / (assign_ms * 1e-3) / VALU_ISSUE_PEAK, "traffic": None},
+        # what the matrix cores really execute in the default variant: 16 k-slots per (vector, centroid) pair and MFMA
+        # (3 fp16 parts x d products + the norm slots; d = 16: 48 slots), against the dense fp16 MFMA peak
+        "roofline_mfma_f16": ({"bound": "mfma", "kernel": "assign (E-step), whole codebook scored",
+                               "achieved": 2.0 * 16 * ((3 * d + 3 + 15) // 16 if d != 16 else 3) * N * K / (assign_ms * 1e-3) / 1e12,
+                               "peak": 2500.0, "unit": "TFLOP/s",
+                               "frac": 2.0 * 16 * ((3 * d + 3 + 15) // 16 if d != 16 else 3) * N * K / (assign_ms * 1e-3) / 1e12 / 2500.0,
+                               "traffic": None} if args.assign_mode in (0, 3) else None),
         "standalone_lloyd_iter_ms": iter_ms,
         "other_kernels": {
             "update": {"bound": "hbm", "achieved": update_bytes / (update_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,

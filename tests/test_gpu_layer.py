@@ -262,7 +262,11 @@ def test_layer_weight_q_bit_exact(cc, out_features, in_features, g, K, dt, bits)
 
 @pytest.mark.parametrize("bits", [8, 4])
 @pytest.mark.parametrize("dt", ["f16", "bf16"])
-@pytest.mark.parametrize("M,in_features,out_features,g,K,with_bias", FORWARD_CASES + [(3, 2048, 1024, 4, 65536, True)])
+@pytest.mark.parametrize("M,in_features,out_features,g,K,with_bias",
+                         FORWARD_CASES + [(3, 2048, 1024, 4, 65536, True),
+                                          # 16 < M <= 64 with g = 4 / 8 and an LDS-sized codebook: matrix cores + LDS codebook
+                                          (40, 512, 320, 4, 65536, True), (64, 264, 200, 8, 9000, False),
+                                          (17, 1024, 1024, 4, 30000, True), (33, 72, 70, 4, 100, False)])
 def test_layer_forward_q(cc, M, in_features, out_features, g, K, with_bias, dt, bits):
     rng = np.random.default_rng(M + in_features + out_features + g + bits)
     T = TORCH_DT[dt]
