@@ -142,16 +142,22 @@ int run_assign(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t 
 // the cluster sums are accumulated by the scoring kernel itself (no second pass over the vectors).
 // idx == NULL (only inside the fit loop, pruned path) skips the copy of the codes to input order.
 int run_lloyd_iter(const float* X, uint32_t N, uint32_t d, float* C, uint32_t K, uint32_t* idx, double* inertia,
-                   uint32_t* counts, const cc::Workspace& w, bool pruned, bool have_hint, hipStream_t s)
+                   uint32_t* counts, const cc::Workspace& w, bool pruned, bool have_hint, hipStream_t s,
+                   bool sums_follow = false)
 {
     if (use_matrix_cores(K)) {
+        // sums_follow (inside a fit, pruned path, after an M-step by buckets of the same fit): the workspace holds the
+        // integer sums and counts of the codes in w.idx_sorted; keep a copy of those codes so that the M-step can
+        // move just the vectors whose code changes
+        if (sums_follow) CC_TRY_HIP(cc::launch_copy_u32(w.idx_sorted, w.idx_prev, N, s), "update (previous codes)");
         // A pruned E-step is shorter than the atomic traffic of the fused accumulation (which then becomes the
         // bottleneck), so there the M-step groups the vectors by bucket of clusters and sums in LDS instead.
         const bool by_buckets = pruned && w.bucket_ok;
         if (!by_buckets) CC_TRY_HIP(cc::launch_zero_accumulators(w, K, d, nullptr, 0, s), "update (clear)");
         if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, !by_buckets, pruned, have_hint, s)) return rc;
         if (by_buckets)
-            CC_TRY_HIP(cc::launch_update_buckets(w.xsorted, N, d, w.idx_sorted, C, K, C, counts, w, true, true, s), "update (buckets)");
+            CC_TRY_HIP(cc::launch_update_buckets(w.xsorted, N, d, w.idx_sorted, C, K, C, counts, w, true, true, s,
+                                                 sums_follow ? w.idx_prev : nullptr), "update (buckets)");
         else
             CC_TRY_HIP(cc::launch_finalize(C, C, counts, K, d, N, w, true, s), "update (means)");
         if (pruned && idx != nullptr) CC_TRY_HIP(cc::launch_unpermute(N, idx, w, s), "assign (codes to input order)");
@@ -229,7 +235,10 @@ int cc_kmeans_fit(const float* vectors, uint64_t N, uint32_t d, uint32_t K, int3
     for (int32_t t = 0; t < iters; ++t) {
         // only the matrix-core path can leave its codes in the workspace; the others write idx directly
         uint32_t* step_idx = pruned ? nullptr : idx;
-        if (int rc = run_lloyd_iter(o.X, n, D, o.C_work, K, step_idx, nullptr, nullptr, w, pruned, t > 0, s))
+        // from the third iteration on the M-step only moves the vectors whose code changed (the first iterations move
+        // too many for that to pay off)
+        const bool sums_follow = pruned && w.bucket_ok && t >= 2;
+        if (int rc = run_lloyd_iter(o.X, n, D, o.C_work, K, step_idx, nullptr, nullptr, w, pruned, t > 0, s, sums_follow))
             return rc;
     }
     if (int rc = run_assign(o.X, n, D, o.C_work, K, idx, inertia, w, pruned, iters > 0, s)) return rc;

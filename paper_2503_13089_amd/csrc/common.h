@@ -50,6 +50,7 @@ struct Workspace {
     WsPersist* persist;
     float* xsorted;            // [N*d]  the vectors in ascending-norm order
     uint32_t* idx_sorted;      // [N]    codes in that order (also the next call's hint)
+    uint32_t* idx_prev;        // [N]    the codes of the previous iteration of a fit (incremental M-step)
     uint32_t* vperm;           // [N]    input position of the p-th vector in norm order
     uint32_t* vperm_tmp;       // [N]
     uint16_t* vkeys;           // [N]    norm keys (sorted after the sort)
@@ -123,6 +124,7 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d_caller, uint32_t K)
     w.refine_list = reinterpret_cast<uint32_t*>(take(size_t(w.refine_cap) * 4));
     w.xsorted = reinterpret_cast<float*>(take(size_t(N) * d * 4));
     w.idx_sorted = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
+    w.idx_prev = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vperm = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vperm_tmp = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vkeys = reinterpret_cast<uint16_t*>(take(size_t(N) * 2));
@@ -247,10 +249,13 @@ hipError_t launch_accumulate(const float* X, uint32_t N, uint32_t d, const uint3
 // M-step by buckets (K <= 65536): counts, scatter into per-bucket records, LDS sums, means (and counts_out if
 // not NULL) in one go. Codes >= K are skipped and counted in WsHeader::skipped_vectors. norm_order = true
 // buckets the clusters by their position in the norm order left by launch_sort_centroids (w.cinv, w.cperm).
-// mean = false writes the plain sums (0 for an empty cluster) instead of the means.
+// mean = false writes the plain sums (0 for an empty cluster) instead of the means. The integer sums and the
+// counts are left in w.sums / w.counts. prev_idx != NULL: those already hold the sums and counts of the codes
+// prev_idx; only the vectors whose code differs are moved (bit-identical to a recomputation from idx).
 hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,
                                  uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order,
-                                 bool mean, hipStream_t s);
+                                 bool mean, hipStream_t s, const uint32_t* prev_idx = nullptr);
+hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, size_t n, hipStream_t s);
 // out[i][j] = j < d_in ? in[i][j] : 0 for rows of d_out >= d_in floats, and the reverse (drop the tail).
 hipError_t launch_pad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s);
 hipError_t launch_unpad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s);
