@@ -248,7 +248,8 @@ int cc_layer_forward_q(const void *x, uint64_t M, const void *qbook, int bits, c
 /* Selects the E-step kernel. 0 = automatic (default): for K >= 128 the matrix cores, with the fp16 MFMA
  * (centroids split into three fp16 parts, exact products) when every input is an fp16 number and
  * the fp32 MFMA otherwise, both with guard band + direct-form refinement; direct form for small K;
- * for K >= 8192 vectors and centroids are additionally visited in the order of a (norm, cosine to a
+ * for K >= 8192 (inside cc_kmeans_fit already for K >= 256, when N >= 2^19 and iters >= 5, where the
+ * ordering is paid once) vectors and centroids are additionally visited in the order of a (norm, cosine to a
  * fixed direction) key and a workgroup skips the parts of the codebook that the triangle inequality
  * rules out (an exact shortcut: a centroid whose norm, or whose projection on the fixed direction,
  * differs from a vector's by more than a known upper bound of its nearest distance cannot be the

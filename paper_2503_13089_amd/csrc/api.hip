@@ -70,8 +70,15 @@ bool use_matrix_cores(uint32_t K)
     return mode == 2 || ((mode == 0 || mode == 3) && K >= 128);
 }
 
-// Norm-window pruning: only in the automatic mode and only where the ordering overhead can pay off.
-bool use_pruning(uint32_t K) { return g_assign_mode.load() == 0 && K >= 8192; }
+// Norm-window pruning: only in the automatic mode and only where the ordering overhead can pay off. A single
+// E-step pays for ordering the vectors by itself, so it needs a large codebook; a fit orders once and keeps the
+// integer cluster sums up to date across its iterations, which pays from a few hundred centroids on once there
+// are enough vectors to fill the chip (measured break-even: about 3e5 vectors, 5 iterations).
+bool use_pruning(uint64_t N, uint32_t K, int32_t iters)
+{
+    if (g_assign_mode.load() != 0) return false;
+    return K >= 8192 || (K >= 256 && N >= (1u << 19) && iters >= 5);
+}
 
 // Scoring + refinement on the matrix cores. The input scan (WsHeader::x_not_f16) must have run on this
 // workspace since the last header reset; with pruned = true the vectors must have been norm-ordered
@@ -230,7 +237,7 @@ int cc_kmeans_fit(const float* vectors, uint64_t N, uint32_t d, uint32_t K, int3
     CC_TRY_HIP(cc::launch_scan_inputs(o.X, N * D, w.hdr, s), "input scan");
     if (o.C_work != o.C_in)
         CC_TRY_HIP(cc::launch_copy_f32(o.C_in, o.C_work, size_t(K) * D, s), "centroid copy");
-    const bool pruned = use_matrix_cores(K) && use_pruning(K);
+    const bool pruned = use_matrix_cores(K) && use_pruning(N, K, iters);
     if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(o.X, n, D, K, w, true, s), "norm ordering");
     for (int32_t t = 0; t < iters; ++t) {
         // only the matrix-core path can leave its codes in the workspace; the others write idx directly
@@ -259,7 +266,7 @@ int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroi
     Operands o;
     if (int rc = enter(vectors, centroids, nullptr, uint32_t(N), d, K, w, s, o)) return rc;
     CC_TRY_HIP(cc::launch_scan_inputs(o.X, N * w.d, w.hdr, s), "input scan");
-    const bool pruned = use_matrix_cores(K) && use_pruning(K);
+    const bool pruned = use_matrix_cores(K) && use_pruning(N, K, 1);
     if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(o.X, uint32_t(N), w.d, K, w, false, s), "norm ordering");
     return run_assign(o.X, uint32_t(N), w.d, o.C_in, K, idx, inertia, w, pruned, false, s);
 }
@@ -279,7 +286,7 @@ int cc_lloyd_iter(const float* vectors, uint64_t N, uint32_t d, float* centroids
     Operands o;
     if (int rc = enter(vectors, centroids, centroids, uint32_t(N), d, K, w, s, o)) return rc;
     CC_TRY_HIP(cc::launch_scan_inputs(o.X, N * w.d, w.hdr, s), "input scan");
-    const bool pruned = use_matrix_cores(K) && use_pruning(K);
+    const bool pruned = use_matrix_cores(K) && use_pruning(N, K, 1);
     if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(o.X, uint32_t(N), w.d, K, w, false, s), "norm ordering");
     if (int rc = run_lloyd_iter(o.X, uint32_t(N), w.d, o.C_work, K, idx, inertia, counts, w, pruned, false, s)) return rc;
     return leave(centroids, d, K, w, s);

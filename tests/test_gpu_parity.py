@@ -27,8 +27,8 @@ def g():
 @pytest.fixture(params=[0, 1, 2, 3], ids=["auto", "direct", "fp32-mfma", "auto-unpruned"])
 def mode(request, g):
     """Runs a test once per E-step selection: 0 = automatic (fp16 MFMA for these fp16-representable inputs when
-    K >= 128, norm-window pruning when K >= 8192), 1 = direct form only, 2 = fp32 MFMA + guard band + refinement,
-    3 = automatic without pruning."""
+    K >= 128, norm-window pruning when K >= 8192 or in long fits of many vectors), 1 = direct form only,
+    2 = fp32 MFMA + guard band + refinement, 3 = automatic without pruning."""
     import paper_2503_13089_amd as cc
 
     cc.set_assign_mode(request.param)
@@ -295,6 +295,36 @@ def test_pruned_estep_is_bit_identical_whatever_the_hint(g, N, d, K):
     parity.check_assignment(X, C1, ref_idx, k1, D1, D2)
     if d == 4:
         assert st.scored_stages < 0.9 * st.total_stages  # at 4 dimensions the windows really are narrower
+
+
+@pytest.mark.parametrize("N,d,K,iters", [(530011, 4, 300, 6), (524288, 8, 1025, 5), (540001, 6, 256, 5)])
+def test_windowed_fit_with_a_small_codebook(g, N, d, K, iters):
+    """With at least 2^19 vectors and 5 iterations a fit takes the windowed E-step and the incremental M-step from
+    256 centroids on. Its codes and centroids must be the bits of the whole-codebook fit, and the final assignment
+    must be the oracle's argmin for the final centroids."""
+    import paper_2503_13089_amd as cc
+
+    X, C0 = workloads.make_small(N, d, K, seed=4100 + K)
+    Xd = g.dev(X)
+    try:
+        cc.set_assign_mode(3)
+        C_ref, idx_ref, J_ref, _ = g.gpu_fit(X, C0, iters, Xd=Xd)
+        cc.set_assign_mode(0)
+        ws = g.workspace(N, d, K)
+        C, idx, J, st = g.gpu_fit(X, C0, iters, ws=ws, Xd=Xd)
+        C_short, _, _, st_short = g.gpu_fit(X, C0, iters - 1 if iters == 5 else 4, Xd=Xd)  # below 5 iterations: no windows
+    finally:
+        cc.set_assign_mode(0)
+    assert 0 < st.scored_stages < st.total_stages
+    assert st_short.scored_stages == st_short.total_stages or st_short.total_stages == 0
+    assert C.tobytes() == C_ref.tobytes() and np.array_equal(idx, idx_ref)
+    assert J == pytest.approx(J_ref, rel=1e-12)
+    k1, D1, _, D2 = oracle.assign_top2(X, C)
+    parity.check_assignment(X, C, idx, k1, D1, D2)
+    parity.check_inertia(J, oracle.inertia(X, C, idx))
+    # the oracle's own trajectory from the same start: same objective within the near-tie allowance
+    _, _, J_or, _ = oracle.kmeans_fit(X, C0, iters)
+    assert J == pytest.approx(J_or, rel=1e-3)
 
 
 def _awkward_vectors(N, d, rng):
