@@ -253,8 +253,8 @@ int cc_layer_forward_q(const void *x, uint64_t M, const void *qbook, int bits, c
  * fixed direction) key and a workgroup skips the parts of the codebook that the triangle inequality
  * rules out (an exact shortcut: a centroid whose norm, or whose projection on the fixed direction,
  * differs from a vector's by more than a known upper bound of its nearest distance cannot be the
- * nearest; the previous call's codes on the same workspace - or a bootstrap pass over every 16th
- * centroid - provide that bound, and a poor bound costs time, never correctness).
+ * nearest; the previous call's codes on the same workspace - or a bootstrap pass over a guessed
+ * neighbourhood of each vector - provide that bound, and a poor bound costs time, never correctness).
  * 1 = direct-form vector-ALU kernel only. 2 = fp32 MFMA kernel always, whole codebook.
  * 3 = as 0 but always the whole codebook. Process-wide; for tests and profiling.
  * Returns the previous value, or CC_ERR_SHAPE for an unknown mode. */

@@ -1,6 +1,7 @@
 // C ABI of libcluscomp: argument validation on the host, then the kernel sequence of each call.
 // See include/cluscomp.h for the contract of every entry point.
 #include <atomic>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 
@@ -80,6 +81,15 @@ bool use_pruning(uint64_t N, uint32_t K, int32_t iters)
     return K >= 8192 || (K >= 256 && N >= (1u << 19) && iters >= 5);
 }
 
+// Relative half-width of the guessed windows of the bootstrap pass. The nearest-centroid distance of a vector of
+// norm r is of the order of r * K^(-1/d) when the centroids follow the vectors' own distribution; a window about
+// that wide usually holds a near neighbour and is cheap to score. Capped where (large d) no window would be narrow.
+float guess_width(uint32_t K, uint32_t d)
+{
+    const float w = 1.1f * std::pow(float(K), -1.0f / float(d));
+    return std::min(0.1f, std::max(0.04f, w));
+}
+
 // Scoring + refinement on the matrix cores. The input scan (WsHeader::x_not_f16) must have run on this
 // workspace since the last header reset; with pruned = true the vectors must have been norm-ordered
 // (launch_sort_vectors) and the codes are left in norm order in w.idx_sorted.
@@ -95,20 +105,21 @@ int run_assign_matrix(const float* X, uint32_t N, uint32_t d, const float* C, ui
     e.idx = pruned ? w.idx_sorted : idx;
     if (pruned) {
         CC_TRY_HIP(cc::launch_sort_centroids(C, d, K, w, s), "assign (centroid norm order)");
-        // Bootstrap (only runs on the device when the workspace holds no hint): nearest among every 16th
-        // centroid of the norm order; its codes are only the upper bounds that size the windows below.
+        // Bootstrap (only runs on the device when the workspace holds no hint): the nearest centroid inside a
+        // guessed window around each vector's own norm and projection. Its codes are only the upper bounds that
+        // size the real windows below, so a poor guess costs time, never correctness.
         if (!have_hint) {
-            CC_TRY_HIP(cc::launch_subsample_centroids(d, K, w, s), "assign (bootstrap codebook)");
+            CC_TRY_HIP(cc::launch_windows(C, N, d, K, w, guess_width(K, d), s), "assign (guessed windows)");
             cc::EStep b = e;
-            b.pack_rows = w.csub; b.pack_perm = nullptr; b.rows = w.csub; b.row_ids = w.csub_ids; b.K = w.ksub;
-            b.packed = w.packed_sub; b.packed_tiles = w.packed_sub_tiles; b.windows = nullptr;
+            b.pack_rows = C; b.pack_perm = w.cperm; b.rows = w.csorted; b.row_ids = w.cperm; b.K = K;
+            b.packed = w.packed; b.packed_tiles = w.packed_tiles; b.windows = w.windows;
             b.accumulate = false; b.hint_only = true;
             b.gate = cc::kGateIfF16 | cc::kGateNoHint;
             CC_TRY_HIP(cc::launch_assign_mfma_f16(b, d, w, s), "assign (bootstrap, fp16 matrix cores)");
             b.gate = cc::kGateIfNotF16 | cc::kGateNoHint;
             CC_TRY_HIP(cc::launch_assign_mfma_f32(b, d, w, s), "assign (bootstrap, fp32 matrix cores)");
         }
-        CC_TRY_HIP(cc::launch_windows(C, N, d, K, w, true, s), "assign (norm windows)");
+        CC_TRY_HIP(cc::launch_windows(C, N, d, K, w, 0.0f, s), "assign (norm windows)");
     }
     e.pack_rows = C; e.pack_perm = pruned ? w.cperm : nullptr;
     e.rows = pruned ? w.csorted : C; e.row_ids = pruned ? w.cperm : nullptr;

@@ -64,9 +64,6 @@ struct Workspace {
     uint32_t* key_starts;      // [65537] first norm-ordered centroid position with ordering key >= v
     uint32_t* sort_hist;       // [256 * sort blocks]
     uint2* windows;            // [ceil(N/512)][kWinStride] window list (runs of codebook stages) per 512-vector tile
-    float* csub;               // [Ksub*d] every kBootstrapStride-th centroid in norm order
-    uint32_t* csub_ids;        // [Ksub]   their centroid indices
-    void* packed_sub;          // operand tiles of that sub-codebook
     // M-step by buckets (K <= kMaxBuckets * kBucketClusters)
     char* records;             // [N] x (4d + 16) bytes: the vectors, each with its code, grouped by bucket
     uint32_t* bucket_hist;     // [blocks][buckets] members of each bucket in each block of kBucketChunk vectors
@@ -74,7 +71,6 @@ struct Workspace {
     uint32_t* bucket_totals;   // [buckets]
     uint32_t* bucket_base;     // [buckets + 1] first record of each bucket
     bool bucket_ok;
-    uint32_t ksub, packed_sub_tiles;
     uint32_t refine_cap;
     uint32_t partial_slots;
     uint32_t packed_tiles;     // number of 32-centroid tiles in `packed` (K rounded up, padded)
@@ -84,7 +80,6 @@ struct Workspace {
 constexpr uint32_t kTileCentroids = 32;   // centroids per matrix-core tile
 constexpr uint32_t kGroupTiles = 2;       // tiles per tracking group of the matrix-core E-step
 constexpr uint32_t kStageTilesMax = 8;    // the packed codebook is padded to whole LDS stages of this many tiles
-constexpr uint32_t kBootstrapStride = 16; // the bootstrap hint pass scores every 16th centroid (in norm order)
 constexpr uint32_t kStageTiles = 4;       // tiles per LDS stage of the matrix-core E-step kernels
 constexpr uint32_t kWinQuad = kTileCentroids;  // window lists count runs in tiles = 32 positions; runs never share a stage
 constexpr int kWinSlots = 32;             // most runs a window list can hold (one per norm shell)
@@ -138,11 +133,6 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d_caller, uint32_t K)
     w.key_starts = reinterpret_cast<uint32_t*>(take(size_t(65537) * 4));
     w.sort_hist = reinterpret_cast<uint32_t*>(take((size_t(N) / 4096 + 3) * 256 * 4));  // histogram + 256 totals
     w.windows = reinterpret_cast<uint2*>(take((size_t(N) / 512 + 1) * kWinStride * 8));
-    w.ksub = (K + kBootstrapStride - 1) / kBootstrapStride;
-    w.packed_sub_tiles = uint32_t((uint64_t(w.ksub) + stage - 1) / stage) * kStageTilesMax;
-    w.csub = reinterpret_cast<float*>(take(size_t(w.ksub) * d * 4));
-    w.csub_ids = reinterpret_cast<uint32_t*>(take(size_t(w.ksub) * 4));
-    w.packed_sub = take(size_t(w.packed_sub_tiles) * kTileCentroids * (6 * d + 16));
     if (w.padded) {
         w.xpad = reinterpret_cast<float*>(take(size_t(N) * d * 4));
         w.cpad = reinterpret_cast<float*>(take(size_t(K) * d * 4));
@@ -214,9 +204,7 @@ hipError_t launch_assign_mfma_f16(const EStep& e, uint32_t d, const Workspace& w
 hipError_t launch_sort_vectors(const float* X, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, bool drop_hint,
                                hipStream_t s);
 hipError_t launch_sort_centroids(const float* C, uint32_t d, uint32_t K, const Workspace& w, hipStream_t s);
-// Every kBootstrapStride-th centroid in norm order (rows + indices), for the bootstrap hint pass.
-hipError_t launch_subsample_centroids(uint32_t d, uint32_t K, const Workspace& w, hipStream_t s);
-hipError_t launch_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, bool assume_hint,
+hipError_t launch_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, float guess,
                           hipStream_t s);
 hipError_t launch_unpermute(uint32_t N, uint32_t* idx, const Workspace& w, hipStream_t s);
 

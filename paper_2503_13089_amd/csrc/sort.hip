@@ -230,34 +230,31 @@ __global__ __launch_bounds__(kThreads) void key_starts_kernel(const uint16_t* __
 }
 
 // Window list of one 512-vector tile: the runs of the ordered codebook (in units of kWinQuad = 32
-// positions, one operand tile) that can hold the nearest centroid of any of its vectors. For vector x with bound u (the
-// distance to its hinted centroid, slightly enlarged), a candidate c has its norm within u of ||x|| and
-// its projection e.c within u of e.x. The tile takes the hull of those bands over its 512 (neighbouring,
-// hence similar) vectors; per shell s inside the norm band the cosine e.c/||c|| is then confined to
-// [t_lo, t_hi] computed from the shell's radius range, i.e. to a run of ordering keys (s, q_lo..q_hi). Norm keys are widened by one step (0.8 %) and cosine buckets by one (1/64) on
-// each side, far more than any rounding in the norms, projections and u. Runs of neighbouring shells
-// that touch are merged. If the band spans more than kWinSlots shells the list degrades to the single
-// run of all keys inside the norm band.
+// positions, one operand tile) that can hold the nearest centroid of any of its vectors. For vector x with
+// bound u (the distance to its hinted centroid, slightly enlarged), a candidate c has its norm within u of
+// ||x|| and its projection e.c within u of e.x. The tile takes the hull of those bands over its 512
+// (neighbouring, hence similar) vectors; per shell s inside the norm band the cosine e.c/||c|| is then
+// confined to [t_lo, t_hi] computed from the shell's radius range, i.e. to a run of ordering keys
+// (s, q_lo..q_hi). Norm keys are widened by one step (0.8 %) and cosine buckets by one (1/64) on each side,
+// far more than any rounding in the norms, projections and u. Runs of neighbouring shells that touch are
+// merged. If the band spans more than kWinSlots shells the list degrades to the single run of all keys
+// inside the norm band.
+// guess > 0 (no codes yet): u = guess * ||x|| instead, a window that proves nothing but is likely to hold a
+// centroid close to x; the nearest centroid inside it then serves as the hint of the real pass.
 // Layout per tile: entry 0 = (number of runs, their total length), entries 1.. = (first quad, end quad).
 template <int D>
 __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restrict__ Xs, uint32_t N,
                                                           const float* __restrict__ C, uint32_t K,
                                                           const uint32_t* __restrict__ hint, const WsPersist* persist,
-                                                          const uint32_t* __restrict__ ckey_starts, int assume_hint,
+                                                          const uint32_t* __restrict__ ckey_starts, float guess,
                                                           const WsHeader* __restrict__ hdr, uint2* __restrict__ win)
 {
     __shared__ float red[4][kThreads / 64];
     __shared__ uint2 runs[kWinSlots];
     const uint32_t quads = (K + kWinQuad - 1) / kWinQuad;
     uint2* out = win + size_t(blockIdx.x) * kWinStride;
-    const bool have_hint = assume_hint || persist->hint_valid != 0;
-    if (!have_hint) {
-        if (threadIdx.x == 0) {
-            out[0] = make_uint2(1, quads);
-            out[1] = make_uint2(0, quads);
-        }
-        return;
-    }
+    const bool guessing = guess > 0.0f;
+    if (guessing && persist->hint_valid != 0) return;  // a hint exists: the pass these windows are for will not run
     const uint32_t base = shell_base(hdr->absmax_bits, D);
     // phase 1: hull over the tile's vectors of the norm band [||x|| - u, ||x|| + u] and of the projection band
     // [e.x - u, e.x + u] (the hull of a union of intervals contains the union, so this only ever adds candidates)
@@ -266,14 +263,20 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
     for (int v = 0; v < 2; ++v) {
         const uint32_t p = blockIdx.x * 512 + v * kThreads + threadIdx.x;
         if (p < N) {
-            float x[D], c[D];
+            float x[D];
             load_row<D>(Xs + size_t(p) * D, x);
-            load_row<D>(C + size_t(min(hint[p], K - 1)) * D, c);
-            const float u = __builtin_sqrtf(direct_sqdist<D>(x, c)) * 1.001f + 1e-30f;
             float s = 0.0f, prj;
 #pragma unroll
             for (int j = 0; j < D; ++j) s = __builtin_fmaf(x[j], x[j], s);
             const float nrm = __builtin_sqrtf(s);
+            float u;
+            if (guessing) {
+                u = guess * nrm + 1e-30f;
+            } else {
+                float c[D];
+                load_row<D>(C + size_t(min(hint[p], K - 1)) * D, c);
+                u = __builtin_sqrtf(direct_sqdist<D>(x, c)) * 1.001f + 1e-30f;
+            }
             (void)ordering_key<D>(x, nrm, base, prj);
             nlo = __builtin_fminf(nlo, nrm - u);
             nhi = __builtin_fmaxf(nhi, nrm + u);
@@ -349,9 +352,12 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
             out[n] = last;
         }
     }
-    if (n == 0) {  // cannot happen (the hinted centroid itself lies inside its own runs); stay safe
+    if (n == 0) {
+        // With a hint this cannot happen (the hinted centroid itself lies inside its own runs); stay safe. A guessed
+        // window may well be empty: any one tile will do then, every centroid gives a valid bound.
         n = 1;
-        out[1] = make_uint2(0, quads);
+        out[1] = guessing ? make_uint2(min(ckey_starts[smin << 7] / kWinQuad, quads - 1), 0) : make_uint2(0, quads);
+        if (guessing) out[1].y = out[1].x + 1;
     }
     uint32_t total = 0;
     for (uint32_t r = 1; r <= n; ++r) total += out[r].y - out[r].x;
@@ -360,8 +366,9 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
 
 // Sum of the window sizes of the last E-step (statistics only).
 __global__ __launch_bounds__(1024) void window_stats_kernel(const uint2* __restrict__ win, uint32_t tiles, uint32_t K,
-                                                            WsHeader* hdr)
+                                                            WsHeader* hdr, int only_without_hint)
 {
+    if (only_without_hint && !gate_open(hdr, kGateAlways | kGateNoHint)) return;
     __shared__ unsigned long long red[16];
     unsigned long long s = 0;
     for (uint32_t t = blockIdx.x * 1024 + threadIdx.x; t < tiles; t += gridDim.x * 1024) s += win[size_t(t) * kWinStride].y;
@@ -441,22 +448,6 @@ hipError_t launch_sort_vectors(const float* X, uint32_t N, uint32_t d, uint32_t 
     return hipGetLastError();
 }
 
-// Every kBootstrapStride-th centroid of the norm order: rows and centroid indices (only when no hint exists).
-template <int D>
-__global__ __launch_bounds__(kThreads) void subsample_centroids_kernel(const float* __restrict__ csorted,
-                                                                       const uint32_t* __restrict__ cperm, uint32_t K,
-                                                                       uint32_t ksub, float* __restrict__ csub,
-                                                                       uint32_t* __restrict__ csub_ids,
-                                                                       const WsHeader* __restrict__ hdr)
-{
-    if (!gate_open(hdr, kGateAlways | kGateNoHint)) return;
-    const uint32_t p = blockIdx.x * kThreads + threadIdx.x;
-    if (p >= ksub) return;
-    const uint32_t src = min(p * kBootstrapStride, K - 1);
-    for (int j = 0; j < D; ++j) csub[size_t(p) * D + j] = csorted[size_t(src) * D + j];
-    csub_ids[p] = cperm[src];
-}
-
 // cinv[cperm[p]] = p
 __global__ __launch_bounds__(kThreads) void invert_perm_kernel(const uint32_t* __restrict__ perm, uint32_t n,
                                                                uint32_t* __restrict__ inv)
@@ -490,33 +481,25 @@ hipError_t launch_sort_centroids(const float* C, uint32_t d, uint32_t K, const W
     return hipGetLastError();
 }
 
-hipError_t launch_subsample_centroids(uint32_t d, uint32_t K, const Workspace& w, hipStream_t s)
-{
-    const dim3 grid((w.ksub + kThreads - 1) / kThreads);
-    switch (d) {
-        case 4: hipLaunchKernelGGL(subsample_centroids_kernel<4>, grid, dim3(kThreads), 0, s, w.csorted, w.cperm, K, w.ksub, w.csub, w.csub_ids, w.hdr); break;
-        case 8: hipLaunchKernelGGL(subsample_centroids_kernel<8>, grid, dim3(kThreads), 0, s, w.csorted, w.cperm, K, w.ksub, w.csub, w.csub_ids, w.hdr); break;
-        case 16: hipLaunchKernelGGL(subsample_centroids_kernel<16>, grid, dim3(kThreads), 0, s, w.csorted, w.cperm, K, w.ksub, w.csub, w.csub_ids, w.hdr); break;
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
-}
-
 template <int D>
-static void windows_t(const float* C, uint32_t N, uint32_t K, const Workspace& w, bool assume_hint, hipStream_t s)
+static void windows_t(const float* C, uint32_t N, uint32_t K, const Workspace& w, float guess, hipStream_t s)
 {
     hipLaunchKernelGGL(window_kernel<D>, dim3((N + 511) / 512), dim3(kThreads), 0, s, w.xsorted, N, C, K, w.idx_sorted,
-                       w.persist, w.key_starts, assume_hint ? 1 : 0, w.hdr, w.windows);
-    hipLaunchKernelGGL(window_stats_kernel, dim3(32), dim3(1024), 0, s, w.windows, (N + 511) / 512, K, w.hdr);
+                       w.persist, w.key_starts, guess, w.hdr, w.windows);
+    hipLaunchKernelGGL(window_stats_kernel, dim3(32), dim3(1024), 0, s, w.windows, (N + 511) / 512, K, w.hdr,
+                       guess > 0.0f ? 1 : 0);
 }
 
-hipError_t launch_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, bool assume_hint,
+// guess = 0: windows from the codes in w.idx_sorted (which must be valid codes of these vectors, however stale).
+// guess > 0: no codes needed - windows of relative half-width `guess` around every vector's own norm and
+// projection, for the bootstrap pass that produces the first codes; does nothing if the workspace holds a hint.
+hipError_t launch_windows(const float* C, uint32_t N, uint32_t d, uint32_t K, const Workspace& w, float guess,
                           hipStream_t s)
 {
     switch (d) {
-        case 4: windows_t<4>(C, N, K, w, assume_hint, s); break;
-        case 8: windows_t<8>(C, N, K, w, assume_hint, s); break;
-        case 16: windows_t<16>(C, N, K, w, assume_hint, s); break;
+        case 4: windows_t<4>(C, N, K, w, guess, s); break;
+        case 8: windows_t<8>(C, N, K, w, guess, s); break;
+        case 16: windows_t<16>(C, N, K, w, guess, s); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
