@@ -55,8 +55,8 @@ typedef enum cc_status {
 } cc_status;
 
 /* Host-only query: bytes of device workspace that cc_kmeans_fit / cc_assign / cc_lloyd_iter / cc_update
- * need for this problem size (about 8*N*d + 38*N bytes: an ordered copy of the vectors, a copy grouped
- * by cluster for the M-step, permutations and sort buffers, with d rounded up to 4, 8 or 16; plus one
+ * need for this problem size (about 12*N*d + 54*N bytes: an ordered copy of the vectors, room for two
+ * copies grouped by cluster for the M-step, permutations and sort buffers, with d rounded up to 4, 8 or 16; plus one
  * more padded copy of the vectors if d is not one of those). Returns 0 for an unsupported shape. The
  * first 256 bytes keep a little state between calls (problem shape, "codes of the previous E-step are
  * present"): a workspace that held something else in between is still safe to reuse - stale state can

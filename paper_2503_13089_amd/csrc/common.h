@@ -65,7 +65,7 @@ struct Workspace {
     uint32_t* sort_hist;       // [256 * sort blocks]
     uint2* windows;            // [ceil(N/512)][kWinStride] window list (runs of codebook stages) per 512-vector tile
     // M-step by buckets (K <= kMaxBuckets * kBucketClusters)
-    char* records;             // [N] x (4d + 16) bytes: the vectors, each with its code, grouped by bucket
+    char* records;             // [2N] x (4d + 16) bytes: the vectors, each with its code, grouped by bucket
     uint32_t* bucket_hist;     // [blocks][buckets] members of each bucket in each block of kBucketChunk vectors
     uint32_t* bucket_gtot;     // [groups of kBucketGroup blocks][buckets]
     uint32_t* bucket_totals;   // [buckets]
@@ -137,10 +137,12 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d_caller, uint32_t K)
         w.xpad = reinterpret_cast<float*>(take(size_t(N) * d * 4));
         w.cpad = reinterpret_cast<float*>(take(size_t(K) * d * 4));
     }
-    w.bucket_ok = K <= kMaxBuckets * kBucketClusters;
+    w.bucket_ok = K <= kMaxBuckets * kBucketClusters && N < (uint64_t(1) << 31);  // record positions are 32-bit
     if (w.bucket_ok) {
         const size_t buckets = (size_t(K) + kBucketClusters - 1) / kBucketClusters;
-        w.records = take(size_t(N) * (4 * d + 16));
+        // 2N records: an incremental M-step writes two records (plus, minus) per vector whose code changed, and
+        // nothing bounds how many change in one iteration
+        w.records = take(size_t(N) * 2 * (4 * d + 16));
         w.bucket_hist = reinterpret_cast<uint32_t*>(take(buckets * (size_t(N) / kBucketChunk + 1) * 4));
         w.bucket_gtot = reinterpret_cast<uint32_t*>(take(buckets * (size_t(N) / kBucketChunk / kBucketGroup + 1) * 4));
         w.bucket_totals = reinterpret_cast<uint32_t*>(take(buckets * 4));
