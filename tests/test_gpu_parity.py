@@ -380,6 +380,39 @@ def test_pruned_estep_on_awkward_data(g, d, fp16):
         parity.check_assignment(X, C, ref[name][0], k1, D1, D2)
 
 
+@pytest.mark.parametrize("case", ["centroids near the origin", "centroids far out", "one shell apart"])
+def test_cold_estep_when_no_centroid_is_near_the_guess(g, case):
+    """The first E-step on a workspace without codes guesses where each vector's neighbours are (a window around its
+    own norm and projection). When the centroids lie somewhere else entirely - every guessed window empty - the guess
+    only costs time: the codes are still the argmin over all centroids, bit for bit those of the unpruned run."""
+    import paper_2503_13089_amd as cc
+
+    rng = np.random.default_rng(77)
+    N, d, K = 50021, 4, 8200
+    X = (rng.standard_normal((N, d)) * 0.05).astype(np.float16).astype(np.float32)
+    C = (rng.standard_normal((K, d))).astype(np.float32)
+    if case == "centroids near the origin":
+        C *= np.float32(1e-4)
+    elif case == "centroids far out":
+        C *= np.float32(30.0)
+    else:  # all centroids on one thin shell just outside every guessed window of the bulk
+        C = (C / np.linalg.norm(C, axis=1, keepdims=True) * 0.5).astype(np.float32)
+    Xd = g.dev(X)
+    try:
+        cc.set_assign_mode(3)
+        ref_idx, ref_J = g.gpu_assign(Xd, C)
+        cc.set_assign_mode(0)
+        ws = g.workspace(N, d, K)
+        idx, J = g.gpu_assign(Xd, C, ws=ws)        # cold: guessed windows, then real ones
+        idx2, J2 = g.gpu_assign(Xd, C, ws=ws)      # hinted
+    finally:
+        cc.set_assign_mode(0)
+    assert np.array_equal(idx, ref_idx) and np.array_equal(idx2, ref_idx)
+    assert J == pytest.approx(ref_J, rel=1e-12) and J2 == pytest.approx(ref_J, rel=1e-12)
+    k1, D1, _, D2 = oracle.assign_top2(X, C)
+    parity.check_assignment(X, C, idx, k1, D1, D2)
+
+
 def test_more_than_65536_clusters(g, mode):
     """K above the 16-bit code range: the M-step cannot use its bucket formulation there (the sums are accumulated
     by the E-step kernel, or by atomics), with and without the window pruning of the automatic mode."""
