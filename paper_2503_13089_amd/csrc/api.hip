@@ -96,7 +96,8 @@ float guess_width(uint32_t K, uint32_t d)
 // have_hint = true: the caller knows that this workspace holds the codes of a previous E-step of the same
 // call (later iterations of a fit), so the bootstrap pass need not even be enqueued.
 int run_assign_matrix(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                      const cc::Workspace& w, bool accumulate, bool pruned, bool have_hint, hipStream_t s)
+                      const cc::Workspace& w, bool accumulate, bool pruned, bool have_hint, hipStream_t s,
+                      bool track_changes = false)
 {
     const bool both = g_assign_mode.load() != 2;  // fp16 and fp32 variants enqueued, the device gate picks one
     cc::EStep e{};
@@ -126,6 +127,8 @@ int run_assign_matrix(const float* X, uint32_t N, uint32_t d, const float* C, ui
     e.K = K; e.packed = w.packed; e.packed_tiles = w.packed_tiles;
     e.windows = pruned ? w.windows : nullptr;
     e.accumulate = accumulate; e.hint_only = false;
+    // (incremental M-step) the kernel notes which vectors leave the code that e.idx held on entry, and that code
+    if (track_changes) { e.prev_out = w.idx_prev; e.changed = w.changed; }
     if (both) {
         e.gate = cc::kGateIfF16;
         CC_TRY_HIP(cc::launch_assign_mfma_f16(e, d, w, s), "assign (fp16 matrix cores)");
@@ -165,17 +168,17 @@ int run_lloyd_iter(const float* X, uint32_t N, uint32_t d, float* C, uint32_t K,
 {
     if (use_matrix_cores(K)) {
         // sums_follow (inside a fit, pruned path, after an M-step by buckets of the same fit): the workspace holds the
-        // integer sums and counts of the codes in w.idx_sorted; keep a copy of those codes so that the M-step can
-        // move just the vectors whose code changes
-        if (sums_follow) CC_TRY_HIP(cc::launch_copy_u32(w.idx_sorted, w.idx_prev, N, s), "update (previous codes)");
+        // integer sums and counts of the codes in w.idx_sorted. The E-step kernel then flags the vectors that leave
+        // those codes (and keeps the code they had), so that the M-step can move just these.
         // A pruned E-step is shorter than the atomic traffic of the fused accumulation (which then becomes the
         // bottleneck), so there the M-step groups the vectors by bucket of clusters and sums in LDS instead.
         const bool by_buckets = pruned && w.bucket_ok;
         if (!by_buckets) CC_TRY_HIP(cc::launch_zero_accumulators(w, K, d, nullptr, 0, s), "update (clear)");
-        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, !by_buckets, pruned, have_hint, s)) return rc;
+        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, !by_buckets, pruned, have_hint, s, sums_follow)) return rc;
         if (by_buckets)
             CC_TRY_HIP(cc::launch_update_buckets(w.xsorted, N, d, w.idx_sorted, C, K, C, counts, w, true, true, s,
-                                                 sums_follow ? w.idx_prev : nullptr), "update (buckets)");
+                                                 sums_follow ? w.idx_prev : nullptr, sums_follow ? w.changed : nullptr),
+                    "update (buckets)");
         else
             CC_TRY_HIP(cc::launch_finalize(C, C, counts, K, d, N, w, true, s), "update (means)");
         if (pruned && idx != nullptr) CC_TRY_HIP(cc::launch_unpermute(N, idx, w, s), "assign (codes to input order)");

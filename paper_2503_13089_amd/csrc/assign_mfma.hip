@@ -88,7 +88,9 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
                                                                WsHeader* hdr, uint32_t* __restrict__ refine_list,
                                                                uint32_t refine_cap, int gate, long long* sums,
                                                                uint32_t* counts, const uint2* __restrict__ windows,
-                                                               const uint32_t* __restrict__ cperm, int hint_only)
+                                                               const uint32_t* __restrict__ cperm, int hint_only,
+                                                               uint32_t* __restrict__ prev_out,
+                                                               uint32_t* __restrict__ changed)
 {
     constexpr int KS = D / 2;                 // MFMA k-steps per tile
     if (!gate_open(hdr, gate)) return;        // uniform over the grid
@@ -255,7 +257,15 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
         for (int j = 0; j < D; ++j) xn = __builtin_fmaf(x[j], x[j], xn);
         const float delta = kGuardSafety * 2.0f * kUnit * (float(5 * D + 2) * xn + float(4 * D + 2) * dstar) + 1e-36f;
         const bool safe = (sstar - bstar) > delta;  // false for NaN as well
+        bool moved = false;
         if (h == 0 && i_raw < N) {
+            if (changed != nullptr) {
+                // the code this vector had so far, kept wherever the M-step will have to look at it again: the
+                // code differs, or the refinement may still change it
+                const uint32_t old = idx[i];
+                moved = old != kstar || !safe;
+                if (moved) prev_out[i] = old;
+            }
             idx[i] = kstar;
             dmin[i] = dstar;
             if (sums != nullptr) accumulate_vector<D>(x, kstar, sums, counts, fixed_point_exp(hdr->absmax_bits, N), +1);
@@ -263,6 +273,10 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
                 const uint32_t pos = atomicAdd(&hdr->refine_count, 1u);
                 if (pos < refine_cap) refine_list[pos] = i;
             }
+        }
+        if (changed != nullptr) {  // uniform over the wave; lanes 0..31 hold the 32 consecutive vectors of this tile
+            const unsigned long long m = __ballot(moved);
+            if (lane == 0 && vbase + vt * 32 < N) changed[(vbase + vt * 32) >> 5] = uint32_t(m);
         }
     }
 }
@@ -282,7 +296,8 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
     hipLaunchKernelGGL(kernel, dim3((e.N + per_block - 1) / per_block), dim3(kThreads), 0, s,
                        e.X, e.N, e.rows, e.K, static_cast<const float*>(e.packed), e.packed_tiles, e.idx, w.dmin, w.hdr,
                        w.refine_list, w.refine_cap, e.gate, e.accumulate ? w.sums : nullptr,
-                       e.accumulate ? w.counts : nullptr, e.windows, e.row_ids, e.hint_only ? 1 : 0);
+                       e.accumulate ? w.counts : nullptr, e.windows, e.row_ids, e.hint_only ? 1 : 0,
+                       e.prev_out, e.changed);
     return hipGetLastError();
 }
 

@@ -168,7 +168,8 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
     const float* __restrict__ X, uint32_t N, const float* __restrict__ C, uint32_t K, const char* __restrict__ packed,
     uint32_t ntiles, uint32_t* __restrict__ idx, float* __restrict__ dmin, WsHeader* hdr,
     uint32_t* __restrict__ refine_list, uint32_t refine_cap, int gate,
-    long long* sums, uint32_t* counts, const uint2* __restrict__ windows, const uint32_t* __restrict__ cperm, int hint_only)
+    long long* sums, uint32_t* counts, const uint2* __restrict__ windows, const uint32_t* __restrict__ cperm, int hint_only,
+    uint32_t* __restrict__ prev_out, uint32_t* __restrict__ changed)
 {
     using S = F16Shape<D>;
     constexpr int KM = S::KM;
@@ -365,7 +366,15 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
         const float delta = kGuardSafety * 2.0f * kAccumUlps * kUnit * (sigma * (5.0f * xn + 4.0f * dstar) + inflation) +
                             kGuardSafety * (2.0f * kUnit * x1 + 1e-11f) + 1e-36f;
         const bool safe = (sstar - bstar) > delta;  // false for NaN as well
+        bool moved = false;
         if (h == 0 && i_raw < N) {
+            if (changed != nullptr) {
+                // the code this vector had so far, kept wherever the M-step will have to look at it again: the
+                // code differs, or the refinement may still change it
+                const uint32_t old = idx[i];
+                moved = old != kstar || !safe;
+                if (moved) prev_out[i] = old;
+            }
             idx[i] = kstar;
             dmin[i] = dstar;
             if (sums != nullptr) accumulate_vector<D>(x, kstar, sums, counts, fixed_point_exp(hdr->absmax_bits, N), +1);
@@ -373,6 +382,10 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
                 const uint32_t pos = atomicAdd(&hdr->refine_count, 1u);
                 if (pos < refine_cap) refine_list[pos] = i;
             }
+        }
+        if (changed != nullptr) {  // uniform over the wave; lanes 0..31 hold the 32 consecutive vectors of this tile
+            const unsigned long long m = __ballot(moved);
+            if (lane == 0 && vbase + vt * 32 < N) changed[(vbase + vt * 32) >> 5] = uint32_t(m);
         }
     }
 }
@@ -396,7 +409,8 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
     hipLaunchKernelGGL(kernel, dim3((e.N + per_block - 1) / per_block), dim3(kThreads),
                        0, s, e.X, e.N, e.rows, e.K, static_cast<const char*>(e.packed), e.packed_tiles, e.idx, w.dmin, w.hdr,
                        w.refine_list, w.refine_cap, e.gate, e.accumulate ? w.sums : nullptr,
-                       e.accumulate ? w.counts : nullptr, e.windows, e.row_ids, e.hint_only ? 1 : 0);
+                       e.accumulate ? w.counts : nullptr, e.windows, e.row_ids, e.hint_only ? 1 : 0,
+                       e.prev_out, e.changed);
     return hipGetLastError();
 }
 

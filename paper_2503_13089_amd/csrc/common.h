@@ -50,7 +50,8 @@ struct Workspace {
     WsPersist* persist;
     float* xsorted;            // [N*d]  the vectors in ascending-norm order
     uint32_t* idx_sorted;      // [N]    codes in that order (also the next call's hint)
-    uint32_t* idx_prev;        // [N]    the codes of the previous iteration of a fit (incremental M-step)
+    uint32_t* idx_prev;        // [N]    the previous iteration's code of every vector flagged in `changed` (incremental M-step)
+    uint32_t* changed;         // [ceil(N/32)] one bit per ordered vector: its code may differ from the previous iteration's
     uint32_t* vperm;           // [N]    input position of the p-th vector in norm order
     uint32_t* vperm_tmp;       // [N]
     uint16_t* vkeys;           // [N]    norm keys (sorted after the sort)
@@ -120,6 +121,7 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d_caller, uint32_t K)
     w.xsorted = reinterpret_cast<float*>(take(size_t(N) * d * 4));
     w.idx_sorted = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.idx_prev = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
+    w.changed = reinterpret_cast<uint32_t*>(take((size_t(N) / 32 + 1) * 4));
     w.vperm = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vperm_tmp = reinterpret_cast<uint32_t*>(take(size_t(N) * 4));
     w.vkeys = reinterpret_cast<uint16_t*>(take(size_t(N) * 2));
@@ -189,6 +191,8 @@ struct EStep {
     uint32_t* idx;              // codes out
     bool accumulate;            // also add every vector to the cluster sums/counts of its provisional code
     bool hint_only;             // only write codes: no guard band, no distances, no refine list
+    uint32_t* prev_out;         // with `changed`: where the code that idx held before goes, for every vector flagged there
+    uint32_t* changed;          // NULL, or one bit per vector, set where the code differs from what idx held or is not final yet
     int gate;
 };
 
@@ -241,10 +245,13 @@ hipError_t launch_accumulate(const float* X, uint32_t N, uint32_t d, const uint3
 // buckets the clusters by their position in the norm order left by launch_sort_centroids (w.cinv, w.cperm).
 // mean = false writes the plain sums (0 for an empty cluster) instead of the means. The integer sums and the
 // counts are left in w.sums / w.counts. prev_idx != NULL: those already hold the sums and counts of the codes
-// prev_idx; only the vectors whose code differs are moved (bit-identical to a recomputation from idx).
+// prev_idx; only the vectors whose code differs are moved (bit-identical to a recomputation from idx). With
+// `changed` (one bit per vector) prev_idx is only read, and only needs to be valid, where the bit is set; a vector
+// whose bit is clear must have kept its code.
 hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,
                                  uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order,
-                                 bool mean, hipStream_t s, const uint32_t* prev_idx = nullptr);
+                                 bool mean, hipStream_t s, const uint32_t* prev_idx = nullptr,
+                                 const uint32_t* changed = nullptr);
 hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, size_t n, hipStream_t s);
 // out[i][j] = j < d_in ? in[i][j] : 0 for rows of d_out >= d_in floats, and the reverse (drop the tail).
 hipError_t launch_pad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s);

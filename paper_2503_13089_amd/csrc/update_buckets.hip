@@ -18,6 +18,8 @@
 // four steps (18 % of them in the second iteration of the 4-bit benchmark, 2 % in the twentieth), each as
 // two records - plus for the new cluster, minus for the old one - and step 4 adds the bucket's net change
 // to the sums and counts that the previous iteration left in the workspace. Bit-identical to a recomputation.
+// The E-step kernel that produced the codes leaves a bitmap of the vectors that may have changed (and their
+// previous code), so steps 1 and 3 read one bit per vector instead of two code arrays.
 #include <algorithm>
 
 #include "common.h"
@@ -55,12 +57,23 @@ __device__ __forceinline__ uint32_t slot_of_code(uint32_t k, const uint32_t* __r
     return cinv != nullptr ? cinv[k] : k;
 }
 
+// The flagged vectors among the 16 that thread t of a block looks after (vectors lo + 16 t .. lo + 16 t + 15 of a
+// chunk starting at lo, a multiple of 32): 16 bits of the `changed` bitmap, 0 beyond the last vector.
+__device__ __forceinline__ uint32_t flagged16(const uint32_t* __restrict__ changed, uint32_t lo, uint32_t N)
+{
+    const uint32_t first = lo + 16 * threadIdx.x;
+    if (first >= N) return 0;
+    return (changed[first >> 5] >> (first & 31)) & 0xffffu;
+}
+
 // ---- 1. bucket histogram of one block of vectors: row `block` of hist[blocks][nbuckets]
 __global__ __launch_bounds__(kThreads) void bucket_count_kernel(const uint32_t* __restrict__ idx,
-                                                                const uint32_t* __restrict__ prev, uint32_t N, uint32_t K,
+                                                                const uint32_t* __restrict__ prev,
+                                                                const uint32_t* __restrict__ changed, uint32_t N, uint32_t K,
                                                                 const uint32_t* __restrict__ cinv, uint32_t nbuckets,
                                                                 uint32_t* __restrict__ hist, WsHeader* hdr)
 {
+    static_assert(kBucketChunk == 16 * kThreads, "one thread per 16 bits of the change bitmap");
     __shared__ uint32_t h[kMaxBuckets];
     __shared__ uint32_t bad_total;
     for (uint32_t b = threadIdx.x; b < nbuckets; b += kThreads) h[b] = 0;
@@ -68,7 +81,17 @@ __global__ __launch_bounds__(kThreads) void bucket_count_kernel(const uint32_t* 
     __syncthreads();
     const uint32_t lo = blockIdx.x * kBucketChunk, hi = min(lo + kBucketChunk, N);
     uint32_t bad = 0;
-    for (uint32_t i = lo + threadIdx.x; i < hi; i += kThreads) {
+    if (changed != nullptr) {  // only the flagged vectors are looked at (bits beyond N are never set)
+        for (uint32_t bits = flagged16(changed, lo, N); bits != 0; bits &= bits - 1) {
+            const uint32_t i = lo + 16 * threadIdx.x + uint32_t(__ffs(int(bits)) - 1);
+            const uint32_t k = idx[i], kp = prev[i];
+            if (k != kp && k < K && kp < K) {
+                atomicAdd(&h[slot_of_code(k, cinv) / kBucketClusters], 1u);
+                atomicAdd(&h[slot_of_code(kp, cinv) / kBucketClusters], 1u);
+            }
+        }
+    }
+    for (uint32_t i = lo + threadIdx.x; changed == nullptr && i < hi; i += kThreads) {
         const uint32_t k = idx[i];
         if (prev != nullptr) {  // only vectors whose code changed: one record for the new cluster, one for the old
             const uint32_t kp = prev[i];
@@ -241,7 +264,8 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(const float* _
 template <int D>
 __global__ __launch_bounds__(kThreads) void bucket_scatter_delta_kernel(const float* __restrict__ X, uint32_t N,
                                                                         const uint32_t* __restrict__ idx,
-                                                                        const uint32_t* __restrict__ prev, uint32_t K,
+                                                                        const uint32_t* __restrict__ prev,
+                                                                        const uint32_t* __restrict__ changed, uint32_t K,
                                                                         const uint32_t* __restrict__ cinv,
                                                                         uint32_t nbuckets,
                                                                         const uint32_t* __restrict__ hist,
@@ -255,6 +279,29 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_delta_kernel(const fl
         cursor[b] = base[b] + gtot[size_t(blockIdx.x / kBucketGroup) * nbuckets + b] + hist[size_t(blockIdx.x) * nbuckets + b];
     __syncthreads();
     const uint32_t lo = blockIdx.x * kBucketChunk;
+    // one record for the new cluster (minus = 0), one for the old (minus = 1)
+    auto emit = [&](uint32_t i, uint32_t k_new, uint32_t k_old) {
+        float4 row[D / 4];
+#pragma unroll
+        for (int q = 0; q < D / 4; ++q) row[q] = reinterpret_cast<const float4*>(X + size_t(i) * D)[q];
+#pragma unroll
+        for (uint32_t minus = 0; minus < 2; ++minus) {
+            const uint32_t slot = slot_of_code(minus ? k_old : k_new, cinv);
+            const uint32_t pos = atomicAdd(&cursor[slot / kBucketClusters], 1u);
+            char* rec = records + size_t(pos) * Record<D>::kBytes;
+#pragma unroll
+            for (int q = 0; q < D / 4; ++q) reinterpret_cast<float4*>(rec)[q] = row[q];
+            *reinterpret_cast<uint4*>(rec + D * 4) = make_uint4(slot, i, minus, 0u);
+        }
+    };
+    if (changed != nullptr) {
+        for (uint32_t bits = flagged16(changed, lo, N); bits != 0; bits &= bits - 1) {
+            const uint32_t i = lo + 16 * threadIdx.x + uint32_t(__ffs(int(bits)) - 1);
+            const uint32_t k = idx[i], kp = prev[i];
+            if (k != kp && k < K && kp < K) emit(i, k, kp);
+        }
+        return;
+    }
     uint32_t kn[kPer], kp[kPer];
 #pragma unroll
     for (int r = 0; r < kPer; ++r) {
@@ -265,19 +312,7 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_delta_kernel(const fl
 #pragma unroll
     for (int r = 0; r < kPer; ++r) {
         if (kn[r] == kp[r] || kn[r] >= K || kp[r] >= K) continue;
-        const uint32_t i = lo + r * kThreads + threadIdx.x;
-        float4 row[D / 4];
-#pragma unroll
-        for (int q = 0; q < D / 4; ++q) row[q] = reinterpret_cast<const float4*>(X + size_t(i) * D)[q];
-#pragma unroll
-        for (uint32_t minus = 0; minus < 2; ++minus) {
-            const uint32_t slot = slot_of_code(minus ? kp[r] : kn[r], cinv);
-            const uint32_t pos = atomicAdd(&cursor[slot / kBucketClusters], 1u);
-            char* rec = records + size_t(pos) * Record<D>::kBytes;
-#pragma unroll
-            for (int q = 0; q < D / 4; ++q) reinterpret_cast<float4*>(rec)[q] = row[q];
-            *reinterpret_cast<uint4*>(rec + D * 4) = make_uint4(slot, i, minus, 0u);
-        }
+        emit(lo + r * kThreads + threadIdx.x, kn[r], kp[r]);
     }
 }
 
@@ -342,17 +377,17 @@ __global__ __launch_bounds__(kThreads) void bucket_sum_kernel(const char* __rest
 }
 
 template <int D>
-static void update_buckets_t(const float* X, uint32_t N, const uint32_t* idx, const uint32_t* prev_idx, const float* prev,
-                             uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order, bool mean,
-                             hipStream_t s)
+static void update_buckets_t(const float* X, uint32_t N, const uint32_t* idx, const uint32_t* prev_idx,
+                             const uint32_t* changed, const float* prev, uint32_t K, float* out, uint32_t* counts_out,
+                             const Workspace& w, bool norm_order, bool mean, hipStream_t s)
 {
     const uint32_t nbuckets = (K + kBucketClusters - 1) / kBucketClusters;
     const uint32_t blocks = (N + kBucketChunk - 1) / kBucketChunk;
     const uint32_t* cinv = norm_order ? w.cinv : nullptr;
     const uint32_t* cperm = norm_order ? w.cperm : nullptr;
     const bool delta = prev_idx != nullptr;
-    hipLaunchKernelGGL(bucket_count_kernel, dim3(blocks), dim3(kThreads), 0, s, idx, prev_idx, N, K, cinv, nbuckets,
-                       w.bucket_hist, w.hdr);
+    hipLaunchKernelGGL(bucket_count_kernel, dim3(blocks), dim3(kThreads), 0, s, idx, prev_idx, delta ? changed : nullptr, N, K,
+                       cinv, nbuckets, w.bucket_hist, w.hdr);
     const uint32_t groups = (blocks + kBucketGroup - 1) / kBucketGroup;
     const uint32_t bwg = (nbuckets + kThreads - 1) / kThreads;
     hipLaunchKernelGGL(bucket_groupscan_kernel, dim3(bwg, groups), dim3(kThreads), 0, s, w.bucket_hist, blocks, nbuckets,
@@ -361,8 +396,8 @@ static void update_buckets_t(const float* X, uint32_t N, const uint32_t* idx, co
                        w.bucket_totals);
     hipLaunchKernelGGL(bucket_base_kernel, dim3(1), dim3(kThreads), 0, s, w.bucket_totals, nbuckets, w.bucket_base);
     if (delta)
-        hipLaunchKernelGGL(bucket_scatter_delta_kernel<D>, dim3(blocks), dim3(kThreads), 0, s, X, N, idx, prev_idx, K, cinv,
-                           nbuckets, w.bucket_hist, w.bucket_gtot, w.bucket_base, w.records);
+        hipLaunchKernelGGL(bucket_scatter_delta_kernel<D>, dim3(blocks), dim3(kThreads), 0, s, X, N, idx, prev_idx, changed, K,
+                           cinv, nbuckets, w.bucket_hist, w.bucket_gtot, w.bucket_base, w.records);
     else
         hipLaunchKernelGGL(bucket_scatter_kernel<D>, dim3(blocks), dim3(kThreads), 0, s, X, N, idx, K, cinv, nbuckets,
                            w.bucket_hist, w.bucket_gtot, w.bucket_base, w.records);
@@ -372,13 +407,13 @@ static void update_buckets_t(const float* X, uint32_t N, const uint32_t* idx, co
 
 hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,
                                  uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order,
-                                 bool mean, hipStream_t s, const uint32_t* prev_idx)
+                                 bool mean, hipStream_t s, const uint32_t* prev_idx, const uint32_t* changed)
 {
     if (K > kMaxBuckets * kBucketClusters || w.records == nullptr) return hipErrorInvalidValue;
     switch (d) {
-        case 4: update_buckets_t<4>(X, N, idx, prev_idx, prev, K, out, counts_out, w, norm_order, mean, s); break;
-        case 8: update_buckets_t<8>(X, N, idx, prev_idx, prev, K, out, counts_out, w, norm_order, mean, s); break;
-        case 16: update_buckets_t<16>(X, N, idx, prev_idx, prev, K, out, counts_out, w, norm_order, mean, s); break;
+        case 4: update_buckets_t<4>(X, N, idx, prev_idx, changed, prev, K, out, counts_out, w, norm_order, mean, s); break;
+        case 8: update_buckets_t<8>(X, N, idx, prev_idx, changed, prev, K, out, counts_out, w, norm_order, mean, s); break;
+        case 16: update_buckets_t<16>(X, N, idx, prev_idx, changed, prev, K, out, counts_out, w, norm_order, mean, s); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
