@@ -89,6 +89,7 @@ constexpr uint32_t kBucketClusters = 64;  // M-step by buckets: consecutive clus
 constexpr uint32_t kMaxBuckets = 1024;    // so K <= 65536 for that path
 constexpr uint32_t kBucketGroup = 64;     // blocks per group in the two-level scan of the bucket histogram
 constexpr uint32_t kBucketChunk = 4096;   // vectors per workgroup in its counting and scatter passes
+constexpr uint32_t kDeltaChunk = 16384;   // the same for an incremental pass, which looks only at the flagged vectors
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -245,9 +246,9 @@ hipError_t launch_accumulate(const float* X, uint32_t N, uint32_t d, const uint3
 // buckets the clusters by their position in the norm order left by launch_sort_centroids (w.cinv, w.cperm).
 // mean = false writes the plain sums (0 for an empty cluster) instead of the means. The integer sums and the
 // counts are left in w.sums / w.counts. prev_idx != NULL: those already hold the sums and counts of the codes
-// prev_idx; only the vectors whose code differs are moved (bit-identical to a recomputation from idx). With
-// `changed` (one bit per vector) prev_idx is only read, and only needs to be valid, where the bit is set; a vector
-// whose bit is clear must have kept its code.
+// prev_idx; only the vectors whose code differs are moved (bit-identical to a recomputation from idx). That needs
+// `changed` too, one bit per vector: prev_idx is only read, and only needs to be valid, where the bit is set, and a
+// vector whose bit is clear must have kept its code.
 hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev,
                                  uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order,
                                  bool mean, hipStream_t s, const uint32_t* prev_idx = nullptr,

@@ -335,33 +335,42 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
         runs[threadIdx.x] = r;
     }
     __syncthreads();
-    if (threadIdx.x != 0) return;
-    uint32_t n = 0;
-    uint2 last = make_uint2(0, 0);
-    for (uint32_t t = 0; t < nslots; ++t) {
-        const uint2 r = runs[t];
-        if (r.x >= r.y) continue;
-        // touches or overlaps the previous run, or starts in the stage where it ended (positions ascend with
-        // the shell): merge, so that no stage - and no tracking group - is ever visited twice
-        if (n > 0 && r.x / kStageTiles <= (last.y - 1) / kStageTiles) {
-            last.y = max(last.y, r.y);
-            out[n] = last;
-        } else {
-            ++n;
-            last = r;
-            out[n] = last;
+    // One thread merges the (at most kWinSlots) runs in LDS; the list then leaves with one store per thread. (Merging
+    // straight into global memory and reading the list back for its total made this serial tail the longest part
+    // of the kernel.)
+    __shared__ uint2 merged[kWinSlots];
+    __shared__ uint32_t merged_n, merged_total;
+    if (threadIdx.x == 0) {
+        uint32_t n = 0;
+        uint2 last = make_uint2(0, 0);
+        for (uint32_t t = 0; t < nslots; ++t) {
+            const uint2 r = runs[t];
+            if (r.x >= r.y) continue;
+            // touches or overlaps the previous run, or starts in the stage where it ended (positions ascend with
+            // the shell): merge, so that no stage - and no tracking group - is ever visited twice
+            if (n > 0 && r.x / kStageTiles <= (last.y - 1) / kStageTiles) {
+                last.y = max(last.y, r.y);
+                merged[n - 1] = last;
+            } else {
+                last = r;
+                merged[n++] = last;
+            }
         }
+        if (n == 0) {
+            // With a hint this cannot happen (the hinted centroid itself lies inside its own runs); stay safe. A guessed
+            // window may well be empty: any one tile will do then, every centroid gives a valid bound.
+            n = 1;
+            const uint32_t q = min(ckey_starts[smin << 7] / kWinQuad, quads - 1);
+            merged[0] = guessing ? make_uint2(q, q + 1) : make_uint2(0, quads);
+        }
+        uint32_t total = 0;
+        for (uint32_t r = 0; r < n; ++r) total += merged[r].y - merged[r].x;
+        merged_n = n;
+        merged_total = total;
     }
-    if (n == 0) {
-        // With a hint this cannot happen (the hinted centroid itself lies inside its own runs); stay safe. A guessed
-        // window may well be empty: any one tile will do then, every centroid gives a valid bound.
-        n = 1;
-        out[1] = guessing ? make_uint2(min(ckey_starts[smin << 7] / kWinQuad, quads - 1), 0) : make_uint2(0, quads);
-        if (guessing) out[1].y = out[1].x + 1;
-    }
-    uint32_t total = 0;
-    for (uint32_t r = 1; r <= n; ++r) total += out[r].y - out[r].x;
-    out[0] = make_uint2(n, total);
+    __syncthreads();
+    if (threadIdx.x < merged_n) out[1 + threadIdx.x] = merged[threadIdx.x];
+    if (threadIdx.x == 0) out[0] = make_uint2(merged_n, merged_total);
 }
 
 // Sum of the window sizes of the last E-step (statistics only).

@@ -57,13 +57,19 @@ __device__ __forceinline__ uint32_t slot_of_code(uint32_t k, const uint32_t* __r
     return cinv != nullptr ? cinv[k] : k;
 }
 
-// The flagged vectors among the 16 that thread t of a block looks after (vectors lo + 16 t .. lo + 16 t + 15 of a
-// chunk starting at lo, a multiple of 32): 16 bits of the `changed` bitmap, 0 beyond the last vector.
-__device__ __forceinline__ uint32_t flagged16(const uint32_t* __restrict__ changed, uint32_t lo, uint32_t N)
+// Calls f(i) for every flagged vector among the kDeltaChunk / kThreads = 64 consecutive ones that this thread
+// looks after in the chunk starting at lo (two words of the `changed` bitmap; bits beyond N are never set).
+template <typename F>
+__device__ __forceinline__ void for_each_flagged(const uint32_t* __restrict__ changed, uint32_t lo, uint32_t N, F f)
 {
-    const uint32_t first = lo + 16 * threadIdx.x;
-    if (first >= N) return 0;
-    return (changed[first >> 5] >> (first & 31)) & 0xffffu;
+    static_assert(kDeltaChunk == 64 * kThreads, "two bitmap words per thread");
+    const uint32_t first = lo + 64 * threadIdx.x;
+#pragma unroll
+    for (uint32_t w = 0; w < 2; ++w) {
+        if (first + 32 * w >= N) break;
+        for (uint32_t bits = changed[(first >> 5) + w]; bits != 0; bits &= bits - 1)
+            f(first + 32 * w + uint32_t(__ffs(int(bits)) - 1));
+    }
 }
 
 // ---- 1. bucket histogram of one block of vectors: row `block` of hist[blocks][nbuckets]
@@ -73,34 +79,27 @@ __global__ __launch_bounds__(kThreads) void bucket_count_kernel(const uint32_t* 
                                                                 const uint32_t* __restrict__ cinv, uint32_t nbuckets,
                                                                 uint32_t* __restrict__ hist, WsHeader* hdr)
 {
-    static_assert(kBucketChunk == 16 * kThreads, "one thread per 16 bits of the change bitmap");
     __shared__ uint32_t h[kMaxBuckets];
     __shared__ uint32_t bad_total;
     for (uint32_t b = threadIdx.x; b < nbuckets; b += kThreads) h[b] = 0;
     if (threadIdx.x == 0) bad_total = 0;
     __syncthreads();
-    const uint32_t lo = blockIdx.x * kBucketChunk, hi = min(lo + kBucketChunk, N);
+    // a full pass works on chunks of kBucketChunk vectors; an incremental one (changed != NULL) on chunks of
+    // kDeltaChunk, looks only at the flagged vectors, and counts one record for the new cluster and one for the old
+    const uint32_t chunk = changed != nullptr ? kDeltaChunk : kBucketChunk;
+    const uint32_t lo = blockIdx.x * chunk, hi = min(lo + chunk, N);
     uint32_t bad = 0;
-    if (changed != nullptr) {  // only the flagged vectors are looked at (bits beyond N are never set)
-        for (uint32_t bits = flagged16(changed, lo, N); bits != 0; bits &= bits - 1) {
-            const uint32_t i = lo + 16 * threadIdx.x + uint32_t(__ffs(int(bits)) - 1);
+    if (changed != nullptr) {
+        for_each_flagged(changed, lo, N, [&](uint32_t i) {
             const uint32_t k = idx[i], kp = prev[i];
             if (k != kp && k < K && kp < K) {
                 atomicAdd(&h[slot_of_code(k, cinv) / kBucketClusters], 1u);
                 atomicAdd(&h[slot_of_code(kp, cinv) / kBucketClusters], 1u);
             }
-        }
+        });
     }
     for (uint32_t i = lo + threadIdx.x; changed == nullptr && i < hi; i += kThreads) {
         const uint32_t k = idx[i];
-        if (prev != nullptr) {  // only vectors whose code changed: one record for the new cluster, one for the old
-            const uint32_t kp = prev[i];
-            if (k != kp && k < K && kp < K) {
-                atomicAdd(&h[slot_of_code(k, cinv) / kBucketClusters], 1u);
-                atomicAdd(&h[slot_of_code(kp, cinv) / kBucketClusters], 1u);
-            }
-            continue;
-        }
         if (k < K) atomicAdd(&h[slot_of_code(k, cinv) / kBucketClusters], 1u);
         else ++bad;
     }
@@ -273,19 +272,19 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_delta_kernel(const fl
                                                                         const uint32_t* __restrict__ base,
                                                                         char* __restrict__ records)
 {
-    constexpr int kPer = kBucketChunk / kThreads;
     __shared__ uint32_t cursor[kMaxBuckets];  // next free record of (bucket, this block)
     for (uint32_t b = threadIdx.x; b < nbuckets; b += kThreads)
         cursor[b] = base[b] + gtot[size_t(blockIdx.x / kBucketGroup) * nbuckets + b] + hist[size_t(blockIdx.x) * nbuckets + b];
     __syncthreads();
-    const uint32_t lo = blockIdx.x * kBucketChunk;
-    // one record for the new cluster (minus = 0), one for the old (minus = 1)
-    auto emit = [&](uint32_t i, uint32_t k_new, uint32_t k_old) {
+    const uint32_t lo = blockIdx.x * kDeltaChunk;
+    for_each_flagged(changed, lo, N, [&](uint32_t i) {
+        const uint32_t k_new = idx[i], k_old = prev[i];
+        if (k_new == k_old || k_new >= K || k_old >= K) return;
         float4 row[D / 4];
 #pragma unroll
         for (int q = 0; q < D / 4; ++q) row[q] = reinterpret_cast<const float4*>(X + size_t(i) * D)[q];
 #pragma unroll
-        for (uint32_t minus = 0; minus < 2; ++minus) {
+        for (uint32_t minus = 0; minus < 2; ++minus) {  // a record for the new cluster, one for the old
             const uint32_t slot = slot_of_code(minus ? k_old : k_new, cinv);
             const uint32_t pos = atomicAdd(&cursor[slot / kBucketClusters], 1u);
             char* rec = records + size_t(pos) * Record<D>::kBytes;
@@ -293,27 +292,7 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_delta_kernel(const fl
             for (int q = 0; q < D / 4; ++q) reinterpret_cast<float4*>(rec)[q] = row[q];
             *reinterpret_cast<uint4*>(rec + D * 4) = make_uint4(slot, i, minus, 0u);
         }
-    };
-    if (changed != nullptr) {
-        for (uint32_t bits = flagged16(changed, lo, N); bits != 0; bits &= bits - 1) {
-            const uint32_t i = lo + 16 * threadIdx.x + uint32_t(__ffs(int(bits)) - 1);
-            const uint32_t k = idx[i], kp = prev[i];
-            if (k != kp && k < K && kp < K) emit(i, k, kp);
-        }
-        return;
-    }
-    uint32_t kn[kPer], kp[kPer];
-#pragma unroll
-    for (int r = 0; r < kPer; ++r) {
-        const uint32_t i = lo + r * kThreads + threadIdx.x;
-        kn[r] = i < N ? idx[i] : 0u;
-        kp[r] = i < N ? prev[i] : 0u;
-    }
-#pragma unroll
-    for (int r = 0; r < kPer; ++r) {
-        if (kn[r] == kp[r] || kn[r] >= K || kp[r] >= K) continue;
-        emit(lo + r * kThreads + threadIdx.x, kn[r], kp[r]);
-    }
+    });
 }
 
 // ---- 4. one workgroup per bucket: sums in LDS (component-major, so that the clusters of a bucket spread over
@@ -382,11 +361,12 @@ static void update_buckets_t(const float* X, uint32_t N, const uint32_t* idx, co
                              const Workspace& w, bool norm_order, bool mean, hipStream_t s)
 {
     const uint32_t nbuckets = (K + kBucketClusters - 1) / kBucketClusters;
-    const uint32_t blocks = (N + kBucketChunk - 1) / kBucketChunk;
+    const bool delta = prev_idx != nullptr && changed != nullptr;
+    const uint32_t chunk = delta ? kDeltaChunk : kBucketChunk;
+    const uint32_t blocks = (N + chunk - 1) / chunk;
     const uint32_t* cinv = norm_order ? w.cinv : nullptr;
     const uint32_t* cperm = norm_order ? w.cperm : nullptr;
-    const bool delta = prev_idx != nullptr;
-    hipLaunchKernelGGL(bucket_count_kernel, dim3(blocks), dim3(kThreads), 0, s, idx, prev_idx, delta ? changed : nullptr, N, K,
+    hipLaunchKernelGGL(bucket_count_kernel, dim3(blocks), dim3(kThreads), 0, s, idx, delta ? prev_idx : nullptr, delta ? changed : nullptr, N, K,
                        cinv, nbuckets, w.bucket_hist, w.hdr);
     const uint32_t groups = (blocks + kBucketGroup - 1) / kBucketGroup;
     const uint32_t bwg = (nbuckets + kThreads - 1) / kThreads;
@@ -409,7 +389,8 @@ hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const u
                                  uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order,
                                  bool mean, hipStream_t s, const uint32_t* prev_idx, const uint32_t* changed)
 {
-    if (K > kMaxBuckets * kBucketClusters || w.records == nullptr) return hipErrorInvalidValue;
+    if (K > kMaxBuckets * kBucketClusters || w.records == nullptr || (prev_idx != nullptr) != (changed != nullptr))
+        return hipErrorInvalidValue;
     switch (d) {
         case 4: update_buckets_t<4>(X, N, idx, prev_idx, changed, prev, K, out, counts_out, w, norm_order, mean, s); break;
         case 8: update_buckets_t<8>(X, N, idx, prev_idx, changed, prev, K, out, counts_out, w, norm_order, mean, s); break;
