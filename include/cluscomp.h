@@ -128,7 +128,8 @@ typedef struct cc_stats {
                                   512-vector tiles of all assigns; 0 when pruning did not run */
     uint64_t total_stages;     /* the same sum if every tile had scored the whole codebook */
     int32_t  fixed_point_exp;  /* e: cluster sums are held as round(x * 2^e) in int64 */
-    uint32_t reserved;
+    uint32_t fp16_inputs;      /* 1 if the vectors of the last call qualified for the fp16 matrix-core kernels
+                                  (|x| < 2^15 and every |x| >= 2^-14 an fp16 number), else 0 */
 } cc_stats;
 int cc_read_stats(const void *workspace, size_t workspace_bytes, cc_stats *host_out, void *stream);
 

@@ -31,7 +31,7 @@ class _CStats(ctypes.Structure):
     _fields_ = [("refined_vectors", ctypes.c_uint64), ("skipped_vectors", ctypes.c_uint64),
                 ("assign_calls", ctypes.c_uint64), ("scored_stages", ctypes.c_uint64),
                 ("total_stages", ctypes.c_uint64), ("fixed_point_exp", ctypes.c_int32),
-                ("reserved", ctypes.c_uint32)]
+                ("fp16_inputs", ctypes.c_uint32)]
 
 
 @dataclass
@@ -42,6 +42,7 @@ class Stats:
     scored_stages: int
     total_stages: int
     fixed_point_exp: int
+    fp16_inputs: int = 0
 
 
 def lib_path() -> str:
@@ -217,7 +218,7 @@ def read_stats(workspace) -> Stats:
     _check(load_library().cc_read_stats(_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
                                         ctypes.byref(st), _stream()))
     return Stats(int(st.refined_vectors), int(st.skipped_vectors), int(st.assign_calls), int(st.scored_stages),
-                 int(st.total_stages), int(st.fixed_point_exp))
+                 int(st.total_stages), int(st.fixed_point_exp), int(st.fp16_inputs))
 
 
 def set_assign_mode(mode: int) -> int:

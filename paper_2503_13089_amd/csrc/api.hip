@@ -584,7 +584,7 @@ int cc_read_stats(const void* workspace, size_t workspace_bytes, cc_stats* host_
     host_out->scored_stages = h.window_stages;
     host_out->total_stages = h.window_total;
     host_out->fixed_point_exp = h.fixed_point_exp;
-    host_out->reserved = 0;
+    host_out->fp16_inputs = h.x_not_f16 == 0 ? 1u : 0u;
     return CC_OK;
 }
 

@@ -6,7 +6,8 @@
 // the products run on v_mfma_f32_32x32x16_f16, whose rate is 16x that of the fp32 MFMA and which,
 // unlike the fp32 MFMA, leaves the vector ALUs free for the min-reduction while it runs.
 //
-// Exactness: every input x is an fp16 number (checked on the device; otherwise the fp32 kernel runs).
+// Exactness: every input x of the fp16 normal range is an fp16 number (checked on the device; otherwise the
+// fp32 kernel runs); smaller ones may lose up to 2^-25 in the operand, which the guard band accounts for.
 // Each fp32 centroid component, scaled by a power of two sigma so that it fits the fp16 range, is
 // split into three fp16 parts c*sigma = h1 + h2 + h3 (each part the fp16 rounding of what is left;
 // the residual is below 2^-33 |c*sigma| or the fp16 subnormal step 2^-24). An fp16 x fp16 product
@@ -349,11 +350,14 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
             if (h == 0 && i_raw < N) idx[i] = kstar;
             continue;
         }
-        float xn = 0.0f, x1 = 0.0f;
+        float xn = 0.0f, x1 = 0.0f, xlost = 0.0f;
 #pragma unroll
         for (int j = 0; j < D; ++j) {
             xn = __builtin_fmaf(x[j], x[j], xn);
             x1 += __builtin_fabsf(x[j]);
+            // what the fp16 operand -2 x_j lost: nonzero only below the fp16 normal range, at most 2^-25, exact in fp32
+            const float t = -2.0f * x[j];
+            xlost += __builtin_fabsf(t - float(_Float16(t)));
         }
         // accumulation rounding of winner + true nearest (||c||^2 <= 2||x||^2 + 2D for both); what fp16
         // subnormal factors add to the sum of |terms| (with a = 2^-14: each of the 3D product slots at most
@@ -363,8 +367,11 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
         constexpr float kA = 6.103515625e-05f;  // 2^-14
         const float inflation = 6.0f * kA * x1 + 1.002f * kA * sigma * __builtin_sqrtf(float(D) * (2.0f * xn + 2.0f * dstar)) +
                                 3.0f * float(D) * kA * kA + (S::kNormInK ? 0.015634f : 0.0f);
+        // a lost part of -2 x_j moves every score of this vector by at most |it| * sigma * max|c| * 1.002 (the three
+        // parts of a centroid component), the best and its competitor in opposite directions at worst
+        const float operand_loss = 2.0f * 1.002f * sigma * __uint_as_float(hdr->cmax_bits) * xlost;
         const float delta = kGuardSafety * 2.0f * kAccumUlps * kUnit * (sigma * (5.0f * xn + 4.0f * dstar) + inflation) +
-                            kGuardSafety * (2.0f * kUnit * x1 + 1e-11f) + 1e-36f;
+                            kGuardSafety * (2.0f * kUnit * x1 + 1e-11f + operand_loss) + 1e-36f;
         const bool safe = (sstar - bstar) > delta;  // false for NaN as well
         bool moved = false;
         if (h == 0 && i_raw < N) {

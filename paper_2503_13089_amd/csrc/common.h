@@ -12,7 +12,7 @@ constexpr uint32_t kMaxK = 1u << 24;
 struct WsHeader {
     uint32_t absmax_bits;      // max over all inputs of the fp32 bit pattern of |x|
     uint32_t refine_count;     // length of the refine list written by the last matrix-core assign
-    uint32_t x_not_f16;        // != 0: some input is not exactly representable in fp16 (or |x| >= 2^15)
+    uint32_t x_not_f16;        // != 0: some |x| >= 2^15, or some |x| >= 2^-14 is not an fp16 number
     uint32_t cmax_bits;        // max over the current codebook of the fp32 bit pattern of |c|
     unsigned long long refined_vectors;
     unsigned long long skipped_vectors;

@@ -50,8 +50,11 @@ hipError_t launch_bump_assign_calls(WsHeader* hdr, hipStream_t s)
 }
 
 // One pass over the inputs: max |x| as the maximum of the (sign-cleared) fp32 bit patterns (for finite
-// floats the integer order of the patterns is the order of the magnitudes), and whether every value
-// survives a round trip through fp16 with |x| < 2^15 (then -2x is also an fp16 number).
+// floats the integer order of the patterns is the order of the magnitudes), and whether the vectors qualify
+// for the fp16 matrix-core kernels: |x| < 2^15, and every value of the fp16 normal range (|x| >= 2^-14)
+// survives a round trip through fp16 (then -2x is also an fp16 number). Smaller values need not be fp16
+// numbers - bf16 weights have many that are not: what their fp16 rounding loses is at most 2^-25 each, which
+// those kernels add to their guard band per vector.
 __global__ __launch_bounds__(kThreads) void scan_inputs_kernel(const float4* __restrict__ X4, uint64_t n4, WsHeader* hdr)
 {
     __shared__ uint32_t red_m[kThreads / 64], red_f[kThreads / 64];
@@ -64,7 +67,7 @@ __global__ __launch_bounds__(kThreads) void scan_inputs_kernel(const float4* __r
             const uint32_t a = __float_as_uint(v[j]) & 0x7fffffffu;
             m = max(m, a);
             const float back = float(_Float16(v[j]));
-            bad |= (back != v[j]) || (a >= 0x47000000u /* 2^15 */);
+            bad |= (back != v[j] && a >= 0x38800000u /* 2^-14 */) || (a >= 0x47000000u /* 2^15 */);
         }
     }
     for (int off = 32; off > 0; off >>= 1) {

@@ -413,6 +413,51 @@ def test_cold_estep_when_no_centroid_is_near_the_guess(g, case):
     parity.check_assignment(X, C, idx, k1, D1, D2)
 
 
+@pytest.mark.parametrize("d,K", [(4, 1300), (8, 700), (16, 300), (4, 8300)])
+def test_bf16_weights_take_the_fp16_kernels(g, d, K):
+    """bf16 weights are fp16 numbers except where they are tiny (below 2^-17 a bf16 number generally is not). Such
+    inputs still go to the fp16 matrix-core kernels, whose guard band then carries what the operand lost; codes and
+    objective must be those of the fp32 kernels and of the oracle."""
+    import paper_2503_13089_amd as cc
+    from oracle import layer as olayer
+
+    rng = np.random.default_rng(500 + d)
+    N = 60013
+    X = olayer.bf16_round((rng.standard_normal((N, d)) * 0.02).astype(np.float32))
+    X[::7, 0] = olayer.bf16_round((rng.standard_normal(len(X[::7])) * 1e-7).astype(np.float32))
+    X[3::11, d - 1] = olayer.bf16_round((rng.standard_normal(len(X[3::11])) * 1e-12).astype(np.float32))
+    X[5::13] = olayer.bf16_round((rng.standard_normal((len(X[5::13]), d)) * 3e-6).astype(np.float32))  # whole tiny vectors
+    assert not np.array_equal(X.astype(np.float16).astype(np.float32), X)
+    C0 = np.ascontiguousarray(X[rng.choice(N, K, replace=False)])
+    k0, _, _, _ = oracle.assign_top2(X, C0)
+    C1, _ = oracle.update(X, k0, C0)
+    Xd = g.dev(X)
+    ws = g.workspace(N, d, K)
+    try:
+        for C in (C0, C1):
+            cc.set_assign_mode(0)
+            idx, J = g.gpu_assign(Xd, C, ws=ws)
+            assert cc.read_stats(ws).fp16_inputs == 1
+            cc.set_assign_mode(2)
+            idx32, J32 = g.gpu_assign(Xd, C)
+            assert np.array_equal(idx, idx32) and J == pytest.approx(J32, rel=1e-12)
+            k1, D1, _, D2 = oracle.assign_top2(X, C)
+            parity.check_assignment(X, C, idx, k1, D1, D2)
+            parity.check_inertia(J, float(D1.sum()))
+        cc.set_assign_mode(0)
+        Cf, idf, Jf, _ = g.gpu_fit(X, C0, 3, ws=ws, Xd=Xd)
+        cc.set_assign_mode(2)
+        Cg, idg, Jg, _ = g.gpu_fit(X, C0, 3, Xd=Xd)
+    finally:
+        cc.set_assign_mode(0)
+    assert np.array_equal(idf, idg) and Cf.tobytes() == Cg.tobytes() and Jf == pytest.approx(Jg, rel=1e-12)
+    # values of the fp16 normal range that are not fp16 numbers still send the call to the fp32 kernels
+    X2 = X.copy()
+    X2[1, 0] = np.float32(0.0200001)
+    g.gpu_assign(g.dev(X2), C1, ws=ws)
+    assert cc.read_stats(ws).fp16_inputs == 0
+
+
 def test_more_than_65536_clusters(g, mode):
     """K above the 16-bit code range: the M-step cannot use its bucket formulation there (the sums are accumulated
     by the E-step kernel, or by atomics), with and without the window pruning of the automatic mode."""
