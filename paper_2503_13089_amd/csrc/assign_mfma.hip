@@ -223,6 +223,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
     }
 
     // ---- epilogue: index recovery in direct form, merge of the two half-waves, guard-band test
+    const int sum_exp = sums != nullptr ? fixed_point_exp(hdr->absmax_bits, N) : 0;  // read once, not per vector
 #pragma unroll
     for (int vt = 0; vt < VT; ++vt) {
         const uint32_t i_raw = vbase + vt * 32 + n;
@@ -268,7 +269,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
             }
             idx[i] = kstar;
             dmin[i] = dstar;
-            if (sums != nullptr) accumulate_vector<D>(x, kstar, sums, counts, fixed_point_exp(hdr->absmax_bits, N), +1);
+            if (sums != nullptr) accumulate_vector<D>(x, kstar, sums, counts, sum_exp, +1);
             if (!safe) {
                 const uint32_t pos = atomicAdd(&hdr->refine_count, 1u);
                 if (pos < refine_cap) refine_list[pos] = i;

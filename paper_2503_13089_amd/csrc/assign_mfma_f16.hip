@@ -320,7 +320,12 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
 
     // ---- epilogue: index recovery in direct form, merge of the two half-waves, guard-band test.
     // Scores are in sigma-scaled units; the band is scaled to match.
-    const float sigma = __builtin_ldexpf(1.0f, centroid_scale_log2(hdr->cmax_bits, D));
+    // read once: the header's cache line is the target of the refine-list atomics below, and a reload per vector
+    // (which the compiler would emit, since those atomics may alias it) costs a trip to memory each time
+    const uint32_t cmax_bits = hdr->cmax_bits;
+    const float sigma = __builtin_ldexpf(1.0f, centroid_scale_log2(cmax_bits, D));
+    const float sigma_cmax = sigma * __uint_as_float(cmax_bits);
+    const int sum_exp = sums != nullptr ? fixed_point_exp(hdr->absmax_bits, N) : 0;
 #pragma unroll
     for (int vt = 0; vt < VT; ++vt) {
         const uint32_t i_raw = vbase + vt * 32 + n;
@@ -369,7 +374,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
                                 3.0f * float(D) * kA * kA + (S::kNormInK ? 0.015634f : 0.0f);
         // a lost part of -2 x_j moves every score of this vector by at most |it| * sigma * max|c| * 1.002 (the three
         // parts of a centroid component), the best and its competitor in opposite directions at worst
-        const float operand_loss = 2.0f * 1.002f * sigma * __uint_as_float(hdr->cmax_bits) * xlost;
+        const float operand_loss = 2.0f * 1.002f * sigma_cmax * xlost;
         const float delta = kGuardSafety * 2.0f * kAccumUlps * kUnit * (sigma * (5.0f * xn + 4.0f * dstar) + inflation) +
                             kGuardSafety * (2.0f * kUnit * x1 + 1e-11f + operand_loss) + 1e-36f;
         const bool safe = (sstar - bstar) > delta;  // false for NaN as well
@@ -384,7 +389,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
             }
             idx[i] = kstar;
             dmin[i] = dstar;
-            if (sums != nullptr) accumulate_vector<D>(x, kstar, sums, counts, fixed_point_exp(hdr->absmax_bits, N), +1);
+            if (sums != nullptr) accumulate_vector<D>(x, kstar, sums, counts, sum_exp, +1);
             if (!safe) {
                 const uint32_t pos = atomicAdd(&hdr->refine_count, 1u);
                 if (pos < refine_cap) refine_list[pos] = i;
