@@ -9,13 +9,15 @@
 // Exactness: every input x of the fp16 normal range is an fp16 number (checked on the device; otherwise the
 // fp32 kernel runs); smaller ones may lose up to 2^-25 in the operand, which the guard band accounts for.
 // Each fp32 centroid component, scaled by a power of two sigma so that it fits the fp16 range, is
-// split into three fp16 parts c*sigma = h1 + h2 + h3 (each part the fp16 rounding of what is left;
-// the residual is below 2^-33 |c*sigma| or the fp16 subnormal step 2^-24). An fp16 x fp16 product
-// has at most 22 significant bits, so every product h_p * (-2 x) is exact in the fp32 accumulator:
-// the only rounding is in the accumulation. The k = 16 slots of one MFMA hold, for d = 4, the 12
-// products (3 parts x 4 components) and three more slots that add sigma * ||c||^2, itself split into
-// three fp16 parts against the fixed multipliers 2^8, 2^-3, 2^-14 (d = 8: 27 of 32 slots in two
-// MFMAs; d = 16: 48 slots in three MFMAs and sigma * ||c||^2 as the fp32 C operand instead).
+// split into fp16 parts c*sigma = h1 + h2 (+ h3), each part the fp16 rounding of what is left. An
+// fp16 x fp16 product has at most 22 significant bits, so every product h_p * (-2 x) is exact in the
+// fp32 accumulator: the only rounding is in the accumulation. d = 4 takes three parts (residual below
+// 2^-33 |c*sigma| or the fp16 subnormal step 2^-24): the k = 16 slots of one MFMA hold the 12 products
+// and three more slots that add sigma * ||c||^2, itself split into three fp16 parts against the fixed
+// multipliers 2^8, 2^-3, 2^-14. d = 8 and 16 take two parts (residual 2^-22 |c*sigma|, which the guard
+// band carries as a term of its own - about a quarter on top of the accumulation term): 16 and 32
+// slots, one and two MFMAs per tile instead of the two and three that three parts would need, with
+// sigma * ||c||^2 as the fp32 C operand.
 //
 // Guard band: measured on gfx950, the accumulated result differs from the exact sum by at most
 // ~3 * 2^-24 * (sum of |terms|), where the matrix core aligns a product by the exponent FIELDS of its
@@ -41,8 +43,9 @@ constexpr float kAccumUlps = 8.0f;
 
 template <int D>
 struct F16Shape {
-    static constexpr bool kNormInK = (D != 16);             // ||c||^2 rides in spare k slots
-    static constexpr int kSlots = 3 * D + (kNormInK ? 3 : 0);
+    static constexpr int kParts = (D == 4) ? 3 : 2;         // fp16 parts per centroid component
+    static constexpr bool kNormInK = (D == 4);              // ||c||^2 rides in spare k slots
+    static constexpr int kSlots = kParts * D + (kNormInK ? 3 : 0);
     static constexpr int KM = (kSlots + 15) / 16;           // MFMAs per tile
     static constexpr int kTileBytes = 64 * KM * 16 + (kNormInK ? 0 : 128);
 };
@@ -112,7 +115,7 @@ __global__ __launch_bounds__(kThreads) void pack_codebook_f16_kernel(const float
     const uint32_t pos = 32 * tile + 16 * ((m >> 2) & 1) + (m & 3) + 4 * (m >> 3);
     const bool valid = pos < K;
     const uint32_t k = (cperm != nullptr && valid) ? cperm[pos] : pos;  // norm order when pruning
-    _Float16 parts[D][3];
+    _Float16 parts[D][3];  // the first S::kParts are used
     double norm = 0.0;
 #pragma unroll
     for (int j = 0; j < D; ++j) {
@@ -138,8 +141,8 @@ __global__ __launch_bounds__(kThreads) void pack_codebook_f16_kernel(const float
             for (int half = 0; half < 2; ++half) {
                 const int q = 16 * mi + 8 * half + q8;
                 _Float16 v = _Float16(0.0f);
-                if (q < 3 * D) v = parts[q % D][q / D];
-                else if (S::kNormInK && q < 3 * D + 3) v = g[q - 3 * D];
+                if (q < S::kParts * D) v = parts[q % D][q / D];
+                else if (S::kNormInK && q < S::kParts * D + 3) v = g[q - S::kParts * D];
                 if (half == 0) lo[q8] = v; else hi[q8] = v;
             }
         }
@@ -203,10 +206,11 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
                 for (int half = 0; half < 2; ++half) {
                     const int q = 16 * mi + 8 * half + q8;
                     v[half] = _Float16(0.0f);
-                    if (q < 3 * D) v[half] = _Float16(-2.0f * x[q % D]);
-                    else if (S::kNormInK && q == 3 * D) v[half] = _Float16(256.0f);
-                    else if (S::kNormInK && q == 3 * D + 1) v[half] = _Float16(0.125f);
-                    else if (S::kNormInK && q == 3 * D + 2) v[half] = _Float16(6.103515625e-05f);  // 2^-14
+                    constexpr int PD = S::kParts * D;
+                    if (q < PD) v[half] = _Float16(-2.0f * x[q % D]);
+                    else if (S::kNormInK && q == PD) v[half] = _Float16(256.0f);
+                    else if (S::kNormInK && q == PD + 1) v[half] = _Float16(0.125f);
+                    else if (S::kNormInK && q == PD + 2) v[half] = _Float16(6.103515625e-05f);  // 2^-14
                 }
                 b[vt][mi][q8] = h ? v[1] : v[0];
             }
@@ -365,18 +369,23 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
             xlost += __builtin_fabsf(t - float(_Float16(t)));
         }
         // accumulation rounding of winner + true nearest (||c||^2 <= 2||x||^2 + 2D for both); what fp16
-        // subnormal factors add to the sum of |terms| (with a = 2^-14: each of the 3D product slots at most
+        // subnormal factors add to the sum of |terms| (with a = 2^-14: each of the P*D product slots at most
         // a |2 x_j| + a |part| + a^2, the parts of one centroid summing to <= 1.002 sigma ||c||_1, and the
         // norm slots at most 2^-6 + 2^-17 + 2^-28); then the split residuals: 2^-25 per component against
         // |2 x_j|, twice, and the norm residual
         constexpr float kA = 6.103515625e-05f;  // 2^-14
-        const float inflation = 6.0f * kA * x1 + 1.002f * kA * sigma * __builtin_sqrtf(float(D) * (2.0f * xn + 2.0f * dstar)) +
-                                3.0f * float(D) * kA * kA + (S::kNormInK ? 0.015634f : 0.0f);
-        // a lost part of -2 x_j moves every score of this vector by at most |it| * sigma * max|c| * 1.002 (the three
+        constexpr int P = S::kParts;
+        const float inflation = 2.0f * float(P) * kA * x1 + 1.002f * kA * sigma * __builtin_sqrtf(float(D) * (2.0f * xn + 2.0f * dstar)) +
+                                float(P * D) * kA * kA + (S::kNormInK ? 0.015634f : 0.0f);
+        // two parts leave a relative residual: |c sigma - h1 - h2| <= 2^-22 |c sigma| per component (each part is a
+        // rounding to 11 bits), against |2 x_j|: at most 2^-21 sigma ||x|| ||c|| per score, for the best and for its
+        // competitor (three parts leave 2^-33, which the accumulation term dwarfs)
+        const float split_rel = P == 2 ? 9.5367431640625e-07f * sigma * __builtin_sqrtf(xn * (2.0f * xn + 2.0f * dstar)) : 0.0f;
+        // a lost part of -2 x_j moves every score of this vector by at most |it| * sigma * max|c| * 1.002 (the
         // parts of a centroid component), the best and its competitor in opposite directions at worst
         const float operand_loss = 2.0f * 1.002f * sigma_cmax * xlost;
         const float delta = kGuardSafety * 2.0f * kAccumUlps * kUnit * (sigma * (5.0f * xn + 4.0f * dstar) + inflation) +
-                            kGuardSafety * (2.0f * kUnit * x1 + 1e-11f + operand_loss) + 1e-36f;
+                            kGuardSafety * (2.0f * kUnit * x1 + 1e-11f + operand_loss + split_rel) + 1e-36f;
         const bool safe = (sstar - bstar) > delta;  // false for NaN as well
         bool moved = false;
         if (h == 0 && i_raw < N) {
