@@ -253,7 +253,6 @@ hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const u
                                  uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order,
                                  bool mean, hipStream_t s, const uint32_t* prev_idx = nullptr,
                                  const uint32_t* changed = nullptr);
-hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, size_t n, hipStream_t s);
 // out[i][j] = j < d_in ? in[i][j] : 0 for rows of d_out >= d_in floats, and the reverse (drop the tail).
 hipError_t launch_pad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s);
 hipError_t launch_unpad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s);

@@ -117,25 +117,6 @@ __global__ __launch_bounds__(kThreads) void copy_f32_kernel(const float* __restr
     if (i < n) dst[i] = src[i];
 }
 
-__global__ __launch_bounds__(kThreads) void copy_u32x4_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n4,
-                                                              const uint32_t* __restrict__ src_tail,
-                                                              uint32_t* __restrict__ dst_tail, uint32_t tail)
-{
-    const size_t i = size_t(blockIdx.x) * kThreads + threadIdx.x;
-    if (i < n4) dst[i] = src[i];
-    if (i < tail) dst_tail[i] = src_tail[i];
-}
-
-// dst = src for n 32-bit words (both 16-byte aligned)
-hipError_t launch_copy_u32(const uint32_t* src, uint32_t* dst, size_t n, hipStream_t s)
-{
-    const size_t n4 = n / 4;
-    hipLaunchKernelGGL(copy_u32x4_kernel, dim3(uint32_t((std::max<size_t>(n4, 4) + kThreads - 1) / kThreads)), dim3(kThreads), 0, s,
-                       reinterpret_cast<const uint4*>(src), reinterpret_cast<uint4*>(dst), n4, src + 4 * n4, dst + 4 * n4,
-                       uint32_t(n - 4 * n4));
-    return hipGetLastError();
-}
-
 hipError_t launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t s)
 {
     hipLaunchKernelGGL(copy_f32_kernel, dim3(uint32_t((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, src, dst, n);
