@@ -458,6 +458,41 @@ def test_bf16_weights_take_the_fp16_kernels(g, d, K):
     assert cc.read_stats(ws).fp16_inputs == 0
 
 
+@pytest.mark.parametrize("d", [8, 16, 6, 12])
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_many_near_ties_at_longer_vectors(g, d, seed):
+    """At d = 8 and 16 the fp16 kernel splits a centroid component into two parts and carries the 2^-22 residual in
+    its guard band. Vectors on a coarse lattice and centroids that are means of a few of them make exact ties and
+    near-ties by the thousand, where a band that is too narrow shows as a wrong code: the codes must be those of the
+    fp32 kernels and of the oracle, for the initial centroids and after an update, with and without windows."""
+    import paper_2503_13089_amd as cc
+
+    rng = np.random.default_rng(9000 + 10 * d + seed)
+    N, K = 90001, 8300 if seed == 1 else 1900
+    scale = np.float32(2.0 ** -(4 + seed))
+    X = (rng.integers(-24, 25, size=(N, d)).astype(np.float32) * scale)
+    X[::5] *= np.float32(0.125)       # a second, finer lattice: short and long vectors side by side
+    C0 = np.ascontiguousarray(X[rng.choice(N, K, replace=False)])
+    k0, _, _, _ = oracle.assign_top2(X, C0)
+    C1, _ = oracle.update(X, k0, C0)
+    Xd = g.dev(X)
+    ws = g.workspace(N, d, K)
+    try:
+        for C in (C0, C1):
+            k1, D1, _, D2 = oracle.assign_top2(X, C)
+            cc.set_assign_mode(2)
+            idx32, J32 = g.gpu_assign(Xd, C)
+            for m in (0, 3):
+                cc.set_assign_mode(m)
+                idx, J = g.gpu_assign(Xd, C, ws=ws)
+                assert cc.read_stats(ws).fp16_inputs == 1
+                assert np.array_equal(idx, idx32), (m, int((idx != idx32).sum()))
+                assert J == pytest.approx(J32, rel=1e-12)
+                parity.check_assignment(X, C, idx, k1, D1, D2)
+    finally:
+        cc.set_assign_mode(0)
+
+
 def test_more_than_65536_clusters(g, mode):
     """K above the 16-bit code range: the M-step cannot use its bucket formulation there (the sums are accumulated
     by the E-step kernel, or by atomics), with and without the window pruning of the automatic mode."""
