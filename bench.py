@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
 VALU_ISSUE_PEAK = 1024 * 2.4e9 / 4   # wave-instructions/s: 1024 SIMDs, one 64-lane VALU instruction per 4 cycles
 
 # HBM bytes per launch of the E-step kernel from rocprofv3 counters (profiles/pmc_bench_cfg3.md):
-# FETCH_SIZE 290,816 KiB x 2.000 + WRITE_SIZE 88,406 KiB x 1.000, scale factors from a device copy of known size.
-MEASURED_TRAFFIC_BYTES = {("cfg3_4096x11008_d4_k65536", 0): (290816 * 2.0 + 88406 * 1.0) * 1024}
+# FETCH_SIZE 295,033 KiB x 2.000 + WRITE_SIZE 88,484 KiB x 1.000, scale factors from a device copy of known size.
+MEASURED_TRAFFIC_BYTES = {("cfg3_4096x11008_d4_k65536", 0): (295033 * 2.0 + 88484 * 1.0) * 1024}
 
 
 def cpu_baseline(w, X, C0, sample_log2=20):
@@ -268,9 +268,10 @@ def main():
                          "peak": VALU_ISSUE_PEAK / 1e9, "unit": "G wave-instr/s",
                          "frac": N * K / 128.0 / (assign_ms * 1e-3) / VALU_ISSUE_PEAK, "traffic": None},
         # what the matrix cores really execute in the default variant: 16 k-slots per (vector, centroid) pair and MFMA
-        # (3 fp16 parts x d products + the norm slots; d = 16: 48 slots), against the dense fp16 MFMA peak
+        # (d = 4: 3 fp16 parts x d products + 3 norm slots = one MFMA; d = 8, 16: 2 parts x d = one, two MFMAs),
+        # against the dense fp16 MFMA peak
         "roofline_mfma_f16": ({"bound": "mfma", "kernel": "assign (E-step), whole codebook scored",
-                               "achieved": 2.0 * 16 * ((3 * d + 3 + 15) // 16 if d != 16 else 3) * N * K / (assign_ms * 1e-3) / 1e12,
+                               "achieved": 2.0 * 16 * (1 if d <= 8 else 2) * N * K / (assign_ms * 1e-3) / 1e12,
                                "peak": 2500.0, "unit": "TFLOP/s",
                                "frac": 2.0 * 16 * ((3 * d + 3 + 15) // 16 if d != 16 else 3) * N * K / (assign_ms * 1e-3) / 1e12 / 2500.0,
                                "traffic": None} if args.assign_mode in (0, 3) else None),
