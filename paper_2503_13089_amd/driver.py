@@ -85,21 +85,30 @@ def compress_model(layers, g: int, K: int, iters: int = 20, seed: int = 0, keep_
         main.wait_event(ready[slot])
         _b.layer_compress(staged[slot], g, iters, ids, book, codes, inertia, ws)
         consumed[slot].record(main)
+        computed = torch.cuda.Event()
+        computed.record(main)
         if pending is not None:
             yield pending()
-        if keep_outputs:
-            book_h = torch.empty(book.shape, dtype=book.dtype, pin_memory=True)
-            codes_h = torch.empty(codes.shape, dtype=codes.dtype, pin_memory=True)
-            book_h.copy_(book, non_blocking=True)
-            codes_h.copy_(codes, non_blocking=True)
-        else:
-            book_h = codes_h = None
         done = torch.cuda.Event()
-        done.record(main)
+        # the results go back on the copy stream, behind the weight that is already on its way, so that neither the
+        # next layer's clustering nor the host (which would otherwise wait on the main stream to read the objective)
+        # is held up by them
+        inertia_h = torch.empty(1, dtype=torch.float64, pin_memory=True)
+        book_h = torch.empty(book.shape, dtype=book.dtype, pin_memory=True) if keep_outputs else None
+        codes_h = torch.empty(codes.shape, dtype=codes.dtype, pin_memory=True) if keep_outputs else None
+        with torch.cuda.stream(copy_stream):
+            copy_stream.wait_event(computed)
+            inertia_h.copy_(inertia, non_blocking=True)
+            if keep_outputs:
+                book_h.copy_(book, non_blocking=True)
+                codes_h.copy_(codes, non_blocking=True)
+            done.record(copy_stream)
+        for t in (book, codes, inertia):
+            t.record_stream(copy_stream)  # the allocator must not hand the memory out again before the copies ran
 
-        def finish(name=name, i=in_features, o=out_features, b=book_h, c=codes_h, j=inertia, done=done):
+        def finish(name=name, i=in_features, o=out_features, b=book_h, c=codes_h, j=inertia_h, done=done):
             done.synchronize()
-            return CompressedLayer(name, i, o, b, c, float(j.item()))
+            return CompressedLayer(name, i, o, b, c, float(j[0]))
 
         pending = finish
         cur = nxt
