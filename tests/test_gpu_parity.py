@@ -493,6 +493,41 @@ def test_many_near_ties_at_longer_vectors(g, d, seed):
         cc.set_assign_mode(0)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_problem_fits_agree_with_and_without_windows(g, seed):
+    """Seeded random shapes (d = 1..16, a few hundred to twelve thousand centroids, short and long fits, fp16- and
+    bf16-valued vectors): the automatic path - windows, guessed bootstrap, incremental M-step where they apply -
+    must return the bits of the whole-codebook path, and codes that are the oracle's argmin for the final centroids."""
+    import paper_2503_13089_amd as cc
+    from oracle import layer as olayer
+
+    rng = np.random.default_rng(424200 + seed)
+    d = int(rng.choice([1, 2, 3, 4, 4, 5, 6, 7, 8, 9, 12, 16]))
+    big = seed % 3 == 0
+    N = int(rng.integers(530000, 700000)) if big else int(rng.integers(9000, 150000))
+    K = int(rng.integers(256, 2500)) if big else int(rng.choice([rng.integers(130, 4000), rng.integers(8192, 11000)]))
+    K = min(K, N)
+    iters = int(rng.integers(2, 8))
+    X, C0 = workloads.make_small(N, d, K, seed=int(rng.integers(1 << 30)))
+    if seed % 4 == 1:
+        X = olayer.bf16_round(X * np.float32(1e-3))
+        C0 = np.ascontiguousarray(X[rng.choice(N, K, replace=False)])
+    print(f"random problem N={N} d={d} K={K} iters={iters}", flush=True)
+    Xd = g.dev(X)
+    try:
+        cc.set_assign_mode(3)
+        Cr, ir, Jr, _ = g.gpu_fit(X, C0, iters, Xd=Xd)
+        cc.set_assign_mode(0)
+        Cp, ip, Jp, _ = g.gpu_fit(X, C0, iters, Xd=Xd)
+    finally:
+        cc.set_assign_mode(0)
+    assert Cp.tobytes() == Cr.tobytes() and np.array_equal(ip, ir)
+    assert Jp == pytest.approx(Jr, rel=1e-12)
+    k1, D1, _, D2 = oracle.assign_top2(X, Cp)
+    parity.check_assignment(X, Cp, ip, k1, D1, D2)
+    parity.check_inertia(Jp, oracle.inertia(X, Cp, ip))
+
+
 def test_more_than_65536_clusters(g, mode):
     """K above the 16-bit code range: the M-step cannot use its bucket formulation there (the sums are accumulated
     by the E-step kernel, or by atomics), with and without the window pruning of the automatic mode."""
