@@ -69,7 +69,6 @@ struct Workspace {
     char* records;             // [2N] x (4d + 16) bytes: the vectors, each with its code, grouped by bucket
     uint32_t* bucket_hist;     // [blocks][buckets] members of each bucket in each block of kBucketChunk vectors
     uint32_t* bucket_gtot;     // [groups of kBucketGroup blocks][buckets]
-    uint32_t* bucket_totals;   // [buckets]
     uint32_t* bucket_base;     // [buckets + 1] first record of each bucket
     bool bucket_ok;
     uint32_t refine_cap;
@@ -148,7 +147,6 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d_caller, uint32_t K)
         w.records = take(size_t(N) * 2 * (4 * d + 16));
         w.bucket_hist = reinterpret_cast<uint32_t*>(take(buckets * (size_t(N) / kBucketChunk + 1) * 4));
         w.bucket_gtot = reinterpret_cast<uint32_t*>(take(buckets * (size_t(N) / kBucketChunk / kBucketGroup + 1) * 4));
-        w.bucket_totals = reinterpret_cast<uint32_t*>(take(buckets * 4));
         w.bucket_base = reinterpret_cast<uint32_t*>(take((buckets + 1) * 4));
     }
     w.bytes = off;

@@ -214,21 +214,6 @@ __global__ __launch_bounds__(kThreads) void centroid_keys_kernel(const float* __
     ids[k] = k;
 }
 
-// starts[v] = first position of the ascending 16-bit keys that holds a key >= v, for v = 0 .. nvals
-// (starts[nvals] = n): turns "the run of keys in [a, b]" into two table reads.
-__global__ __launch_bounds__(kThreads) void key_starts_kernel(const uint16_t* __restrict__ sorted_keys, uint32_t n,
-                                                              uint32_t nvals, uint32_t* __restrict__ starts)
-{
-    const uint32_t v = blockIdx.x * kThreads + threadIdx.x;
-    if (v > nvals) return;
-    uint32_t a = 0, b = n;
-    while (a < b) {
-        const uint32_t m = (a + b) / 2;
-        if (sorted_keys[m] >= v) b = m; else a = m + 1;
-    }
-    starts[v] = a;
-}
-
 // Window list of one 512-vector tile: the runs of the ordered codebook (in units of kWinQuad = 32
 // positions, one operand tile) that can hold the nearest centroid of any of its vectors. For vector x with
 // bound u (the distance to its hinted centroid, slightly enlarged), a candidate c has its norm within u of
@@ -457,12 +442,27 @@ hipError_t launch_sort_vectors(const float* X, uint32_t N, uint32_t d, uint32_t 
     return hipGetLastError();
 }
 
-// cinv[cperm[p]] = p
-__global__ __launch_bounds__(kThreads) void invert_perm_kernel(const uint32_t* __restrict__ perm, uint32_t n,
-                                                               uint32_t* __restrict__ inv)
+// What the E-step needs from the ordered centroids, in one launch: the key -> first position table (starts[v] for
+// v = 0 .. 65536), the inverse permutation (cinv[cperm[p]] = p) and the ordered copy of the rows.
+template <int D>
+__global__ __launch_bounds__(kThreads) void centroid_tables_kernel(const uint16_t* __restrict__ sorted_keys,
+                                                                   const uint32_t* __restrict__ perm, uint32_t K,
+                                                                   const float* __restrict__ C, uint32_t* __restrict__ starts,
+                                                                   uint32_t* __restrict__ inv, float* __restrict__ csorted)
 {
-    const uint32_t p = blockIdx.x * kThreads + threadIdx.x;
-    if (p < n) inv[perm[p]] = p;
+    constexpr int Q = D / 4;
+    const uint32_t t = blockIdx.x * kThreads + threadIdx.x;
+    if (t <= 65536u) {
+        uint32_t a = 0, b = K;
+        while (a < b) {
+            const uint32_t m = (a + b) / 2;
+            if (sorted_keys[m] >= t) b = m; else a = m + 1;
+        }
+        starts[t] = a;
+    }
+    if (t < K) inv[perm[t]] = t;
+    if (uint64_t(t) < uint64_t(K) * Q)
+        reinterpret_cast<float4*>(csorted)[t] = reinterpret_cast<const float4*>(C)[size_t(perm[t / Q]) * Q + t % Q];
 }
 
 template <int D>
@@ -471,12 +471,10 @@ static void sort_centroids_t(const float* C, uint32_t K, const Workspace& w, hip
     hipLaunchKernelGGL(centroid_keys_kernel<D>, dim3((K + kThreads - 1) / kThreads), dim3(kThreads), 0, s, C, K, w.ckeys,
                        w.cperm, w.hdr);
     radix_sort16(w.ckeys, w.cperm, w.ckeys_tmp, w.cperm_tmp, K, w.sort_hist, s);
-    hipLaunchKernelGGL(key_starts_kernel, dim3((65536 + kThreads) / kThreads), dim3(kThreads), 0, s, w.ckeys, K, 65536u,
-                       w.key_starts);
-    hipLaunchKernelGGL(invert_perm_kernel, dim3((K + kThreads - 1) / kThreads), dim3(kThreads), 0, s, w.cperm, K, w.cinv);
     const uint64_t pieces = uint64_t(K) * (D / 4);
-    hipLaunchKernelGGL(gather_rows_kernel<D>, dim3(uint32_t((pieces + kThreads - 1) / kThreads)), dim3(kThreads), 0, s, C,
-                       w.cperm, K, w.csorted);
+    const uint32_t threads = uint32_t(std::max<uint64_t>(pieces, 65537));
+    hipLaunchKernelGGL(centroid_tables_kernel<D>, dim3((threads + kThreads - 1) / kThreads), dim3(kThreads), 0, s, w.ckeys,
+                       w.cperm, K, C, w.key_starts, w.cinv, w.csorted);
 }
 
 hipError_t launch_sort_centroids(const float* C, uint32_t d, uint32_t K, const Workspace& w, hipStream_t s)

@@ -129,39 +129,39 @@ __global__ __launch_bounds__(kThreads) void bucket_groupscan_kernel(uint32_t* __
     gtot[size_t(blockIdx.y) * nbuckets + b] = run;
 }
 
-// ---- 2b. second level: every column of gtot becomes its exclusive prefix over the groups; totals[bucket]
-__global__ __launch_bounds__(kThreads) void bucket_totals_kernel(uint32_t* __restrict__ gtot, uint32_t groups,
-                                                                 uint32_t nbuckets, uint32_t* __restrict__ totals)
+// ---- 2b. second level, one workgroup: every column of gtot becomes its exclusive prefix over the groups, and the
+// exclusive prefix of the column totals is the first record of every bucket (base[nbuckets] = number of records)
+__global__ __launch_bounds__(kMaxBuckets) void bucket_base_kernel(uint32_t* __restrict__ gtot, uint32_t groups,
+                                                                   uint32_t nbuckets, uint32_t* __restrict__ base)
 {
-    const uint32_t b = blockIdx.x * kThreads + threadIdx.x;
-    if (b >= nbuckets) return;
+    __shared__ uint32_t wave_sum[kMaxBuckets / 64];
+    const uint32_t b = threadIdx.x;
     uint32_t run = 0;
+    if (b < nbuckets) {
 #pragma unroll 16
-    for (uint32_t g = 0; g < groups; ++g) {
-        const size_t o = size_t(g) * nbuckets + b;
-        const uint32_t v = gtot[o];
-        gtot[o] = run;
-        run += v;
+        for (uint32_t g = 0; g < groups; ++g) {
+            const size_t o = size_t(g) * nbuckets + b;
+            const uint32_t v = gtot[o];
+            gtot[o] = run;
+            run += v;
+        }
     }
-    totals[b] = run;
-}
-
-// ---- 2c. first record of every bucket: exclusive prefix of the totals (one workgroup), base[nbuckets] = all
-__global__ __launch_bounds__(kThreads) void bucket_base_kernel(const uint32_t* __restrict__ totals, uint32_t nbuckets,
-                                                               uint32_t* __restrict__ base)
-{
-    __shared__ uint32_t wave_sum[kThreads / 64];
-    const uint32_t per = (nbuckets + kThreads - 1) / kThreads;
-    const uint32_t first = min(threadIdx.x * per, nbuckets), last = min(first + per, nbuckets);
-    uint32_t s = 0;
-    for (uint32_t i = first; i < last; ++i) s += totals[i];
-    uint32_t total;
-    uint32_t before = block_exclusive_scan(s, wave_sum, total);
-    for (uint32_t i = first; i < last; ++i) {
-        base[i] = before;
-        before += totals[i];
+    // exclusive scan of `run` over the workgroup (one bucket per thread)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t incl = run;
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = uint32_t(__shfl_up(int(incl), off, 64));
+        if (lane >= off) incl += t;
     }
-    if (threadIdx.x == 0) base[nbuckets] = total;
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    uint32_t before = incl - run, total = 0;
+    for (int w = 0; w < int(kMaxBuckets / 64); ++w) {
+        if (w < wave) before += wave_sum[w];
+        total += wave_sum[w];
+    }
+    if (b < nbuckets) base[b] = before;
+    if (b == 0) base[nbuckets] = total;
 }
 
 // A record: the d floats of the vector, then 16 bytes whose first word is the code's slot.
@@ -372,9 +372,7 @@ static void update_buckets_t(const float* X, uint32_t N, const uint32_t* idx, co
     const uint32_t bwg = (nbuckets + kThreads - 1) / kThreads;
     hipLaunchKernelGGL(bucket_groupscan_kernel, dim3(bwg, groups), dim3(kThreads), 0, s, w.bucket_hist, blocks, nbuckets,
                        w.bucket_gtot);
-    hipLaunchKernelGGL(bucket_totals_kernel, dim3(bwg), dim3(kThreads), 0, s, w.bucket_gtot, groups, nbuckets,
-                       w.bucket_totals);
-    hipLaunchKernelGGL(bucket_base_kernel, dim3(1), dim3(kThreads), 0, s, w.bucket_totals, nbuckets, w.bucket_base);
+    hipLaunchKernelGGL(bucket_base_kernel, dim3(1), dim3(kMaxBuckets), 0, s, w.bucket_gtot, groups, nbuckets, w.bucket_base);
     if (delta)
         hipLaunchKernelGGL(bucket_scatter_delta_kernel<D>, dim3(blocks), dim3(kThreads), 0, s, X, N, idx, prev_idx, changed, K,
                            cinv, nbuckets, w.bucket_hist, w.bucket_gtot, w.bucket_base, w.records);
