@@ -403,7 +403,11 @@ size_t cc_layer_forward_workspace_bytes(uint64_t M, uint32_t in_features, uint32
 {
     if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;
     const uint32_t splits = cc::layer_forward_splits(M, in_features, out_features);
-    return splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
+    const size_t fused = splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
+    if (M < cc::kDenseMinM || !cc::dense_available()) return fused;
+    // the rebuilt 16-bit weight, then the GEMM library's own scratch
+    const size_t dense = cc::align256(size_t(in_features) * out_features * 2) + cc::kDenseScratchBytes;
+    return dense > fused ? dense : fused;
 }
 
 int cc_layer_forward(const void* x, uint64_t M, const void* codebook, int dtype, uint32_t K, uint32_t g,
@@ -422,8 +426,19 @@ int cc_layer_forward(const void* x, uint64_t M, const void* codebook, int dtype,
         if (!aligned(workspace, 256)) return fail(CC_ERR_ALIGN, "workspace must be 256-byte aligned");
         if (workspace_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
     }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (M >= cc::kDenseMinM && cc::dense_available()) {
+        char* scratch = static_cast<char*>(workspace) + cc::align256(size_t(in_features) * out_features * 2);
+        CC_TRY_HIP(cc::launch_layer_weight(codebook, dtype, K, g, codes, in_features, out_features, workspace, s),
+                   "layer weight");
+        const hipError_t e = cc::launch_dense_forward(x, uint32_t(M), workspace, dtype, in_features, out_features, bias, y,
+                                                      scratch, s);
+        if (e == hipSuccess) return CC_OK;
+        if (e != hipErrorNotSupported) CC_TRY_HIP(e, "dense product");
+        // no library algorithm for this shape: the fused kernel below serves it
+    }
     CC_TRY_HIP(cc::launch_layer_forward(x, uint32_t(M), codebook, dtype, K, g, codes, in_features, out_features, bias, y,
-                                        static_cast<float*>(workspace), static_cast<hipStream_t>(stream)), "layer forward");
+                                        static_cast<float*>(workspace), s), "layer forward");
     return CC_OK;
 }
 

@@ -272,6 +272,12 @@ uint32_t layer_forward_splits(uint64_t M, uint32_t in_features, uint32_t out_fea
 hipError_t launch_layer_forward(const void* x, uint32_t M, const void* codebook, int dtype, uint32_t K, uint32_t g,
                                 const uint16_t* codes, uint32_t in_features, uint32_t out_features, const void* bias,
                                 void* y, float* partial, hipStream_t s);
+// ---- prefill-sized batches (dense.hip): W rebuilt into memory, then the vendor library's GEMM
+constexpr uint64_t kDenseMinM = 128;               // from here on the rebuilt-weight route is the faster one
+constexpr size_t kDenseScratchBytes = 64u << 20;   // what the GEMM library may use for itself
+bool dense_available();
+hipError_t launch_dense_forward(const void* x, uint32_t M, const void* weight, int dtype, uint32_t in_features,
+                                uint32_t out_features, const void* bias, void* y, void* scratch, hipStream_t s);
 // ---- uniformly quantised codebook (layer_quant.hip); bits = 8 or 4
 hipError_t launch_codebook_quantize(const float* centroids, size_t n, int bits, void* qbook, float* scale,
                                     uint32_t* absmax_scratch, hipStream_t s);

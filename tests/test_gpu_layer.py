@@ -157,6 +157,11 @@ FORWARD_CASES = [  # (M, in_features, out_features, g, K, bias)
     (32, 1024, 1024, 8, 65536, True),
     (5, 64, 70, 7, 3, False),
     (200, 4096, 256, 4, 65536, False),
+    # prefill-sized batches: the weight is rebuilt and multiplied by the GEMM library
+    (128, 2048, 2048, 4, 65536, True),
+    (256, 512, 768, 4, 65536, True),
+    (1000, 1024, 520, 8, 4096, False),
+    (384, 1536, 1000, 6, 30000, True),
 ]
 
 
@@ -189,6 +194,38 @@ def test_layer_forward(cc, M, in_features, out_features, g, K, with_bias, dt):
     bad = np.abs(got - want) > tol
     assert not bad.any(), (int(bad.sum()), float(np.max(np.abs(got - want) / tol)))
     # same inputs, same bits
+    y2 = torch.empty_like(y)
+    cc.layer_forward(x, book, codes, out_features, bias, y2, ws)
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+
+
+def test_layer_forward_prefill_at_model_size(cc):
+    """A prefill batch through an MLP-sized layer (the rebuilt-weight route where the GEMM library is there):
+    sampled rows of y against the definition, and the same bits on a second call."""
+    rng = np.random.default_rng(77)
+    M, in_features, out_features, g, K = 2048, 4096, 11008, 4, 65536
+    T = torch.bfloat16
+    x = _dev(rng.standard_normal((M, in_features)).astype(np.float32), T)
+    book = _dev(rng.standard_normal((K, g)).astype(np.float32) * 0.02, T)
+    bias = _dev(rng.standard_normal(out_features).astype(np.float32), T)
+    n = L.num_codes(in_features, out_features, g)
+    codes_np = rng.integers(0, K, size=n).astype(np.uint16)
+    codes = _dev(codes_np.view(np.int16)).view(torch.uint16)
+    y = torch.full((M, out_features), 9.0, dtype=T, device="cuda")
+    nbytes = cc.layer_forward_workspace_bytes(M, in_features, out_features)
+    assert nbytes >= in_features * out_features * 2, "the GEMM library did not load on this box"
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    print(f"layer_forward M={M} {in_features}->{out_features} ws={nbytes}", flush=True)
+    cc.layer_forward(x, book, codes, out_features, bias, y, ws)
+    rows = np.concatenate([[0, M - 1], rng.choice(M, size=30, replace=False)])
+    xh = x.float().cpu().numpy()[rows]
+    bh, biash = book.float().cpu().numpy(), bias.float().cpu().numpy()
+    want = L.layer_forward(xh, bh, codes_np, in_features, out_features, biash)
+    mag = L.layer_forward(np.abs(xh), np.abs(bh), codes_np, in_features, out_features, np.abs(biash))
+    got = y.float().cpu().numpy()[rows].astype(np.float64)
+    tol = 2.0 ** -8 * np.abs(want) + in_features * 2.0 ** -24 * mag + 1e-38
+    bad = np.abs(got - want) > tol
+    assert not bad.any(), (int(bad.sum()), float(np.max(np.abs(got - want) / tol)))
     y2 = torch.empty_like(y)
     cc.layer_forward(x, book, codes, out_features, bias, y2, ws)
     assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
