@@ -58,6 +58,10 @@ def load_library():
         raise FileNotFoundError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_2503_13089_amd.build` "
             "(or __graft_entry__.build()); this package has no CPU fallback")
+    # PyTorch ships a HIP runtime of its own, and the tensors passed in live in that runtime's context: it has
+    # to be the one this process loads first, so that the library binds to it and not to a second copy
+    import torch  # noqa: F401
+
     lib = ctypes.CDLL(_LIB_PATH)
     u64, u32, i32, vp, sz = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
     lib.cc_workspace_bytes.argtypes = [u64, u32, u32]
