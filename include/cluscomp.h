@@ -243,7 +243,9 @@ int cc_layer_weight_q(const void *qbook, int bits, const float *scale, uint32_t 
 /* cc_layer_forward with the quantised codebook (x, bias, y in `dtype`): y = s * (x . Q) (+ bias), where Q is the
  * weight rebuilt from the integers q themselves. The products x * q are exact, the sum is fp32, the scale
  * multiplies the finished sum, and y is rounded once - so this is slightly more accurate than a product with
- * the 16-bit weight of cc_layer_weight_q, whose entries are each rounded to 16 bits. Same contract otherwise.
+ * the 16-bit weight of cc_layer_weight_q, whose entries are each rounded to 16 bits. Same contract otherwise,
+ * both routes included: for M >= 128 the integers q are written out as a 16-bit matrix (exact), the GEMM library
+ * returns the fp32 sums, and one more kernel applies scale, bias and the rounding.
  * Workspace: cc_layer_forward_q_workspace_bytes(M, in_features, out_features). */
 size_t cc_layer_forward_q_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features);
 int cc_layer_forward_q(const void *x, uint64_t M, const void *qbook, int bits, const float *scale, uint32_t K,

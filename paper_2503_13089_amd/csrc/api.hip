@@ -432,7 +432,7 @@ int cc_layer_forward(const void* x, uint64_t M, const void* codebook, int dtype,
         CC_TRY_HIP(cc::launch_layer_weight(codebook, dtype, K, g, codes, in_features, out_features, workspace, s),
                    "layer weight");
         const hipError_t e = cc::launch_dense_forward(x, uint32_t(M), workspace, dtype, in_features, out_features, bias, y,
-                                                      scratch, s);
+                                                      false, scratch, s);
         if (e == hipSuccess) return CC_OK;
         if (e != hipErrorNotSupported) CC_TRY_HIP(e, "dense product");
         // no library algorithm for this shape: the fused kernel below serves it
@@ -559,7 +559,12 @@ size_t cc_layer_forward_q_workspace_bytes(uint64_t M, uint32_t in_features, uint
 {
     if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;
     const uint32_t splits = cc::layer_forward_q_max_splits(M, in_features, out_features);
-    return splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
+    const size_t fused = splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
+    if (M < cc::kDenseMinM || !cc::dense_available()) return fused;
+    // the integer weight in 16 bits, the fp32 sums, one constant, then the GEMM library's own scratch
+    const size_t dense = cc::align256(size_t(in_features) * out_features * 2) + cc::align256(size_t(M) * out_features * 4) +
+                         256 + cc::kDenseScratchBytes;
+    return dense > fused ? dense : fused;
 }
 
 int cc_layer_forward_q(const void* x, uint64_t M, const void* qbook, int bits, const float* scale, uint32_t K, uint32_t g,
@@ -580,8 +585,25 @@ int cc_layer_forward_q(const void* x, uint64_t M, const void* qbook, int bits, c
         if (!aligned(workspace, 256)) return fail(CC_ERR_ALIGN, "workspace must be 256-byte aligned");
         if (workspace_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
     }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (M >= cc::kDenseMinM && cc::dense_available()) {
+        char* base = static_cast<char*>(workspace);
+        float* sums = reinterpret_cast<float*>(base + cc::align256(size_t(in_features) * out_features * 2));
+        float* one = reinterpret_cast<float*>(reinterpret_cast<char*>(sums) + cc::align256(size_t(M) * out_features * 4));
+        char* scratch = reinterpret_cast<char*>(one) + 256;
+        CC_TRY_HIP(cc::launch_layer_weight_q_integers(qbook, bits, K, g, codes, in_features, out_features, dtype, base, one, s),
+                   "integer weight");
+        const hipError_t e = cc::launch_dense_forward(x, uint32_t(M), base, dtype, in_features, out_features, nullptr, sums,
+                                                      true, scratch, s);
+        if (e == hipSuccess) {
+            CC_TRY_HIP(cc::launch_forward_q_finish(sums, uint32_t(M), out_features, scale, bias, y, dtype, s), "scale and bias");
+            return CC_OK;
+        }
+        if (e != hipErrorNotSupported) CC_TRY_HIP(e, "dense product");
+        // no library algorithm for this shape: the fused kernel below serves it
+    }
     CC_TRY_HIP(cc::launch_layer_forward_q(x, uint32_t(M), qbook, bits, scale, K, g, codes, in_features, out_features, bias, y,
-                                          dtype, static_cast<float*>(workspace), static_cast<hipStream_t>(stream)),
+                                          dtype, static_cast<float*>(workspace), s),
                "layer forward (quantised codebook)");
     return CC_OK;
 }

@@ -277,7 +277,8 @@ constexpr uint64_t kDenseMinM = 128;               // from here on the rebuilt-w
 constexpr size_t kDenseScratchBytes = 64u << 20;   // what the GEMM library may use for itself
 bool dense_available();
 hipError_t launch_dense_forward(const void* x, uint32_t M, const void* weight, int dtype, uint32_t in_features,
-                                uint32_t out_features, const void* bias, void* y, void* scratch, hipStream_t s);
+                                uint32_t out_features, const void* bias, void* y, bool f32_out, void* scratch,
+                                hipStream_t s);
 // ---- uniformly quantised codebook (layer_quant.hip); bits = 8 or 4
 hipError_t launch_codebook_quantize(const float* centroids, size_t n, int bits, void* qbook, float* scale,
                                     uint32_t* absmax_scratch, hipStream_t s);
@@ -288,6 +289,13 @@ uint32_t layer_forward_q_max_splits(uint64_t M, uint32_t in_features, uint32_t o
 hipError_t launch_layer_forward_q(const void* x, uint32_t M, const void* qbook, int bits, const float* scale, uint32_t K,
                                   uint32_t g, const uint16_t* codes, uint32_t in_features, uint32_t out_features,
                                   const void* bias, void* y, int dtype, float* partial, hipStream_t s);
+// the integers q themselves as a 16-bit weight (`one`: a device float this call sets to 1), and the finish of fp32
+// sums [M][out_features]: y = round(scale * sum (+ bias))
+hipError_t launch_layer_weight_q_integers(const void* qbook, int bits, uint32_t K, uint32_t g, const uint16_t* codes,
+                                          uint32_t in_features, uint32_t out_features, int dtype, void* weight, float* one,
+                                          hipStream_t s);
+hipError_t launch_forward_q_finish(const float* sums, uint32_t M, uint32_t out_features, const float* scale, const void* bias,
+                                   void* y, int dtype, hipStream_t s);
 // grad_weight [in, out] (dtype) -> fp32 vectors [num_codes][d_pad] (zero padding columns and components) and
 // codes widened to 32 bits
 hipError_t launch_layer_grad_vectors(const void* grad, int dtype, uint32_t in_features, uint32_t out_features,

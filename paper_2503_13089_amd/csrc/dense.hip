@@ -65,13 +65,13 @@ struct Plan {
     size_t scratch = 0;
 };
 
-using Key = std::tuple<int, uint32_t, uint32_t, uint32_t, int, bool>;
+using Key = std::tuple<int, uint32_t, uint32_t, uint32_t, int, bool, bool>;
 std::mutex g_mutex;
 std::map<int, hipblasLtHandle_t> g_handles;
 std::map<Key, Plan> g_plans;
 
 Plan make_plan(const Lt& L, hipblasLtHandle_t h, uint32_t M, uint32_t in_features, uint32_t out_features, int dtype,
-               bool with_bias)
+               bool with_bias, bool f32_out)
 {
     Plan p;
     const hipDataType t = dtype == 1 ? HIP_R_16F : HIP_R_16BF;
@@ -86,7 +86,7 @@ Plan make_plan(const Lt& L, hipblasLtHandle_t h, uint32_t M, uint32_t in_feature
     // Row-major y [M][out] = x [M][in] . W [in][out] is, read column-major, y^T (out x M) = W^T (out x in) . x^T (in x M).
     if (L.LayoutCreate(&p.a, t, out_features, in_features, out_features) != HIPBLAS_STATUS_SUCCESS ||
         L.LayoutCreate(&p.b, t, in_features, M, in_features) != HIPBLAS_STATUS_SUCCESS ||
-        L.LayoutCreate(&p.c, t, out_features, M, out_features) != HIPBLAS_STATUS_SUCCESS)
+        L.LayoutCreate(&p.c, f32_out ? HIP_R_32F : t, out_features, M, out_features) != HIPBLAS_STATUS_SUCCESS)
         return p;
     hipblasLtMatmulPreference_t pref = nullptr;
     if (L.PrefCreate(&pref) != HIPBLAS_STATUS_SUCCESS) return p;
@@ -112,12 +112,13 @@ Plan make_plan(const Lt& L, hipblasLtHandle_t h, uint32_t M, uint32_t in_feature
 
 bool dense_available() { return lt().ok; }
 
-// y = x . W (+ bias) with W [in][out] already in memory in the same 16-bit dtype. Returns hipErrorNotSupported
-// when the library has no algorithm for the shape (the caller then takes the fused kernel); `scratch` has
-// kDenseScratchBytes bytes.
+// y = x . W (+ bias) with W [in][out] already in memory in the same 16-bit dtype; with f32_out, y holds the fp32
+// sums themselves (no bias then). Returns hipErrorNotSupported when the library has no algorithm for the shape
+// (the caller then takes the fused kernel); `scratch` has kDenseScratchBytes bytes.
 hipError_t launch_dense_forward(const void* x, uint32_t M, const void* weight, int dtype, uint32_t in_features,
-                                uint32_t out_features, const void* bias, void* y, void* scratch, hipStream_t s)
+                                uint32_t out_features, const void* bias, void* y, bool f32_out, void* scratch, hipStream_t s)
 {
+    if (f32_out && bias) return hipErrorInvalidValue;
     const Lt& L = lt();
     if (!L.ok) return hipErrorNotSupported;
     int device = 0;
@@ -128,9 +129,10 @@ hipError_t launch_dense_forward(const void* x, uint32_t M, const void* weight, i
         h = nullptr;
         return hipErrorNotSupported;
     }
-    const Key key{device, M, in_features, out_features, dtype, bias != nullptr};
+    const Key key{device, M, in_features, out_features, dtype, bias != nullptr, f32_out};
     auto it = g_plans.find(key);
-    if (it == g_plans.end()) it = g_plans.emplace(key, make_plan(L, h, M, in_features, out_features, dtype, bias != nullptr)).first;
+    if (it == g_plans.end())
+        it = g_plans.emplace(key, make_plan(L, h, M, in_features, out_features, dtype, bias != nullptr, f32_out)).first;
     const Plan& p = it->second;
     if (!p.valid) return hipErrorNotSupported;
     if (bias && L.DescSet(p.desc, HIPBLASLT_MATMUL_DESC_BIAS_POINTER, &bias, sizeof(bias)) != HIPBLAS_STATUS_SUCCESS)
