@@ -72,6 +72,17 @@ __device__ __forceinline__ void for_each_flagged(const uint32_t* __restrict__ ch
     }
 }
 
+// Which chunk of vectors a workgroup takes. Workgroups are dealt to the 8 XCDs in turn, and the records of
+// neighbouring chunks are neighbours in every bucket's range: with chunk = workgroup id, each cache line on the
+// border of two runs would be written in part by two XCDs, i.e. from two L2s that cannot merge the halves.
+// This order gives each XCD a contiguous range of chunks instead (any bijection is correct; the histogram
+// and the scatter pass only have to agree).
+__device__ __forceinline__ uint32_t chunk_of_workgroup()
+{
+    const uint32_t n = gridDim.x, q = n / 8, r = n % 8, x = blockIdx.x % 8;
+    return x * q + min(x, r) + blockIdx.x / 8;
+}
+
 // ---- 1. bucket histogram of one block of vectors: row `block` of hist[blocks][nbuckets]
 __global__ __launch_bounds__(kThreads) void bucket_count_kernel(const uint32_t* __restrict__ idx,
                                                                 const uint32_t* __restrict__ prev,
@@ -87,7 +98,8 @@ __global__ __launch_bounds__(kThreads) void bucket_count_kernel(const uint32_t* 
     // a full pass works on chunks of kBucketChunk vectors; an incremental one (changed != NULL) on chunks of
     // kDeltaChunk, looks only at the flagged vectors, and counts one record for the new cluster and one for the old
     const uint32_t chunk = changed != nullptr ? kDeltaChunk : kBucketChunk;
-    const uint32_t lo = blockIdx.x * chunk, hi = min(lo + chunk, N);
+    const uint32_t blk = chunk_of_workgroup();
+    const uint32_t lo = blk * chunk, hi = min(lo + chunk, N);
     uint32_t bad = 0;
     if (changed != nullptr) {
         for_each_flagged(changed, lo, N, [&](uint32_t i) {
@@ -105,7 +117,7 @@ __global__ __launch_bounds__(kThreads) void bucket_count_kernel(const uint32_t* 
     }
     if (bad) atomicAdd(&bad_total, bad);
     __syncthreads();
-    for (uint32_t b = threadIdx.x; b < nbuckets; b += kThreads) hist[size_t(blockIdx.x) * nbuckets + b] = h[b];
+    for (uint32_t b = threadIdx.x; b < nbuckets; b += kThreads) hist[size_t(blk) * nbuckets + b] = h[b];
     if (threadIdx.x == 0 && bad_total) atomicAdd(&hdr->skipped_vectors, static_cast<unsigned long long>(bad_total));
 }
 
@@ -188,13 +200,13 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(const float* _
     __shared__ uint32_t first_rec[kMaxBuckets];    // first record of (bucket, this block)
     __shared__ uint2 stage[kBucketChunk];          // (vector, record) in bucket order
     __shared__ uint32_t wave_sum[kThreads / 64];
+    const uint32_t blk = chunk_of_workgroup();
     for (uint32_t b = threadIdx.x; b < nbuckets; b += kThreads) {
         h[b] = 0;
-        first_rec[b] = base[b] + gtot[size_t(blockIdx.x / kBucketGroup) * nbuckets + b] +
-                       hist[size_t(blockIdx.x) * nbuckets + b];
+        first_rec[b] = base[b] + gtot[size_t(blk / kBucketGroup) * nbuckets + b] + hist[size_t(blk) * nbuckets + b];
     }
     __syncthreads();
-    const uint32_t lo = blockIdx.x * kBucketChunk;
+    const uint32_t lo = blk * kBucketChunk;
     uint32_t slot[kPer], rank[kPer];
 #pragma unroll
     for (int r = 0; r < kPer; ++r) {
@@ -273,10 +285,11 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_delta_kernel(const fl
                                                                         char* __restrict__ records)
 {
     __shared__ uint32_t cursor[kMaxBuckets];  // next free record of (bucket, this block)
+    const uint32_t blk = chunk_of_workgroup();
     for (uint32_t b = threadIdx.x; b < nbuckets; b += kThreads)
-        cursor[b] = base[b] + gtot[size_t(blockIdx.x / kBucketGroup) * nbuckets + b] + hist[size_t(blockIdx.x) * nbuckets + b];
+        cursor[b] = base[b] + gtot[size_t(blk / kBucketGroup) * nbuckets + b] + hist[size_t(blk) * nbuckets + b];
     __syncthreads();
-    const uint32_t lo = blockIdx.x * kDeltaChunk;
+    const uint32_t lo = blk * kDeltaChunk;
     for_each_flagged(changed, lo, N, [&](uint32_t i) {
         const uint32_t k_new = idx[i], k_old = prev[i];
         if (k_new == k_old || k_new >= K || k_old >= K) return;
