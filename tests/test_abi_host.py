@@ -132,6 +132,14 @@ def test_forward_and_quantised_entry_points_reject_bad_arguments():
     assert lib.cc_layer_weight_q(A16, 2, A16, 10, 4, A16, 8, 8, BF16, A16, None) == -2
     assert lib.cc_layer_weight_q(A16, 4, None, 10, 4, A16, 8, 8, BF16, A16, None) == -1
     assert lib.cc_layer_forward_q_workspace_bytes(1, 4096, 4096) >= lib.cc_layer_forward_workspace_bytes(1, 4096, 4096)
+    # prefill-sized batches: either the GEMM library opened (room for the rebuilt weight and its scratch) or the
+    # fused kernel serves them (one in-feature slice at this size: no workspace at all)
+    big = lib.cc_layer_forward_workspace_bytes(2048, 4096, 4096)
+    assert big == 0 or (big >= 4096 * 4096 * 2 + (64 << 20) and big % 256 == 0)
+    big_q = lib.cc_layer_forward_q_workspace_bytes(2048, 4096, 4096)
+    assert (big == 0) == (big_q < 4096 * 4096 * 2) and big_q % 256 == 0
+    if big:
+        assert lib.cc_layer_forward(A16, 2048, A16, BF16, 10, 4, A16, 4096, 4096, None, A16, WS, 16, None) == -5
     assert lib.cc_layer_forward_q(A16, 1, A16, 4, A16, 10, 4, A16, 64, 64, None, A16, BF16, None, 0, None) == -1
     assert lib.cc_layer_forward_q(A16, 1, A16, 5, A16, 10, 4, A16, 64, 64, None, A16, BF16, WS, 1 << 30, None) == -2
     assert lib.cc_layer_forward_q(A16, 1, A16, 4, A16, 10, 4, A16, 64, 64, None, A16, BF16, WS, 16, None) == -5
