@@ -118,6 +118,15 @@ def layer_kernels(cc, torch, timed, w, ws, idx, Cd):
           2.0 * n + 2.0 * K * g + 2.0 * in_features * out_features)
     entry("layer_codebook_grad", timed(lambda: cc.layer_codebook_grad(rebuilt, codes, K, g, grad, ws)),
           2.0 * in_features * out_features + 2.0 * n + 4.0 * K * g)
+    # the training form: the order of the (fixed) codes prepared once, then one pass over the gradient per step
+    plan = torch.empty(cc.layer_grad_plan_bytes(n, K), dtype=torch.uint8, device="cuda")
+    pws = torch.empty(cc.layer_grad_plan_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    plan_ms = timed(lambda: cc.layer_grad_plan(codes, K, plan, pws))
+    gws = torch.empty(cc.layer_codebook_grad_planned_workspace_bytes(n, K, g), dtype=torch.uint8, device="cuda")
+    entry("layer_codebook_grad_planned", timed(lambda: cc.layer_codebook_grad_planned(rebuilt, K, g, plan, grad, gws), reps=10),
+          2.0 * in_features * out_features + 4.0 * n + 4.0 * K * g)
+    res["layer_codebook_grad_planned"]["plan_build_ms"] = plan_ms
+    del plan, pws, gws
     fwd = {}
     for M in (1, 32):
         x = torch.randn(M, in_features, device="cuda").to(bf)

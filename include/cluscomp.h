@@ -206,6 +206,28 @@ int cc_layer_codebook_grad(const void *grad_weight, int grad_dtype, uint32_t in_
                            void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same gradient for training loops (Section 3.3: only the codebook is trained, the codes of a layer never
+ * change): cc_layer_grad_plan orders the code positions by cluster once; cc_layer_codebook_grad_planned then
+ * reads every gradient entry once, straight from grad_weight, and adds each cluster's entries in fp64 in a
+ * fixed order (same inputs, same bits; each sum is within count * 2^-53 * sum |terms| of exact before its one
+ * rounding to fp32, i.e. the rounded exact sum for 16-bit gradients in practice). Codes >= K are left out.
+ *   plan       device memory, cc_layer_grad_plan_bytes(num_codes, K) bytes, 256-byte aligned; written by
+ *              cc_layer_grad_plan, read-only afterwards, owned by the caller for as long as the codes live.
+ *   workspace  scratch: cc_layer_grad_plan_workspace_bytes(num_codes) for the build,
+ *              cc_layer_codebook_grad_planned_workspace_bytes(num_codes, K, g) for each gradient; 256-byte aligned.
+ * grad_weight must be 16-byte aligned; K <= 65536, num_codes < 2^32. A plan built for another (num_codes, K) is
+ * detected on the device: grad_codebook then comes back as NaN.
+ */
+size_t cc_layer_grad_plan_bytes(uint64_t num_codes, uint32_t K);
+size_t cc_layer_grad_plan_workspace_bytes(uint64_t num_codes);
+int cc_layer_grad_plan(const uint16_t *codes, uint64_t num_codes, uint32_t K, void *plan, size_t plan_bytes,
+                       void *workspace, size_t workspace_bytes, void *stream);
+size_t cc_layer_codebook_grad_planned_workspace_bytes(uint64_t num_codes, uint32_t K, uint32_t g);
+int cc_layer_codebook_grad_planned(const void *grad_weight, int grad_dtype, uint32_t in_features,
+                                   uint32_t out_features, uint32_t K, uint32_t g, const void *plan, size_t plan_bytes,
+                                   float *grad_codebook, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * One layer in one call (Sections 3.1-3.2): cc_layer_vectors, then the centroids start from the vectors listed in
  * init_ids [K] (indices < num_codes, e.g. a seeded sample without replacement drawn by the caller; an index past
  * the end is clamped), `iters` Lloyd iterations (cc_kmeans_fit), then cc_layer_pack: codebook [K * g] in

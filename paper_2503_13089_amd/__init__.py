@@ -14,6 +14,11 @@ from .binding import (  # noqa: F401
     kmeans_fit,
     last_error,
     layer_codebook_grad,
+    layer_codebook_grad_planned,
+    layer_codebook_grad_planned_workspace_bytes,
+    layer_grad_plan,
+    layer_grad_plan_bytes,
+    layer_grad_plan_workspace_bytes,
     layer_compress,
     layer_compress_workspace_bytes,
     layer_deficiency,

@@ -17,6 +17,8 @@ EXPORTS = (
     "cc_read_stats", "cc_set_assign_mode", "cc_last_error", "cc_version",
     "cc_layer_deficiency", "cc_layer_num_codes", "cc_layer_vectors", "cc_layer_pack", "cc_layer_weight",
     "cc_layer_codebook_grad", "cc_layer_forward", "cc_layer_forward_workspace_bytes",
+    "cc_layer_grad_plan_bytes", "cc_layer_grad_plan_workspace_bytes", "cc_layer_grad_plan",
+    "cc_layer_codebook_grad_planned_workspace_bytes", "cc_layer_codebook_grad_planned",
     "cc_layer_compress", "cc_layer_compress_workspace_bytes", "cc_codebook_quantize", "cc_layer_weight_q", "cc_layer_forward_q", "cc_layer_forward_q_workspace_bytes",
 )
 
@@ -90,6 +92,16 @@ def load_library():
     lib.cc_layer_pack.restype = ctypes.c_int
     lib.cc_layer_weight.argtypes = [vp, ctypes.c_int, u32, u32, vp, u32, u32, vp, vp]
     lib.cc_layer_weight.restype = ctypes.c_int
+    lib.cc_layer_grad_plan_bytes.argtypes = [u64, u32]
+    lib.cc_layer_grad_plan_bytes.restype = sz
+    lib.cc_layer_grad_plan_workspace_bytes.argtypes = [u64]
+    lib.cc_layer_grad_plan_workspace_bytes.restype = sz
+    lib.cc_layer_grad_plan.argtypes = [vp, u64, u32, vp, sz, vp, sz, vp]
+    lib.cc_layer_grad_plan.restype = ctypes.c_int
+    lib.cc_layer_codebook_grad_planned_workspace_bytes.argtypes = [u64, u32, u32]
+    lib.cc_layer_codebook_grad_planned_workspace_bytes.restype = sz
+    lib.cc_layer_codebook_grad_planned.argtypes = [vp, ctypes.c_int, u32, u32, u32, u32, vp, sz, vp, vp, sz, vp]
+    lib.cc_layer_codebook_grad_planned.restype = ctypes.c_int
     lib.cc_layer_forward_workspace_bytes.argtypes = [u64, u32, u32]
     lib.cc_layer_forward_workspace_bytes.restype = sz
     lib.cc_layer_forward.argtypes = [vp, u64, vp, ctypes.c_int, u32, u32, vp, u32, u32, vp, vp, vp, sz, vp]
@@ -294,6 +306,38 @@ def layer_codebook_grad(grad_weight, codes, K: int, g: int, grad_codebook, works
                                                  out_features, _ptr(codes, torch.uint16, "codes"), K, g,
                                                  _ptr(grad_codebook, torch.float32, "grad_codebook"),
                                                  _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
+
+
+def layer_grad_plan_bytes(num_codes: int, K: int) -> int:
+    return load_library().cc_layer_grad_plan_bytes(num_codes, K)
+
+
+def layer_grad_plan_workspace_bytes(num_codes: int) -> int:
+    return load_library().cc_layer_grad_plan_workspace_bytes(num_codes)
+
+
+def layer_grad_plan(codes, K: int, plan, workspace) -> None:
+    """Orders the code positions by cluster into `plan` (uint8 device tensor), once per layer."""
+    import torch
+
+    _check(load_library().cc_layer_grad_plan(_ptr(codes, torch.uint16, "codes"), codes.numel(), K,
+                                             _ptr(plan, torch.uint8, "plan"), plan.numel(),
+                                             _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
+
+
+def layer_codebook_grad_planned_workspace_bytes(num_codes: int, K: int, g: int) -> int:
+    return load_library().cc_layer_codebook_grad_planned_workspace_bytes(num_codes, K, g)
+
+
+def layer_codebook_grad_planned(grad_weight, K: int, g: int, plan, grad_codebook, workspace) -> None:
+    import torch
+
+    in_features, out_features = grad_weight.shape
+    _check(load_library().cc_layer_codebook_grad_planned(_any_ptr(grad_weight, "grad_weight"), _dtype_code(grad_weight),
+                                                         in_features, out_features, K, g, _ptr(plan, torch.uint8, "plan"),
+                                                         plan.numel(), _ptr(grad_codebook, torch.float32, "grad_codebook"),
+                                                         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                                         _stream()))
 
 
 def layer_forward_workspace_bytes(M: int, in_features: int, out_features: int) -> int:

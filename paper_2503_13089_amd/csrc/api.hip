@@ -555,6 +555,62 @@ int cc_layer_weight_q(const void* qbook, int bits, const float* scale, uint32_t 
     return CC_OK;
 }
 
+size_t cc_layer_grad_plan_bytes(uint64_t num_codes, uint32_t K)
+{
+    if (num_codes == 0 || num_codes >= (1ull << 32) || K == 0 || K > 65536) return 0;
+    return cc::layer_grad_plan_bytes(num_codes, K);
+}
+
+size_t cc_layer_grad_plan_workspace_bytes(uint64_t num_codes)
+{
+    if (num_codes == 0 || num_codes >= (1ull << 32)) return 0;
+    return cc::layer_grad_plan_build_bytes(num_codes);
+}
+
+int cc_layer_grad_plan(const uint16_t* codes, uint64_t num_codes, uint32_t K, void* plan, size_t plan_bytes, void* workspace,
+                       size_t workspace_bytes, void* stream)
+{
+    if (!codes || !plan || !workspace) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (num_codes == 0 || num_codes >= (1ull << 32)) return fail(CC_ERR_SHAPE, "num_codes = %llu", (unsigned long long)num_codes);
+    if (K == 0 || K > 65536) return fail(CC_ERR_SHAPE, "K = %u is not in 1..65536", K);
+    if (!aligned(codes, 2) || !aligned(plan, 256) || !aligned(workspace, 256))
+        return fail(CC_ERR_ALIGN, "plan and workspace must be 256-byte aligned, codes 2");
+    if (plan_bytes < cc::layer_grad_plan_bytes(num_codes, K))
+        return fail(CC_ERR_WORKSPACE, "plan has %zu bytes, %zu needed", plan_bytes, cc::layer_grad_plan_bytes(num_codes, K));
+    if (workspace_bytes < cc::layer_grad_plan_build_bytes(num_codes))
+        return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes,
+                    cc::layer_grad_plan_build_bytes(num_codes));
+    CC_TRY_HIP(cc::launch_layer_grad_plan(codes, uint32_t(num_codes), K, plan, workspace, static_cast<hipStream_t>(stream)),
+               "gradient plan");
+    return CC_OK;
+}
+
+size_t cc_layer_codebook_grad_planned_workspace_bytes(uint64_t num_codes, uint32_t K, uint32_t g)
+{
+    if (num_codes == 0 || num_codes >= (1ull << 32) || K == 0 || K > 65536 || g == 0 || g > 16) return 0;
+    return cc::layer_grad_planned_bytes(num_codes, K, g);
+}
+
+int cc_layer_codebook_grad_planned(const void* grad_weight, int grad_dtype, uint32_t in_features, uint32_t out_features,
+                                   uint32_t K, uint32_t g, const void* plan, size_t plan_bytes, float* grad_codebook,
+                                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!grad_weight || !plan || !grad_codebook || !workspace) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (int rc = check_layer(in_features, out_features, g, K, grad_dtype, true)) return rc;
+    const uint64_t N = cc_layer_num_codes(in_features, out_features, g);
+    if (N >= (1ull << 32)) return fail(CC_ERR_SHAPE, "num_codes = %llu does not fit 32-bit positions", (unsigned long long)N);
+    if (!aligned(grad_weight, 16) || !aligned(grad_codebook, 4) || !aligned(plan, 256) || !aligned(workspace, 256))
+        return fail(CC_ERR_ALIGN, "grad_weight needs 16-byte alignment, plan and workspace 256");
+    if (plan_bytes < cc::layer_grad_plan_bytes(N, K))
+        return fail(CC_ERR_WORKSPACE, "plan has %zu bytes, %zu needed for these shapes", plan_bytes, cc::layer_grad_plan_bytes(N, K));
+    const size_t need = cc::layer_grad_planned_bytes(N, K, g);
+    if (workspace_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    CC_TRY_HIP(cc::launch_layer_grad_planned(grad_weight, grad_dtype, in_features, out_features, K, g, uint32_t(N), plan,
+                                             grad_codebook, workspace, static_cast<hipStream_t>(stream)),
+               "codebook gradient (planned)");
+    return CC_OK;
+}
+
 size_t cc_layer_forward_q_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features)
 {
     if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;

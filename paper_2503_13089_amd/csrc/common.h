@@ -272,6 +272,17 @@ uint32_t layer_forward_splits(uint64_t M, uint32_t in_features, uint32_t out_fea
 hipError_t launch_layer_forward(const void* x, uint32_t M, const void* codebook, int dtype, uint32_t K, uint32_t g,
                                 const uint16_t* codes, uint32_t in_features, uint32_t out_features, const void* bias,
                                 void* y, float* partial, hipStream_t s);
+// ---- codebook gradient from a prepared order of the codes (layer_grad_plan.hip); sort helpers from sort.hip
+size_t sort_hist_bytes(uint64_t n);
+hipError_t launch_sort_u16(uint16_t* keys_a, uint32_t* ids_a, uint16_t* keys_b, uint32_t* ids_b, uint32_t n, uint32_t* hist,
+                           hipStream_t s);
+size_t layer_grad_plan_bytes(uint64_t num_codes, uint32_t K);
+size_t layer_grad_plan_build_bytes(uint64_t num_codes);
+size_t layer_grad_planned_bytes(uint64_t num_codes, uint32_t K, uint32_t g);
+hipError_t launch_layer_grad_plan(const uint16_t* codes, uint32_t n, uint32_t K, void* plan, void* workspace, hipStream_t s);
+hipError_t launch_layer_grad_planned(const void* grad, int dtype, uint32_t in_features, uint32_t out_features, uint32_t K,
+                                     uint32_t g, uint32_t n, const void* plan, float* grad_codebook, void* workspace,
+                                     hipStream_t s);
 // ---- prefill-sized batches (dense.hip): W rebuilt into memory, then the vendor library's GEMM
 constexpr uint64_t kDenseMinM = 128;               // from here on the rebuilt-weight route is the faster one
 constexpr size_t kDenseScratchBytes = 64u << 20;   // what the GEMM library may use for itself

@@ -418,6 +418,18 @@ static void radix_sort16(uint16_t* keys_a, uint32_t* ids_a, uint16_t* keys_b, ui
                        keys_a, ids_a);
 }
 
+// The same stable two-pass sort for other callers: keys_a/ids_a in, sorted keys_a/ids_a out; keys_b/ids_b hold n
+// entries each and hist sort_hist_bytes(n) bytes.
+size_t sort_hist_bytes(uint64_t n) { return (size_t(n) / kSortChunk + 3) * 256 * 4; }
+
+hipError_t launch_sort_u16(uint16_t* keys_a, uint32_t* ids_a, uint16_t* keys_b, uint32_t* ids_b, uint32_t n, uint32_t* hist,
+                           hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    radix_sort16(keys_a, ids_a, keys_b, ids_b, n, hist, s);
+    return hipGetLastError();
+}
+
 template <int D>
 static void sort_vectors_t(const float* X, uint32_t N, const Workspace& w, hipStream_t s)
 {

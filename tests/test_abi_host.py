@@ -145,6 +145,31 @@ def test_forward_and_quantised_entry_points_reject_bad_arguments():
     assert lib.cc_layer_forward_q(A16, 1, A16, 4, A16, 10, 4, A16, 64, 64, None, A16, BF16, WS, 16, None) == -5
 
 
+def test_planned_gradient_entry_points_reject_bad_arguments():
+    lib = cc.load_library()
+    BF16 = 2
+    P = ctypes.c_void_p(0x1100)
+    n = 96 * 50  # codes of a 96 x 200 layer at g = 4
+    assert lib.cc_layer_grad_plan_bytes(0, 10) == 0 and lib.cc_layer_grad_plan_bytes(n, 70000) == 0
+    need = lib.cc_layer_grad_plan_bytes(n, 50)
+    assert need >= 4 * n + 2 * 4 * 51 and need % 256 == 0
+    assert lib.cc_layer_grad_plan_workspace_bytes(n) >= 8 * n
+    assert lib.cc_layer_codebook_grad_planned_workspace_bytes(n, 50, 4) >= 50 * 4 * 8
+    assert lib.cc_layer_codebook_grad_planned_workspace_bytes(n, 50, 17) == 0
+    assert lib.cc_layer_grad_plan(None, n, 50, P, 1 << 30, P, 1 << 30, None) == -1
+    assert lib.cc_layer_grad_plan(A16, 0, 50, P, 1 << 30, P, 1 << 30, None) == -2
+    assert lib.cc_layer_grad_plan(A16, n, 70000, P, 1 << 30, P, 1 << 30, None) == -2
+    assert lib.cc_layer_grad_plan(A16, n, 50, MISALIGNED, 1 << 30, P, 1 << 30, None) == -4
+    assert lib.cc_layer_grad_plan(A16, n, 50, P, need - 1, P, 1 << 30, None) == -5
+    assert lib.cc_layer_grad_plan(A16, n, 50, P, need, P, 16, None) == -5
+    assert lib.cc_layer_codebook_grad_planned(None, BF16, 96, 200, 50, 4, P, need, A16, P, 1 << 30, None) == -1
+    assert lib.cc_layer_codebook_grad_planned(A16, BF16, 96, 200, 50, 17, P, need, A16, P, 1 << 30, None) == -2
+    assert lib.cc_layer_codebook_grad_planned(A16, BF16, 96, 200, 50, 4, P, need - 1, A16, P, 1 << 30, None) == -5
+    assert "plan has" in cc.last_error()
+    assert lib.cc_layer_codebook_grad_planned(A16, BF16, 96, 200, 50, 4, P, need, A16, P, 16, None) == -5
+    assert lib.cc_layer_codebook_grad_planned(MISALIGNED, BF16, 96, 200, 50, 4, P, need, A16, P, 1 << 30, None) == -4
+
+
 def test_binding_refuses_host_tensors():
     import torch
 

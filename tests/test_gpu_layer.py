@@ -148,6 +148,77 @@ def test_codebook_grad(cc, out_features, in_features, g, K, dt):
     assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
 
 
+def _plan(cc, codes, K):
+    n = codes.numel()
+    plan = torch.empty(cc.layer_grad_plan_bytes(n, K), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(cc.layer_grad_plan_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    cc.layer_grad_plan(codes, K, plan, ws)
+    return plan
+
+
+@pytest.mark.parametrize("dt", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("out_features,in_features,g,K", [(256, 192, 4, 500), (250, 131, 4, 9000), (129, 67, 6, 300),
+                                                          (100, 300, 9, 64), (513, 300, 5, 8200), (7, 5, 7, 3),
+                                                          (600, 512, 8, 65536), (1024, 1536, 4, 3), (640, 333, 16, 2),
+                                                          (2048, 1024, 8, 1)])
+def test_codebook_grad_planned(cc, out_features, in_features, g, K, dt):
+    """The gradient from a prepared order of the codes: against the definition, against the unplanned entry point,
+    and the same bits on a second call. The last cases have clusters of 10^5..10^6 members (many work items each)."""
+    rng = np.random.default_rng(out_features + in_features + g + K)
+    G = _dev(rng.standard_normal((in_features, out_features)).astype(np.float32) * 1e-3, TORCH_DT[dt])
+    n = L.num_codes(in_features, out_features, g)
+    codes_np = rng.integers(0, K, size=n).astype(np.uint16)
+    if K > 100:
+        codes_np[codes_np == 7] = 8  # an empty cluster
+    codes = _dev(codes_np.view(np.int16)).view(torch.uint16)
+    print(f"codebook_grad_planned {out_features}x{in_features} g={g} K={K} {dt}", flush=True)
+    plan = _plan(cc, codes, K)
+    out = torch.full((K, g), 3.0, dtype=torch.float32, device="cuda")
+    ws = torch.empty(cc.layer_codebook_grad_planned_workspace_bytes(n, K, g), dtype=torch.uint8, device="cuda")
+    cc.layer_codebook_grad_planned(G, K, g, plan, out, ws)
+    Gh = G.float().cpu().numpy()
+    want = L.gather_backward(Gh, codes_np, K, g)
+    got = out.cpu().numpy().astype(np.float64)
+    # fp64 accumulation (count * 2^-53 * sum|terms|), then one rounding to fp32
+    absG = L.gather_backward(np.abs(Gh), codes_np, K, g)
+    counts = L.gather_backward(np.ones_like(Gh), codes_np, K, g)
+    tol = 2.0 ** -24 * np.abs(want) + counts * 2.0 ** -52 * absG + 1e-45
+    assert np.all(np.abs(got - want) <= tol), float(np.max(np.abs(got - want) / tol))
+    if K > 100:
+        assert np.all(got[7] == 0.0)
+    if dt != "f32":
+        # 16-bit terms of this spread add up exactly in fp64: the rounded exact sum, as the unplanned entry point gives
+        assert np.array_equal(got, want.astype(np.float32).astype(np.float64))
+        out1 = torch.empty_like(out)
+        ws1 = torch.empty(cc.workspace_bytes(max(n, K), g, K), dtype=torch.uint8, device="cuda")
+        cc.layer_codebook_grad(G, codes, K, g, out1, ws1)
+        assert torch.equal(out.view(torch.int32), out1.view(torch.int32))
+    out2 = torch.empty_like(out)
+    cc.layer_codebook_grad_planned(G, K, g, plan, out2, ws)
+    assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
+
+
+def test_codebook_grad_planned_leaves_out_codes_beyond_k_and_rejects_a_foreign_plan(cc):
+    rng = np.random.default_rng(5)
+    in_features, out_features, g, K = 96, 200, 4, 50
+    G = _dev(rng.standard_normal((in_features, out_features)).astype(np.float32), torch.bfloat16)
+    n = L.num_codes(in_features, out_features, g)
+    codes_np = rng.integers(0, 64, size=n).astype(np.uint16)  # codes 50..63 have no cluster
+    codes = _dev(codes_np.view(np.int16)).view(torch.uint16)
+    plan = _plan(cc, codes, K)
+    out = torch.empty((K, g), dtype=torch.float32, device="cuda")
+    ws = torch.empty(cc.layer_codebook_grad_planned_workspace_bytes(n, K, g), dtype=torch.uint8, device="cuda")
+    cc.layer_codebook_grad_planned(G, K, g, plan, out, ws)
+    want = L.gather_backward(G.float().cpu().numpy(), codes_np, 64, g)[:K]
+    assert np.array_equal(out.cpu().numpy(), want.astype(np.float32))
+    # a plan for another codebook size: detected on the device
+    other = _plan(cc, codes, 64)
+    big = torch.empty(max(other.numel(), plan.numel()), dtype=torch.uint8, device="cuda")
+    big[:other.numel()] = other
+    cc.layer_codebook_grad_planned(G, K, g, big, out, ws)
+    assert torch.isnan(out).all()
+
+
 FORWARD_CASES = [  # (M, in_features, out_features, g, K, bias)
     (1, 256, 192, 4, 500, False),
     (7, 512, 250, 4, 9000, True),     # padding columns, ragged column tile
