@@ -165,3 +165,12 @@ def test_layer_path_at_full_size(g):
     Gh = W.float().numpy().T
     wantg = L.gather_backward(Gh, codes_np, K, gdim)
     assert np.array_equal(grad.cpu().numpy(), wantg.astype(np.float32))  # exact sums of bf16 values, one rounding
+    del wsz
+    print("layer path full size: codebook gradient from the prepared order", flush=True)
+    plan = torch.empty(cc.layer_grad_plan_bytes(n, K), dtype=torch.uint8, device="cuda")
+    pws = torch.empty(cc.layer_grad_plan_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    cc.layer_grad_plan(codes, K, plan, pws)
+    gws = torch.empty(cc.layer_codebook_grad_planned_workspace_bytes(n, K, gdim), dtype=torch.uint8, device="cuda")
+    grad2 = torch.empty_like(grad)
+    cc.layer_codebook_grad_planned(Wd.t().contiguous(), K, gdim, plan, grad2, gws)
+    assert np.array_equal(grad2.cpu().numpy(), wantg.astype(np.float32))
