@@ -32,8 +32,8 @@ PlanView view(void* base, uint64_t n, uint32_t K)
 {
     PlanView v;
     size_t off = 0;
-    auto take = [&](size_t bytes) {
-        char* p = static_cast<char*>(base) + off;
+    auto take = [&](size_t bytes) {  // base == nullptr: only the size is wanted
+        char* p = base ? static_cast<char*>(base) + off : nullptr;
         off += align256(bytes);
         return p;
     };
@@ -158,15 +158,18 @@ __global__ __launch_bounds__(kThreads) void grad_items_kernel(const void* __rest
     const uint32_t it = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
     if (it >= hdr->n_items) return;
     const int lane = threadIdx.x & 63;
+    // The clamps below change nothing for a plan as cc_layer_grad_plan wrote it; they keep every access in
+    // bounds should the caller's buffer have been overwritten since.
     const uint32_t k = item_cluster[it];
-    const uint32_t j0 = starts[k] + (it - item_starts[k]) * kItem;
-    const uint32_t j1 = min(j0 + kItem, starts[k + 1]);
+    if (k >= K) return;
+    const uint32_t j1 = min(min(starts[k] + (it - item_starts[k] + 1) * kItem, starts[k + 1]), n);
+    const uint32_t j0 = min(starts[k] + (it - item_starts[k]) * kItem, j1);
     double acc[G];
 #pragma unroll
     for (int c = 0; c < G; ++c) acc[c] = 0.0;
 #pragma unroll 4
     for (uint32_t j = j0 + lane; j < j1; j += 64) {
-        const uint32_t p = order[j];
+        const uint32_t p = min(order[j], n - 1);
         const uint32_t r = p / per_row, col = (p - r * per_row) * g;
         const uint64_t at = uint64_t(r) * out_features + col;
         if constexpr (VEC) {
@@ -198,7 +201,8 @@ __global__ __launch_bounds__(kThreads) void grad_items_kernel(const void* __rest
 // One thread per codebook entry: the cluster's work items in order, one rounding to fp32. A plan that was not
 // built for these (num_codes, K) gives NaN everywhere.
 __global__ __launch_bounds__(kThreads) void grad_finish_kernel(const double* __restrict__ partial, uint32_t g, uint32_t n,
-                                                               uint32_t K, const PlanHeader* __restrict__ hdr,
+                                                               uint32_t K, uint32_t item_cap,
+                                                               const PlanHeader* __restrict__ hdr,
                                                                const uint32_t* __restrict__ item_starts,
                                                                float* __restrict__ grad_codebook)
 {
@@ -210,7 +214,8 @@ __global__ __launch_bounds__(kThreads) void grad_finish_kernel(const double* __r
     }
     const uint32_t k = t / g, c = t - k * g;
     double s = 0.0;
-    for (uint32_t it = item_starts[k]; it < item_starts[k + 1]; ++it) s += partial[size_t(it) * g + c];
+    const uint32_t end = min(item_starts[k + 1], min(hdr->n_items, item_cap));
+    for (uint32_t it = item_starts[k]; it < end; ++it) s += partial[size_t(it) * g + c];
     grad_codebook[t] = float(s);
 }
 
@@ -279,7 +284,7 @@ hipError_t launch_layer_grad_planned(const void* grad, int dtype, uint32_t in_fe
     if (e != hipSuccess) return e;
     const uint32_t entries = K * g;  // K <= 65536, g <= 16
     hipLaunchKernelGGL(grad_finish_kernel, dim3((entries + kThreads - 1) / kThreads), dim3(kThreads), 0, s, partial, g, n, K,
-                       v.hdr, v.item_starts, grad_codebook);
+                       uint32_t(max_items(n, K)), v.hdr, v.item_starts, grad_codebook);
     return hipGetLastError();
 }
 
