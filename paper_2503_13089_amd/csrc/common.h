@@ -4,7 +4,12 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 namespace cc {
+
+// bytes of the radix sort's histogram buffer for n elements (sort.hip)
+size_t sort_hist_bytes(uint64_t n);
 
 constexpr uint32_t kMaxK = 1u << 24;
 
@@ -133,7 +138,8 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d_caller, uint32_t K)
     w.ckeys = reinterpret_cast<uint16_t*>(take(size_t(K) * 2));
     w.ckeys_tmp = reinterpret_cast<uint16_t*>(take(size_t(K) * 2));
     w.key_starts = reinterpret_cast<uint32_t*>(take(size_t(65537) * 4));
-    w.sort_hist = reinterpret_cast<uint32_t*>(take((size_t(N) / 4096 + 3) * 256 * 4));  // histogram + 256 totals
+    // histogram rows + 256 totals, for the vectors' sort and for the centroids' (whose blocks are smaller)
+    w.sort_hist = reinterpret_cast<uint32_t*>(take(std::max(sort_hist_bytes(N), sort_hist_bytes(K))));
     w.windows = reinterpret_cast<uint2*>(take((size_t(N) / 512 + 1) * kWinStride * 8));
     if (w.padded) {
         w.xpad = reinterpret_cast<float*>(take(size_t(N) * d * 4));
@@ -273,7 +279,6 @@ hipError_t launch_layer_forward(const void* x, uint32_t M, const void* codebook,
                                 const uint16_t* codes, uint32_t in_features, uint32_t out_features, const void* bias,
                                 void* y, float* partial, hipStream_t s);
 // ---- codebook gradient from a prepared order of the codes (layer_grad_plan.hip); sort helpers from sort.hip
-size_t sort_hist_bytes(uint64_t n);
 hipError_t launch_sort_u16(uint16_t* keys_a, uint32_t* ids_a, uint16_t* keys_b, uint32_t* ids_b, uint32_t n, uint32_t* hist,
                            hipStream_t s);
 size_t layer_grad_plan_bytes(uint64_t num_codes, uint32_t K);

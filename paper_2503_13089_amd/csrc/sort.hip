@@ -87,12 +87,12 @@ __global__ __launch_bounds__(kThreads) void vector_keys_kernel(const float* __re
 
 // One radix pass over 8 bits of the key. hist is digit-major: hist[digit * blocks + block].
 __global__ __launch_bounds__(kSortThreads) void radix_hist_kernel(const uint16_t* __restrict__ keys, uint32_t n,
-                                                                  int shift, uint32_t* __restrict__ hist)
+                                                                  uint32_t chunk, int shift, uint32_t* __restrict__ hist)
 {
     __shared__ uint32_t h[256];
     if (threadIdx.x < 256) h[threadIdx.x] = 0;
     __syncthreads();
-    const uint32_t lo = blockIdx.x * kSortChunk, hi = min(lo + kSortChunk, n);
+    const uint32_t lo = blockIdx.x * chunk, hi = min(lo + chunk, n);
     for (uint32_t i = lo + threadIdx.x; i < hi; i += kSortThreads) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
     __syncthreads();
     if (threadIdx.x < 256) hist[threadIdx.x * gridDim.x + blockIdx.x] = h[threadIdx.x];
@@ -129,7 +129,8 @@ __global__ __launch_bounds__(1024) void radix_rowscan_kernel(uint32_t* __restric
 // position, so the result is the same whatever the scheduling.
 __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uint16_t* __restrict__ keys_in,
                                                                      const uint32_t* __restrict__ ids_in, uint32_t n,
-                                                                     int shift, const uint32_t* __restrict__ hist,
+                                                                     uint32_t chunk, int shift,
+                                                                     const uint32_t* __restrict__ hist,
                                                                      const uint32_t* __restrict__ totals,
                                                                      uint16_t* __restrict__ keys_out,
                                                                      uint32_t* __restrict__ ids_out)
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(kSortThreads) void radix_scatter_kernel(const uint1
         base[threadIdx.x] = before + hist[threadIdx.x * gridDim.x + blockIdx.x];
     }
     __syncthreads();
-    const uint32_t lo = blockIdx.x * kSortChunk, hi = min(lo + kSortChunk, n);
+    const uint32_t lo = blockIdx.x * chunk, hi = min(lo + chunk, n);
     for (uint32_t r0 = lo; r0 < hi; r0 += kSortThreads) {
         for (int t = threadIdx.x; t < kWaves * 256; t += kSortThreads) (&cnt[0][0])[t] = 0;
         __syncthreads();
@@ -402,25 +403,31 @@ __global__ void persist_check_kernel(WsPersist* persist, uint32_t N, uint32_t d,
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Elements per block and pass: a large array streams through 4096-element chunks (8 rounds of the scatter's
+// ranking per block); a small one (the centroids, every iteration) is latency-bound, so it is spread over as many
+// blocks as it has rounds.
+static uint32_t sort_chunk(uint64_t n) { return n <= (1u << 18) ? uint32_t(kSortThreads) : kSortChunk; }
+
 static void radix_sort16(uint16_t* keys_a, uint32_t* ids_a, uint16_t* keys_b, uint32_t* ids_b, uint32_t n,
                          uint32_t* hist, hipStream_t s)
 {
-    const uint32_t blocks = (n + kSortChunk - 1) / kSortChunk;
+    const uint32_t chunk = sort_chunk(n);
+    const uint32_t blocks = (n + chunk - 1) / chunk;
     // pass 1: low byte a -> b; pass 2: high byte b -> a
     uint32_t* totals = hist + size_t(256) * blocks;
-    hipLaunchKernelGGL(radix_hist_kernel, dim3(blocks), dim3(kSortThreads), 0, s, keys_a, n, 0, hist);
+    hipLaunchKernelGGL(radix_hist_kernel, dim3(blocks), dim3(kSortThreads), 0, s, keys_a, n, chunk, 0, hist);
     hipLaunchKernelGGL(radix_rowscan_kernel, dim3(256), dim3(1024), 0, s, hist, blocks, totals);
-    hipLaunchKernelGGL(radix_scatter_kernel, dim3(blocks), dim3(kSortThreads), 0, s, keys_a, ids_a, n, 0, hist, totals,
+    hipLaunchKernelGGL(radix_scatter_kernel, dim3(blocks), dim3(kSortThreads), 0, s, keys_a, ids_a, n, chunk, 0, hist, totals,
                        keys_b, ids_b);
-    hipLaunchKernelGGL(radix_hist_kernel, dim3(blocks), dim3(kSortThreads), 0, s, keys_b, n, 8, hist);
+    hipLaunchKernelGGL(radix_hist_kernel, dim3(blocks), dim3(kSortThreads), 0, s, keys_b, n, chunk, 8, hist);
     hipLaunchKernelGGL(radix_rowscan_kernel, dim3(256), dim3(1024), 0, s, hist, blocks, totals);
-    hipLaunchKernelGGL(radix_scatter_kernel, dim3(blocks), dim3(kSortThreads), 0, s, keys_b, ids_b, n, 8, hist, totals,
+    hipLaunchKernelGGL(radix_scatter_kernel, dim3(blocks), dim3(kSortThreads), 0, s, keys_b, ids_b, n, chunk, 8, hist, totals,
                        keys_a, ids_a);
 }
 
 // The same stable two-pass sort for other callers: keys_a/ids_a in, sorted keys_a/ids_a out; keys_b/ids_b hold n
 // entries each and hist sort_hist_bytes(n) bytes.
-size_t sort_hist_bytes(uint64_t n) { return (size_t(n) / kSortChunk + 3) * 256 * 4; }
+size_t sort_hist_bytes(uint64_t n) { return (size_t(n) / sort_chunk(n) + 3) * 256 * 4; }
 
 hipError_t launch_sort_u16(uint16_t* keys_a, uint32_t* ids_a, uint16_t* keys_b, uint32_t* ids_b, uint32_t n, uint32_t* hist,
                            hipStream_t s)
