@@ -178,13 +178,15 @@ int cc_layer_weight(const void *codebook, int dtype, uint32_t K, uint32_t g, con
  * Forward pass of the layer (layer listing): y [M * out_features] = x [M * in_features] . W (+ bias), with W
  * as rebuilt by cc_layer_weight. x, codebook, bias (may be NULL) and y share one 16-bit dtype (CC_F16 or
  * CC_BF16); products are exact, accumulation is fp32, y is rounded once (to nearest even). in_features must be
- * a multiple of 8, M <= 2^22; x, y and codebook 16-byte aligned. Two routes, chosen by M alone:
- *   M < 128 (decoding): W is never written to memory: codebook rows are gathered straight into matrix-core
+ * a multiple of 8, M <= 2^22; x, y and codebook 16-byte aligned. Two routes, chosen by the shape alone (the
+ * second from M = 128 on, and for layers of 2^25 weights or more already from M = 65, or 33 if out_features >=
+ * 2 * in_features):
+ *   few rows (decoding): W is never written to memory: codebook rows are gathered straight into matrix-core
  *     operand tiles. The summation order is fixed: same inputs, same bits. Workspace: fp32 partial sums of the
  *     in-feature slices that fill the chip when M is small.
- *   M >= 128 (prefill): the listing's own order. W is rebuilt once into the workspace and multiplied by the
- *     vendor GEMM library (hipBLASLt, opened at run time; bias in its epilogue), whose algorithm is chosen once
- *     per shape and process. Workspace: W plus 64 MiB for the library. Where the library cannot be opened, or
+ *   many rows (prefill, wide decoding batches): the listing's own order. W is rebuilt once into the workspace
+ *     and multiplied by the vendor GEMM library (hipBLASLt, opened at run time; bias in its epilogue), whose
+ *     algorithm is chosen once per shape and process. Workspace: W plus 64 MiB for the library. Where the library cannot be opened, or
  *     has no algorithm for the shape, the first route serves every M.
  * cc_layer_forward_workspace_bytes(M, in_features, out_features) bytes, 256-byte aligned; may be NULL if that is 0.
  */
@@ -266,8 +268,9 @@ int cc_layer_weight_q(const void *qbook, int bits, const float *scale, uint32_t 
  * weight rebuilt from the integers q themselves. The products x * q are exact, the sum is fp32, the scale
  * multiplies the finished sum, and y is rounded once - so this is slightly more accurate than a product with
  * the 16-bit weight of cc_layer_weight_q, whose entries are each rounded to 16 bits. Same contract otherwise,
- * both routes included: for M >= 128 the integers q are written out as a 16-bit matrix (exact), the GEMM library
- * returns the fp32 sums, and one more kernel applies scale, bias and the rounding.
+ * both routes included (the second from M = 65 on, from M = 17 on for layers of 2^25 weights or more): there the
+ * integers q are written out as a 16-bit matrix (exact), the GEMM library returns the fp32 sums, and one more
+ * kernel applies scale, bias and the rounding.
  * Workspace: cc_layer_forward_q_workspace_bytes(M, in_features, out_features). */
 size_t cc_layer_forward_q_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features);
 int cc_layer_forward_q(const void *x, uint64_t M, const void *qbook, int bits, const float *scale, uint32_t K,

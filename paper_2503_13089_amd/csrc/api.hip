@@ -404,7 +404,7 @@ size_t cc_layer_forward_workspace_bytes(uint64_t M, uint32_t in_features, uint32
     if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;
     const uint32_t splits = cc::layer_forward_splits(M, in_features, out_features);
     const size_t fused = splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
-    if (M < cc::kDenseMinM || !cc::dense_available()) return fused;
+    if (!cc::dense_rows(M, in_features, out_features) || !cc::dense_available()) return fused;
     // the rebuilt 16-bit weight, then the GEMM library's own scratch
     const size_t dense = cc::align256(size_t(in_features) * out_features * 2) + cc::kDenseScratchBytes;
     return dense > fused ? dense : fused;
@@ -427,7 +427,7 @@ int cc_layer_forward(const void* x, uint64_t M, const void* codebook, int dtype,
         if (workspace_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (M >= cc::kDenseMinM && cc::dense_available()) {
+    if (cc::dense_rows(M, in_features, out_features) && cc::dense_available()) {
         char* scratch = static_cast<char*>(workspace) + cc::align256(size_t(in_features) * out_features * 2);
         CC_TRY_HIP(cc::launch_layer_weight(codebook, dtype, K, g, codes, in_features, out_features, workspace, s),
                    "layer weight");
@@ -616,7 +616,7 @@ size_t cc_layer_forward_q_workspace_bytes(uint64_t M, uint32_t in_features, uint
     if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;
     const uint32_t splits = cc::layer_forward_q_max_splits(M, in_features, out_features);
     const size_t fused = splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
-    if (M < cc::kDenseMinM || !cc::dense_available()) return fused;
+    if (!cc::dense_rows_q(M, in_features, out_features) || !cc::dense_available()) return fused;
     // the integer weight in 16 bits, the fp32 sums, one constant, then the GEMM library's own scratch
     const size_t dense = cc::align256(size_t(in_features) * out_features * 2) + cc::align256(size_t(M) * out_features * 4) +
                          256 + cc::kDenseScratchBytes;
@@ -642,7 +642,7 @@ int cc_layer_forward_q(const void* x, uint64_t M, const void* qbook, int bits, c
         if (workspace_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (M >= cc::kDenseMinM && cc::dense_available()) {
+    if (cc::dense_rows_q(M, in_features, out_features) && cc::dense_available()) {
         char* base = static_cast<char*>(workspace);
         float* sums = reinterpret_cast<float*>(base + cc::align256(size_t(in_features) * out_features * 2));
         float* one = reinterpret_cast<float*>(reinterpret_cast<char*>(sums) + cc::align256(size_t(M) * out_features * 4));

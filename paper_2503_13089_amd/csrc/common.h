@@ -289,7 +289,23 @@ hipError_t launch_layer_grad_planned(const void* grad, int dtype, uint32_t in_fe
                                      uint32_t g, uint32_t n, const void* plan, float* grad_codebook, void* workspace,
                                      hipStream_t s);
 // ---- prefill-sized batches (dense.hip): W rebuilt into memory, then the vendor library's GEMM
-constexpr uint64_t kDenseMinM = 128;               // from here on the rebuilt-weight route is the faster one
+// From where on the rebuilt-weight route is the faster one: 128 rows for any layer, fewer for a large one, where
+// the fused kernels repeat their gathers per row tile and the rebuild (47 us for 45 M weights) is small against
+// the product. Measured on 4096 x 4096, 4096 x 11008, 8192 x 8192 and 11008 x 4096 (bf16, K = 65536, g = 4;
+// fused / rebuilt + dense, us): 16-bit codebook, 4096 x 11008 at 33 rows 102 / 78, at 96 rows 169 / 83;
+// 8192 x 8192 at 64 rows 100 / 130, at 96 rows 167 / 134; 4-bit codebook, 4096 x 11008 at 32 rows 140 / 73,
+// 8192 x 8192 at 33 rows 147 / 103, 4096 x 4096 at 64 rows 60 / 72, at 96 rows 105 / 72.
+constexpr uint64_t kDenseMinM = 128;
+inline bool dense_rows(uint64_t M, uint32_t in_features, uint32_t out_features)
+{
+    const bool large = uint64_t(in_features) * out_features >= (1ull << 25);
+    return M >= kDenseMinM || (large && (M > 64 || (M > 32 && out_features >= 2 * uint64_t(in_features))));
+}
+inline bool dense_rows_q(uint64_t M, uint32_t in_features, uint32_t out_features)  // quantised codebook
+{
+    const bool large = uint64_t(in_features) * out_features >= (1ull << 25);
+    return M > 64 || (large && M > 16);
+}
 constexpr size_t kDenseScratchBytes = 64u << 20;   // what the GEMM library may use for itself
 bool dense_available();
 hipError_t launch_dense_forward(const void* x, uint32_t M, const void* weight, int dtype, uint32_t in_features,
