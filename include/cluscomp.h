@@ -186,7 +186,8 @@ int cc_layer_weight(const void *codebook, int dtype, uint32_t K, uint32_t g, con
  *     in-feature slices that fill the chip when M is small.
  *   many rows (prefill, wide decoding batches): the listing's own order. W is rebuilt once into the workspace
  *     and multiplied by the vendor GEMM library (hipBLASLt, opened at run time; bias in its epilogue), whose
- *     algorithm is chosen once per shape and process. Workspace: W plus 64 MiB for the library. Where the library cannot be opened, or
+ *     algorithm is chosen once per shape and process (the first such call on a device creates the library's
+ *     handle and the first per shape asks for its algorithm: both allocate; later calls do not). Workspace: W plus 64 MiB for the library. Where the library cannot be opened, or
  *     has no algorithm for the shape, the first route serves every M.
  * cc_layer_forward_workspace_bytes(M, in_features, out_features) bytes, 256-byte aligned; may be NULL if that is 0.
  */
