@@ -176,3 +176,15 @@ def test_binding_refuses_host_tensors():
     x = torch.zeros(16, 4)
     with pytest.raises(TypeError):
         cc.decode(x, torch.zeros(16, dtype=torch.int32), x)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before touching a device."""
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    proc = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                          timeout=120)
+    assert proc.returncode == 2
+    assert "one GPU" in proc.stderr and proc.stdout.strip() == ""
