@@ -270,11 +270,12 @@ def test_layer_forward(cc, M, in_features, out_features, g, K, with_bias, dt):
     assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
 
 
-def test_layer_forward_prefill_at_model_size(cc):
-    """A prefill batch through an MLP-sized layer (the rebuilt-weight route where the GEMM library is there):
-    sampled rows of y against the definition, and the same bits on a second call."""
+@pytest.mark.parametrize("M", [40, 2048])
+def test_layer_forward_prefill_at_model_size(cc, M):
+    """A prefill batch, and a wide decoding batch, through an MLP-sized layer (the rebuilt-weight route where the
+    GEMM library is there): sampled rows of y against the definition, and the same bits on a second call."""
     rng = np.random.default_rng(77)
-    M, in_features, out_features, g, K = 2048, 4096, 11008, 4, 65536
+    in_features, out_features, g, K = 4096, 11008, 4, 65536
     T = torch.bfloat16
     x = _dev(rng.standard_normal((M, in_features)).astype(np.float32), T)
     book = _dev(rng.standard_normal((K, g)).astype(np.float32) * 0.02, T)
@@ -288,7 +289,7 @@ def test_layer_forward_prefill_at_model_size(cc):
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     print(f"layer_forward M={M} {in_features}->{out_features} ws={nbytes}", flush=True)
     cc.layer_forward(x, book, codes, out_features, bias, y, ws)
-    rows = np.concatenate([[0, M - 1], rng.choice(M, size=30, replace=False)])
+    rows = np.concatenate([[0, M - 1], rng.choice(M, size=min(30, M), replace=False)])
     xh = x.float().cpu().numpy()[rows]
     bh, biash = book.float().cpu().numpy(), bias.float().cpu().numpy()
     want = L.layer_forward(xh, bh, codes_np, in_features, out_features, biash)
@@ -374,7 +375,9 @@ def test_layer_weight_q_bit_exact(cc, out_features, in_features, g, K, dt, bits)
                          FORWARD_CASES + [(3, 2048, 1024, 4, 65536, True),
                                           # 16 < M <= 64 with g = 4 / 8 and an LDS-sized codebook: matrix cores + LDS codebook
                                           (40, 512, 320, 4, 65536, True), (64, 264, 200, 8, 9000, False),
-                                          (17, 1024, 1024, 4, 30000, True), (33, 72, 70, 4, 100, False)])
+                                          (17, 1024, 1024, 4, 30000, True), (33, 72, 70, 4, 100, False),
+                                          # a wide decoding batch on a layer of 2^25 weights: rebuilt integer weight + GEMM
+                                          (24, 4096, 8448, 4, 65536, True)])
 def test_layer_forward_q(cc, M, in_features, out_features, g, K, with_bias, dt, bits):
     rng = np.random.default_rng(M + in_features + out_features + g + bits)
     T = TORCH_DT[dt]
