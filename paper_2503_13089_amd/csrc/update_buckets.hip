@@ -57,19 +57,28 @@ __device__ __forceinline__ uint32_t slot_of_code(uint32_t k, const uint32_t* __r
     return cinv != nullptr ? cinv[k] : k;
 }
 
-// Calls f(i) for every flagged vector among the kDeltaChunk / kThreads = 64 consecutive ones that this thread
-// looks after in the chunk starting at lo (two words of the `changed` bitmap; bits beyond N are never set).
+// Calls f(i) for every flagged vector of the chunk of kDeltaChunk vectors starting at lo (bits beyond N are never
+// set). Each thread reads the 64 flags of its own stretch (two words of the `changed` bitmap), the flagged offsets
+// are packed into `list` (LDS, kDeltaChunk entries) and then dealt out evenly: with a few per cent of the flags set,
+// a thread working through its own stretch alone would wait for the unluckiest lane of its wave.
 template <typename F>
-__device__ __forceinline__ void for_each_flagged(const uint32_t* __restrict__ changed, uint32_t lo, uint32_t N, F f)
+__device__ __forceinline__ void for_each_flagged(const uint32_t* __restrict__ changed, uint32_t lo, uint32_t N,
+                                                 uint16_t* list, uint32_t* wave_sum, F f)
 {
-    static_assert(kDeltaChunk == 64 * kThreads, "two bitmap words per thread");
+    static_assert(kDeltaChunk == 64 * kThreads && kDeltaChunk <= 65536, "two bitmap words per thread, 16-bit offsets");
     const uint32_t first = lo + 64 * threadIdx.x;
+    uint32_t word[2] = {0u, 0u};
 #pragma unroll
-    for (uint32_t w = 0; w < 2; ++w) {
-        if (first + 32 * w >= N) break;
-        for (uint32_t bits = changed[(first >> 5) + w]; bits != 0; bits &= bits - 1)
-            f(first + 32 * w + uint32_t(__ffs(int(bits)) - 1));
-    }
+    for (uint32_t w = 0; w < 2; ++w)
+        if (first + 32 * w < N) word[w] = changed[(first >> 5) + w];
+    uint32_t total;
+    uint32_t pos = block_exclusive_scan(uint32_t(__popc(word[0]) + __popc(word[1])), wave_sum, total);
+#pragma unroll
+    for (uint32_t w = 0; w < 2; ++w)
+        for (uint32_t bits = word[w]; bits != 0; bits &= bits - 1)
+            list[pos++] = uint16_t(64 * threadIdx.x + 32 * w + uint32_t(__ffs(int(bits)) - 1));
+    __syncthreads();
+    for (uint32_t e = threadIdx.x; e < total; e += kThreads) f(lo + list[e]);
 }
 
 // Which chunk of vectors a workgroup takes. Workgroups are dealt to the 8 XCDs in turn, and the records of
@@ -92,6 +101,8 @@ __global__ __launch_bounds__(kThreads) void bucket_count_kernel(const uint32_t* 
 {
     __shared__ uint32_t h[kMaxBuckets];
     __shared__ uint32_t bad_total;
+    __shared__ uint16_t flagged[kDeltaChunk];
+    __shared__ uint32_t wave_sum[kThreads / 64];
     for (uint32_t b = threadIdx.x; b < nbuckets; b += kThreads) h[b] = 0;
     if (threadIdx.x == 0) bad_total = 0;
     __syncthreads();
@@ -102,7 +113,7 @@ __global__ __launch_bounds__(kThreads) void bucket_count_kernel(const uint32_t* 
     const uint32_t lo = blk * chunk, hi = min(lo + chunk, N);
     uint32_t bad = 0;
     if (changed != nullptr) {
-        for_each_flagged(changed, lo, N, [&](uint32_t i) {
+        for_each_flagged(changed, lo, N, flagged, wave_sum, [&](uint32_t i) {
             const uint32_t k = idx[i], kp = prev[i];
             if (k != kp && k < K && kp < K) {
                 atomicAdd(&h[slot_of_code(k, cinv) / kBucketClusters], 1u);
@@ -285,12 +296,14 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_delta_kernel(const fl
                                                                         char* __restrict__ records)
 {
     __shared__ uint32_t cursor[kMaxBuckets];  // next free record of (bucket, this block)
+    __shared__ uint16_t flagged[kDeltaChunk];
+    __shared__ uint32_t wave_sum[kThreads / 64];
     const uint32_t blk = chunk_of_workgroup();
     for (uint32_t b = threadIdx.x; b < nbuckets; b += kThreads)
         cursor[b] = base[b] + gtot[size_t(blk / kBucketGroup) * nbuckets + b] + hist[size_t(blk) * nbuckets + b];
     __syncthreads();
     const uint32_t lo = blk * kDeltaChunk;
-    for_each_flagged(changed, lo, N, [&](uint32_t i) {
+    for_each_flagged(changed, lo, N, flagged, wave_sum, [&](uint32_t i) {
         const uint32_t k_new = idx[i], k_old = prev[i];
         if (k_new == k_old || k_new >= K || k_old >= K) return;
         float4 row[D / 4];
