@@ -197,6 +197,22 @@ int cc_layer_forward(const void *x, uint64_t M, const void *codebook, int dtype,
                      void *y, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Optional, for start-up: the GEMM library offers several algorithms per product and its own first choice is not
+ * always the fastest (2048 x 4096 x 11008 in bf16: 286 us against 173 us for the best of its candidates). This
+ * call runs every candidate a few times for the product that cc_layer_forward (quantised = 0) or
+ * cc_layer_forward_q (quantised != 0) would issue for these M, shapes, dtype and bias on the current device, and
+ * keeps the fastest for all later calls of this process. UNLIKE EVERY OTHER CALL IT SYNCHRONISES `stream` and blocks
+ * the host for a few milliseconds; it refuses a stream under graph capture. Where the rebuilt-weight route does
+ * not apply (few rows, library missing) it does nothing and returns CC_OK. The operands are synthetic, held in
+ *   workspace      device, cc_layer_forward_tune_workspace_bytes(M, in_features, out_features), 256-byte aligned
+ *   host_times_us  host, [2], may be NULL: time of the algorithm now kept, and of the library's first choice
+ * Results do not depend on the algorithm beyond the order of the fp32 accumulation.
+ */
+size_t cc_layer_forward_tune_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features);
+int cc_layer_forward_tune(uint64_t M, uint32_t in_features, uint32_t out_features, int dtype, int with_bias,
+                          int quantised, void *workspace, size_t workspace_bytes, float *host_times_us, void *stream);
+
+/*
  * Gradient of the codebook (the only trainable tensor of the layer, Sections 3.2-3.3): every weight entry
  * is a copy of one codebook entry, so grad_codebook [K * g] (fp32) [k][j] is the sum of grad_weight
  * [in_features * out_features] (grad_dtype) over the entries rebuilt from codebook[k][j]. Sums are

@@ -555,6 +555,53 @@ int cc_layer_weight_q(const void* qbook, int bits, const float* scale, uint32_t 
     return CC_OK;
 }
 
+size_t cc_layer_forward_tune_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features)
+{
+    if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;
+    return cc::align256(size_t(in_features) * out_features * 2) + cc::align256(size_t(M) * in_features * 2) +
+           cc::align256(size_t(M) * out_features * 4) + cc::align256(size_t(out_features) * 2) + cc::kDenseScratchBytes;
+}
+
+int cc_layer_forward_tune(uint64_t M, uint32_t in_features, uint32_t out_features, int dtype, int with_bias, int quantised,
+                          void* workspace, size_t workspace_bytes, float* host_times_us, void* stream)
+{
+    if (host_times_us) host_times_us[0] = host_times_us[1] = 0.0f;
+    if (!workspace) return fail(CC_ERR_NULL, "workspace is NULL");
+    if (int rc = check_layer(in_features, out_features, 1, 1, dtype, false)) return rc;
+    if (M == 0 || M > (1ull << 22)) return fail(CC_ERR_SHAPE, "M = %llu is not in 1..2^22", (unsigned long long)M);
+    if (in_features % 8 != 0) return fail(CC_ERR_SHAPE, "in_features = %u is not a multiple of 8", in_features);
+    if (!aligned(workspace, 256)) return fail(CC_ERR_ALIGN, "workspace must be 256-byte aligned");
+    const size_t need = cc_layer_forward_tune_workspace_bytes(M, in_features, out_features);
+    if (workspace_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+    const bool routed = quantised ? cc::dense_rows_q(M, in_features, out_features) : cc::dense_rows(M, in_features, out_features);
+    if (!routed || !cc::dense_available()) return CC_OK;  // these calls take the fused kernels: nothing to choose
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    CC_TRY_HIP(hipStreamIsCapturing(s, &capturing), "capture query");
+    if (capturing != hipStreamCaptureStatusNone)
+        return fail(CC_ERR_HIP, "cc_layer_forward_tune synchronises and cannot run on a stream that is being captured");
+    char* w = static_cast<char*>(workspace);
+    char* x = w + cc::align256(size_t(in_features) * out_features * 2);
+    char* y = x + cc::align256(size_t(M) * in_features * 2);
+    char* bias = y + cc::align256(size_t(M) * out_features * 4);
+    char* scratch = bias + cc::align256(size_t(out_features) * 2);
+    CC_TRY_HIP(cc::launch_fill_operand(w, size_t(in_features) * out_features, s), "operand fill");
+    CC_TRY_HIP(cc::launch_fill_operand(x, size_t(M) * in_features, s), "operand fill");
+    CC_TRY_HIP(cc::launch_fill_operand(bias, out_features, s), "operand fill");
+    float kept = 0.0f, first = 0.0f;
+    // the quantised route multiplies into fp32 sums and adds the bias afterwards
+    const hipError_t e = cc::tune_dense_forward(x, uint32_t(M), w, dtype, in_features, out_features,
+                                                (with_bias && !quantised) ? bias : nullptr, y, quantised != 0, scratch, s,
+                                                &kept, &first);
+    if (e == hipErrorNotSupported) return CC_OK;  // no algorithm for the shape: the fused kernels serve it
+    CC_TRY_HIP(e, "algorithm timing");
+    if (host_times_us) {
+        host_times_us[0] = kept;
+        host_times_us[1] = first;
+    }
+    return CC_OK;
+}
+
 size_t cc_layer_grad_plan_bytes(uint64_t num_codes, uint32_t K)
 {
     if (num_codes == 0 || num_codes >= (1ull << 32) || K == 0 || K > 65536) return 0;

@@ -311,6 +311,10 @@ bool dense_available();
 hipError_t launch_dense_forward(const void* x, uint32_t M, const void* weight, int dtype, uint32_t in_features,
                                 uint32_t out_features, const void* bias, void* y, bool f32_out, void* scratch,
                                 hipStream_t s);
+hipError_t launch_fill_operand(void* p, size_t n16, hipStream_t s);
+hipError_t tune_dense_forward(const void* x, uint32_t M, const void* weight, int dtype, uint32_t in_features,
+                              uint32_t out_features, const void* bias, void* y, bool f32_out, void* scratch, hipStream_t s,
+                              float* kept_us, float* first_us);
 // ---- uniformly quantised codebook (layer_quant.hip); bits = 8 or 4
 hipError_t launch_codebook_quantize(const float* centroids, size_t n, int bits, void* qbook, float* scale,
                                     uint32_t* absmax_scratch, hipStream_t s);

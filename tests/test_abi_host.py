@@ -145,6 +145,26 @@ def test_forward_and_quantised_entry_points_reject_bad_arguments():
     assert lib.cc_layer_forward_q(A16, 1, A16, 4, A16, 10, 4, A16, 64, 64, None, A16, BF16, WS, 16, None) == -5
 
 
+def test_forward_tune_rejects_bad_arguments():
+    lib = cc.load_library()
+    BF16, F32 = 2, 0
+    P = ctypes.c_void_p(0x1100)
+    need = lib.cc_layer_forward_tune_workspace_bytes(256, 512, 768)
+    assert need >= 512 * 768 * 2 + 256 * 512 * 2 + 256 * 768 * 4 + 768 * 2 + (64 << 20) and need % 256 == 0
+    assert lib.cc_layer_forward_tune_workspace_bytes(0, 512, 768) == 0
+    assert lib.cc_layer_forward_tune(256, 512, 768, BF16, 0, 0, None, need, None, None) == -1
+    assert lib.cc_layer_forward_tune(0, 512, 768, BF16, 0, 0, P, need, None, None) == -2
+    assert lib.cc_layer_forward_tune(256, 512, 768, F32, 0, 0, P, need, None, None) == -2
+    assert lib.cc_layer_forward_tune(256, 500, 768, BF16, 0, 0, P, need, None, None) == -2
+    assert lib.cc_layer_forward_tune(256, 512, 768, BF16, 0, 0, MISALIGNED, need, None, None) == -4
+    assert lib.cc_layer_forward_tune(256, 512, 768, BF16, 0, 0, P, need - 1, None, None) == -5
+    # few rows: the fused kernels serve such calls; nothing to time, nothing launched
+    times = (ctypes.c_float * 2)(1.0, 1.0)
+    assert lib.cc_layer_forward_tune(4, 512, 768, BF16, 0, 0, P, lib.cc_layer_forward_tune_workspace_bytes(4, 512, 768),
+                                     times, None) == 0
+    assert times[0] == 0.0 and times[1] == 0.0
+
+
 def test_planned_gradient_entry_points_reject_bad_arguments():
     lib = cc.load_library()
     BF16 = 2

@@ -303,6 +303,42 @@ def test_layer_forward_prefill_at_model_size(cc, M):
     assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
 
 
+def test_layer_forward_tune_keeps_results_and_never_picks_a_slower_algorithm(cc):
+    """The start-up timing of the GEMM library's candidates: afterwards the forward pass still meets the definition
+    (only the accumulation order may change), and the algorithm kept is at least as fast as the library's own first
+    choice was in the same timing run."""
+    rng = np.random.default_rng(123)
+    M, in_features, out_features, g, K = 192, 1024, 2560, 4, 65536
+    T = torch.bfloat16
+    x = _dev(rng.standard_normal((M, in_features)).astype(np.float32), T)
+    book = _dev(rng.standard_normal((K, g)).astype(np.float32) * 0.02, T)
+    bias = _dev(rng.standard_normal(out_features).astype(np.float32), T)
+    n = L.num_codes(in_features, out_features, g)
+    codes_np = rng.integers(0, K, size=n).astype(np.uint16)
+    codes = _dev(codes_np.view(np.int16)).view(torch.uint16)
+    ws = torch.empty(cc.layer_forward_workspace_bytes(M, in_features, out_features), dtype=torch.uint8, device="cuda")
+    assert ws.numel() >= in_features * out_features * 2, "the GEMM library did not load on this box"
+    tws = torch.empty(cc.layer_forward_tune_workspace_bytes(M, in_features, out_features), dtype=torch.uint8, device="cuda")
+    print("layer_forward_tune", flush=True)
+    kept, first = cc.layer_forward_tune(M, in_features, out_features, T, True, False, tws)
+    assert 0.0 < kept <= first
+    kept_q, first_q = cc.layer_forward_tune(M, in_features, out_features, T, True, True, tws)
+    assert 0.0 < kept_q <= first_q
+    # few rows: the fused kernels serve the call, nothing to time
+    assert cc.layer_forward_tune(8, in_features, out_features, T, True, False, tws) == (0.0, 0.0)
+    y = torch.full((M, out_features), 9.0, dtype=T, device="cuda")
+    cc.layer_forward(x, book, codes, out_features, bias, y, ws)
+    xh, bh, biash = x.float().cpu().numpy(), book.float().cpu().numpy(), bias.float().cpu().numpy()
+    want = L.layer_forward(xh, bh, codes_np, in_features, out_features, biash)
+    mag = L.layer_forward(np.abs(xh), np.abs(bh), codes_np, in_features, out_features, np.abs(biash))
+    got = y.float().cpu().numpy().astype(np.float64)
+    tol = 2.0 ** -8 * np.abs(want) + in_features * 2.0 ** -24 * mag + 1e-38
+    assert np.all(np.abs(got - want) <= tol), float(np.max(np.abs(got - want) / tol))
+    y2 = torch.empty_like(y)
+    cc.layer_forward(x, book, codes, out_features, bias, y2, ws)
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+
+
 def test_layer_forward_reads_out_single_weight_rows(cc):
     """One-hot inputs: y must equal rows of the reconstructed weight exactly (no arithmetic error possible)."""
     rng = np.random.default_rng(2)
