@@ -417,7 +417,9 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
     // Tiles per tracking group: the epilogue re-evaluates the winning group in direct form, 8 * GT centroids per
     // lane. Over the whole codebook that is noise and a wide group keeps the hot loop lean; a windowed launch
     // scores only a few per cent of the codebook, the epilogue is then a third of the kernel, so groups are narrower.
-    constexpr int GT = 4, GT_WINDOWED = 2;
+    // From 32768 centroids on, 8-tile groups pay over the whole codebook (19.0 -> 18.75 ms at K = 65536, N = 11.3 M);
+    // at K = 4096 the doubled epilogue would cost more than the loop saves.
+    constexpr int GT = 4, GT_WIDE = ST >= 8 ? 8 : 4, GT_WINDOWED = 2;
     const size_t n4 = size_t(e.K) * D / 4;
     hipLaunchKernelGGL(codebook_absmax_kernel, dim3(uint32_t(std::min<size_t>((n4 + kThreads - 1) / kThreads, 64))),
                        dim3(kThreads), 0, s, reinterpret_cast<const float4*>(e.pack_rows), n4, w.hdr, e.gate);
@@ -426,7 +428,8 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
                        e.pack_perm);
     const uint32_t per_block = 4 * 32 * VT;
     const auto kernel = e.windows != nullptr ? assign_mfma_f16_kernel<D, VT, int(kStageTiles), GT_WINDOWED, true>
-                                             : assign_mfma_f16_kernel<D, VT, ST, GT, false>;
+                        : (e.K >= 32768  ? assign_mfma_f16_kernel<D, VT, ST, GT_WIDE, false>
+                                         : assign_mfma_f16_kernel<D, VT, ST, GT, false>);
     hipLaunchKernelGGL(kernel, dim3((e.N + per_block - 1) / per_block), dim3(kThreads),
                        0, s, e.X, e.N, e.rows, e.K, static_cast<const char*>(e.packed), e.packed_tiles, e.idx, w.dmin, w.hdr,
                        w.refine_list, w.refine_cap, e.gate, e.accumulate ? w.sums : nullptr,
