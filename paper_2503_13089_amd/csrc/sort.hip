@@ -289,11 +289,19 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
         plo = __builtin_fminf(plo, red[2][w]);
         phi = __builtin_fmaxf(phi, red[3][w]);
     }
-    // shells of the norm band, widened by one norm key (0.8 %) on each side
+    // Both bands are widened by 1e-5 of the largest norm in play: the norms, projections and distances behind them
+    // (sums of d fp32 products, a square root) are each within a few 1e-7 of that scale of their exact values, for
+    // the vectors here and for the centroids' own keys alike, and u already carries a factor 1.001.
+    const float slack = nhi < 3.0e38f ? 1e-5f * nhi : 0.0f;
+    nlo -= slack;
+    nhi += slack;
+    plo -= slack;
+    phi += slack;
+    // shells of the norm band
     const uint32_t ka = nlo > 0.0f ? norm_key(nlo) : 0u;
     const uint32_t kb = nhi < 3.0e38f ? norm_key(nhi) : 0xffffu;
-    const uint32_t smin = shell_of_key(ka > 0 ? ka - 1 : 0u, base);
-    const uint32_t smax = shell_of_key(min(kb + 1, 0xffffu), base);
+    const uint32_t smin = shell_of_key(ka, base);
+    const uint32_t smax = shell_of_key(kb, base);
     const bool wide = smax - smin + 1 > uint32_t(kWinSlots);
     // phase 3: key runs -> position runs (the ordered keys are ascending), in quads
     const uint32_t nslots = wide ? 1 : smax - smin + 1;
@@ -303,15 +311,17 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
             klo = smin << 7;
             khi = (smax << 7) | 127u;
         } else {
-            // cosine e.c/||c|| of a candidate in shell s: e.c in [plo, phi], ||c|| in [rlo, rhi); one bucket of slack
+            // cosine e.c/||c|| of a candidate in shell s: e.c in [plo, phi], ||c|| in [rlo, rhi); 1e-4 of slack for
+            // the two divisions (the centroid's own, when its key was made, and the one here: 1e-7 each)
             const uint32_t sh = smin + threadIdx.x;
             const float rlo = shell_rlo(sh, base), rhi = shell_rhi(sh, base);
             float tlo, thi;
             if (plo >= 0.0f) tlo = rhi < INFINITY ? plo / rhi : 0.0f; else tlo = rlo > 0.0f ? plo / rlo : -1.0f;
             if (phi >= 0.0f) thi = rlo > 0.0f ? phi / rlo : 1.0f; else thi = rhi < INFINITY ? phi / rhi : 0.0f;
-            const uint32_t qa = cos_bucket(__builtin_fmaxf(tlo, -1.0f)), qb = cos_bucket(__builtin_fminf(thi, 1.0f));
-            klo = (sh << 7) | (qa > 0 ? qa - 1 : 0u);
-            khi = (sh << 7) | min(qb + 1, 127u);
+            const uint32_t qa = cos_bucket(__builtin_fmaxf(tlo - 1e-4f, -1.0f));
+            const uint32_t qb = cos_bucket(__builtin_fminf(thi + 1e-4f, 1.0f));
+            klo = (sh << 7) | qa;
+            khi = (sh << 7) | qb;
         }
         uint2 r = make_uint2(0, 0);
         if (klo <= khi) {
