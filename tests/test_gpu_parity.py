@@ -380,6 +380,42 @@ def test_pruned_estep_on_awkward_data(g, d, fp16):
         parity.check_assignment(X, C, ref[name][0], k1, D1, D2)
 
 
+@pytest.mark.parametrize("d", [4, 8])
+def test_pruned_estep_with_norms_and_cosines_on_key_boundaries(g, d):
+    """Small-integer lattice points scaled by powers of two: norms that are exactly the lower edge of a norm key or
+    shell, cosines exactly on the edge of a cosine bucket, and exact ties everywhere. The window bounds carry only
+    rounding-level slack, so this is where an off-by-one-cell would show: pruned and unpruned runs must agree bit
+    for bit, and with the oracle."""
+    import paper_2503_13089_amd as cc
+
+    rng = np.random.default_rng(91 + d)
+    N, K = 120000, 8704
+    scale = np.exp2(rng.integers(-6, 1, size=(N, 1))).astype(np.float32)
+    X = np.ascontiguousarray(rng.integers(-3, 4, size=(N, d)).astype(np.float32) * scale)
+    distinct = np.unique(X, axis=0)
+    assert len(distinct) >= K
+    C0 = np.ascontiguousarray(distinct[rng.choice(len(distinct), K, replace=False)])
+    k0, _, _, _ = oracle.assign_top2(X, C0)
+    C1, _ = oracle.update(X, k0, C0)
+    Xd = g.dev(X)
+    try:
+        ws = g.workspace(N, d, K)
+        for C in (C0, C1):
+            cc.set_assign_mode(3)
+            ref, Jref = g.gpu_assign(Xd, C)
+            cc.set_assign_mode(0)
+            for _ in range(2):  # cold (guessed windows), then with the codes of the first call as the hint
+                idx, J = g.gpu_assign(Xd, C, ws=ws)
+                assert np.array_equal(idx, ref)
+                assert J == pytest.approx(Jref, rel=1e-12)
+            k1, D1, _, D2 = oracle.assign_top2(X, C)
+            parity.check_assignment(X, C, ref, k1, D1, D2)
+            if C is C0:  # lattice centroids: every distance is exact in fp32, so even the ties must match (lowest index)
+                assert np.array_equal(ref, k1)
+    finally:
+        cc.set_assign_mode(0)
+
+
 @pytest.mark.parametrize("case", ["centroids near the origin", "centroids far out", "one shell apart"])
 def test_cold_estep_when_no_centroid_is_near_the_guess(g, case):
     """The first E-step on a workspace without codes guesses where each vector's neighbours are (a window around its
