@@ -125,7 +125,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
     // ntiles is a multiple of ST (padding rows carry ||c||^2 = +inf), so every stage is whole
     const float4* P4 = reinterpret_cast<const float4*>(packed);
     // Stages to score: the whole packed codebook, or the runs of this workgroup's 512-vector tile.
-    const uint2* wl = WINDOWED ? windows + size_t((blockIdx.x * (4 * 32 * VT)) / 512) * kWinStride : nullptr;
+    const uint2* wl = WINDOWED ? windows + size_t((blockIdx.x * (4 * 32 * VT)) / kWinTile) * kWinStride : nullptr;
     const uint32_t nruns = WINDOWED ? wl[0].x : 1u;
     uint32_t run = 0;
     uint2 cur_run = WINDOWED ? wl[1] : make_uint2(0, ntiles);  // [first tile, end tile)
@@ -291,8 +291,9 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
     hipLaunchKernelGGL(pack_codebook_kernel<D>, dim3(uint32_t((packed_floats + kThreads - 1) / kThreads)),
                        dim3(kThreads), 0, s, e.pack_rows, e.K, e.packed_tiles, static_cast<float*>(e.packed), w.hdr, e.gate,
                        e.pack_perm);
-    const uint32_t per_block = 4 * 32 * VT;
-    const auto kernel = e.windows != nullptr ? assign_mfma_kernel<D, VT, int(kStageTiles), GT, true>
+    constexpr int VTW = VT * 128 > int(kWinTile) ? int(kWinTile) / 128 : VT;
+    const uint32_t per_block = 4 * 32 * (e.windows != nullptr ? VTW : VT);
+    const auto kernel = e.windows != nullptr ? assign_mfma_kernel<D, VTW, int(kStageTiles), GT, true>
                                              : assign_mfma_kernel<D, VT, ST, GT, false>;
     hipLaunchKernelGGL(kernel, dim3((e.N + per_block - 1) / per_block), dim3(kThreads), 0, s,
                        e.X, e.N, e.rows, e.K, static_cast<const float*>(e.packed), e.packed_tiles, e.idx, w.dmin, w.hdr,

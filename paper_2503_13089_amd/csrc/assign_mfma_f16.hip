@@ -227,7 +227,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_f16_kernel(
 
     const float4* P4 = reinterpret_cast<const float4*>(packed);
     // Stages to score: the whole packed codebook, or the runs of this workgroup's 512-vector tile.
-    const uint2* wl = WINDOWED ? windows + size_t((blockIdx.x * (4 * 32 * VT)) / 512) * kWinStride : nullptr;
+    const uint2* wl = WINDOWED ? windows + size_t((blockIdx.x * (4 * 32 * VT)) / kWinTile) * kWinStride : nullptr;
     const uint32_t nruns = WINDOWED ? wl[0].x : 1u;
     uint32_t run = 0;
     uint2 cur_run = WINDOWED ? wl[1] : make_uint2(0, ntiles);  // [first tile, end tile)
@@ -426,8 +426,10 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
     hipLaunchKernelGGL(pack_codebook_f16_kernel<D>, dim3((e.packed_tiles * 64 + kThreads - 1) / kThreads),
                        dim3(kThreads), 0, s, e.pack_rows, e.K, e.packed_tiles, static_cast<char*>(e.packed), w.hdr, e.gate,
                        e.pack_perm);
-    const uint32_t per_block = 4 * 32 * VT;
-    const auto kernel = e.windows != nullptr ? assign_mfma_f16_kernel<D, VT, int(kStageTiles), GT_WINDOWED, true>
+    // a windowed workgroup scores the vectors of one window list (or a part of them)
+    constexpr int VTW = VT * 128 > int(kWinTile) ? int(kWinTile) / 128 : VT;
+    const uint32_t per_block = 4 * 32 * (e.windows != nullptr ? VTW : VT);
+    const auto kernel = e.windows != nullptr ? assign_mfma_f16_kernel<D, VTW, int(kStageTiles), GT_WINDOWED, true>
                         : (e.K >= 32768  ? assign_mfma_f16_kernel<D, VT, ST, GT_WIDE, false>
                                          : assign_mfma_f16_kernel<D, VT, ST, GT, false>);
     hipLaunchKernelGGL(kernel, dim3((e.N + per_block - 1) / per_block), dim3(kThreads),

@@ -88,6 +88,10 @@ constexpr uint32_t kStageTilesMax = 8;    // the packed codebook is padded to wh
 constexpr uint32_t kStageTiles = 4;       // tiles per LDS stage of the matrix-core E-step kernels
 constexpr uint32_t kWinQuad = kTileCentroids;  // window lists count runs in tiles = 32 positions; runs never share a stage
 constexpr int kWinSlots = 32;             // most runs a window list can hold (one per norm shell)
+// Vectors (neighbours in the norm order) that share one window list: what one workgroup of the windowed kernels
+// scores (4 waves x 4 tiles of 32). Half of that gives tighter hulls but halves the work per staged codebook tile:
+// measured 29.0 -> 31.9 ms per cfg3 fit.
+constexpr uint32_t kWinTile = 512;
 constexpr int kWinStride = kWinSlots + 1; // uint2 entries per 512-vector tile: (count, -), then the runs
 constexpr uint32_t kBucketClusters = 64;  // M-step by buckets: consecutive clusters summed by one workgroup
 constexpr uint32_t kMaxBuckets = 1024;    // so K <= 65536 for that path
@@ -140,7 +144,7 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d_caller, uint32_t K)
     w.key_starts = reinterpret_cast<uint32_t*>(take(size_t(65537) * 4));
     // histogram rows + 256 totals, for the vectors' sort and for the centroids' (whose blocks are smaller)
     w.sort_hist = reinterpret_cast<uint32_t*>(take(std::max(sort_hist_bytes(N), sort_hist_bytes(K))));
-    w.windows = reinterpret_cast<uint2*>(take((size_t(N) / 512 + 1) * kWinStride * 8));
+    w.windows = reinterpret_cast<uint2*>(take((size_t(N) / kWinTile + 1) * kWinStride * 8));
     if (w.padded) {
         w.xpad = reinterpret_cast<float*>(take(size_t(N) * d * 4));
         w.cpad = reinterpret_cast<float*>(take(size_t(K) * d * 4));

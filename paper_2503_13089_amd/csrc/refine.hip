@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kThreads) void refine_kernel(const float* __restric
         const uint32_t i = refine_list[e];
         float x[D];
         load_row<D>(X + size_t(i) * D, x);
-        const uint2* wl = windows != nullptr ? windows + size_t(i / 512) * kWinStride : nullptr;
+        const uint2* wl = windows != nullptr ? windows + size_t(i / kWinTile) * kWinStride : nullptr;
         const uint32_t nruns = wl != nullptr ? wl[0].x : 1u;
         unsigned long long best = ~0ull;
         for (uint32_t r = 0; r < nruns; ++r) {

@@ -246,8 +246,8 @@ __global__ __launch_bounds__(kThreads) void window_kernel(const float* __restric
     // [e.x - u, e.x + u] (the hull of a union of intervals contains the union, so this only ever adds candidates)
     float nlo = INFINITY, nhi = 0.0f, plo = INFINITY, phi = -INFINITY;
 #pragma unroll
-    for (int v = 0; v < 2; ++v) {
-        const uint32_t p = blockIdx.x * 512 + v * kThreads + threadIdx.x;
+    for (int v = 0; v < int(kWinTile) / kThreads; ++v) {
+        const uint32_t p = blockIdx.x * kWinTile + v * kThreads + threadIdx.x;
         if (p < N) {
             float x[D];
             load_row<D>(Xs + size_t(p) * D, x);
@@ -520,9 +520,9 @@ hipError_t launch_sort_centroids(const float* C, uint32_t d, uint32_t K, const W
 template <int D>
 static void windows_t(const float* C, uint32_t N, uint32_t K, const Workspace& w, float guess, hipStream_t s)
 {
-    hipLaunchKernelGGL(window_kernel<D>, dim3((N + 511) / 512), dim3(kThreads), 0, s, w.xsorted, N, C, K, w.idx_sorted,
+    hipLaunchKernelGGL(window_kernel<D>, dim3((N + kWinTile - 1) / kWinTile), dim3(kThreads), 0, s, w.xsorted, N, C, K, w.idx_sorted,
                        w.persist, w.key_starts, guess, w.hdr, w.windows);
-    hipLaunchKernelGGL(window_stats_kernel, dim3(32), dim3(1024), 0, s, w.windows, (N + 511) / 512, K, w.hdr,
+    hipLaunchKernelGGL(window_stats_kernel, dim3(32), dim3(1024), 0, s, w.windows, (N + kWinTile - 1) / kWinTile, K, w.hdr,
                        guess > 0.0f ? 1 : 0);
 }
 
