@@ -26,6 +26,9 @@
  *     that case (except for CC_ERR_HIP, where a launch itself failed).
  *   - Same inputs give the same output bits on every run (the cluster sums are accumulated in
  *     integer fixed point, so they do not depend on scheduling order).
+ *   - Every input value must be finite. The library checks: an Inf or NaN among the vectors sets
+ *     cc_stats::nonfinite_inputs, such a component is left out of every cluster sum (the other components
+ *     and the cluster size still count), and the code of its vector is unspecified (but below K).
  *
  * Readings of what the paper leaves open
  *   - E-step ties: the lowest centroid index wins among exactly equal distances; when two distances
@@ -54,6 +57,68 @@ typedef enum cc_status {
     CC_ERR_HIP = -6        /* the HIP runtime reported an error at launch */
 } cc_status;
 
+/*
+ * Per-call options of the *_ex entry points (every other entry point behaves like its *_ex form with options =
+ * NULL). Zero the struct, set struct_bytes = sizeof(cc_options), then the fields wanted. Options belong to one
+ * call: nothing in the library is process-wide, so concurrent callers cannot change each other's kernels.
+ *
+ * assign_mode selects the E-step kernel (Section 3.1, the argmin over the centroids); every choice returns the same
+ * codes, they differ in speed and exist for tests and profiling:
+ *   CC_ASSIGN_AUTO        for K >= 128 the matrix cores - the fp16 MFMA with the centroids split into fp16 parts
+ *                         (exact products, fp32 accumulation) when every input is an fp16 number, the fp32 MFMA
+ *                         otherwise, both with a rounding guard band + direct-form refinement - and the direct form
+ *                         on the vector ALUs for smaller K. For K >= 8192 (inside cc_kmeans_fit already for K >= 256
+ *                         when N >= 2^19 and iters >= 5, where the ordering is paid once) vectors and centroids are
+ *                         additionally visited in the order of a (norm, cosine to a fixed direction) key and a
+ *                         workgroup skips the parts of the codebook that the triangle inequality rules out: a centroid
+ *                         whose norm, or whose projection on the fixed direction, differs from a vector's by more than
+ *                         a known upper bound of its nearest distance cannot be the nearest. The previous E-step's
+ *                         codes on the same workspace - or a bootstrap pass over a guessed neighbourhood of each
+ *                         vector - provide that bound; a poor bound costs time, never correctness.
+ *   CC_ASSIGN_DIRECT      direct-form vector-ALU kernel only.
+ *   CC_ASSIGN_MFMA_F32    fp32 MFMA kernel always, whole codebook.
+ *   CC_ASSIGN_AUTO_WHOLE  as CC_ASSIGN_AUTO but always the whole codebook, and every M-step recomputed.
+ *
+ * profile (may be NULL): a cc_profile in which the call records the device time of its own kernels.
+ */
+typedef enum cc_assign_mode {
+    CC_ASSIGN_AUTO = 0, CC_ASSIGN_DIRECT = 1, CC_ASSIGN_MFMA_F32 = 2, CC_ASSIGN_AUTO_WHOLE = 3
+} cc_assign_mode;
+
+typedef struct cc_profile cc_profile;   /* opaque host object */
+
+typedef struct cc_options {
+    uint32_t struct_bytes;  /* sizeof(cc_options) */
+    int32_t assign_mode;    /* a cc_assign_mode */
+    cc_profile *profile;    /* NULL, or see cc_profile_create */
+} cc_options;
+
+/*
+ * Device time of the library's kernels, measured with HIP events recorded on the stream of the call that the
+ * profile is passed to (for benchmarks: the time of the dominant kernel inside a whole fit). Each launch - or short
+ * run of launches - named by a slot takes one record:
+ *   CC_PROF_ESTEP_F16     the scoring kernel of the E-step on the fp16 matrix cores, one record per launch
+ *   CC_PROF_ESTEP_F32     the same on the fp32 matrix cores (both are enqueued; the one whose inputs do not
+ *                         qualify returns at once)
+ *   CC_PROF_ESTEP_DIRECT  the direct-form E-step kernel
+ *   CC_PROF_REFINE        re-decision of the guard-band vectors
+ *   CC_PROF_MSTEP         all kernels of one M-step
+ *   CC_PROF_ORDER         key ordering of vectors / centroids, window lists
+ * cc_profile_create allocates (host memory and max_records pairs of events) and is the only profile call that does;
+ * slot_mask selects the slots to record (bit s = slot s) - an event pair costs a few microseconds of stream time.
+ * cc_profile_read waits for the recorded events (it synchronises with the work they bracket), adds up ms[slot]
+ * (milliseconds) and launches[slot] (both host arrays of CC_PROF_SLOTS entries), reports in *dropped (host, may be
+ * NULL) how many records did not fit, and empties the profile. Not for use on a stream under graph capture, and
+ * one profile serves one stream at a time.
+ */
+typedef enum cc_profile_slot {
+    CC_PROF_ESTEP_F16 = 0, CC_PROF_ESTEP_F32 = 1, CC_PROF_ESTEP_DIRECT = 2, CC_PROF_REFINE = 3, CC_PROF_MSTEP = 4,
+    CC_PROF_ORDER = 5, CC_PROF_SLOTS = 6
+} cc_profile_slot;
+int cc_profile_create(uint32_t max_records, uint32_t slot_mask, cc_profile **out);
+int cc_profile_read(cc_profile *profile, double *ms, uint32_t *launches, uint32_t *dropped);
+void cc_profile_destroy(cc_profile *profile);
+
 /* Host-only query: bytes of device workspace that cc_kmeans_fit / cc_assign / cc_lloyd_iter / cc_update
  * need for this problem size (about 12*N*d + 54*N bytes: an ordered copy of the vectors, room for two
  * copies grouped by cluster for the M-step, permutations and sort buffers, with d rounded up to 4, 8 or 16; plus one
@@ -76,6 +141,9 @@ size_t cc_workspace_bytes(uint64_t N, uint32_t d, uint32_t K);
 int cc_kmeans_fit(const float *vectors, uint64_t N, uint32_t d, uint32_t K, int32_t iters,
                   const float *init_centroids, float *centroids, uint32_t *idx, double *inertia,
                   void *workspace, size_t workspace_bytes, void *stream);
+int cc_kmeans_fit_ex(const float *vectors, uint64_t N, uint32_t d, uint32_t K, int32_t iters,
+                     const float *init_centroids, float *centroids, uint32_t *idx, double *inertia,
+                     void *workspace, size_t workspace_bytes, void *stream, const cc_options *options);
 
 /*
  * E-step alone (Section 3.1): idx_i = argmin_k ||w_i - c_k||^2, and optionally the objective
@@ -83,6 +151,9 @@ int cc_kmeans_fit(const float *vectors, uint64_t N, uint32_t d, uint32_t K, int3
  */
 int cc_assign(const float *vectors, uint64_t N, uint32_t d, const float *centroids, uint32_t K,
               uint32_t *idx, double *inertia, void *workspace, size_t workspace_bytes, void *stream);
+int cc_assign_ex(const float *vectors, uint64_t N, uint32_t d, const float *centroids, uint32_t K,
+                 uint32_t *idx, double *inertia, void *workspace, size_t workspace_bytes, void *stream,
+                 const cc_options *options);
 
 /*
  * One Lloyd iteration (Section 3.1: an E-step followed by an M-step), the unit the fit repeats:
@@ -95,6 +166,9 @@ int cc_assign(const float *vectors, uint64_t N, uint32_t d, const float *centroi
  */
 int cc_lloyd_iter(const float *vectors, uint64_t N, uint32_t d, float *centroids, uint32_t K, uint32_t *idx,
                   double *inertia, uint32_t *counts, void *workspace, size_t workspace_bytes, void *stream);
+int cc_lloyd_iter_ex(const float *vectors, uint64_t N, uint32_t d, float *centroids, uint32_t K, uint32_t *idx,
+                     double *inertia, uint32_t *counts, void *workspace, size_t workspace_bytes, void *stream,
+                     const cc_options *options);
 
 /*
  * M-step alone (Section 3.1): centroids_k = mean of the vectors with idx_i == k; a cluster without
@@ -105,6 +179,9 @@ int cc_lloyd_iter(const float *vectors, uint64_t N, uint32_t d, float *centroids
 int cc_update(const float *vectors, uint64_t N, uint32_t d, const uint32_t *idx,
               const float *prev_centroids, uint32_t K, float *centroids, uint32_t *counts,
               void *workspace, size_t workspace_bytes, void *stream);
+int cc_update_ex(const float *vectors, uint64_t N, uint32_t d, const uint32_t *idx,
+                 const float *prev_centroids, uint32_t K, float *centroids, uint32_t *counts,
+                 void *workspace, size_t workspace_bytes, void *stream, const cc_options *options);
 
 /*
  * Reconstruction (Section 3.1; the gather `codebook[code]` of the paper's layer listing):
@@ -130,6 +207,8 @@ typedef struct cc_stats {
     int32_t  fixed_point_exp;  /* e: cluster sums are held as round(x * 2^e) in int64 */
     uint32_t fp16_inputs;      /* 1 if the vectors of the last call qualified for the fp16 matrix-core kernels
                                   (|x| < 2^15 and every |x| >= 2^-14 an fp16 number), else 0 */
+    uint32_t nonfinite_inputs; /* 1 if some input of the last call was Inf or NaN (a violated precondition) */
+    uint32_t reserved;
 } cc_stats;
 int cc_read_stats(const void *workspace, size_t workspace_bytes, cc_stats *host_out, void *stream);
 
@@ -262,7 +341,10 @@ int cc_layer_compress(const void *weight, int weight_dtype, uint32_t out_feature
 
 /* ------------------------------------------------------------------------------------------------
  * Uniformly quantised codebook (the paper's inference-only variant: "#Bits for Codebook" 8 and 4 in its
- * throughput and perplexity tables; the grid is the symmetric uniform one of Section 2).
+ * throughput and perplexity tables; the grid is the symmetric uniform one of Section 2, with one deviation:
+ * Section 2 prints 2^bits - 1 under the scale, which together with its own clamp to [-2^(bits-1), 2^(bits-1) - 1]
+ * would clip every entry above half the range, so the scale here divides by 2^(bits-1) - 1 and the clamp is a
+ * safeguard only).
  * One scale per codebook: s = max|c| / (2^(bits-1) - 1), q = clamp(round_to_nearest_even(c / s),
  * -2^(bits-1), 2^(bits-1) - 1), both in fp32; the dequantised entry is q * s (fp32) rounded to the layer's
  * 16-bit format. Storage: bits = 8: int8 [K * g]; bits = 4: two's-complement nibbles, element e in byte
@@ -293,21 +375,6 @@ size_t cc_layer_forward_q_workspace_bytes(uint64_t M, uint32_t in_features, uint
 int cc_layer_forward_q(const void *x, uint64_t M, const void *qbook, int bits, const float *scale, uint32_t K,
                        uint32_t g, const uint16_t *codes, uint32_t in_features, uint32_t out_features,
                        const void *bias, void *y, int dtype, void *workspace, size_t workspace_bytes, void *stream);
-
-/* Selects the E-step kernel. 0 = automatic (default): for K >= 128 the matrix cores, with the fp16 MFMA
- * (centroids split into three fp16 parts, exact products) when every input is an fp16 number and
- * the fp32 MFMA otherwise, both with guard band + direct-form refinement; direct form for small K;
- * for K >= 8192 (inside cc_kmeans_fit already for K >= 256, when N >= 2^19 and iters >= 5, where the
- * ordering is paid once) vectors and centroids are additionally visited in the order of a (norm, cosine to a
- * fixed direction) key and a workgroup skips the parts of the codebook that the triangle inequality
- * rules out (an exact shortcut: a centroid whose norm, or whose projection on the fixed direction,
- * differs from a vector's by more than a known upper bound of its nearest distance cannot be the
- * nearest; the previous call's codes on the same workspace - or a bootstrap pass over a guessed
- * neighbourhood of each vector - provide that bound, and a poor bound costs time, never correctness).
- * 1 = direct-form vector-ALU kernel only. 2 = fp32 MFMA kernel always, whole codebook.
- * 3 = as 0 but always the whole codebook. Process-wide; for tests and profiling.
- * Returns the previous value, or CC_ERR_SHAPE for an unknown mode. */
-int cc_set_assign_mode(int mode);
 
 /* Thread-local description of the last error returned on this thread (host pointer, static storage). */
 const char *cc_last_error(void);

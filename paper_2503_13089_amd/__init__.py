@@ -7,6 +7,8 @@ fallback; calling anything without the built library (or without a GPU) raises.
 from .driver import CompressedLayer, compress_model  # noqa: F401
 from .binding import (  # noqa: F401
     CCError,
+    PROFILE_SLOTS,
+    Profile,
     Stats,
     assign,
     codebook_quantize,

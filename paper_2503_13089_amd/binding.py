@@ -14,7 +14,9 @@ _lib = None
 
 EXPORTS = (
     "cc_workspace_bytes", "cc_kmeans_fit", "cc_assign", "cc_lloyd_iter", "cc_update", "cc_decode",
-    "cc_read_stats", "cc_set_assign_mode", "cc_last_error", "cc_version",
+    "cc_kmeans_fit_ex", "cc_assign_ex", "cc_lloyd_iter_ex", "cc_update_ex",
+    "cc_profile_create", "cc_profile_read", "cc_profile_destroy",
+    "cc_read_stats", "cc_last_error", "cc_version",
     "cc_layer_deficiency", "cc_layer_num_codes", "cc_layer_vectors", "cc_layer_pack", "cc_layer_weight",
     "cc_layer_codebook_grad", "cc_layer_forward", "cc_layer_forward_workspace_bytes",
     "cc_layer_forward_tune_workspace_bytes", "cc_layer_forward_tune",
@@ -34,7 +36,14 @@ class _CStats(ctypes.Structure):
     _fields_ = [("refined_vectors", ctypes.c_uint64), ("skipped_vectors", ctypes.c_uint64),
                 ("assign_calls", ctypes.c_uint64), ("scored_stages", ctypes.c_uint64),
                 ("total_stages", ctypes.c_uint64), ("fixed_point_exp", ctypes.c_int32),
-                ("fp16_inputs", ctypes.c_uint32)]
+                ("fp16_inputs", ctypes.c_uint32), ("nonfinite_inputs", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
+class _COptions(ctypes.Structure):
+    _fields_ = [("struct_bytes", ctypes.c_uint32), ("assign_mode", ctypes.c_int32), ("profile", ctypes.c_void_p)]
+
+
+PROFILE_SLOTS = ("estep_f16", "estep_f32", "estep_direct", "refine", "mstep", "order")
 
 
 @dataclass
@@ -46,6 +55,7 @@ class Stats:
     total_stages: int
     fixed_point_exp: int
     fp16_inputs: int = 0
+    nonfinite_inputs: int = 0
 
 
 def lib_path() -> str:
@@ -81,8 +91,21 @@ def load_library():
     lib.cc_decode.restype = ctypes.c_int
     lib.cc_read_stats.argtypes = [vp, sz, ctypes.POINTER(_CStats), vp]
     lib.cc_read_stats.restype = ctypes.c_int
-    lib.cc_set_assign_mode.argtypes = [ctypes.c_int]
-    lib.cc_set_assign_mode.restype = ctypes.c_int
+    op = ctypes.POINTER(_COptions)
+    lib.cc_kmeans_fit_ex.argtypes = lib.cc_kmeans_fit.argtypes + [op]
+    lib.cc_kmeans_fit_ex.restype = ctypes.c_int
+    lib.cc_assign_ex.argtypes = lib.cc_assign.argtypes + [op]
+    lib.cc_assign_ex.restype = ctypes.c_int
+    lib.cc_lloyd_iter_ex.argtypes = lib.cc_lloyd_iter.argtypes + [op]
+    lib.cc_lloyd_iter_ex.restype = ctypes.c_int
+    lib.cc_update_ex.argtypes = lib.cc_update.argtypes + [op]
+    lib.cc_update_ex.restype = ctypes.c_int
+    lib.cc_profile_create.argtypes = [u32, u32, ctypes.POINTER(vp)]
+    lib.cc_profile_create.restype = ctypes.c_int
+    lib.cc_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(u32), ctypes.POINTER(u32)]
+    lib.cc_profile_read.restype = ctypes.c_int
+    lib.cc_profile_destroy.argtypes = [vp]
+    lib.cc_profile_destroy.restype = None
     lib.cc_layer_deficiency.argtypes = [u32, u32]
     lib.cc_layer_deficiency.restype = u32
     lib.cc_layer_num_codes.argtypes = [u64, u64, u32]
@@ -172,56 +195,111 @@ def _idx_dtype():
     return torch.uint32
 
 
+# What the *_ex entry points are called with when a caller of this module does not say: cc_options are per call in
+# the library; this default lives here, in the binding, so that a test can run unchanged code under each E-step kernel.
+_default_assign_mode = 0
+
+
+def set_assign_mode(mode: int) -> int:
+    """Sets the cc_options::assign_mode that calls through this module pass from now on; returns the previous one."""
+    global _default_assign_mode
+    if mode not in (0, 1, 2, 3):
+        raise CCError(-2, f"unknown assign mode {mode}")
+    prev, _default_assign_mode = _default_assign_mode, mode
+    return prev
+
+
+class Profile:
+    """cc_profile: device time of the library's kernels inside the calls it is passed to (`profile=`)."""
+
+    def __init__(self, max_records: int = 256, slots=PROFILE_SLOTS):
+        mask = 0
+        for name in slots:
+            mask |= 1 << PROFILE_SLOTS.index(name)
+        self._h = ctypes.c_void_p()
+        _check(load_library().cc_profile_create(max_records, mask, ctypes.byref(self._h)))
+
+    def read(self):
+        """Waits for the recorded kernels; returns ({slot: ms}, {slot: launches}, dropped) and empties the profile."""
+        n = len(PROFILE_SLOTS)
+        ms, launches, dropped = (ctypes.c_double * n)(), (ctypes.c_uint32 * n)(), ctypes.c_uint32()
+        _check(load_library().cc_profile_read(self._h, ms, launches, ctypes.byref(dropped)))
+        return ({k: float(ms[i]) for i, k in enumerate(PROFILE_SLOTS)},
+                {k: int(launches[i]) for i, k in enumerate(PROFILE_SLOTS)}, int(dropped.value))
+
+    def close(self):
+        if self._h:
+            load_library().cc_profile_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _options(assign_mode, profile):
+    o = _COptions()
+    o.struct_bytes = ctypes.sizeof(_COptions)
+    o.assign_mode = _default_assign_mode if assign_mode is None else assign_mode
+    o.profile = profile._h if profile is not None else None
+    return ctypes.byref(o)
+
+
 def workspace_bytes(N: int, d: int, K: int) -> int:
     return int(load_library().cc_workspace_bytes(N, d, K))
 
 
-def kmeans_fit(vectors, K: int, iters: int, init_centroids, centroids, idx, inertia, workspace) -> None:
-    """cc_kmeans_fit on the current stream. vectors [N,d] f32, init/centroids [K,d] f32, idx [N] uint32,
+def kmeans_fit(vectors, K: int, iters: int, init_centroids, centroids, idx, inertia, workspace, assign_mode=None,
+               profile=None) -> None:
+    """cc_kmeans_fit_ex on the current stream. vectors [N,d] f32, init/centroids [K,d] f32, idx [N] uint32,
     inertia [1] f64 or None, workspace uint8 [>= workspace_bytes]. Asynchronous."""
     import torch
 
     N, d = vectors.shape
     lib = load_library()
-    _check(lib.cc_kmeans_fit(_ptr(vectors, torch.float32, "vectors"), N, d, K, iters,
+    _check(lib.cc_kmeans_fit_ex(_ptr(vectors, torch.float32, "vectors"), N, d, K, iters,
                              _ptr(init_centroids, torch.float32, "init_centroids"),
                              _ptr(centroids, torch.float32, "centroids"), _ptr(idx, _idx_dtype(), "idx"),
                              _ptr(inertia, torch.float64, "inertia"), _ptr(workspace, torch.uint8, "workspace"),
-                             workspace.numel(), _stream()))
+                             workspace.numel(), _stream(), _options(assign_mode, profile)))
 
 
-def assign(vectors, centroids, idx, inertia, workspace) -> None:
+def assign(vectors, centroids, idx, inertia, workspace, assign_mode=None, profile=None) -> None:
     import torch
 
     N, d = vectors.shape
     K = centroids.shape[0]
-    _check(load_library().cc_assign(_ptr(vectors, torch.float32, "vectors"), N, d,
+    _check(load_library().cc_assign_ex(_ptr(vectors, torch.float32, "vectors"), N, d,
                                     _ptr(centroids, torch.float32, "centroids"), K, _ptr(idx, _idx_dtype(), "idx"),
                                     _ptr(inertia, torch.float64, "inertia"), _ptr(workspace, torch.uint8, "workspace"),
-                                    workspace.numel(), _stream()))
+                                    workspace.numel(), _stream(), _options(assign_mode, profile)))
 
 
-def lloyd_iter(vectors, centroids, idx, inertia, counts, workspace) -> None:
-    """cc_lloyd_iter: one E-step + M-step; `centroids` is updated in place."""
+def lloyd_iter(vectors, centroids, idx, inertia, counts, workspace, assign_mode=None, profile=None) -> None:
+    """cc_lloyd_iter_ex: one E-step + M-step; `centroids` is updated in place."""
     import torch
 
     N, d = vectors.shape
     K = centroids.shape[0]
-    _check(load_library().cc_lloyd_iter(_ptr(vectors, torch.float32, "vectors"), N, d,
+    _check(load_library().cc_lloyd_iter_ex(_ptr(vectors, torch.float32, "vectors"), N, d,
                                         _ptr(centroids, torch.float32, "centroids"), K, _ptr(idx, _idx_dtype(), "idx"),
                                         _ptr(inertia, torch.float64, "inertia"), _ptr(counts, _idx_dtype(), "counts"),
-                                        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
+                                        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(),
+                                        _options(assign_mode, profile)))
 
 
-def update(vectors, idx, prev_centroids, centroids, counts, workspace) -> None:
+def update(vectors, idx, prev_centroids, centroids, counts, workspace, profile=None) -> None:
     import torch
 
     N, d = vectors.shape
     K = prev_centroids.shape[0]
-    _check(load_library().cc_update(_ptr(vectors, torch.float32, "vectors"), N, d, _ptr(idx, _idx_dtype(), "idx"),
+    _check(load_library().cc_update_ex(_ptr(vectors, torch.float32, "vectors"), N, d, _ptr(idx, _idx_dtype(), "idx"),
                                     _ptr(prev_centroids, torch.float32, "prev_centroids"), K,
                                     _ptr(centroids, torch.float32, "centroids"), _ptr(counts, _idx_dtype(), "counts"),
-                                    _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
+                                    _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(),
+                                    _options(None, profile)))
 
 
 def decode(centroids, idx, out) -> None:
@@ -240,14 +318,7 @@ def read_stats(workspace) -> Stats:
     _check(load_library().cc_read_stats(_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
                                         ctypes.byref(st), _stream()))
     return Stats(int(st.refined_vectors), int(st.skipped_vectors), int(st.assign_calls), int(st.scored_stages),
-                 int(st.total_stages), int(st.fixed_point_exp), int(st.fp16_inputs))
-
-
-def set_assign_mode(mode: int) -> int:
-    rc = load_library().cc_set_assign_mode(mode)
-    if rc < 0:
-        raise CCError(rc, last_error())
-    return rc
+                 int(st.total_stages), int(st.fixed_point_exp), int(st.fp16_inputs), int(st.nonfinite_inputs))
 
 
 # ---- the compressed linear layer ---------------------------------------------------------------------

@@ -1,9 +1,10 @@
 // C ABI of libcluscomp: argument validation on the host, then the kernel sequence of each call.
 // See include/cluscomp.h for the contract of every entry point.
-#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <new>
+#include <vector>
 
 #include "../../include/cluscomp.h"
 #include "common.h"
@@ -11,7 +12,6 @@
 namespace {
 
 thread_local char g_err[256] = "";
-std::atomic<int> g_assign_mode{0};
 
 int fail(int code, const char* fmt, ...)
 {
@@ -65,19 +65,25 @@ int check_workspace(void* ws, size_t ws_bytes, uint64_t N, uint32_t d, uint32_t 
         if (e_ != hipSuccess) return hip_fail(e_, what); \
     } while (0)
 
-bool use_matrix_cores(uint32_t K)
+// What one call runs with: the E-step selection (cc_options::assign_mode) and, if the caller asked for device
+// times, where they are recorded.
+struct Ctx {
+    int mode = CC_ASSIGN_AUTO;
+    cc::Profile* prof = nullptr;
+};
+
+bool use_matrix_cores(const Ctx& cx, uint32_t K)
 {
-    const int mode = g_assign_mode.load();
-    return mode == 2 || ((mode == 0 || mode == 3) && K >= 128);
+    return cx.mode == CC_ASSIGN_MFMA_F32 || ((cx.mode == CC_ASSIGN_AUTO || cx.mode == CC_ASSIGN_AUTO_WHOLE) && K >= 128);
 }
 
 // Norm-window pruning: only in the automatic mode and only where the ordering overhead can pay off. A single
 // E-step pays for ordering the vectors by itself, so it needs a large codebook; a fit orders once and keeps the
 // integer cluster sums up to date across its iterations, which pays from a few hundred centroids on once there
 // are enough vectors to fill the chip (measured break-even: about 3e5 vectors, 5 iterations).
-bool use_pruning(uint64_t N, uint32_t K, int32_t iters)
+bool use_pruning(const Ctx& cx, uint64_t N, uint32_t K, int32_t iters)
 {
-    if (g_assign_mode.load() != 0) return false;
+    if (cx.mode != CC_ASSIGN_AUTO) return false;
     return K >= 8192 || (K >= 256 && N >= (1u << 19) && iters >= 5);
 }
 
@@ -95,22 +101,29 @@ float guess_width(uint32_t K, uint32_t d)
 // (launch_sort_vectors) and the codes are left in norm order in w.idx_sorted.
 // have_hint = true: the caller knows that this workspace holds the codes of a previous E-step of the same
 // call (later iterations of a fit), so the bootstrap pass need not even be enqueued.
-int run_assign_matrix(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
+int run_assign_matrix(const Ctx& cx, const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
                       const cc::Workspace& w, bool accumulate, bool pruned, bool have_hint, hipStream_t s,
                       bool track_changes = false)
 {
-    const bool both = g_assign_mode.load() != 2;  // fp16 and fp32 variants enqueued, the device gate picks one
+    const bool both = cx.mode != CC_ASSIGN_MFMA_F32;  // fp16 and fp32 variants enqueued, the device gate picks one
     cc::EStep e{};
+    e.profile = cx.prof;
     e.X = pruned ? w.xsorted : X;
     e.N = N;
     e.idx = pruned ? w.idx_sorted : idx;
     if (pruned) {
-        CC_TRY_HIP(cc::launch_sort_centroids(C, d, K, w, s), "assign (centroid norm order)");
+        {
+            cc::ProfileScope order_scope(cx.prof, cc::kProfOrder, s);
+            CC_TRY_HIP(cc::launch_sort_centroids(C, d, K, w, s), "assign (centroid norm order)");
+        }
         // Bootstrap (only runs on the device when the workspace holds no hint): the nearest centroid inside a
         // guessed window around each vector's own norm and projection. Its codes are only the upper bounds that
         // size the real windows below, so a poor guess costs time, never correctness.
         if (!have_hint) {
-            CC_TRY_HIP(cc::launch_windows(C, N, d, K, w, guess_width(K, d), s), "assign (guessed windows)");
+            {
+                cc::ProfileScope order_scope(cx.prof, cc::kProfOrder, s);
+                CC_TRY_HIP(cc::launch_windows(C, N, d, K, w, guess_width(K, d), s), "assign (guessed windows)");
+            }
             cc::EStep b = e;
             b.pack_rows = C; b.pack_perm = w.cperm; b.rows = w.csorted; b.row_ids = w.cperm; b.K = K;
             b.packed = w.packed; b.packed_tiles = w.packed_tiles; b.windows = w.windows;
@@ -120,6 +133,7 @@ int run_assign_matrix(const float* X, uint32_t N, uint32_t d, const float* C, ui
             b.gate = cc::kGateIfNotF16 | cc::kGateNoHint;
             CC_TRY_HIP(cc::launch_assign_mfma_f32(b, d, w, s), "assign (bootstrap, fp32 matrix cores)");
         }
+        cc::ProfileScope order_scope(cx.prof, cc::kProfOrder, s);
         CC_TRY_HIP(cc::launch_windows(C, N, d, K, w, 0.0f, s), "assign (norm windows)");
     }
     e.pack_rows = C; e.pack_perm = pruned ? w.cperm : nullptr;
@@ -138,20 +152,23 @@ int run_assign_matrix(const float* X, uint32_t N, uint32_t d, const float* C, ui
         e.gate = cc::kGateAlways;
         CC_TRY_HIP(cc::launch_assign_mfma_f32(e, d, w, s), "assign (fp32 matrix cores)");
     }
-    CC_TRY_HIP(cc::launch_refine(e.X, N, d, C, K, e.idx, w, accumulate, pruned, s), "assign (refinement)");
+    {
+        cc::ProfileScope refine_scope(cx.prof, cc::kProfRefine, s);
+        CC_TRY_HIP(cc::launch_refine(e.X, N, d, C, K, e.idx, w, accumulate, pruned, s), "assign (refinement)");
+    }
     return CC_OK;
 }
 
 // One E-step pass: idx (and, if inertia != NULL, the objective) for the given centroids.
 // to_user = false leaves norm-ordered codes in the workspace only (intermediate fit iterations).
-int run_assign(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx, double* inertia,
-               const cc::Workspace& w, bool pruned, bool have_hint, hipStream_t s)
+int run_assign(const Ctx& cx, const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
+               double* inertia, const cc::Workspace& w, bool pruned, bool have_hint, hipStream_t s)
 {
-    if (use_matrix_cores(K)) {
-        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, false, pruned, have_hint, s)) return rc;
+    if (use_matrix_cores(cx, K)) {
+        if (int rc = run_assign_matrix(cx, X, N, d, C, K, idx, w, false, pruned, have_hint, s)) return rc;
         if (pruned) CC_TRY_HIP(cc::launch_unpermute(N, idx, w, s), "assign (codes to input order)");
     } else {
-        CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s), "assign (direct form)");
+        CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s, cx.prof), "assign (direct form)");
         CC_TRY_HIP(cc::launch_bump_assign_calls(w.hdr, s), "bookkeeping");
     }
     if (inertia)
@@ -162,11 +179,11 @@ int run_assign(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t 
 // One Lloyd iteration: idx = E-step against C, then C <- M-step(idx) in place. On the matrix-core path
 // the cluster sums are accumulated by the scoring kernel itself (no second pass over the vectors).
 // idx == NULL (only inside the fit loop, pruned path) skips the copy of the codes to input order.
-int run_lloyd_iter(const float* X, uint32_t N, uint32_t d, float* C, uint32_t K, uint32_t* idx, double* inertia,
-                   uint32_t* counts, const cc::Workspace& w, bool pruned, bool have_hint, hipStream_t s,
+int run_lloyd_iter(const Ctx& cx, const float* X, uint32_t N, uint32_t d, float* C, uint32_t K, uint32_t* idx,
+                   double* inertia, uint32_t* counts, const cc::Workspace& w, bool pruned, bool have_hint, hipStream_t s,
                    bool sums_follow = false)
 {
-    if (use_matrix_cores(K)) {
+    if (use_matrix_cores(cx, K)) {
         // sums_follow (inside a fit, pruned path, after an M-step by buckets of the same fit): the workspace holds the
         // integer sums and counts of the codes in w.idx_sorted. The E-step kernel then flags the vectors that leave
         // those codes (and keeps the code they had), so that the M-step can move just these.
@@ -174,17 +191,21 @@ int run_lloyd_iter(const float* X, uint32_t N, uint32_t d, float* C, uint32_t K,
         // bottleneck), so there the M-step groups the vectors by bucket of clusters and sums in LDS instead.
         const bool by_buckets = pruned && w.bucket_ok;
         if (!by_buckets) CC_TRY_HIP(cc::launch_zero_accumulators(w, K, d, nullptr, 0, s), "update (clear)");
-        if (int rc = run_assign_matrix(X, N, d, C, K, idx, w, !by_buckets, pruned, have_hint, s, sums_follow)) return rc;
-        if (by_buckets)
-            CC_TRY_HIP(cc::launch_update_buckets(w.xsorted, N, d, w.idx_sorted, C, K, C, counts, w, true, true, s,
-                                                 sums_follow ? w.idx_prev : nullptr, sums_follow ? w.changed : nullptr),
-                    "update (buckets)");
-        else
-            CC_TRY_HIP(cc::launch_finalize(C, C, counts, K, d, N, w, true, s), "update (means)");
+        if (int rc = run_assign_matrix(cx, X, N, d, C, K, idx, w, !by_buckets, pruned, have_hint, s, sums_follow)) return rc;
+        {
+            cc::ProfileScope mstep_scope(cx.prof, cc::kProfMstep, s);
+            if (by_buckets)
+                CC_TRY_HIP(cc::launch_update_buckets(w.xsorted, N, d, w.idx_sorted, C, K, C, counts, w, true, true, s,
+                                                     sums_follow ? w.idx_prev : nullptr, sums_follow ? w.changed : nullptr),
+                           "update (buckets)");
+            else
+                CC_TRY_HIP(cc::launch_finalize(C, C, counts, K, d, N, w, true, s), "update (means)");
+        }
         if (pruned && idx != nullptr) CC_TRY_HIP(cc::launch_unpermute(N, idx, w, s), "assign (codes to input order)");
     } else {
-        CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s), "assign (direct form)");
+        CC_TRY_HIP(cc::launch_assign_direct(X, N, d, C, K, idx, w.dmin, nullptr, 0, s, cx.prof), "assign (direct form)");
         CC_TRY_HIP(cc::launch_bump_assign_calls(w.hdr, s), "bookkeeping");
+        cc::ProfileScope mstep_scope(cx.prof, cc::kProfMstep, s);
         CC_TRY_HIP(cc::launch_update(X, N, d, idx, C, K, C, counts, w, true, s), "update");
     }
     if (inertia)
@@ -219,9 +240,121 @@ int leave(float* centroids_out, uint32_t d, uint32_t K, const cc::Workspace& w, 
     return CC_OK;
 }
 
+// Reads the caller's options (NULL = defaults).
+int read_options(const cc_options* o, Ctx& cx)
+{
+    cx = Ctx{};
+    if (o == nullptr) return CC_OK;
+    if (o->struct_bytes != sizeof(cc_options))
+        return fail(CC_ERR_SHAPE, "cc_options::struct_bytes = %u, this library expects %zu", o->struct_bytes, sizeof(cc_options));
+    if (o->assign_mode < CC_ASSIGN_AUTO || o->assign_mode > CC_ASSIGN_AUTO_WHOLE)
+        return fail(CC_ERR_SHAPE, "unknown assign mode %d", o->assign_mode);
+    cx.mode = o->assign_mode;
+    cx.prof = reinterpret_cast<cc::Profile*>(o->profile);
+    return CC_OK;
+}
+
 }  // namespace
 
+// ---- device-time records (cc_profile) ---------------------------------------------------------------
+namespace cc {
+
+struct Profile {
+    struct Record {
+        int slot;
+        hipEvent_t start, stop;
+    };
+    std::vector<Record> records;  // events created once, by cc_profile_create
+    uint32_t used = 0;
+    uint32_t dropped = 0;
+    uint32_t mask = 0;
+};
+
+ProfileScope::ProfileScope(Profile* p, int slot, hipStream_t s) : p_(p), s_(s), record_(-1)
+{
+    if (p == nullptr || !(p->mask & (1u << slot))) return;
+    if (p->used >= p->records.size()) {
+        ++p->dropped;
+        return;
+    }
+    record_ = int(p->used++);
+    p->records[record_].slot = slot;
+    (void)hipEventRecord(p->records[record_].start, s);
+}
+
+ProfileScope::~ProfileScope()
+{
+    if (record_ >= 0) (void)hipEventRecord(p_->records[record_].stop, s_);
+}
+
+}  // namespace cc
+
 extern "C" {
+
+int cc_profile_create(uint32_t max_records, uint32_t slot_mask, cc_profile** out)
+{
+    if (out == nullptr) return fail(CC_ERR_NULL, "out is NULL");
+    *out = nullptr;
+    if (max_records == 0 || max_records > 65536) return fail(CC_ERR_SHAPE, "max_records = %u is not in 1..65536", max_records);
+    if (slot_mask == 0 || slot_mask >= (1u << CC_PROF_SLOTS)) return fail(CC_ERR_SHAPE, "slot_mask = 0x%x names no known slot", slot_mask);
+    cc::Profile* p = new (std::nothrow) cc::Profile;
+    if (p == nullptr) return fail(CC_ERR_HIP, "out of host memory");
+    p->mask = slot_mask;
+    p->records.reserve(max_records);
+    for (uint32_t i = 0; i < max_records; ++i) {
+        cc::Profile::Record r{};
+        hipError_t e = hipEventCreate(&r.start);
+        if (e == hipSuccess) {
+            e = hipEventCreate(&r.stop);
+            if (e != hipSuccess) (void)hipEventDestroy(r.start);
+        }
+        if (e != hipSuccess) {
+            cc_profile_destroy(reinterpret_cast<cc_profile*>(p));
+            return hip_fail(e, "event creation");
+        }
+        p->records.push_back(r);
+    }
+    *out = reinterpret_cast<cc_profile*>(p);
+    return CC_OK;
+}
+
+int cc_profile_read(cc_profile* profile, double* ms, uint32_t* launches, uint32_t* dropped)
+{
+    if (profile == nullptr || ms == nullptr || launches == nullptr) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    cc::Profile* p = reinterpret_cast<cc::Profile*>(profile);
+    for (int k = 0; k < CC_PROF_SLOTS; ++k) {
+        ms[k] = 0.0;
+        launches[k] = 0;
+    }
+    int rc = CC_OK;
+    for (uint32_t i = 0; i < p->used; ++i) {
+        const cc::Profile::Record& r = p->records[i];
+        float t = 0.0f;
+        hipError_t e = hipEventSynchronize(r.stop);
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, r.start, r.stop);
+        if (e != hipSuccess) {
+            rc = hip_fail(e, "event read");
+            continue;
+        }
+        ms[r.slot] += double(t);
+        launches[r.slot] += 1;
+    }
+    if (dropped) *dropped = p->dropped;
+    p->used = 0;
+    p->dropped = 0;
+    return rc;
+}
+
+void cc_profile_destroy(cc_profile* profile)
+{
+    cc::Profile* p = reinterpret_cast<cc::Profile*>(profile);
+    if (p == nullptr) return;
+    for (auto& r : p->records) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    delete p;
+}
 
 size_t cc_workspace_bytes(uint64_t N, uint32_t d, uint32_t K)
 {
@@ -233,6 +366,16 @@ int cc_kmeans_fit(const float* vectors, uint64_t N, uint32_t d, uint32_t K, int3
                   float* centroids, uint32_t* idx, double* inertia, void* workspace, size_t workspace_bytes,
                   void* stream)
 {
+    return cc_kmeans_fit_ex(vectors, N, d, K, iters, init_centroids, centroids, idx, inertia, workspace, workspace_bytes,
+                            stream, nullptr);
+}
+
+int cc_kmeans_fit_ex(const float* vectors, uint64_t N, uint32_t d, uint32_t K, int32_t iters, const float* init_centroids,
+                     float* centroids, uint32_t* idx, double* inertia, void* workspace, size_t workspace_bytes,
+                     void* stream, const cc_options* options)
+{
+    Ctx cx;
+    if (int rc = read_options(options, cx)) return rc;
     if (!vectors || !init_centroids || !centroids || !idx) return fail(CC_ERR_NULL, "a required pointer is NULL");
     if (int rc = check_shape(N, d, K)) return rc;
     if (iters < 0) return fail(CC_ERR_ITERS, "iters = %d is negative", iters);
@@ -251,24 +394,35 @@ int cc_kmeans_fit(const float* vectors, uint64_t N, uint32_t d, uint32_t K, int3
     CC_TRY_HIP(cc::launch_scan_inputs(o.X, N * D, w.hdr, s), "input scan");
     if (o.C_work != o.C_in)
         CC_TRY_HIP(cc::launch_copy_f32(o.C_in, o.C_work, size_t(K) * D, s), "centroid copy");
-    const bool pruned = use_matrix_cores(K) && use_pruning(N, K, iters);
-    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(o.X, n, D, K, w, true, s), "norm ordering");
+    const bool pruned = use_matrix_cores(cx, K) && use_pruning(cx, N, K, iters);
+    if (pruned) {
+        cc::ProfileScope order_scope(cx.prof, cc::kProfOrder, s);
+        CC_TRY_HIP(cc::launch_sort_vectors(o.X, n, D, K, w, true, s), "norm ordering");
+    }
     for (int32_t t = 0; t < iters; ++t) {
         // only the matrix-core path can leave its codes in the workspace; the others write idx directly
         uint32_t* step_idx = pruned ? nullptr : idx;
         // from the third iteration on the M-step only moves the vectors whose code changed (the first iterations move
         // too many for that to pay off)
         const bool sums_follow = pruned && w.bucket_ok && t >= 2;
-        if (int rc = run_lloyd_iter(o.X, n, D, o.C_work, K, step_idx, nullptr, nullptr, w, pruned, t > 0, s, sums_follow))
+        if (int rc = run_lloyd_iter(cx, o.X, n, D, o.C_work, K, step_idx, nullptr, nullptr, w, pruned, t > 0, s, sums_follow))
             return rc;
     }
-    if (int rc = run_assign(o.X, n, D, o.C_work, K, idx, inertia, w, pruned, iters > 0, s)) return rc;
+    if (int rc = run_assign(cx, o.X, n, D, o.C_work, K, idx, inertia, w, pruned, iters > 0, s)) return rc;
     return leave(centroids, d, K, w, s);
 }
 
 int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroids, uint32_t K, uint32_t* idx,
               double* inertia, void* workspace, size_t workspace_bytes, void* stream)
 {
+    return cc_assign_ex(vectors, N, d, centroids, K, idx, inertia, workspace, workspace_bytes, stream, nullptr);
+}
+
+int cc_assign_ex(const float* vectors, uint64_t N, uint32_t d, const float* centroids, uint32_t K, uint32_t* idx,
+                 double* inertia, void* workspace, size_t workspace_bytes, void* stream, const cc_options* options)
+{
+    Ctx cx;
+    if (int rc = read_options(options, cx)) return rc;
     if (!vectors || !centroids || !idx) return fail(CC_ERR_NULL, "a required pointer is NULL");
     if (int rc = check_shape(N, d, K)) return rc;
     if (!aligned(vectors, 16) || !aligned(centroids, 16) || !aligned(idx, 4) || (inertia && !aligned(inertia, 8)))
@@ -280,14 +434,26 @@ int cc_assign(const float* vectors, uint64_t N, uint32_t d, const float* centroi
     Operands o;
     if (int rc = enter(vectors, centroids, nullptr, uint32_t(N), d, K, w, s, o)) return rc;
     CC_TRY_HIP(cc::launch_scan_inputs(o.X, N * w.d, w.hdr, s), "input scan");
-    const bool pruned = use_matrix_cores(K) && use_pruning(N, K, 1);
-    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(o.X, uint32_t(N), w.d, K, w, false, s), "norm ordering");
-    return run_assign(o.X, uint32_t(N), w.d, o.C_in, K, idx, inertia, w, pruned, false, s);
+    const bool pruned = use_matrix_cores(cx, K) && use_pruning(cx, N, K, 1);
+    if (pruned) {
+        cc::ProfileScope order_scope(cx.prof, cc::kProfOrder, s);
+        CC_TRY_HIP(cc::launch_sort_vectors(o.X, uint32_t(N), w.d, K, w, false, s), "norm ordering");
+    }
+    return run_assign(cx, o.X, uint32_t(N), w.d, o.C_in, K, idx, inertia, w, pruned, false, s);
 }
 
 int cc_lloyd_iter(const float* vectors, uint64_t N, uint32_t d, float* centroids, uint32_t K, uint32_t* idx,
                   double* inertia, uint32_t* counts, void* workspace, size_t workspace_bytes, void* stream)
 {
+    return cc_lloyd_iter_ex(vectors, N, d, centroids, K, idx, inertia, counts, workspace, workspace_bytes, stream, nullptr);
+}
+
+int cc_lloyd_iter_ex(const float* vectors, uint64_t N, uint32_t d, float* centroids, uint32_t K, uint32_t* idx,
+                     double* inertia, uint32_t* counts, void* workspace, size_t workspace_bytes, void* stream,
+                     const cc_options* options)
+{
+    Ctx cx;
+    if (int rc = read_options(options, cx)) return rc;
     if (!vectors || !centroids || !idx) return fail(CC_ERR_NULL, "a required pointer is NULL");
     if (int rc = check_shape(N, d, K)) return rc;
     if (!aligned(vectors, 16) || !aligned(centroids, 16) || !aligned(idx, 4) || (inertia && !aligned(inertia, 8)) ||
@@ -300,15 +466,27 @@ int cc_lloyd_iter(const float* vectors, uint64_t N, uint32_t d, float* centroids
     Operands o;
     if (int rc = enter(vectors, centroids, centroids, uint32_t(N), d, K, w, s, o)) return rc;
     CC_TRY_HIP(cc::launch_scan_inputs(o.X, N * w.d, w.hdr, s), "input scan");
-    const bool pruned = use_matrix_cores(K) && use_pruning(N, K, 1);
-    if (pruned) CC_TRY_HIP(cc::launch_sort_vectors(o.X, uint32_t(N), w.d, K, w, false, s), "norm ordering");
-    if (int rc = run_lloyd_iter(o.X, uint32_t(N), w.d, o.C_work, K, idx, inertia, counts, w, pruned, false, s)) return rc;
+    const bool pruned = use_matrix_cores(cx, K) && use_pruning(cx, N, K, 1);
+    if (pruned) {
+        cc::ProfileScope order_scope(cx.prof, cc::kProfOrder, s);
+        CC_TRY_HIP(cc::launch_sort_vectors(o.X, uint32_t(N), w.d, K, w, false, s), "norm ordering");
+    }
+    if (int rc = run_lloyd_iter(cx, o.X, uint32_t(N), w.d, o.C_work, K, idx, inertia, counts, w, pruned, false, s)) return rc;
     return leave(centroids, d, K, w, s);
 }
 
 int cc_update(const float* vectors, uint64_t N, uint32_t d, const uint32_t* idx, const float* prev_centroids,
               uint32_t K, float* centroids, uint32_t* counts, void* workspace, size_t workspace_bytes, void* stream)
 {
+    return cc_update_ex(vectors, N, d, idx, prev_centroids, K, centroids, counts, workspace, workspace_bytes, stream, nullptr);
+}
+
+int cc_update_ex(const float* vectors, uint64_t N, uint32_t d, const uint32_t* idx, const float* prev_centroids,
+                 uint32_t K, float* centroids, uint32_t* counts, void* workspace, size_t workspace_bytes, void* stream,
+                 const cc_options* options)
+{
+    Ctx cx;
+    if (int rc = read_options(options, cx)) return rc;
     if (!vectors || !idx || !prev_centroids || !centroids) return fail(CC_ERR_NULL, "a required pointer is NULL");
     if (int rc = check_shape(N, d, K)) return rc;
     if (!aligned(vectors, 16) || !aligned(prev_centroids, 16) || !aligned(centroids, 16) || !aligned(idx, 4) ||
@@ -321,7 +499,10 @@ int cc_update(const float* vectors, uint64_t N, uint32_t d, const uint32_t* idx,
     Operands o;
     if (int rc = enter(vectors, prev_centroids, centroids, uint32_t(N), d, K, w, s, o)) return rc;
     CC_TRY_HIP(cc::launch_scan_inputs(o.X, N * w.d, w.hdr, s), "input scan");
-    CC_TRY_HIP(cc::launch_update(o.X, uint32_t(N), w.d, idx, o.C_in, K, o.C_work, counts, w, true, s), "update");
+    {
+        cc::ProfileScope mstep_scope(cx.prof, cc::kProfMstep, s);
+        CC_TRY_HIP(cc::launch_update(o.X, uint32_t(N), w.d, idx, o.C_in, K, o.C_work, counts, w, true, s), "update");
+    }
     return leave(centroids, d, K, w, s);
 }
 
@@ -725,17 +906,13 @@ int cc_read_stats(const void* workspace, size_t workspace_bytes, cc_stats* host_
     host_out->total_stages = h.window_total;
     host_out->fixed_point_exp = h.fixed_point_exp;
     host_out->fp16_inputs = h.x_not_f16 == 0 ? 1u : 0u;
+    host_out->nonfinite_inputs = h.x_nonfinite != 0 ? 1u : 0u;
+    host_out->reserved = 0;
     return CC_OK;
-}
-
-int cc_set_assign_mode(int mode)
-{
-    if (mode < 0 || mode > 3) return fail(CC_ERR_SHAPE, "unknown assign mode %d", mode);
-    return g_assign_mode.exchange(mode);
 }
 
 const char* cc_last_error(void) { return g_err; }
 
-const char* cc_version(void) { return "cluscomp-gfx950 0.1"; }
+const char* cc_version(void) { return "cluscomp-gfx950 0.2"; }
 
 }  // extern "C"

@@ -69,21 +69,22 @@ __global__ __launch_bounds__(kThreads) void assign_direct_kernel(const float* __
 
 template <int D, int VPT, int TILE>
 static hipError_t launch_t(const float* X, uint32_t N, const float* C, uint32_t K, uint32_t* idx, float* dmin,
-                           const uint32_t* gate, uint32_t gate_limit, hipStream_t s)
+                           const uint32_t* gate, uint32_t gate_limit, hipStream_t s, Profile* profile)
 {
     const uint32_t blocks = (N + kThreads * VPT - 1) / (kThreads * VPT);
+    ProfileScope scope(profile, kProfEstepDirect, s);
     hipLaunchKernelGGL((assign_direct_kernel<D, VPT, TILE>), dim3(blocks), dim3(kThreads), 0, s, X, N, C, K, idx, dmin,
                        gate, gate_limit);
     return hipGetLastError();
 }
 
 hipError_t launch_assign_direct(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K, uint32_t* idx,
-                                float* dmin, const uint32_t* gate, uint32_t gate_limit, hipStream_t s)
+                                float* dmin, const uint32_t* gate, uint32_t gate_limit, hipStream_t s, Profile* profile)
 {
     switch (d) {
-        case 4: return launch_t<4, 4, 1024>(X, N, C, K, idx, dmin, gate, gate_limit, s);
-        case 8: return launch_t<8, 2, 512>(X, N, C, K, idx, dmin, gate, gate_limit, s);
-        case 16: return launch_t<16, 1, 256>(X, N, C, K, idx, dmin, gate, gate_limit, s);
+        case 4: return launch_t<4, 4, 1024>(X, N, C, K, idx, dmin, gate, gate_limit, s, profile);
+        case 8: return launch_t<8, 2, 512>(X, N, C, K, idx, dmin, gate, gate_limit, s, profile);
+        case 16: return launch_t<16, 1, 256>(X, N, C, K, idx, dmin, gate, gate_limit, s, profile);
         default: return hipErrorInvalidValue;
     }
 }

@@ -295,11 +295,14 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
     const uint32_t per_block = 4 * 32 * (e.windows != nullptr ? VTW : VT);
     const auto kernel = e.windows != nullptr ? assign_mfma_kernel<D, VTW, int(kStageTiles), GT, true>
                                              : assign_mfma_kernel<D, VT, ST, GT, false>;
-    hipLaunchKernelGGL(kernel, dim3((e.N + per_block - 1) / per_block), dim3(kThreads), 0, s,
-                       e.X, e.N, e.rows, e.K, static_cast<const float*>(e.packed), e.packed_tiles, e.idx, w.dmin, w.hdr,
-                       w.refine_list, w.refine_cap, e.gate, e.accumulate ? w.sums : nullptr,
-                       e.accumulate ? w.counts : nullptr, e.windows, e.row_ids, e.hint_only ? 1 : 0,
-                       e.prev_out, e.changed);
+    {
+        ProfileScope scope(e.profile, kProfEstepF32, s);
+        hipLaunchKernelGGL(kernel, dim3((e.N + per_block - 1) / per_block), dim3(kThreads), 0, s,
+                           e.X, e.N, e.rows, e.K, static_cast<const float*>(e.packed), e.packed_tiles, e.idx, w.dmin, w.hdr,
+                           w.refine_list, w.refine_cap, e.gate, e.accumulate ? w.sums : nullptr,
+                           e.accumulate ? w.counts : nullptr, e.windows, e.row_ids, e.hint_only ? 1 : 0,
+                           e.prev_out, e.changed);
+    }
     return hipGetLastError();
 }
 

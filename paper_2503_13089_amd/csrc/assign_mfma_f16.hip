@@ -432,11 +432,14 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
     const auto kernel = e.windows != nullptr ? assign_mfma_f16_kernel<D, VTW, int(kStageTiles), GT_WINDOWED, true>
                         : (e.K >= 32768  ? assign_mfma_f16_kernel<D, VT, ST, GT_WIDE, false>
                                          : assign_mfma_f16_kernel<D, VT, ST, GT, false>);
-    hipLaunchKernelGGL(kernel, dim3((e.N + per_block - 1) / per_block), dim3(kThreads),
-                       0, s, e.X, e.N, e.rows, e.K, static_cast<const char*>(e.packed), e.packed_tiles, e.idx, w.dmin, w.hdr,
-                       w.refine_list, w.refine_cap, e.gate, e.accumulate ? w.sums : nullptr,
-                       e.accumulate ? w.counts : nullptr, e.windows, e.row_ids, e.hint_only ? 1 : 0,
-                       e.prev_out, e.changed);
+    {
+        ProfileScope scope(e.profile, kProfEstepF16, s);
+        hipLaunchKernelGGL(kernel, dim3((e.N + per_block - 1) / per_block), dim3(kThreads),
+                           0, s, e.X, e.N, e.rows, e.K, static_cast<const char*>(e.packed), e.packed_tiles, e.idx, w.dmin, w.hdr,
+                           w.refine_list, w.refine_cap, e.gate, e.accumulate ? w.sums : nullptr,
+                           e.accumulate ? w.counts : nullptr, e.windows, e.row_ids, e.hint_only ? 1 : 0,
+                           e.prev_out, e.changed);
+    }
     return hipGetLastError();
 }
 

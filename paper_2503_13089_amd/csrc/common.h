@@ -13,6 +13,23 @@ size_t sort_hist_bytes(uint64_t n);
 
 constexpr uint32_t kMaxK = 1u << 24;
 
+// Device time of the library's own kernels, for callers that ask for it (cc_profile in the public header): a pool
+// of HIP events created once; a scope records one event before and one after the launches it brackets, on the
+// stream of the call. Slots follow cc_profile_slot. A NULL profile, a slot outside the caller's mask or a full pool
+// turns a scope into a no-op.
+struct Profile;
+struct ProfileScope {
+    ProfileScope(Profile* p, int slot, hipStream_t s);
+    ~ProfileScope();
+    ProfileScope(const ProfileScope&) = delete;
+    ProfileScope& operator=(const ProfileScope&) = delete;
+    Profile* p_;
+    hipStream_t s_;
+    int record_;
+};
+enum ProfileSlot : int { kProfEstepF16 = 0, kProfEstepF32 = 1, kProfEstepDirect = 2, kProfRefine = 3, kProfMstep = 4,
+                         kProfOrder = 5, kProfSlots = 6 };
+
 // Device-side bookkeeping at the start of the workspace (one 256-byte slot).
 struct WsHeader {
     uint32_t absmax_bits;      // max over all inputs of the fp32 bit pattern of |x|
@@ -25,7 +42,7 @@ struct WsHeader {
     unsigned long long window_stages;   // sum over 512-vector tiles of the codebook stages they had to score
     unsigned long long window_total;    // what that sum would be without pruning
     int32_t fixed_point_exp;
-    uint32_t reserved;
+    uint32_t x_nonfinite;      // != 0: some input is Inf or NaN (the sums then skip such components)
 };
 
 // Survives between calls on the same workspace (not touched by the per-call header reset): whether the
@@ -169,7 +186,7 @@ inline Workspace carve(void* base, uint64_t N, uint32_t d_caller, uint32_t K)
 // unless *gate > gate_limit (used as the overflow path of the matrix-core E-step).
 hipError_t launch_assign_direct(const float* X, uint32_t N, uint32_t d, const float* C, uint32_t K,
                                 uint32_t* idx, float* dmin, const uint32_t* gate, uint32_t gate_limit,
-                                hipStream_t s);
+                                hipStream_t s, Profile* profile = nullptr);
 
 // Which inputs a gated kernel runs for (decided on the device from WsHeader::x_not_f16).
 // kGateNoHint (a flag on top of the three) additionally requires that the workspace holds no usable hint.
@@ -203,6 +220,7 @@ struct EStep {
     uint32_t* prev_out;         // with `changed`: where the code that idx held before goes, for every vector flagged there
     uint32_t* changed;          // NULL, or one bit per vector, set where the code differs from what idx held or is not final yet
     int gate;
+    Profile* profile;           // NULL, or where the scoring kernel's device time is recorded
 };
 
 // Matrix-core E-step, fp32 MFMA: packs the codebook and runs the scoring kernel (provisional idx,
@@ -358,6 +376,13 @@ __device__ __forceinline__ int fixed_point_exp(uint32_t absmax_bits, uint32_t N)
     return e < 100 ? e : 100;                      // keep ldexp away from fp64 overflow for tiny inputs
 }
 
+// One input as a fixed-point term of the cluster sums. A non-finite input (which the input scan flags in
+// WsHeader::x_nonfinite) contributes nothing: its conversion to an integer would be undefined.
+__device__ __forceinline__ long long fixed_point_term(float x, int e)
+{
+    return (__float_as_uint(x) & 0x7f800000u) == 0x7f800000u ? 0ll : __double2ll_rn(ldexp(double(x), e));
+}
+
 // Adds (sign = +1) or removes (sign = -1) one vector to/from cluster k's fixed-point sums and count.
 // Integer adds commute, so the totals do not depend on the order in which these atomics land.
 template <int D>
@@ -367,7 +392,7 @@ __device__ __forceinline__ void accumulate_vector(const float (&x)[D], uint32_t 
     unsigned long long* dst = reinterpret_cast<unsigned long long*>(sums + size_t(k) * D);
 #pragma unroll
     for (int j = 0; j < D; ++j) {
-        const long long f = __double2ll_rn(ldexp(double(x[j]), e));
+        const long long f = fixed_point_term(x[j], e);
         if (f != 0) atomicAdd(dst + j, static_cast<unsigned long long>(sign > 0 ? f : -f));
     }
     atomicAdd(counts + k, sign > 0 ? 1u : 0xffffffffu);

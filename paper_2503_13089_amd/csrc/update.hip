@@ -28,7 +28,7 @@ __global__ void reset_header_kernel(WsHeader* hdr)
         hdr->window_stages = 0;
         hdr->window_total = 0;
         hdr->fixed_point_exp = 0;
-        hdr->reserved = 0;
+        hdr->x_nonfinite = 0;
     }
 }
 
@@ -49,8 +49,10 @@ hipError_t launch_bump_assign_calls(WsHeader* hdr, hipStream_t s)
     return hipGetLastError();
 }
 
-// One pass over the inputs: max |x| as the maximum of the (sign-cleared) fp32 bit patterns (for finite
-// floats the integer order of the patterns is the order of the magnitudes), and whether the vectors qualify
+// One pass over the inputs: max |x| over the finite inputs as the maximum of the (sign-cleared) fp32 bit patterns
+// (for finite floats the integer order of the patterns is the order of the magnitudes), whether any input is Inf
+// or NaN (the caller's precondition is that none is; such a component is left out of the cluster sums and the
+// fact is reported in the statistics), and whether the vectors qualify
 // for the fp16 matrix-core kernels: |x| < 2^15, and every value of the fp16 normal range (|x| >= 2^-14)
 // survives a round trip through fp16 (then -2x is also an fp16 number). Smaller values need not be fp16
 // numbers - bf16 weights have many that are not: what their fp16 rounding loses is at most 2^-25 each, which
@@ -58,16 +60,18 @@ hipError_t launch_bump_assign_calls(WsHeader* hdr, hipStream_t s)
 __global__ __launch_bounds__(kThreads) void scan_inputs_kernel(const float4* __restrict__ X4, uint64_t n4, WsHeader* hdr)
 {
     __shared__ uint32_t red_m[kThreads / 64], red_f[kThreads / 64];
-    uint32_t m = 0, bad = 0;
+    uint32_t m = 0, bad = 0;  // bad: bit 0 = not fit for the fp16 kernels, bit 1 = a non-finite input
     for (uint64_t i = uint64_t(blockIdx.x) * kThreads + threadIdx.x; i < n4; i += uint64_t(gridDim.x) * kThreads) {
         const float4 t = X4[i];
         const float v[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t a = __float_as_uint(v[j]) & 0x7fffffffu;
-            m = max(m, a);
+            const bool finite = a < 0x7f800000u;
+            m = finite ? max(m, a) : m;
             const float back = float(_Float16(v[j]));
-            bad |= (back != v[j] && a >= 0x38800000u /* 2^-14 */) || (a >= 0x47000000u /* 2^15 */);
+            bad |= uint32_t((back != v[j] && a >= 0x38800000u /* 2^-14 */) || (a >= 0x47000000u /* 2^15 */)) |
+                   (finite ? 0u : 2u);
         }
     }
     for (int off = 32; off > 0; off >>= 1) {
@@ -85,7 +89,8 @@ __global__ __launch_bounds__(kThreads) void scan_inputs_kernel(const float4* __r
             bad |= red_f[w];
         }
         atomicMax(&hdr->absmax_bits, m);
-        if (bad) atomicOr(&hdr->x_not_f16, 1u);
+        if (bad & 1u) atomicOr(&hdr->x_not_f16, 1u);
+        if (bad & 2u) atomicOr(&hdr->x_nonfinite, 1u);
     }
 }
 

@@ -348,7 +348,7 @@ __global__ __launch_bounds__(kThreads) void bucket_sum_kernel(const char* __rest
         load_row<D>(reinterpret_cast<const float*>(rec), x);
 #pragma unroll
         for (int j = 0; j < D; ++j) {
-            const long long v = __double2ll_rn(ldexp(double(x[j]), e));
+            const long long v = fixed_point_term(x[j], e);
             atomicAdd(&sum[j][local], static_cast<unsigned long long>(minus ? -v : v));  // two's complement: wraps like int64
         }
         atomicAdd(&cnt[local], minus ? 0xffffffffu : 1u);

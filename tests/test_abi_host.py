@@ -81,9 +81,37 @@ def test_other_entry_points_reject_bad_arguments():
     assert lib.cc_decode(A16, 0, 4, A4, 10, A16, None) == -2
     assert lib.cc_decode(A16, 2, 4, A4, 10, MISALIGNED, None) == -4
     assert lib.cc_read_stats(None, 0, None, None) == -1
-    assert lib.cc_set_assign_mode(7) == -2 and lib.cc_set_assign_mode(-1) == -2
-    prev = lib.cc_set_assign_mode(1)
-    assert lib.cc_set_assign_mode(prev) == 1
+
+
+def test_options_and_profile_arguments():
+    """The *_ex entry points take per-call options; nothing about the E-step selection is process-wide."""
+    lib = cc.load_library()
+    o = binding._COptions()
+    o.struct_bytes, o.assign_mode = ctypes.sizeof(binding._COptions), 7
+    assert _fit_ex(lib, o) == -2 and "assign mode 7" in cc.last_error()
+    o.assign_mode = -1
+    assert _fit_ex(lib, o) == -2
+    o.struct_bytes, o.assign_mode = 4, 0
+    assert _fit_ex(lib, o) == -2 and "struct_bytes" in cc.last_error()
+    o.struct_bytes = ctypes.sizeof(binding._COptions)
+    assert _fit_ex(lib, o, K=0) == -2 and "K == 0" in cc.last_error()      # valid options: the usual checks follow
+    assert lib.cc_assign_ex(A16, 10, 4, A16, 20, A4, None, A16, 0, None, None) == -2   # NULL options = defaults
+    assert lib.cc_update_ex(A16, 10, 4, None, A16, 2, A16, None, A16, 0, None, ctypes.byref(o)) == -1
+    assert lib.cc_lloyd_iter_ex(A16, 10, 4, A16, 2, None, None, None, A16, 0, None, ctypes.byref(o)) == -1
+    h = ctypes.c_void_p()
+    assert lib.cc_profile_create(0, 1, ctypes.byref(h)) == -2
+    assert lib.cc_profile_create(16, 0, ctypes.byref(h)) == -2 and lib.cc_profile_create(16, 1 << 6, ctypes.byref(h)) == -2
+    assert lib.cc_profile_create(16, 1, None) == -1
+    assert lib.cc_profile_read(None, None, None, None) == -1
+    lib.cc_profile_destroy(None)
+    with pytest.raises(cc.CCError):
+        cc.set_assign_mode(9)
+    prev = cc.set_assign_mode(1)
+    assert cc.set_assign_mode(prev) == 1
+
+
+def _fit_ex(lib, options, K=8):
+    return lib.cc_kmeans_fit_ex(A16, 1000, 4, K, 1, A16, A16, A4, None, A16, 0, None, ctypes.byref(options))
 
 
 def test_layer_entry_points_reject_bad_arguments():
