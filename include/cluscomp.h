@@ -376,6 +376,19 @@ int cc_layer_forward_q(const void *x, uint64_t M, const void *qbook, int bits, c
                        uint32_t g, const uint16_t *codes, uint32_t in_features, uint32_t out_features,
                        const void *bias, void *y, int dtype, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Diagnostic, for tests: what the fp16 matrix core (v_mfma_f32_32x32x16_f16) returns for caller-chosen operands,
+ * chained as the default E-step of Section 3.1's argmin chains it (km = 1 or 2 instructions, the accumulator preset
+ * per output row). The E-step's guard band assumes that this result is within 8 * 2^-24 * S of the exact sum, S
+ * being the sum over the nonzero products a * b of max(|a|, 2^-14) * max(|b|, 2^-14) plus |c|; the hardware manuals
+ * do not state the accumulation order, so a GPU test pins the bound with this call against exact arithmetic.
+ *   A [tiles * 32 * 16 * km], B [tiles * 32 * 16 * km]  fp16 bit patterns: row m of A against row n of B
+ *   C [tiles * 32]  fp32, start value of the accumulator for output row m
+ *   D [tiles * 32 * 32]  out, fp32: D[m][n] = C[m] + sum_q A[m][q] * B[n][q] as the instruction computes it
+ */
+int cc_mfma_f16_probe(const uint16_t *A, const uint16_t *B, const float *C, float *D, uint32_t tiles, uint32_t km,
+                      void *stream);
+
 /* Thread-local description of the last error returned on this thread (host pointer, static storage). */
 const char *cc_last_error(void);
 

@@ -38,6 +38,7 @@ from .binding import (  # noqa: F401
     lib_path,
     lloyd_iter,
     load_library,
+    mfma_f16_probe,
     read_stats,
     set_assign_mode,
     update,

@@ -16,7 +16,7 @@ EXPORTS = (
     "cc_workspace_bytes", "cc_kmeans_fit", "cc_assign", "cc_lloyd_iter", "cc_update", "cc_decode",
     "cc_kmeans_fit_ex", "cc_assign_ex", "cc_lloyd_iter_ex", "cc_update_ex",
     "cc_profile_create", "cc_profile_read", "cc_profile_destroy",
-    "cc_read_stats", "cc_last_error", "cc_version",
+    "cc_read_stats", "cc_mfma_f16_probe", "cc_last_error", "cc_version",
     "cc_layer_deficiency", "cc_layer_num_codes", "cc_layer_vectors", "cc_layer_pack", "cc_layer_weight",
     "cc_layer_codebook_grad", "cc_layer_forward", "cc_layer_forward_workspace_bytes",
     "cc_layer_forward_tune_workspace_bytes", "cc_layer_forward_tune",
@@ -149,6 +149,8 @@ def load_library():
     lib.cc_layer_forward_q.restype = ctypes.c_int
     lib.cc_layer_codebook_grad.argtypes = [vp, ctypes.c_int, u32, u32, vp, u32, u32, vp, vp, sz, vp]
     lib.cc_layer_codebook_grad.restype = ctypes.c_int
+    lib.cc_mfma_f16_probe.argtypes = [vp, vp, vp, vp, u32, u32, vp]
+    lib.cc_mfma_f16_probe.restype = ctypes.c_int
     lib.cc_last_error.restype = ctypes.c_char_p
     lib.cc_version.restype = ctypes.c_char_p
     _lib = lib
@@ -319,6 +321,18 @@ def read_stats(workspace) -> Stats:
                                         ctypes.byref(st), _stream()))
     return Stats(int(st.refined_vectors), int(st.skipped_vectors), int(st.assign_calls), int(st.scored_stages),
                  int(st.total_stages), int(st.fixed_point_exp), int(st.fp16_inputs), int(st.nonfinite_inputs))
+
+
+def mfma_f16_probe(A, B, C, D) -> None:
+    """cc_mfma_f16_probe: A, B float16 [tiles, 32, 16 * km], C float32 [tiles, 32], D float32 [tiles, 32, 32] (out)."""
+    import torch
+
+    tiles, rows, slots = A.shape
+    if rows != 32 or slots not in (16, 32) or B.shape != A.shape or C.shape != (tiles, 32) or D.shape != (tiles, 32, 32):
+        raise ValueError("A, B: [tiles, 32, 16 or 32]; C: [tiles, 32]; D: [tiles, 32, 32]")
+    _check(load_library().cc_mfma_f16_probe(_ptr(A, torch.float16, "A"), _ptr(B, torch.float16, "B"),
+                                            _ptr(C, torch.float32, "C"), _ptr(D, torch.float32, "D"), tiles, slots // 16,
+                                            _stream()))
 
 
 # ---- the compressed linear layer ---------------------------------------------------------------------

@@ -892,6 +892,16 @@ int cc_layer_forward_q(const void* x, uint64_t M, const void* qbook, int bits, c
     return CC_OK;
 }
 
+int cc_mfma_f16_probe(const uint16_t* A, const uint16_t* B, const float* C, float* D, uint32_t tiles, uint32_t km, void* stream)
+{
+    if (!A || !B || !C || !D) return fail(CC_ERR_NULL, "a required pointer is NULL");
+    if (tiles == 0 || tiles > (1u << 20)) return fail(CC_ERR_SHAPE, "tiles = %u is not in 1..2^20", tiles);
+    if (km != 1 && km != 2) return fail(CC_ERR_SHAPE, "km = %u is not 1 or 2", km);
+    if (!aligned(A, 2) || !aligned(B, 2) || !aligned(C, 4) || !aligned(D, 4)) return fail(CC_ERR_ALIGN, "misaligned pointer");
+    CC_TRY_HIP(cc::launch_mfma_f16_probe(A, B, C, D, tiles, km, static_cast<hipStream_t>(stream)), "matrix-core probe");
+    return CC_OK;
+}
+
 int cc_read_stats(const void* workspace, size_t workspace_bytes, cc_stats* host_out, void* stream)
 {
     if (!workspace || !host_out) return fail(CC_ERR_NULL, "a required pointer is NULL");

@@ -360,6 +360,10 @@ hipError_t launch_layer_grad_vectors(const void* grad, int dtype, uint32_t in_fe
                                      uint32_t g, uint32_t d_pad, const uint16_t* codes, uint64_t num_codes, float* vectors,
                                      uint32_t* idx, hipStream_t s);
 
+// Diagnostic (probe.hip): the fp16 matrix-core instruction of the E-step on caller-chosen operands.
+hipError_t launch_mfma_f16_probe(const uint16_t* A, const uint16_t* B, const float* C, float* D, uint32_t tiles, uint32_t km,
+                                 hipStream_t s);
+
 // Reconstruction.
 hipError_t launch_decode(const float* C, uint32_t K, uint32_t d, const uint32_t* idx, uint64_t N, float* out,
                          hipStream_t s);

@@ -221,8 +221,10 @@ __global__ __launch_bounds__(kThreads) void centroid_keys_kernel(const float* __
 // ||x|| and its projection e.c within u of e.x. The tile takes the hull of those bands over its 512
 // (neighbouring, hence similar) vectors; per shell s inside the norm band the cosine e.c/||c|| is then
 // confined to [t_lo, t_hi] computed from the shell's radius range, i.e. to a run of ordering keys
-// (s, q_lo..q_hi). Norm keys are widened by one step (0.8 %) and cosine buckets by one (1/64) on each side,
-// far more than any rounding in the norms, projections and u. Runs of neighbouring shells that touch are
+// (s, q_lo..q_hi). Rounding slack: both bands are widened by 1e-5 of the largest norm in play and every cosine
+// bound by 1e-4. The fp32 norms, projections and quotients behind them - here and where the centroids' keys were
+// made - are each within a few 1e-7 of that scale of their exact values, and u already carries a factor 1.001,
+// so the slack is some fifty times what rounding can move a bound. Runs of neighbouring shells that touch are
 // merged. If the band spans more than kWinSlots shells the list degrades to the single run of all keys
 // inside the norm band.
 // guess > 0 (no codes yet): u = guess * ||x|| instead, a window that proves nothing but is likely to hold a

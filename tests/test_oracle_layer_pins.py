@@ -1,6 +1,8 @@
 """Pins of the layer oracle (oracle/layer.py) against things other than itself: element-by-element brute force on tiny
 inputs, torch's CPU library routines (embedding, matmul, bfloat16 conversion, autograd), the constructor arithmetic of
 the paper's layer listing, and round trips."""
+from fractions import Fraction
+
 import numpy as np
 import pytest
 import torch
@@ -116,6 +118,46 @@ def test_gather_backward_matches_autograd_and_bruteforce(g, out_features):
     assert got.sum() == pytest.approx(G.sum(), rel=1e-12)
     unused = np.setdiff1d(np.arange(K), codes)
     assert np.all(got[unused] == 0.0)
+
+
+def _half_grid():
+    """Every finite non-negative IEEE half value built from the format's definition: subnormals m * 2^-24
+    (m = 0..1023), normals (1024 + m) * 2^(e - 25) for biased exponents e = 1..30."""
+    vals = [Fraction(m, 2 ** 24) for m in range(1024)]
+    for e in range(1, 31):
+        vals += [Fraction(1024 + m) * Fraction(2) ** (e - 25) for m in range(1024)]
+    return vals
+
+
+def test_fp16_round_is_round_to_nearest_even_on_the_half_grid():
+    """Pins oracle.layer.fp16_round without calling numpy's own half conversion: the nearest point of the half grid
+    (constructed from the format's definition) in exact rational arithmetic, ties to the even mantissa, overflow to
+    infinity from 65520 on; and torch's conversion as a second, independent routine."""
+    import bisect
+
+    grid = _half_grid()
+    assert grid[-1] == 65504 and grid[1] == Fraction(1, 2 ** 24) and grid[1024] == Fraction(1, 2 ** 14)
+    rng = np.random.default_rng(61)
+    a = np.concatenate([
+        (rng.standard_normal(3000) * 10.0 ** rng.integers(-9, 5, size=3000)).astype(np.float32),
+        # exact ties between neighbouring half values, at several exponents, and the neighbourhood of the overflow
+        np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 2.0 ** -24 * 1.5, 2.0 ** -24 * 2.5, 2.0 ** -25, 2.0 ** -26,
+                  65504.0, 65519.996, 65520.0, 70000.0, 0.0, 2.0 ** -14 - 2.0 ** -25, 1e-8, 3.0e38], np.float32)])
+    a = np.concatenate([a, -a])
+    got = layer.fp16_round(a)
+    for x, y in zip(a.tolist(), got.tolist()):
+        fx = abs(Fraction(x))
+        if fx >= Fraction(65520):
+            want = float("inf")
+        else:
+            i = bisect.bisect_left(grid, fx)
+            cands = [j for j in (i - 1, i) if 0 <= j < len(grid)]
+            best = min(cands, key=lambda j: (abs(grid[j] - fx), j % 2))  # even index = even mantissa (the grid is contiguous)
+            want = float(grid[best])
+        assert abs(y) == want and (y == 0 or (y < 0) == (x < 0)), (x, y, want)
+    want_t = torch.from_numpy(a).to(torch.float16).to(torch.float32).numpy()
+    assert got.tobytes() == want_t.tobytes()
+    assert np.array_equal(layer.fp16_round(got[np.isfinite(got)]), got[np.isfinite(got)])  # idempotent
 
 
 # ------------------------------------------------------------------ uniformly quantised codebook
