@@ -149,23 +149,18 @@ def layer_kernels(cc, torch, timed, w, ws, idx, Cd):
         nbytes = 2.0 * n + 2.0 * K * g + 2.0 * M * (in_features + out_features)
         fwd["M%d" % M] = {"avg_ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9, "bytes_per_launch": nbytes,
                           "dense_matmul_on_rebuilt_weight_ms": dense_ms}
-    # prefill-sized batch: weight rebuilt once + the GEMM library (a contraction: priced against the bf16 MFMA peak)
+    # prefill-sized batch: weight rebuilt once (transposed) + the library's own matrix-core product (a contraction:
+    # priced against the bf16 MFMA peak; the rebuild is inside the time)
     M = 2048
     x = torch.randn(M, in_features, device="cuda").to(bf)
     y = torch.empty(M, out_features, dtype=bf, device="cuda")
     fws = torch.empty(max(cc.layer_forward_workspace_bytes(M, in_features, out_features), 256), dtype=torch.uint8,
                       device="cuda")
-    untuned_ms = timed(lambda: cc.layer_forward(x, book, codes, out_features, None, y, fws), reps=10)
-    # start-up step of a serving process: time the library's candidate algorithms for this product once
-    tws = torch.empty(cc.layer_forward_tune_workspace_bytes(M, in_features, out_features), dtype=torch.uint8, device="cuda")
-    cc.layer_forward_tune(M, in_features, out_features, bf, False, False, tws)
-    del tws
     ms = timed(lambda: cc.layer_forward(x, book, codes, out_features, None, y, fws), reps=10)
     flop = 2.0 * M * in_features * out_features
     fwd["M%d" % M] = {"avg_ms": ms, "bound": "mfma", "achieved": flop / (ms * 1e-3) / 1e12, "peak": 2500.0,
                       "unit": "TFLOP/s", "frac": flop / (ms * 1e-3) / 1e12 / 2500.0, "flop_per_launch": flop,
-                      "avg_ms_with_the_library's_first_algorithm": untuned_ms,
-                      "dense_matmul_on_rebuilt_weight_ms": timed(lambda: torch.matmul(x, rebuilt, out=y), reps=10)}
+                      "framework_matmul_on_a_ready_weight_ms": timed(lambda: torch.matmul(x, rebuilt, out=y), reps=10)}
     res["layer_forward"] = fwd
     # the paper's inference variant: codebook quantised to 4 bits (128 KB: held in LDS by persistent workgroups)
     qbook = torch.empty(K * g // 2, dtype=torch.uint8, device="cuda")

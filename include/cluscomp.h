@@ -264,32 +264,16 @@ int cc_layer_weight(const void *codebook, int dtype, uint32_t K, uint32_t g, con
  *     operand tiles. The summation order is fixed: same inputs, same bits. Workspace: fp32 partial sums of the
  *     in-feature slices that fill the chip when M is small.
  *   many rows (prefill, wide decoding batches): the listing's own order. W is rebuilt once into the workspace
- *     and multiplied by the vendor GEMM library (hipBLASLt, opened at run time; bias in its epilogue), whose
- *     algorithm is chosen once per shape and process (the first such call on a device creates the library's
- *     handle and the first per shape asks for its algorithm: both allocate; later calls do not). Workspace: W plus 64 MiB for the library. Where the library cannot be opened, or
- *     has no algorithm for the shape, the first route serves every M.
+ *     (transposed, so that both operands are contiguous along in_features) and multiplied by the library's own
+ *     matrix-core kernel: 256 x 128 tiles of y, operands staged in LDS, fp32 accumulation in a fixed order, bias
+ *     added to the finished sum, one rounding. With few tiles the contraction is also split over workgroups and
+ *     the fp32 partial tiles are added in a fixed order by a second kernel. Workspace: W plus those partial tiles.
  * cc_layer_forward_workspace_bytes(M, in_features, out_features) bytes, 256-byte aligned; may be NULL if that is 0.
  */
 size_t cc_layer_forward_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features);
 int cc_layer_forward(const void *x, uint64_t M, const void *codebook, int dtype, uint32_t K, uint32_t g,
                      const uint16_t *codes, uint32_t in_features, uint32_t out_features, const void *bias,
                      void *y, void *workspace, size_t workspace_bytes, void *stream);
-
-/*
- * Optional, for start-up: the GEMM library offers several algorithms per product and its own first choice is not
- * always the fastest (2048 x 4096 x 11008 in bf16: 286 us against 173 us for the best of its candidates). This
- * call runs every candidate a few times for the product that cc_layer_forward (quantised = 0) or
- * cc_layer_forward_q (quantised != 0) would issue for these M, shapes, dtype and bias on the current device, and
- * keeps the fastest for all later calls of this process. UNLIKE EVERY OTHER CALL IT SYNCHRONISES `stream` and blocks
- * the host for a few milliseconds; it refuses a stream under graph capture. Where the rebuilt-weight route does
- * not apply (few rows, library missing) it does nothing and returns CC_OK. The operands are synthetic, held in
- *   workspace      device, cc_layer_forward_tune_workspace_bytes(M, in_features, out_features), 256-byte aligned
- *   host_times_us  host, [2], may be NULL: time of the algorithm now kept, and of the library's first choice
- * Results do not depend on the algorithm beyond the order of the fp32 accumulation.
- */
-size_t cc_layer_forward_tune_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features);
-int cc_layer_forward_tune(uint64_t M, uint32_t in_features, uint32_t out_features, int dtype, int with_bias,
-                          int quantised, void *workspace, size_t workspace_bytes, float *host_times_us, void *stream);
 
 /*
  * Gradient of the codebook (the only trainable tensor of the layer, Sections 3.2-3.3): every weight entry
@@ -368,8 +352,8 @@ int cc_layer_weight_q(const void *qbook, int bits, const float *scale, uint32_t 
  * multiplies the finished sum, and y is rounded once - so this is slightly more accurate than a product with
  * the 16-bit weight of cc_layer_weight_q, whose entries are each rounded to 16 bits. Same contract otherwise,
  * both routes included (the second from M = 65 on, from M = 17 on for layers of 2^25 weights or more): there the
- * integers q are written out as a 16-bit matrix (exact), the GEMM library returns the fp32 sums, and one more
- * kernel applies scale, bias and the rounding.
+ * integers q are written out as a 16-bit matrix (exact) and transposed, the same matrix-core kernel returns the
+ * fp32 sums, and one more kernel applies scale, bias and the rounding.
  * Workspace: cc_layer_forward_q_workspace_bytes(M, in_features, out_features). */
 size_t cc_layer_forward_q_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features);
 int cc_layer_forward_q(const void *x, uint64_t M, const void *qbook, int bits, const float *scale, uint32_t K,

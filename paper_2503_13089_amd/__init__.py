@@ -27,8 +27,6 @@ from .binding import (  # noqa: F401
     layer_forward,
     layer_forward_q,
     layer_forward_q_workspace_bytes,
-    layer_forward_tune,
-    layer_forward_tune_workspace_bytes,
     layer_forward_workspace_bytes,
     layer_num_codes,
     layer_pack,

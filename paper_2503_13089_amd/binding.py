@@ -19,7 +19,6 @@ EXPORTS = (
     "cc_read_stats", "cc_mfma_f16_probe", "cc_last_error", "cc_version",
     "cc_layer_deficiency", "cc_layer_num_codes", "cc_layer_vectors", "cc_layer_pack", "cc_layer_weight",
     "cc_layer_codebook_grad", "cc_layer_forward", "cc_layer_forward_workspace_bytes",
-    "cc_layer_forward_tune_workspace_bytes", "cc_layer_forward_tune",
     "cc_layer_grad_plan_bytes", "cc_layer_grad_plan_workspace_bytes", "cc_layer_grad_plan",
     "cc_layer_codebook_grad_planned_workspace_bytes", "cc_layer_codebook_grad_planned",
     "cc_layer_compress", "cc_layer_compress_workspace_bytes", "cc_codebook_quantize", "cc_layer_weight_q", "cc_layer_forward_q", "cc_layer_forward_q_workspace_bytes",
@@ -116,11 +115,6 @@ def load_library():
     lib.cc_layer_pack.restype = ctypes.c_int
     lib.cc_layer_weight.argtypes = [vp, ctypes.c_int, u32, u32, vp, u32, u32, vp, vp]
     lib.cc_layer_weight.restype = ctypes.c_int
-    lib.cc_layer_forward_tune_workspace_bytes.argtypes = [u64, u32, u32]
-    lib.cc_layer_forward_tune_workspace_bytes.restype = sz
-    lib.cc_layer_forward_tune.argtypes = [u64, u32, u32, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, sz,
-                                          ctypes.POINTER(ctypes.c_float), vp]
-    lib.cc_layer_forward_tune.restype = ctypes.c_int
     lib.cc_layer_grad_plan_bytes.argtypes = [u64, u32]
     lib.cc_layer_grad_plan_bytes.restype = sz
     lib.cc_layer_grad_plan_workspace_bytes.argtypes = [u64]
@@ -397,24 +391,6 @@ def layer_codebook_grad(grad_weight, codes, K: int, g: int, grad_codebook, works
                                                  out_features, _ptr(codes, torch.uint16, "codes"), K, g,
                                                  _ptr(grad_codebook, torch.float32, "grad_codebook"),
                                                  _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()))
-
-
-def layer_forward_tune_workspace_bytes(M: int, in_features: int, out_features: int) -> int:
-    return load_library().cc_layer_forward_tune_workspace_bytes(M, in_features, out_features)
-
-
-def layer_forward_tune(M: int, in_features: int, out_features: int, dtype, with_bias: bool, quantised: bool, workspace):
-    """Start-up call (synchronises): times the GEMM library's candidates for this product and keeps the fastest.
-    Returns (microseconds of the algorithm kept, of the library's first choice); (0, 0) where nothing applies."""
-    import torch
-
-    code = {torch.float16: 1, torch.bfloat16: 2}.get(dtype)
-    if code is None:
-        raise TypeError("dtype must be torch.float16 or torch.bfloat16")
-    times = (ctypes.c_float * 2)()
-    _check(load_library().cc_layer_forward_tune(M, in_features, out_features, code, int(bool(with_bias)), int(bool(quantised)),
-                                                _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), times, _stream()))
-    return float(times[0]), float(times[1])
 
 
 def layer_grad_plan_bytes(num_codes: int, K: int) -> int:

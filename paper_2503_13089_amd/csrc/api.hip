@@ -585,10 +585,9 @@ size_t cc_layer_forward_workspace_bytes(uint64_t M, uint32_t in_features, uint32
     if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;
     const uint32_t splits = cc::layer_forward_splits(M, in_features, out_features);
     const size_t fused = splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
-    if (!cc::dense_rows(M, in_features, out_features) || !cc::dense_available()) return fused;
-    // the rebuilt 16-bit weight, then the GEMM library's own scratch
-    const size_t dense = cc::align256(size_t(in_features) * out_features * 2) + cc::kDenseScratchBytes;
-    return dense > fused ? dense : fused;
+    if (!cc::dense_rows(M, in_features, out_features)) return fused;
+    // the rebuilt 16-bit weight (transposed), then the fp32 partial tiles of a contraction split over workgroups
+    return cc::align256(size_t(in_features) * out_features * 2) + cc::layer_gemm_partial_bytes(M, in_features, out_features);
 }
 
 int cc_layer_forward(const void* x, uint64_t M, const void* codebook, int dtype, uint32_t K, uint32_t g,
@@ -608,15 +607,12 @@ int cc_layer_forward(const void* x, uint64_t M, const void* codebook, int dtype,
         if (workspace_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (cc::dense_rows(M, in_features, out_features) && cc::dense_available()) {
-        char* scratch = static_cast<char*>(workspace) + cc::align256(size_t(in_features) * out_features * 2);
-        CC_TRY_HIP(cc::launch_layer_weight(codebook, dtype, K, g, codes, in_features, out_features, workspace, s),
-                   "layer weight");
-        const hipError_t e = cc::launch_dense_forward(x, uint32_t(M), workspace, dtype, in_features, out_features, bias, y,
-                                                      false, scratch, s);
-        if (e == hipSuccess) return CC_OK;
-        if (e != hipErrorNotSupported) CC_TRY_HIP(e, "dense product");
-        // no library algorithm for this shape: the fused kernel below serves it
+    if (cc::dense_rows(M, in_features, out_features)) {
+        char* partial = static_cast<char*>(workspace) + cc::align256(size_t(in_features) * out_features * 2);
+        CC_TRY_HIP(cc::launch_layer_weight_t(codebook, K, g, codes, in_features, out_features, workspace, s), "layer weight");
+        CC_TRY_HIP(cc::launch_layer_gemm(x, uint32_t(M), workspace, dtype, in_features, out_features, nullptr, bias, y,
+                                         reinterpret_cast<float*>(partial), s), "dense product");
+        return CC_OK;
     }
     CC_TRY_HIP(cc::launch_layer_forward(x, uint32_t(M), codebook, dtype, K, g, codes, in_features, out_features, bias, y,
                                         static_cast<float*>(workspace), s), "layer forward");
@@ -736,53 +732,6 @@ int cc_layer_weight_q(const void* qbook, int bits, const float* scale, uint32_t 
     return CC_OK;
 }
 
-size_t cc_layer_forward_tune_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features)
-{
-    if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;
-    return cc::align256(size_t(in_features) * out_features * 2) + cc::align256(size_t(M) * in_features * 2) +
-           cc::align256(size_t(M) * out_features * 4) + cc::align256(size_t(out_features) * 2) + cc::kDenseScratchBytes;
-}
-
-int cc_layer_forward_tune(uint64_t M, uint32_t in_features, uint32_t out_features, int dtype, int with_bias, int quantised,
-                          void* workspace, size_t workspace_bytes, float* host_times_us, void* stream)
-{
-    if (host_times_us) host_times_us[0] = host_times_us[1] = 0.0f;
-    if (!workspace) return fail(CC_ERR_NULL, "workspace is NULL");
-    if (int rc = check_layer(in_features, out_features, 1, 1, dtype, false)) return rc;
-    if (M == 0 || M > (1ull << 22)) return fail(CC_ERR_SHAPE, "M = %llu is not in 1..2^22", (unsigned long long)M);
-    if (in_features % 8 != 0) return fail(CC_ERR_SHAPE, "in_features = %u is not a multiple of 8", in_features);
-    if (!aligned(workspace, 256)) return fail(CC_ERR_ALIGN, "workspace must be 256-byte aligned");
-    const size_t need = cc_layer_forward_tune_workspace_bytes(M, in_features, out_features);
-    if (workspace_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
-    const bool routed = quantised ? cc::dense_rows_q(M, in_features, out_features) : cc::dense_rows(M, in_features, out_features);
-    if (!routed || !cc::dense_available()) return CC_OK;  // these calls take the fused kernels: nothing to choose
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
-    CC_TRY_HIP(hipStreamIsCapturing(s, &capturing), "capture query");
-    if (capturing != hipStreamCaptureStatusNone)
-        return fail(CC_ERR_HIP, "cc_layer_forward_tune synchronises and cannot run on a stream that is being captured");
-    char* w = static_cast<char*>(workspace);
-    char* x = w + cc::align256(size_t(in_features) * out_features * 2);
-    char* y = x + cc::align256(size_t(M) * in_features * 2);
-    char* bias = y + cc::align256(size_t(M) * out_features * 4);
-    char* scratch = bias + cc::align256(size_t(out_features) * 2);
-    CC_TRY_HIP(cc::launch_fill_operand(w, size_t(in_features) * out_features, s), "operand fill");
-    CC_TRY_HIP(cc::launch_fill_operand(x, size_t(M) * in_features, s), "operand fill");
-    CC_TRY_HIP(cc::launch_fill_operand(bias, out_features, s), "operand fill");
-    float kept = 0.0f, first = 0.0f;
-    // the quantised route multiplies into fp32 sums and adds the bias afterwards
-    const hipError_t e = cc::tune_dense_forward(x, uint32_t(M), w, dtype, in_features, out_features,
-                                                (with_bias && !quantised) ? bias : nullptr, y, quantised != 0, scratch, s,
-                                                &kept, &first);
-    if (e == hipErrorNotSupported) return CC_OK;  // no algorithm for the shape: the fused kernels serve it
-    CC_TRY_HIP(e, "algorithm timing");
-    if (host_times_us) {
-        host_times_us[0] = kept;
-        host_times_us[1] = first;
-    }
-    return CC_OK;
-}
-
 size_t cc_layer_grad_plan_bytes(uint64_t num_codes, uint32_t K)
 {
     if (num_codes == 0 || num_codes >= (1ull << 32) || K == 0 || K > 65536) return 0;
@@ -844,10 +793,10 @@ size_t cc_layer_forward_q_workspace_bytes(uint64_t M, uint32_t in_features, uint
     if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;
     const uint32_t splits = cc::layer_forward_q_max_splits(M, in_features, out_features);
     const size_t fused = splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
-    if (!cc::dense_rows_q(M, in_features, out_features) || !cc::dense_available()) return fused;
-    // the integer weight in 16 bits, the fp32 sums, one constant, then the GEMM library's own scratch
-    const size_t dense = cc::align256(size_t(in_features) * out_features * 2) + cc::align256(size_t(M) * out_features * 4) +
-                         256 + cc::kDenseScratchBytes;
+    if (!cc::dense_rows_q(M, in_features, out_features)) return fused;
+    // the integer weight in 16 bits, its transpose, one constant, then the fp32 sums of the product
+    const size_t dense = 2 * cc::align256(size_t(in_features) * out_features * 2) + 256 +
+                         cc::layer_gemm_partial_bytes(M, in_features, out_features);
     return dense > fused ? dense : fused;
 }
 
@@ -870,21 +819,20 @@ int cc_layer_forward_q(const void* x, uint64_t M, const void* qbook, int bits, c
         if (workspace_bytes < need) return fail(CC_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (cc::dense_rows_q(M, in_features, out_features) && cc::dense_available()) {
+    if (cc::dense_rows_q(M, in_features, out_features)) {
+        // the integers q themselves as a 16-bit matrix (exact), transposed, multiplied into fp32 sums; scale and bias
+        // meet the finished sum
         char* base = static_cast<char*>(workspace);
-        float* sums = reinterpret_cast<float*>(base + cc::align256(size_t(in_features) * out_features * 2));
-        float* one = reinterpret_cast<float*>(reinterpret_cast<char*>(sums) + cc::align256(size_t(M) * out_features * 4));
-        char* scratch = reinterpret_cast<char*>(one) + 256;
+        const size_t wbytes = cc::align256(size_t(in_features) * out_features * 2);
+        char* wt = base + wbytes;
+        float* one = reinterpret_cast<float*>(wt + wbytes);
+        float* sums = reinterpret_cast<float*>(reinterpret_cast<char*>(one) + 256);
         CC_TRY_HIP(cc::launch_layer_weight_q_integers(qbook, bits, K, g, codes, in_features, out_features, dtype, base, one, s),
                    "integer weight");
-        const hipError_t e = cc::launch_dense_forward(x, uint32_t(M), base, dtype, in_features, out_features, nullptr, sums,
-                                                      true, scratch, s);
-        if (e == hipSuccess) {
-            CC_TRY_HIP(cc::launch_forward_q_finish(sums, uint32_t(M), out_features, scale, bias, y, dtype, s), "scale and bias");
-            return CC_OK;
-        }
-        if (e != hipErrorNotSupported) CC_TRY_HIP(e, "dense product");
-        // no library algorithm for this shape: the fused kernel below serves it
+        CC_TRY_HIP(cc::launch_transpose16(base, in_features, out_features, wt, s), "transpose");
+        CC_TRY_HIP(cc::launch_layer_gemm(x, uint32_t(M), wt, dtype, in_features, out_features, scale, bias, y, sums, s),
+                   "dense product");
+        return CC_OK;
     }
     CC_TRY_HIP(cc::launch_layer_forward_q(x, uint32_t(M), qbook, bits, scale, K, g, codes, in_features, out_features, bias, y,
                                           dtype, static_cast<float*>(workspace), s),

@@ -310,7 +310,7 @@ hipError_t launch_layer_grad_plan(const uint16_t* codes, uint32_t n, uint32_t K,
 hipError_t launch_layer_grad_planned(const void* grad, int dtype, uint32_t in_features, uint32_t out_features, uint32_t K,
                                      uint32_t g, uint32_t n, const void* plan, float* grad_codebook, void* workspace,
                                      hipStream_t s);
-// ---- prefill-sized batches (dense.hip): W rebuilt into memory, then the vendor library's GEMM
+// ---- prefill-sized batches (layer_gemm.hip): W rebuilt into memory, then one dense product on the matrix cores
 // From where on the rebuilt-weight route is the faster one: 128 rows for any layer, fewer for a large one, where
 // the fused kernels repeat their gathers per row tile and the rebuild (47 us for 45 M weights) is small against
 // the product. Measured on 4096 x 4096, 4096 x 11008, 8192 x 8192 and 11008 x 4096 (bf16, K = 65536, g = 4;
@@ -328,15 +328,15 @@ inline bool dense_rows_q(uint64_t M, uint32_t in_features, uint32_t out_features
     const bool large = uint64_t(in_features) * out_features >= (1ull << 25);
     return M > 64 || (large && M > 16);
 }
-constexpr size_t kDenseScratchBytes = 64u << 20;   // what the GEMM library may use for itself
-bool dense_available();
-hipError_t launch_dense_forward(const void* x, uint32_t M, const void* weight, int dtype, uint32_t in_features,
-                                uint32_t out_features, const void* bias, void* y, bool f32_out, void* scratch,
-                                hipStream_t s);
-hipError_t launch_fill_operand(void* p, size_t n16, hipStream_t s);
-hipError_t tune_dense_forward(const void* x, uint32_t M, const void* weight, int dtype, uint32_t in_features,
-                              uint32_t out_features, const void* bias, void* y, bool f32_out, void* scratch, hipStream_t s,
-                              float* kept_us, float* first_us);
+// layer_gemm.hip: the weight rebuilt transposed (wt [out][in], contiguous along the contraction), a plain 16-bit
+// transpose, and y [M][out] = x [M][in] . wt^T (scale: device pointer or NULL, multiplies the finished sum; partial:
+// layer_gemm_partial_bytes(...) bytes of fp32 tiles for the tiles whose contraction is cut into slices)
+size_t layer_gemm_partial_bytes(uint64_t M, uint32_t in_features, uint32_t out_features);
+hipError_t launch_layer_weight_t(const void* codebook, uint32_t K, uint32_t g, const uint16_t* codes, uint32_t in_features,
+                                 uint32_t out_features, void* wt, hipStream_t s);
+hipError_t launch_transpose16(const void* w, uint32_t rows, uint32_t cols, void* wt, hipStream_t s);
+hipError_t launch_layer_gemm(const void* x, uint32_t M, const void* wt, int dtype, uint32_t in_features, uint32_t out_features,
+                             const float* scale, const void* bias, void* y, float* partial, hipStream_t s);
 // ---- uniformly quantised codebook (layer_quant.hip); bits = 8 or 4
 hipError_t launch_codebook_quantize(const float* centroids, size_t n, int bits, void* qbook, float* scale,
                                     uint32_t* absmax_scratch, hipStream_t s);
