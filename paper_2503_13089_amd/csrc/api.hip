@@ -194,7 +194,9 @@ int run_lloyd_iter(const Ctx& cx, const float* X, uint32_t N, uint32_t d, float*
         if (int rc = run_assign_matrix(cx, X, N, d, C, K, idx, w, !by_buckets, pruned, have_hint, s, sums_follow)) return rc;
         {
             cc::ProfileScope mstep_scope(cx.prof, cc::kProfMstep, s);
-            if (by_buckets)
+            if (by_buckets && !sums_follow && cc::update_sliced_applies(N, d, K, w))
+                CC_TRY_HIP(cc::launch_update_sliced(w.xsorted, N, d, w.idx_sorted, C, K, C, counts, w, true, s), "update (slices)");
+            else if (by_buckets)
                 CC_TRY_HIP(cc::launch_update_buckets(w.xsorted, N, d, w.idx_sorted, C, K, C, counts, w, true, true, s,
                                                      sums_follow ? w.idx_prev : nullptr, sums_follow ? w.changed : nullptr),
                            "update (buckets)");

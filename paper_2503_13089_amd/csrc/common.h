@@ -279,6 +279,12 @@ hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const u
                                  uint32_t K, float* out, uint32_t* counts_out, const Workspace& w, bool norm_order,
                                  bool mean, hipStream_t s, const uint32_t* prev_idx = nullptr,
                                  const uint32_t* changed = nullptr);
+// M-step by cluster slices (update_sliced.hip): one pass over the codes per slice of the clusters, LDS accumulators,
+// no copy of the vectors; for N >= 2^20 and K <= 65536. Same integer sums (left in w.sums / w.counts) and the same
+// result bits as the other formulations. `out` may alias `prev`.
+bool update_sliced_applies(uint32_t N, uint32_t d, uint32_t K, const Workspace& w);
+hipError_t launch_update_sliced(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev, uint32_t K,
+                                float* out, uint32_t* counts_out, const Workspace& w, bool mean, hipStream_t s);
 // out[i][j] = j < d_in ? in[i][j] : 0 for rows of d_out >= d_in floats, and the reverse (drop the tail).
 hipError_t launch_pad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s);
 hipError_t launch_unpad_rows(const float* in, uint32_t n, uint32_t d_in, uint32_t d_out, float* out, hipStream_t s);

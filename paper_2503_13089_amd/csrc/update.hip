@@ -189,7 +189,10 @@ hipError_t launch_update(const float* X, uint32_t N, uint32_t d, const uint32_t*
                          float* out, uint32_t* counts_out, const Workspace& w, bool mean, hipStream_t s)
 {
     hipError_t e;
-    if (w.bucket_ok && N >= 32768) {
+    if (update_sliced_applies(N, d, K, w)) {
+        // many vectors: one pass over the codes per slice of the clusters, sums in LDS, the vectors are not copied
+        return launch_update_sliced(X, N, d, idx, prev, K, out, counts_out, w, mean, s);
+    } else if (w.bucket_ok && N >= 32768) {
         // memory-side atomics are the bottleneck of the scatter formulation: group by bucket, sum in LDS
         return launch_update_buckets(X, N, d, idx, prev, K, out, counts_out, w, false, mean, s);
     } else {

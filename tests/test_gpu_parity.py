@@ -154,6 +154,35 @@ def test_update_lockstep(g, N, d, K):
         assert np.array_equal(got[5], C0[5])
 
 
+@pytest.mark.parametrize("N,d,K", [(1048576 + 1235, 4, 5000), (1048576 + 77, 8, 65536), (1100003, 16, 2049), (1048576, 4, 70),
+                                   (1200001, 6, 9001)])
+def test_update_by_slices_matches_the_oracle(g, N, d, K):
+    """From 2^20 vectors on the M-step runs by cluster slices (LDS accumulators, one pass over the codes per slice):
+    ragged vector ranges, a last slice that is not full, slices that no vector falls into, codes out of range."""
+    rng = np.random.default_rng(N + K)
+    X = (rng.standard_normal((N, d)) * 0.02).astype(np.float16).astype(np.float32)
+    idx = rng.integers(0, K, size=N).astype(np.uint32)
+    idx[rng.integers(0, N, size=N // 3)] = rng.integers(0, max(1, K // 50))   # a crowded low slice
+    empty = np.unique(rng.integers(0, K, size=5))
+    idx[np.isin(idx, empty)] = (empty[0] + 1) % K if K > 1 else 0              # some clusters without members
+    prev = rng.standard_normal((K, d)).astype(np.float32)
+    print(f"update by slices N={N} d={d} K={K}", flush=True)
+    want, counts = oracle.update(X, idx, prev)
+    got, gcounts, stats = g.gpu_update(X, idx, prev)
+    assert stats.skipped_vectors == 0 and np.array_equal(gcounts, counts)
+    assert got.tobytes() == want.tobytes()
+    # codes >= K are skipped and counted
+    bad = idx.copy()
+    where = rng.choice(N, size=11, replace=False)
+    bad[where] = K + rng.integers(0, 1000, size=11).astype(np.uint32)
+    keep = np.ones(N, bool)
+    keep[where] = False
+    want2, counts2 = oracle.update(X[keep], idx[keep], prev)
+    got2, gcounts2, stats2 = g.gpu_update(X, bad, prev)
+    assert stats2.skipped_vectors == 11 and np.array_equal(gcounts2, counts2)
+    assert got2.tobytes() == want2.tobytes()
+
+
 def test_update_general_fp32_inputs_and_bad_codes(g):
     X, C0 = workloads.make_small(50000, 8, 300, seed=5, fp16_round=False)
     X[:100] *= 1e-6   # a wide dynamic range
