@@ -36,7 +36,15 @@ VALU_ISSUE_PEAK = 1024 * 2.4e9 / 4   # wave-instructions/s: 1024 SIMDs, one 64-l
 # HBM bytes per launch from rocprofv3 counter runs of `bench.py --only <kernel>` (FETCH_SIZE and WRITE_SIZE in KiB per
 # dispatch, averaged over the kernel's launches, each scaled by what the same counter reads for a plain device copy of
 # known size; the summaries and the factors are in profiles/pmc_*.md). Keyed by (workload, kernel).
-MEASURED_TRAFFIC_BYTES = {}
+# cfg3 figures from profiles/pmc_bench_cfg3.md: FETCH_SIZE x 1.988, WRITE_SIZE x 0.994 (a device copy of 180.4 MB
+# reads 44,300 KiB x 2 dispatches on FETCH_SIZE and writes 88,580 KiB x 2 on WRITE_SIZE).
+_KIB = 1024.0
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg3_4096x11008_d4_k65536", "fit_estep"): (147500 * 1.988 + 97360 * 0.994) * _KIB,     # windowed kernel, mean of 44 launches
+    ("cfg3_4096x11008_d4_k65536", "estep_whole"): (294000 * 1.988 + 88480 * 0.994) * _KIB,
+    ("cfg3_4096x11008_d4_k65536", "update"): ((110200 + 18450) * 1.988 + (36860 + 3328) * 0.994) * _KIB,  # both kernels
+    ("cfg3_4096x11008_d4_k65536", "decode"): (26120 * 1.988 + 176100 * 0.994) * _KIB,
+}
 
 
 def cpu_baseline(w, X, C0, sample_log2=20):
@@ -193,7 +201,7 @@ def main():
     ap.add_argument("--no-other-configs", action="store_true")
     ap.add_argument("--no-layer-kernels", action="store_true")
     ap.add_argument("--assign-mode", type=int, default=0)
-    ap.add_argument("--only", choices=["fit", "estep_whole", "estep_f32", "update", "decode", "copy"], default=None,
+    ap.add_argument("--only", choices=["fit", "estep_whole", "estep_f32", "update", "decode", "layer_forward"], default=None,
                     help="run just this part a few times and exit (for rocprofv3 counter runs; prints no JSON)")
     ap.add_argument("--model", choices=sorted(MODEL_SHAPES), default=None,
                     help="instead of the default benchmark: cluster every linear layer of a model of this shape "
@@ -437,7 +445,19 @@ def other_configs(cc, torch, workloads, skip, mode):
 def only_job(cc, torch, args, w, Xd, Cd, C0d, idx, J, out, ws):
     """One part of the benchmark, a few launches, nothing else: what a rocprofv3 counter run is pointed at."""
     K = w.K
-    if args.only == "fit":
+    if args.only == "layer_forward":
+        # the benchmark matrix as a linear layer (in = rows, out = cols) at a prefill batch of 2048 rows
+        bf = torch.bfloat16
+        in_features, out_features, g = w.rows, w.cols, w.d
+        n = cc.layer_num_codes(in_features, out_features, g)
+        book = (torch.randn(K, g, device="cuda") * 0.02).to(bf)
+        codes = torch.randint(0, K, (n,), device="cuda", dtype=torch.int32).to(torch.uint16)
+        x = torch.randn(2048, in_features, device="cuda").to(bf)
+        y = torch.empty(2048, out_features, dtype=bf, device="cuda")
+        fws = torch.empty(cc.layer_forward_workspace_bytes(2048, in_features, out_features), dtype=torch.uint8, device="cuda")
+        for _ in range(5):
+            cc.layer_forward(x, book, codes, out_features, None, y, fws)
+    elif args.only == "fit":
         for _ in range(2):
             cc.kmeans_fit(Xd, K, args.steps, C0d, Cd, idx, J, ws, assign_mode=args.assign_mode)
     else:
