@@ -588,8 +588,9 @@ size_t cc_layer_forward_workspace_bytes(uint64_t M, uint32_t in_features, uint32
     const uint32_t splits = cc::layer_forward_splits(M, in_features, out_features);
     const size_t fused = splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
     if (!cc::dense_rows(M, in_features, out_features)) return fused;
-    // the rebuilt 16-bit weight (transposed), then the fp32 partial tiles of a contraction split over workgroups
-    return cc::align256(size_t(in_features) * out_features * 2) + cc::layer_gemm_partial_bytes(M, in_features, out_features);
+    // the rebuilt 16-bit weight (matrix-core operand layout), then the fp32 partial tiles of a contraction split over
+    // workgroups
+    return cc::layer_weight_frag_bytes(in_features, out_features) + cc::layer_gemm_partial_bytes(M, in_features, out_features);
 }
 
 int cc_layer_forward(const void* x, uint64_t M, const void* codebook, int dtype, uint32_t K, uint32_t g,
@@ -610,8 +611,8 @@ int cc_layer_forward(const void* x, uint64_t M, const void* codebook, int dtype,
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (cc::dense_rows(M, in_features, out_features)) {
-        char* partial = static_cast<char*>(workspace) + cc::align256(size_t(in_features) * out_features * 2);
-        CC_TRY_HIP(cc::launch_layer_weight_t(codebook, K, g, codes, in_features, out_features, workspace, s), "layer weight");
+        char* partial = static_cast<char*>(workspace) + cc::layer_weight_frag_bytes(in_features, out_features);
+        CC_TRY_HIP(cc::launch_layer_weight_frag(codebook, K, g, codes, in_features, out_features, workspace, s), "layer weight");
         CC_TRY_HIP(cc::launch_layer_gemm(x, uint32_t(M), workspace, dtype, in_features, out_features, nullptr, bias, y,
                                          reinterpret_cast<float*>(partial), s), "dense product");
         return CC_OK;
@@ -790,14 +791,19 @@ int cc_layer_codebook_grad_planned(const void* grad_weight, int grad_dtype, uint
     return CC_OK;
 }
 
+namespace {
+constexpr size_t kIntegerBookBytes = size_t(65536) * 16 * 2;  // K <= 65536 codes of g <= 16 entries, 16 bits each
+}
+
 size_t cc_layer_forward_q_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features)
 {
     if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;
     const uint32_t splits = cc::layer_forward_q_max_splits(M, in_features, out_features);
     const size_t fused = splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
     if (!cc::dense_rows_q(M, in_features, out_features)) return fused;
-    // the integer weight in 16 bits, its transpose, one constant, then the fp32 sums of the product
-    const size_t dense = 2 * cc::align256(size_t(in_features) * out_features * 2) + 256 +
+    // the integer weight in 16 bits (matrix-core operand layout), the integer codebook in 16 bits (at most 65536 x 16
+    // entries), then the fp32 partial tiles of the product
+    const size_t dense = cc::layer_weight_frag_bytes(in_features, out_features) + kIntegerBookBytes +
                          cc::layer_gemm_partial_bytes(M, in_features, out_features);
     return dense > fused ? dense : fused;
 }
@@ -822,17 +828,14 @@ int cc_layer_forward_q(const void* x, uint64_t M, const void* qbook, int bits, c
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (cc::dense_rows_q(M, in_features, out_features)) {
-        // the integers q themselves as a 16-bit matrix (exact), transposed, multiplied into fp32 sums; scale and bias
-        // meet the finished sum
-        char* base = static_cast<char*>(workspace);
-        const size_t wbytes = cc::align256(size_t(in_features) * out_features * 2);
-        char* wt = base + wbytes;
-        float* one = reinterpret_cast<float*>(wt + wbytes);
-        float* sums = reinterpret_cast<float*>(reinterpret_cast<char*>(one) + 256);
-        CC_TRY_HIP(cc::launch_layer_weight_q_integers(qbook, bits, K, g, codes, in_features, out_features, dtype, base, one, s),
-                   "integer weight");
-        CC_TRY_HIP(cc::launch_transpose16(base, in_features, out_features, wt, s), "transpose");
-        CC_TRY_HIP(cc::launch_layer_gemm(x, uint32_t(M), wt, dtype, in_features, out_features, scale, bias, y, sums, s),
+        // the integers q themselves as a 16-bit codebook (exact), gathered into the operand layout and multiplied into
+        // fp32 sums; scale and bias meet the finished sum
+        char* wf = static_cast<char*>(workspace);
+        char* book16 = wf + cc::layer_weight_frag_bytes(in_features, out_features);
+        float* sums = reinterpret_cast<float*>(book16 + kIntegerBookBytes);
+        CC_TRY_HIP(cc::launch_codebook_integers16(qbook, bits, K, g, dtype, book16, s), "integer codebook");
+        CC_TRY_HIP(cc::launch_layer_weight_frag(book16, K, g, codes, in_features, out_features, wf, s), "integer weight");
+        CC_TRY_HIP(cc::launch_layer_gemm(x, uint32_t(M), wf, dtype, in_features, out_features, scale, bias, y, sums, s),
                    "dense product");
         return CC_OK;
     }

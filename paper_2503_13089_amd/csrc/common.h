@@ -317,31 +317,37 @@ hipError_t launch_layer_grad_planned(const void* grad, int dtype, uint32_t in_fe
                                      uint32_t g, uint32_t n, const void* plan, float* grad_codebook, void* workspace,
                                      hipStream_t s);
 // ---- prefill-sized batches (layer_gemm.hip): W rebuilt into memory, then one dense product on the matrix cores
-// From where on the rebuilt-weight route is the faster one: 128 rows for any layer, fewer for a large one, where
-// the fused kernels repeat their gathers per row tile and the rebuild (47 us for 45 M weights) is small against
-// the product. Measured on 4096 x 4096, 4096 x 11008, 8192 x 8192 and 11008 x 4096 (bf16, K = 65536, g = 4;
-// fused / rebuilt + dense, us): 16-bit codebook, 4096 x 11008 at 33 rows 102 / 78, at 96 rows 169 / 83;
-// 8192 x 8192 at 64 rows 100 / 130, at 96 rows 167 / 134; 4-bit codebook, 4096 x 11008 at 32 rows 140 / 73,
-// 8192 x 8192 at 33 rows 147 / 103, 4096 x 4096 at 64 rows 60 / 72, at 96 rows 105 / 72.
-constexpr uint64_t kDenseMinM = 128;
+// From where on the rebuilt-weight route is the faster one. The fused kernels repeat their gathers per row tile (32,
+// 64, 96, ... rows), the rebuild costs the same for any number of rows (58 us for 45 M weights). Measured on
+// 4096 x 4096, 4096 x 11008, 11008 x 4096 and 8192 x 8192 (bf16, K = 65536, g = 4; fused / rebuilt + product, us):
+// 16-bit codebook: 4096 x 4096 at 64 rows 40 / 51, at 96 rows 59 / 53; 4096 x 11008 at 32 rows 71 / 94, at 48 rows
+// 108 / 94; 11008 x 4096 at 64 rows 73 / 94, at 96 rows 121 / 97; 8192 x 8192 at 64 rows 99 / 130, at 96 rows 165 / 133.
+// 4-bit codebook (the integer codebook is expanded first, + 5 us): 4096 x 4096 at 32 rows 49 / 55, at 48 rows 58 / 55;
+// 4096 x 11008 at 8 rows 56 / 96, at 16 rows 109 / 97; 11008 x 4096 at 16 rows 85 / 96, at 24 rows 99 / 97, at 32 rows
+// 101 / 97; 8192 x 8192 at 16 rows 112 / 131, at 32 rows 136 / 132, at 48 rows 150 / 134.
 inline bool dense_rows(uint64_t M, uint32_t in_features, uint32_t out_features)
 {
-    const bool large = uint64_t(in_features) * out_features >= (1ull << 25);
-    return M >= kDenseMinM || (large && (M > 64 || (M > 32 && out_features >= 2 * uint64_t(in_features))));
+    const uint64_t weights = uint64_t(in_features) * out_features;
+    if (weights < (1ull << 24)) return M >= 128;
+    return M > 64 || (weights >= (1ull << 25) && M > 32 && out_features >= 2 * uint64_t(in_features));
 }
 inline bool dense_rows_q(uint64_t M, uint32_t in_features, uint32_t out_features)  // quantised codebook
 {
-    const bool large = uint64_t(in_features) * out_features >= (1ull << 25);
-    return M > 64 || (large && M > 16);
+    const uint64_t weights = uint64_t(in_features) * out_features;
+    if (weights < (1ull << 24)) return M > 64;
+    if (weights >= (1ull << 25) && out_features >= 2 * uint64_t(in_features)) return M >= 16;
+    return M > 32;
 }
-// layer_gemm.hip: the weight rebuilt transposed (wt [out][in], contiguous along the contraction), a plain 16-bit
-// transpose, and y [M][out] = x [M][in] . wt^T (scale: device pointer or NULL, multiplies the finished sum; partial:
-// layer_gemm_partial_bytes(...) bytes of fp32 tiles for the tiles whose contraction is cut into slices)
+// layer_gemm.hip: the weight rebuilt in the register layout of the matrix cores' B operand (layer_weight_frag_bytes
+// bytes), the integers of a quantised codebook as a 16-bit codebook for that rebuild, and y [M][out] = x [M][in] . W
+// (scale: device pointer or NULL, multiplies the finished sum; partial: layer_gemm_partial_bytes(...) bytes of fp32
+// tiles for the tiles whose contraction is cut into slices)
 size_t layer_gemm_partial_bytes(uint64_t M, uint32_t in_features, uint32_t out_features);
-hipError_t launch_layer_weight_t(const void* codebook, uint32_t K, uint32_t g, const uint16_t* codes, uint32_t in_features,
-                                 uint32_t out_features, void* wt, hipStream_t s);
-hipError_t launch_transpose16(const void* w, uint32_t rows, uint32_t cols, void* wt, hipStream_t s);
-hipError_t launch_layer_gemm(const void* x, uint32_t M, const void* wt, int dtype, uint32_t in_features, uint32_t out_features,
+size_t layer_weight_frag_bytes(uint32_t in_features, uint32_t out_features);
+hipError_t launch_layer_weight_frag(const void* codebook, uint32_t K, uint32_t g, const uint16_t* codes, uint32_t in_features,
+                                    uint32_t out_features, void* wf, hipStream_t s);
+hipError_t launch_codebook_integers16(const void* qbook, int bits, uint32_t K, uint32_t g, int dtype, void* book16, hipStream_t s);
+hipError_t launch_layer_gemm(const void* x, uint32_t M, const void* wf, int dtype, uint32_t in_features, uint32_t out_features,
                              const float* scale, const void* bias, void* y, float* partial, hipStream_t s);
 // ---- uniformly quantised codebook (layer_quant.hip); bits = 8 or 4
 hipError_t launch_codebook_quantize(const float* centroids, size_t n, int bits, void* qbook, float* scale,
@@ -353,13 +359,6 @@ uint32_t layer_forward_q_max_splits(uint64_t M, uint32_t in_features, uint32_t o
 hipError_t launch_layer_forward_q(const void* x, uint32_t M, const void* qbook, int bits, const float* scale, uint32_t K,
                                   uint32_t g, const uint16_t* codes, uint32_t in_features, uint32_t out_features,
                                   const void* bias, void* y, int dtype, float* partial, hipStream_t s);
-// the integers q themselves as a 16-bit weight (`one`: a device float this call sets to 1), and the finish of fp32
-// sums [M][out_features]: y = round(scale * sum (+ bias))
-hipError_t launch_layer_weight_q_integers(const void* qbook, int bits, uint32_t K, uint32_t g, const uint16_t* codes,
-                                          uint32_t in_features, uint32_t out_features, int dtype, void* weight, float* one,
-                                          hipStream_t s);
-hipError_t launch_forward_q_finish(const float* sums, uint32_t M, uint32_t out_features, const float* scale, const void* bias,
-                                   void* y, int dtype, hipStream_t s);
 // grad_weight [in, out] (dtype) -> fp32 vectors [num_codes][d_pad] (zero padding columns and components) and
 // codes widened to 32 bits
 hipError_t launch_layer_grad_vectors(const void* grad, int dtype, uint32_t in_features, uint32_t out_features,

@@ -1,22 +1,25 @@
 // Forward pass of the compressed linear layer at prefill-sized batches (the paper's layer listing: rebuild the
 // weight from (codebook, codes), then y = x . W + bias), as two hand-written kernels:
 //
-//   1. layer_weight_t_kernel: the listing's gather, written TRANSPOSED: Wt[n][k] = codebook[code(k, n)][n % g], so
-//      that both operands of the product are contiguous along the contraction index, which is what the matrix
-//      cores' operand registers want (8 consecutive k per lane). 64 x 64 tiles through LDS: codes are read along a
-//      row of W, Wt is written along its own rows, both in full cache lines.
-//   2. gemm_tn_kernel: y[M][N] = x[M][K] . Wt[N][K]^T on v_mfma_f32_32x32x16_{bf16,f16}. A workgroup of 4 waves owns
-//      a 256 x 128 tile of y (each wave 128 x 64 = 4 x 2 accumulator tiles of 32 x 32, held in registers for the
-//      whole contraction), steps through K in slices of 64, and stages both operand slices in LDS, double-buffered:
-//      the next slice travels global -> registers while the current one is multiplied, then registers -> LDS, one
-//      barrier per slice. LDS rows are padded to 72 halves (36 words) so that the 16-byte fragment reads of a
-//      half-wave fall on 16 different bank quads. Products of two 16-bit values are exact in fp32; the sum is fp32
-//      in a fixed order; bias (and, for the quantised codebook, the scale) are applied to the finished sum and y is
-//      rounded once.
+//   1. layer_weight_frag_kernel: the listing's gather, written straight into the register layout of the matrix
+//      cores' B operand. One fragment = 32 output columns x 16 in-features = 64 lanes x 8 consecutive k = 1 KB, lane
+//      (n % 32) + 32 ((k % 16) / 8); fragments of one column block are contiguous along k. 64 x 64 tiles through LDS:
+//      codes are read along a row of W, fragments leave in whole cache lines. Padding (columns past out_features,
+//      in-features past the end of the last fragment) is written as zeros.
+//   2. gemm_frag_kernel: y[M][N] = x[M][K] . W on v_mfma_f32_32x32x16_{bf16,f16}. A workgroup owns a 256-row tile of
+//      y, each wave 128 x 64 of it (4 x 2 accumulator tiles of 32 x 32, in registers for the whole contraction), and
+//      steps through K in slices of 32. Only x goes through LDS (double-buffered: the next slice travels global ->
+//      registers while the current one is multiplied, then registers -> LDS, one barrier per slice; rows padded to
+//      40 halves so that the 16-byte fragment reads of 16 lanes fall on 16 different bank quads). The fragments of W
+//      come from memory as they are - one fully coalesced 1 KB load per fragment, requested two slices ahead - which
+//      takes a third of the traffic off LDS, the unit that bounds this kernel. Products of two 16-bit values are
+//      exact in fp32; the sum is fp32 in a fixed order; bias (and, for the quantised codebook, the scale) are
+//      applied to the finished sum and y is rounded once.
 //      Workgroups are numbered so that one XCD (they are dealt to the 8 XCDs in turn) works on neighbouring column
-//      panels with all row panels of x: its L2 then holds the Wt panels it is using, and x comes once per XCD.
-//      Few tiles (M of a few hundred): the contraction is also split over workgroups, fp32 partial tiles go to the
-//      workspace and a second kernel adds them in a fixed order - the result never depends on scheduling.
+//      panels with all row panels of x: its L2 then holds the fragments it is using, and x comes once per XCD.
+//      Tiles that do not fill a round of the chip's workgroup slots are cut along the contraction: fp32 partial
+//      tiles go to the workspace and a second kernel adds them in a fixed order - the result never depends on
+//      scheduling.
 //
 // Bound: the bf16 / fp16 matrix cores (2 M N K flop against 2.5 PFLOP/s); the rebuild is HBM-bound (2 bytes written
 // per weight).
@@ -28,11 +31,17 @@ namespace cc {
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int BM = 256, BN = 128, BK = 32;
+constexpr int kThreads = 256;               // rebuild and finishing kernels
+#ifndef CC_GEMM_WN
+#define CC_GEMM_WN 4
+#endif
+constexpr int WN = CC_GEMM_WN;              // waves along the columns of a tile (2 along its rows)
+constexpr int kGemmThreads = 128 * WN;
+constexpr int BM = 256, BN = 64 * WN, BK = 32;
 constexpr int LDT = BK + 8;                 // halves per LDS row (20 words: the 16-byte reads of 16 lanes hit 16 bank quads)
-constexpr int kStageHalves = (BM + BN) * LDT;
-constexpr uint32_t kGemmLdsBytes = 2 * kStageHalves * 2;   // 61,440 bytes: two workgroups per CU
+constexpr int kStageHalves = BM * LDT;
+constexpr uint32_t kGemmLdsBytes = 2 * kStageHalves * 2;   // 40,960 bytes
+constexpr int kFragHalves = 512;            // one B operand: 32 columns x 16 in-features
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -67,17 +76,18 @@ __device__ __forceinline__ uint16_t from_f32(float v)
     }
 }
 
-// ---- 1. transposed rebuild: Wt[n][k], n < out_features, k < in_features, row length ldk = in_features
+// ---- 1. rebuild into B-operand fragments: column block nb = n / 32, in-feature block kb = k / 16, fragment
+// (nb * KB + kb) with KB = ceil(in_features / 16) blocks per column block, lane (n % 32) + 32 ((k % 16) / 8), 8 halves
 // Three steps per 64 x 64 tile: the tile's codes (64 rows of W, the code columns that touch the tile) go to LDS with
 // reads along the rows of the code matrix; then a wave takes one code column and its 64 lanes the 64 rows, so that
 // the elements they write into the transposed tile are neighbours in LDS (lanes along n would hit the same banks);
-// then the tile leaves in 16-byte pieces along k.
+// then the tile leaves as 2 x 4 fragments, 64 lanes x 16 bytes each.
 constexpr int kWtTile = 64;
 constexpr int kWtMaxCols = kWtTile + 2;  // code columns touching a tile: at most 64 / g + 2 <= 66 for g >= 1
-__global__ __launch_bounds__(kThreads) void layer_weight_t_kernel(const uint16_t* __restrict__ codebook, uint32_t K, uint32_t g,
-                                                                  const uint16_t* __restrict__ codes, uint32_t per_row,
-                                                                  uint32_t in_features, uint32_t out_features,
-                                                                  uint16_t* __restrict__ wt)
+__global__ __launch_bounds__(kThreads) void layer_weight_frag_kernel(const uint16_t* __restrict__ codebook, uint32_t K, uint32_t g,
+                                                                     const uint16_t* __restrict__ codes, uint32_t per_row,
+                                                                     uint32_t in_features, uint32_t out_features,
+                                                                     uint32_t NB, uint32_t KB, uint16_t* __restrict__ wf)
 {
     constexpr int T = kWtTile, LT = T + 8;
     __shared__ __attribute__((aligned(16))) uint16_t tile[T * LT];  // [n][k]
@@ -87,14 +97,19 @@ __global__ __launch_bounds__(kThreads) void layer_weight_t_kernel(const uint16_t
     const uint32_t cn_hi = min((n_lo + T - 1) / g, per_row - 1);
     const uint32_t cpr = cn_hi - cn_lo + 1;  // code columns that touch this tile
     const uint32_t items = T * cpr;
+    const bool edge = n_lo + T > out_features || k0 + T > in_features;
+    if (edge)  // padding is stored too, as zeros
+        for (uint32_t e = threadIdx.x; e < T * LT / 2; e += kThreads) reinterpret_cast<uint32_t*>(tile)[e] = 0u;
     for (uint32_t it = threadIdx.x; it < items; it += kThreads) {
         const uint32_t kr = it / cpr, c = it % cpr;
-        const uint32_t k = min(k0 + kr, in_features - 1);  // rows past the edge are never stored
+        const uint32_t k = min(k0 + kr, in_features - 1);
         ctile[kr * cpr + c] = codes[size_t(k) * per_row + cn_lo + c];
     }
     __syncthreads();
+    const int n_end = int(min(uint32_t(T), out_features - n_lo));
     for (uint32_t it = threadIdx.x; it < items; it += kThreads) {
         const uint32_t c = it / T, kr = it % T;
+        if (k0 + kr >= in_features) continue;
         const uint32_t code = min(uint32_t(ctile[kr * cpr + c]), K - 1);
         const uint16_t* row = codebook + size_t(code) * g;
         const int nbase = int((cn_lo + c) * g) - int(n_lo);
@@ -104,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void layer_weight_t_kernel(const uint16_t
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int n = nbase + j;
-                if (n >= 0 && n < T) tile[n * LT + kr] = e[j];
+                if (n >= 0 && n < n_end) tile[n * LT + kr] = e[j];
             }
         } else if (g == 8) {
             const uint4 r = *reinterpret_cast<const uint4*>(row);
@@ -112,44 +127,41 @@ __global__ __launch_bounds__(kThreads) void layer_weight_t_kernel(const uint16_t
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int n = nbase + j;
-                if (n >= 0 && n < T) tile[n * LT + kr] = uint16_t(w[j >> 1] >> (16 * (j & 1)));
+                if (n >= 0 && n < n_end) tile[n * LT + kr] = uint16_t(w[j >> 1] >> (16 * (j & 1)));
             }
         } else {
             for (uint32_t j = 0; j < g; ++j) {
                 const int n = nbase + int(j);
-                if (n >= 0 && n < T) tile[n * LT + kr] = row[j];
+                if (n >= 0 && n < n_end) tile[n * LT + kr] = row[j];
             }
         }
     }
     __syncthreads();
-    // 16-byte pieces along k: 8 threads write the 128 bytes of one row of the tile
+    // fragment q = 4 (column block within the tile) + (in-feature block within the tile): a wave writes one, 1 KB
+    const uint32_t lane = threadIdx.x & 63, l32 = lane & 31, h = lane >> 5;
 #pragma unroll
-    for (int pass = 0; pass < T * 8 / kThreads; ++pass) {
-        const uint32_t n = pass * (kThreads / 8) + threadIdx.x / 8, kc = (threadIdx.x % 8) * 8;
-        if (n_lo + n < out_features && k0 + kc < in_features)  // in_features is a multiple of 8: whole pieces
-            *reinterpret_cast<uint4*>(wt + size_t(n_lo + n) * in_features + k0 + kc) =
-                *reinterpret_cast<const uint4*>(&tile[n * LT + kc]);
+    for (int pass = 0; pass < 2; ++pass) {
+        const uint32_t q = pass * 4 + threadIdx.x / 64;
+        const uint32_t nb = n_lo / 32 + q / 4, kb = k0 / 16 + q % 4;
+        if (nb < NB && kb < KB)
+            *reinterpret_cast<uint4*>(wf + (size_t(nb) * KB + kb) * kFragHalves + lane * 8) =
+                *reinterpret_cast<const uint4*>(&tile[((q / 4) * 32 + l32) * LT + (q % 4) * 16 + 8 * h]);
     }
 }
 
-// Plain transpose of a 16-bit matrix, W[rows][cols] -> Wt[cols][rows] (rows a multiple of 8), 64 x 64 tiles.
-__global__ __launch_bounds__(kThreads) void transpose16_kernel(const uint16_t* __restrict__ w, uint32_t rows, uint32_t cols,
-                                                               uint16_t* __restrict__ wt)
+// The integers of a quantised codebook (8 bits: signed bytes; 4 bits: two's-complement nibbles, element e in byte
+// e / 2, low nibble first) as 16-bit floats, exact in both formats: the codebook the rebuild above gathers from when
+// the product runs over the integers themselves.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void codebook_integers16_kernel(const uint8_t* __restrict__ qbook, int bits, uint32_t n,
+                                                                       uint16_t* __restrict__ out)
 {
-    constexpr int T = 64, LT = T + 8;
-    __shared__ __attribute__((aligned(16))) uint16_t tile[T * LT];  // [col][row]
-    const uint32_t c0 = blockIdx.x * T, r0 = blockIdx.y * T;
-    for (uint32_t e = threadIdx.x; e < T * T; e += kThreads) {
-        const uint32_t r = e / T, c = e % T;
-        if (r0 + r < rows && c0 + c < cols) tile[c * LT + r] = w[size_t(r0 + r) * cols + c0 + c];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int pass = 0; pass < T * 8 / kThreads; ++pass) {
-        const uint32_t c = pass * (kThreads / 8) + threadIdx.x / 8, rc = (threadIdx.x % 8) * 8;
-        if (c0 + c < cols && r0 + rc < rows)
-            *reinterpret_cast<uint4*>(wt + size_t(c0 + c) * rows + r0 + rc) = *reinterpret_cast<const uint4*>(&tile[c * LT + rc]);
-    }
+    const uint32_t e = blockIdx.x * kThreads + threadIdx.x;
+    if (e >= n) return;
+    int q;
+    if (bits == 8) q = int(static_cast<int8_t>(qbook[e]));
+    else q = int(((uint32_t(qbook[e >> 1]) >> (4 * (e & 1))) & 0xFu) ^ 8u) - 8;
+    out[e] = from_f32<DT>(float(q));
 }
 
 // ---- 2. the product
@@ -158,19 +170,18 @@ __global__ __launch_bounds__(kThreads) void transpose16_kernel(const uint16_t* _
 // is short and full instead of long and half empty, and leave fp32 partial tiles for gemm_finish_kernel. The cut
 // depends on the shape alone.
 template <int DT>
-__global__ __launch_bounds__(kThreads, 2) void gemm_tn_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wt,
-                                                              uint32_t M, uint32_t N, uint32_t K,
-                                                              const float* __restrict__ scale,
-                                                              const uint16_t* __restrict__ bias, uint16_t* __restrict__ y,
-                                                              float* __restrict__ partial, uint32_t m_tiles, uint32_t whole,
-                                                              uint32_t f, uint32_t k_per_split, uint32_t jobs)
+__global__ __launch_bounds__(kGemmThreads, WN == 2 ? 2 : 1) void gemm_frag_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ wf, uint32_t M, uint32_t N, uint32_t K, uint32_t NB, uint32_t KB,
+    const float* __restrict__ scale, const uint16_t* __restrict__ bias, uint16_t* __restrict__ y, float* __restrict__ partial,
+    uint32_t m_tiles, uint32_t whole, uint32_t f, uint32_t k_per_split, uint32_t jobs)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h = lane >> 5, l32 = lane & 31;
     const int wm = wave & 1, wn = wave >> 1;
 
-    // job of this workgroup: XCD q (= blockIdx % 8) takes the q-th contiguous share of the whole tiles and then the q-th share of the slices of the cut tiles; within a share the row panels of x vary fastest, so
-    // neighbours share a panel of Wt
+    // job of this workgroup: XCD q (= blockIdx % 8) takes the q-th contiguous share of the whole tiles and then the
+    // q-th share of the slices of the cut tiles; within a share the row panels of x vary fastest, so neighbours
+    // share a column panel of W
     const uint32_t xcd = blockIdx.x % 8, local = blockIdx.x / 8;
     const uint32_t whole_per = (whole + 7) / 8, cut_per = (jobs - whole + 7) / 8;
     uint32_t job;
@@ -190,39 +201,49 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tn_kernel(const uint16_t* __
     const uint32_t k_begin = direct ? 0u : split * k_per_split;
     const uint32_t k_end = direct ? K : min(k_begin + k_per_split, K);
 
-    // global -> register staging: 16-byte pieces, BK / 8 per operand row and slice; thread t takes piece t % PR of
-    // rows t / PR + RP i. Rows past the edge are clamped (their results are never stored); a piece past k_end is
-    // read from the last valid piece of its row instead and replaced by zeros (K and k_per_split are multiples of 8).
-    constexpr int PR = BK / 8, RP = kThreads / PR, NA = BM / RP, NB = BN / RP;
+    // x: global -> registers -> LDS in 16-byte pieces, BK / 8 per row and slice; thread t takes piece t % PR of rows
+    // t / PR + RP i. Rows past the edge are clamped (their results are never stored); a piece past k_end is read from
+    // the last valid piece of its row instead and goes to LDS as zeros (K and k_per_split are multiples of 8).
+    // W: this wave's two column blocks, fragments straight from memory; a block past the last one is clamped (its
+    // columns are never stored), a fragment past the end of the contraction reads the last one (and is never used).
+    //
+    // The global loads of the main loop are written as instructions, with the waits on them placed by hand: the
+    // compiler otherwise moves each request down to the slice that uses it, where its whole latency is exposed. The
+    // memory counter retires loads in order, so a wait names how many younger requests may still be in flight. Every
+    // slice issues the same six requests, past the end of the contraction too (clamped addresses, results unused),
+    // which keeps those numbers the same for every slice.
+    constexpr int PR = BK / 8, RP = kGemmThreads / PR, NA = BM / RP;
+    static_assert(NA == 2, "the wait counts below assume two pieces of x per thread and slice");
     const uint32_t prow = threadIdx.x / PR, pk = (threadIdx.x % PR) * 8;
     const uint16_t* a_src[NA];
-    const uint16_t* b_src[NB];
 #pragma unroll
     for (int i = 0; i < NA; ++i) a_src[i] = x + size_t(min(m0 + prow + RP * i, M - 1)) * K;
+    const uint16_t* b_src[2];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) b_src[i] = wt + size_t(min(n0 + prow + RP * i, N - 1)) * K;
-    uint4 a_reg[NA], b_reg[NB];
-    auto fetch = [&](uint32_t k0) {
-        const bool live = k0 + pk < k_end;
-        const uint32_t k = live ? k0 + pk : K - 8;
+    for (int j = 0; j < 2; ++j)
+        b_src[j] = wf + size_t(min(n0 / 32 + wn * 2 + j, NB - 1)) * KB * kFragHalves + lane * 8;
+    auto request = [](u32x4& r, const uint16_t* p) { asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(p)); };
+    auto fetch_a = [&](u32x4 (&a)[NA], uint32_t k0) {
+        const uint32_t k = k0 + pk < k_end ? k0 + pk : K - 8;
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            const uint4 v = *reinterpret_cast<const uint4*>(a_src[i] + k);
-            a_reg[i] = live ? v : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const uint4 v = *reinterpret_cast<const uint4*>(b_src[i] + k);
-            b_reg[i] = live ? v : make_uint4(0, 0, 0, 0);
-        }
+        for (int i = 0; i < NA; ++i) request(a[i], a_src[i] + k);
     };
-    auto stash = [&](int buf) {
+    auto fetch_b = [&](u32x4 (&b)[2], uint32_t k) {
+        const uint32_t kb = min(k / 16, KB - 1);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) request(b[j], b_src[j] + size_t(kb) * kFragHalves);
+    };
+#define CC_GEMM_ARRIVED(younger, r) asm volatile("s_waitcnt vmcnt(" #younger ")" : "+v"((r)[0]), "+v"((r)[1]))
+    auto stash = [&](const u32x4 (&a)[NA], int buf, uint32_t k0) {
+        const uint32_t keep = k0 + pk < k_end ? 0xffffffffu : 0u;
         uint16_t* As = lds + buf * kStageHalves;
-        uint16_t* Bs = As + BM * LDT;
 #pragma unroll
-        for (int i = 0; i < NA; ++i) *reinterpret_cast<uint4*>(&As[(prow + RP * i) * LDT + pk]) = a_reg[i];
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4*>(&As[(prow + RP * i) * LDT + pk]) = a[i] & keep;
+    };
+    const uint16_t* a_lds = lds + (wm * 128 + l32) * LDT + 8 * h;
+    auto read_frags = [&](u32x4 (&a)[4], int buf, int kk) {
 #pragma unroll
-        for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4*>(&Bs[(prow + RP * i) * LDT + pk]) = b_reg[i];
+        for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const u32x4*>(a_lds + buf * kStageHalves + 32 * i * LDT + 16 * kk);
     };
 
     f32x16 acc[4][2];
@@ -232,32 +253,63 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tn_kernel(const uint16_t* __
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    auto multiply = [&](const u32x4 (&a)[4], const u32x4 (&b)[2]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = mma<DT>(a[i], b[j], acc[i][j]);
+    };
 
-    fetch(k_begin);
-    stash(0);
+    // One slice of 32 in-features = two batches of 8 matrix instructions (16 in-features each) with the barrier
+    // between them: the x fragments of the second batch are read from LDS before the first batch is issued, and those
+    // of the next slice's first batch right after the barrier, before the second batch - the matrix cores always have
+    // a batch to work on while LDS answers. Batch t takes its fragments of W from ring slot t % 4. Slices come in
+    // pairs so that every slot and buffer index is a constant. Requests of slice s, in order:
+    //   at its start   x of slice s + 2 (2), W of the second batch of slice s + 1 (2)
+    //   after barrier  W of the first batch of slice s + 2 (2)
+    // and what it needs: W of its first batch (asked for after the barrier of slice s - 2: 10 younger requests by
+    // then), x of slice s + 1 for LDS (start of slice s - 1: 8 younger), W of its second batch (start of slice
+    // s - 1, after x: 8 younger once this slice's last two are out).
+    // (The hand-over to LDS also runs after the last slice, where it moves zeros.)
+    u32x4 a0[4], a1[4], bq[4][2], ar[2][NA];
+#define CC_GEMM_SLICE(P, k0)                                         \
+    do {                                                             \
+        fetch_a(ar[P], (k0) + 2 * BK);                               \
+        fetch_b(bq[(2 * (P) + 3) % 4], (k0) + BK + 16);              \
+        read_frags(a1, P, 1);                                        \
+        CC_GEMM_ARRIVED(10, bq[2 * (P)]);                            \
+        __builtin_amdgcn_sched_barrier(0);                           \
+        multiply(a0, bq[2 * (P)]);                                   \
+        __builtin_amdgcn_sched_barrier(0);                           \
+        CC_GEMM_ARRIVED(8, ar[1 - (P)]);                             \
+        stash(ar[1 - (P)], 1 - (P), (k0) + BK);                      \
+        __syncthreads();                                             \
+        read_frags(a0, 1 - (P), 0);                                  \
+        fetch_b(bq[2 * (P)], (k0) + 2 * BK);                         \
+        CC_GEMM_ARRIVED(8, bq[2 * (P) + 1]);                         \
+        __builtin_amdgcn_sched_barrier(0);                           \
+        multiply(a1, bq[2 * (P) + 1]);                               \
+    } while (0)
+
+    // before the first slice: the same requests in the same order, as far as they exist
+    fetch_a(ar[0], k_begin);
+    fetch_b(bq[0], k_begin);
+    fetch_a(ar[1], k_begin + BK);
+    fetch_b(bq[1], k_begin + 16);
+    fetch_b(bq[2], k_begin + BK);
+    CC_GEMM_ARRIVED(8, ar[0]);
+    stash(ar[0], 0, k_begin);
     __syncthreads();
-    int cur = 0;
-    for (uint32_t k0 = k_begin; k0 < k_end; k0 += BK) {
-        const bool more = k0 + BK < k_end;
-        if (more) fetch(k0 + BK);
-        const uint16_t* As = lds + cur * kStageHalves + (wm * 128 + l32) * LDT + 8 * h;
-        const uint16_t* Bs = lds + cur * kStageHalves + BM * LDT + (wn * 64 + l32) * LDT + 8 * h;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            u32x4 a[4], b[2];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const u32x4*>(As + 32 * i * LDT + 16 * kk);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const u32x4*>(Bs + 32 * j * LDT + 16 * kk);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = mma<DT>(a[i], b[j], acc[i][j]);
-        }
-        if (more) stash(cur ^ 1);
-        __syncthreads();
-        cur ^= 1;
+    read_frags(a0, 0, 0);
+    for (uint32_t k0 = k_begin;;) {
+        CC_GEMM_SLICE(0, k0);
+        if ((k0 += BK) >= k_end) break;
+        CC_GEMM_SLICE(1, k0);
+        if ((k0 += BK) >= k_end) break;
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // requests past the end still write registers: let them land
+#undef CC_GEMM_SLICE
+#undef CC_GEMM_ARRIVED
 
     // ---- epilogue: accumulator register r of lane (l32, h) is row r % 4 + 8 (r / 4) + 4 h, column l32 of its tile
     const float sc = (direct && scale != nullptr) ? *scale : 1.0f;
@@ -305,8 +357,8 @@ __global__ __launch_bounds__(kThreads) void gemm_finish_kernel(const float* __re
     y[size_t(m) * N + n] = from_f32<DT>(v);
 }
 
-// Workgroups the chip holds at once: 256 compute units, two workgroups each (their LDS and registers allow two).
-constexpr uint32_t kGemmSlots = 512;
+// Workgroups the chip holds at once: 256 compute units, each with room (registers) for 8 waves of this kernel.
+constexpr uint32_t kGemmSlots = WN == 2 ? 512 : 256;
 
 struct GemmShape {
     uint32_t m_tiles, n_tiles, whole, cut_tiles, f, k_per_split, jobs;
@@ -342,51 +394,58 @@ size_t layer_gemm_partial_bytes(uint64_t M, uint32_t in_features, uint32_t out_f
     return align256(size_t(s.cut_tiles) * s.f * BM * BN * 4);
 }
 
-hipError_t launch_layer_weight_t(const void* codebook, uint32_t K, uint32_t g, const uint16_t* codes, uint32_t in_features,
-                                 uint32_t out_features, void* wt, hipStream_t s)
+// bytes of the weight in fragment layout (whole fragments: columns padded to 32, in-features to 16)
+size_t layer_weight_frag_bytes(uint32_t in_features, uint32_t out_features)
+{
+    return align256(size_t((out_features + 31) / 32) * ((in_features + 15) / 16) * kFragHalves * 2);
+}
+
+hipError_t launch_layer_weight_frag(const void* codebook, uint32_t K, uint32_t g, const uint16_t* codes, uint32_t in_features,
+                                    uint32_t out_features, void* wf, hipStream_t s)
 {
     const uint32_t per_row = (out_features + g - 1) / g;
     const dim3 grid((out_features + 63) / 64, (in_features + 63) / 64);
     if (grid.y > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(layer_weight_t_kernel, grid, dim3(kThreads), 0, s, static_cast<const uint16_t*>(codebook), K, g, codes,
-                       per_row, in_features, out_features, static_cast<uint16_t*>(wt));
+    hipLaunchKernelGGL(layer_weight_frag_kernel, grid, dim3(kThreads), 0, s, static_cast<const uint16_t*>(codebook), K, g, codes,
+                       per_row, in_features, out_features, (out_features + 31) / 32, (in_features + 15) / 16,
+                       static_cast<uint16_t*>(wf));
     return hipGetLastError();
 }
 
-hipError_t launch_transpose16(const void* w, uint32_t rows, uint32_t cols, void* wt, hipStream_t s)
+hipError_t launch_codebook_integers16(const void* qbook, int bits, uint32_t K, uint32_t g, int dtype, void* book16, hipStream_t s)
 {
-    const dim3 grid((cols + 63) / 64, (rows + 63) / 64);
-    if (grid.y > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(transpose16_kernel, grid, dim3(kThreads), 0, s, static_cast<const uint16_t*>(w), rows, cols,
-                       static_cast<uint16_t*>(wt));
+    const uint32_t n = K * g;
+    const dim3 grid((n + kThreads - 1) / kThreads);
+    if (dtype == 1)
+        hipLaunchKernelGGL(codebook_integers16_kernel<1>, grid, dim3(kThreads), 0, s, static_cast<const uint8_t*>(qbook), bits, n,
+                           static_cast<uint16_t*>(book16));
+    else if (dtype == 2)
+        hipLaunchKernelGGL(codebook_integers16_kernel<2>, grid, dim3(kThreads), 0, s, static_cast<const uint8_t*>(qbook), bits, n,
+                           static_cast<uint16_t*>(book16));
+    else
+        return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
-// y [M][out] = x [M][in] . wt [out][in]^T; scale (device, may be NULL) multiplies the finished sum; `partial` holds
-// layer_gemm_partial_bytes(...) bytes
-hipError_t launch_layer_gemm(const void* x, uint32_t M, const void* wt, int dtype, uint32_t in_features, uint32_t out_features,
+// y [M][out] = x [M][in] . W, W as written by launch_layer_weight_frag; scale (device, may be NULL) multiplies the
+// finished sum; `partial` holds layer_gemm_partial_bytes(...) bytes
+hipError_t launch_layer_gemm(const void* x, uint32_t M, const void* wf, int dtype, uint32_t in_features, uint32_t out_features,
                              const float* scale, const void* bias, void* y, float* partial, hipStream_t s)
 {
     const GemmShape g = gemm_shape(M, in_features, out_features);
     const dim3 grid(8 * ((g.whole + 7) / 8) + 8 * ((g.jobs - g.whole + 7) / 8));
     const uint16_t* xs = static_cast<const uint16_t*>(x);
-    const uint16_t* ws = static_cast<const uint16_t*>(wt);
+    const uint16_t* ws = static_cast<const uint16_t*>(wf);
     const uint16_t* bs = static_cast<const uint16_t*>(bias);
     uint16_t* ys = static_cast<uint16_t*>(y);
+    const uint32_t NB = (out_features + 31) / 32, KB = (in_features + 15) / 16;
     if (dtype != 1 && dtype != 2) return hipErrorInvalidValue;
-    static bool lds_set[3] = {};
-    if (!lds_set[dtype]) {
-        const void* fn = dtype == 1 ? reinterpret_cast<const void*>(&gemm_tn_kernel<1>) : reinterpret_cast<const void*>(&gemm_tn_kernel<2>);
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, int(kGemmLdsBytes));
-        if (e != hipSuccess) return e;
-        lds_set[dtype] = true;
-    }
     if (dtype == 1)
-        hipLaunchKernelGGL(gemm_tn_kernel<1>, grid, dim3(kThreads), kGemmLdsBytes, s, xs, ws, M, out_features, in_features, scale,
-                           bs, ys, partial, g.m_tiles, g.whole, g.f, g.k_per_split, g.jobs);
+        hipLaunchKernelGGL(gemm_frag_kernel<1>, grid, dim3(kGemmThreads), kGemmLdsBytes, s, xs, ws, M, out_features, in_features, NB,
+                           KB, scale, bs, ys, partial, g.m_tiles, g.whole, g.f, g.k_per_split, g.jobs);
     else
-        hipLaunchKernelGGL(gemm_tn_kernel<2>, grid, dim3(kThreads), kGemmLdsBytes, s, xs, ws, M, out_features, in_features, scale,
-                           bs, ys, partial, g.m_tiles, g.whole, g.f, g.k_per_split, g.jobs);
+        hipLaunchKernelGGL(gemm_frag_kernel<2>, grid, dim3(kGemmThreads), kGemmLdsBytes, s, xs, ws, M, out_features, in_features, NB,
+                           KB, scale, bs, ys, partial, g.m_tiles, g.whole, g.f, g.k_per_split, g.jobs);
     if (g.cut_tiles > 0) {
         const dim3 fgrid(BM * BN / kThreads, g.cut_tiles);
         if (dtype == 1)

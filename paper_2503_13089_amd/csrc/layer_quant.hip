@@ -971,30 +971,4 @@ hipError_t launch_layer_forward_q(const void* x, uint32_t M, const void* qbook, 
     return hipErrorInvalidValue;
 }
 
-// ---- prefill-sized batches: the integers q as a 16-bit matrix (exact in both formats) for a dense product whose
-// fp32 sums are then finished like the partial sums of the fused kernel: scale, bias, one rounding
-namespace {
-__global__ void set_float_kernel(float* p, float v) { *p = v; }
-}  // namespace
-
-hipError_t launch_layer_weight_q_integers(const void* qbook, int bits, uint32_t K, uint32_t g, const uint16_t* codes,
-                                          uint32_t in_features, uint32_t out_features, int dtype, void* weight, float* one,
-                                          hipStream_t s)
-{
-    hipLaunchKernelGGL(set_float_kernel, dim3(1), dim3(1), 0, s, one, 1.0f);
-    return launch_layer_weight_q(qbook, bits, one, K, g, codes, in_features, out_features, dtype, weight, s);
-}
-
-hipError_t launch_forward_q_finish(const float* sums, uint32_t M, uint32_t out_features, const float* scale, const void* bias,
-                                   void* y, int dtype, hipStream_t s)
-{
-    const uint64_t n = uint64_t(M) * out_features;
-    const dim3 grid(uint32_t((n + kThreads - 1) / kThreads));
-    const uint16_t* bs = static_cast<const uint16_t*>(bias);
-    uint16_t* ys = static_cast<uint16_t*>(y);
-    if (dtype == 1) hipLaunchKernelGGL(forward_q_reduce_kernel<1>, grid, dim3(kThreads), 0, s, sums, n, out_features, 1u, scale, bs, ys);
-    else hipLaunchKernelGGL(forward_q_reduce_kernel<2>, grid, dim3(kThreads), 0, s, sums, n, out_features, 1u, scale, bs, ys);
-    return hipGetLastError();
-}
-
 }  // namespace cc

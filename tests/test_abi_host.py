@@ -160,12 +160,14 @@ def test_forward_and_quantised_entry_points_reject_bad_arguments():
     assert lib.cc_layer_weight_q(A16, 2, A16, 10, 4, A16, 8, 8, BF16, A16, None) == -2
     assert lib.cc_layer_weight_q(A16, 4, None, 10, 4, A16, 8, 8, BF16, A16, None) == -1
     assert lib.cc_layer_forward_q_workspace_bytes(1, 4096, 4096) >= lib.cc_layer_forward_workspace_bytes(1, 4096, 4096)
-    # prefill-sized batches: room for the rebuilt (transposed) weight; the quantised route also holds the integer
-    # weight before its transposition and the fp32 sums; a small batch additionally splits the contraction
+    # prefill-sized batches: room for the rebuilt weight (whole matrix-core operands: columns padded to 32, in-features
+    # to 16) and for fp32 partial tiles where the contraction is split; the quantised route also holds the integer
+    # codebook in 16 bits (2 MiB)
     big = lib.cc_layer_forward_workspace_bytes(2048, 4096, 4096)
     assert big >= 4096 * 4096 * 2 and big % 256 == 0
     big_q = lib.cc_layer_forward_q_workspace_bytes(2048, 4096, 4096)
-    assert big_q >= 2 * 4096 * 4096 * 2 + 2048 * 4096 * 4 and big_q % 256 == 0
+    assert big_q == big + (2 << 20)
+    assert lib.cc_layer_forward_workspace_bytes(4096, 4104, 4100) >= 4128 * 4112 * 2
     assert lib.cc_layer_forward_workspace_bytes(128, 4096, 4096) > 4096 * 4096 * 2 + 128 * 4096 * 4
     assert lib.cc_layer_forward(A16, 2048, A16, BF16, 10, 4, A16, 4096, 4096, None, A16, WS, 16, None) == -5
     assert lib.cc_layer_forward_q(A16, 1, A16, 4, A16, 10, 4, A16, 64, 64, None, A16, BF16, None, 0, None) == -1

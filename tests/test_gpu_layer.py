@@ -228,7 +228,7 @@ FORWARD_CASES = [  # (M, in_features, out_features, g, K, bias)
     (32, 1024, 1024, 8, 65536, True),
     (5, 64, 70, 7, 3, False),
     (200, 4096, 256, 4, 65536, False),
-    # prefill-sized batches: the weight is rebuilt and multiplied by the GEMM library
+    # prefill-sized batches: the weight is rebuilt and multiplied by the library's matrix-core product
     (128, 2048, 2048, 4, 65536, True),
     (256, 512, 768, 4, 65536, True),
     (1000, 1024, 520, 8, 4096, False),
@@ -305,8 +305,8 @@ def test_layer_forward_prefill_at_model_size(cc, M):
 @pytest.mark.parametrize("M,in_features,out_features,g,K", [(192, 1024, 2560, 4, 65536), (300, 200, 300, 4, 500),
                                                             (129, 4096, 130, 8, 4096), (513, 72, 1000, 6, 300)])
 def test_layer_forward_many_rows_meets_the_definition_and_reads_out_weight_rows(cc, M, in_features, out_features, g, K, dt):
-    """The rebuilt-weight route (transposed rebuild + the matrix-core product, the contraction split over workgroups
-    where the tiles are few, in_features not a multiple of the 64-wide step, ragged edges in both directions): every
+    """The rebuilt-weight route (rebuild into matrix-core operands + the product, the contraction split over workgroups
+    where the tiles are few, in_features not a multiple of the operand's 16, ragged edges in both directions): every
     output against the definition, the same bits on a second call, and one-hot inputs must return rows of the
     reconstructed weight exactly (no arithmetic error possible)."""
     rng = np.random.default_rng(M + in_features)
@@ -416,7 +416,7 @@ def test_layer_weight_q_bit_exact(cc, out_features, in_features, g, K, dt, bits)
                                           # 16 < M <= 64 with g = 4 / 8 and an LDS-sized codebook: matrix cores + LDS codebook
                                           (40, 512, 320, 4, 65536, True), (64, 264, 200, 8, 9000, False),
                                           (17, 1024, 1024, 4, 30000, True), (33, 72, 70, 4, 100, False),
-                                          # a wide decoding batch on a layer of 2^25 weights: rebuilt integer weight + GEMM
+                                          # a wide decoding batch on a layer of 2^25 weights: rebuilt integer weight + matrix-core product
                                           (24, 4096, 8448, 4, 65536, True)])
 def test_layer_forward_q(cc, M, in_features, out_features, g, K, with_bias, dt, bits):
     rng = np.random.default_rng(M + in_features + out_features + g + bits)
