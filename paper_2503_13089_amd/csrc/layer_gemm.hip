@@ -6,23 +6,24 @@
 //      (n % 32) + 32 ((k % 16) / 8); fragments of one column block are contiguous along k. 64 x 64 tiles through LDS:
 //      codes are read along a row of W, fragments leave in whole cache lines. Padding (columns past out_features,
 //      in-features past the end of the last fragment) is written as zeros.
-//   2. gemm_frag_kernel: y[M][N] = x[M][K] . W on v_mfma_f32_32x32x16_{bf16,f16}. A workgroup owns a 256-row tile of
-//      y, each wave 128 x 64 of it (4 x 2 accumulator tiles of 32 x 32, in registers for the whole contraction), and
-//      steps through K in slices of 32. Only x goes through LDS (double-buffered: the next slice travels global ->
-//      registers while the current one is multiplied, then registers -> LDS, one barrier per slice; rows padded to
-//      40 halves so that the 16-byte fragment reads of 16 lanes fall on 16 different bank quads). The fragments of W
-//      come from memory as they are - one fully coalesced 1 KB load per fragment, requested two slices ahead - which
-//      takes a third of the traffic off LDS, the unit that bounds this kernel. Products of two 16-bit values are
-//      exact in fp32; the sum is fp32 in a fixed order; bias (and, for the quantised codebook, the scale) are
-//      applied to the finished sum and y is rounded once.
+//   2. gemm_frag_kernel: y[M][N] = x[M][K] . W on v_mfma_f32_32x32x16_{bf16,f16}. A workgroup of 8 waves owns a
+//      256 x 256 tile of y, each wave 128 x 64 of it (4 x 2 accumulator tiles of 32 x 32, in registers for the whole
+//      contraction), and steps through K in slices of 32. Only x goes through LDS (double-buffered, rows padded to 40
+//      halves so that the 16-byte fragment reads of 16 lanes fall on 16 different bank quads). The fragments of W
+//      come from memory as they are: one fully coalesced 1 KB load per fragment, requested two slices ahead.
+//      Products of two 16-bit values are exact in fp32; the sum is fp32 in a fixed order; bias (and, for the
+//      quantised codebook, the scale) are applied to the finished sum and y is rounded once.
 //      Workgroups are numbered so that one XCD (they are dealt to the 8 XCDs in turn) works on neighbouring column
 //      panels with all row panels of x: its L2 then holds the fragments it is using, and x comes once per XCD.
 //      Tiles that do not fill a round of the chip's workgroup slots are cut along the contraction: fp32 partial
 //      tiles go to the workspace and a second kernel adds them in a fixed order - the result never depends on
 //      scheduling.
 //
-// Bound: the bf16 / fp16 matrix cores (2 M N K flop against 2.5 PFLOP/s); the rebuild is HBM-bound (2 bytes written
-// per weight).
+// Bound: the bf16 / fp16 matrix cores (2 M N K flop against 2.5 PFLOP/s). Measured at M = 2048, 4096 x 11008: the
+// product runs at 0.89 PFLOP/s with the matrix cores busy 41 % of the time; three variants with very different loads
+// on LDS and on the vector memory path (both operands through LDS with 256 x 128 or 256 x 256 tiles, W from memory
+// with 4 or 8 waves) all end within 10 % of each other. The rebuild is bound by one codebook row lookup per code, a
+// cache line fill each (58 us for 45 M weights), not by the 2 bytes it writes per weight.
 #include <algorithm>
 
 #include "common.h"
@@ -32,10 +33,7 @@ namespace cc {
 namespace {
 
 constexpr int kThreads = 256;               // rebuild and finishing kernels
-#ifndef CC_GEMM_WN
-#define CC_GEMM_WN 4
-#endif
-constexpr int WN = CC_GEMM_WN;              // waves along the columns of a tile (2 along its rows)
+constexpr int WN = 4;                       // waves along the columns of a tile (2 along its rows)
 constexpr int kGemmThreads = 128 * WN;
 constexpr int BM = 256, BN = 64 * WN, BK = 32;
 constexpr int LDT = BK + 8;                 // halves per LDS row (20 words: the 16-byte reads of 16 lanes hit 16 bank quads)
@@ -170,7 +168,7 @@ __global__ __launch_bounds__(kThreads) void codebook_integers16_kernel(const uin
 // is short and full instead of long and half empty, and leave fp32 partial tiles for gemm_finish_kernel. The cut
 // depends on the shape alone.
 template <int DT>
-__global__ __launch_bounds__(kGemmThreads, WN == 2 ? 2 : 1) void gemm_frag_kernel(
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_frag_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ wf, uint32_t M, uint32_t N, uint32_t K, uint32_t NB, uint32_t KB,
     const float* __restrict__ scale, const uint16_t* __restrict__ bias, uint16_t* __restrict__ y, float* __restrict__ partial,
     uint32_t m_tiles, uint32_t whole, uint32_t f, uint32_t k_per_split, uint32_t jobs)
@@ -357,8 +355,8 @@ __global__ __launch_bounds__(kThreads) void gemm_finish_kernel(const float* __re
     y[size_t(m) * N + n] = from_f32<DT>(v);
 }
 
-// Workgroups the chip holds at once: 256 compute units, each with room (registers) for 8 waves of this kernel.
-constexpr uint32_t kGemmSlots = WN == 2 ? 512 : 256;
+// Workgroups the chip holds at once: 256 compute units, each with room (registers) for the 8 waves of one workgroup.
+constexpr uint32_t kGemmSlots = 256;
 
 struct GemmShape {
     uint32_t m_tiles, n_tiles, whole, cut_tiles, f, k_per_split, jobs;
