@@ -41,7 +41,7 @@ VALU_ISSUE_PEAK = 1024 * 2.4e9 / 4   # wave-instructions/s: 1024 SIMDs, one 64-l
 _KIB = 1024.0
 MEASURED_TRAFFIC_BYTES = {
     ("cfg3_4096x11008_d4_k65536", "fit_estep"): (147500 * 1.988 + 97360 * 0.994) * _KIB,     # windowed kernel, mean of 44 launches
-    ("cfg3_4096x11008_d4_k65536", "estep_whole"): (294000 * 1.988 + 88480 * 0.994) * _KIB,
+    ("cfg3_4096x11008_d4_k65536", "estep_whole"): (283040 * 1.988 + 88480 * 0.994) * _KIB,
     ("cfg3_4096x11008_d4_k65536", "update"): ((110200 + 18450) * 1.988 + (36860 + 3328) * 0.994) * _KIB,  # both kernels
     ("cfg3_4096x11008_d4_k65536", "decode"): (26120 * 1.988 + 176100 * 0.994) * _KIB,
 }
