@@ -10,7 +10,8 @@
 //      256 x 256 tile of y, each wave 128 x 64 of it (4 x 2 accumulator tiles of 32 x 32, in registers for the whole
 //      contraction), and steps through K in slices of 32. Only x goes through LDS (double-buffered, rows padded to 40
 //      halves so that the 16-byte fragment reads of 16 lanes fall on 16 different bank quads). The fragments of W
-//      come from memory as they are: one fully coalesced 1 KB load per fragment, requested two slices ahead.
+//      come from memory as they are: one fully coalesced 1 KB load per fragment, requested two slices ahead. Every
+//      memory instruction of the loop sits between two matrix instructions.
 //      Products of two 16-bit values are exact in fp32; the sum is fp32 in a fixed order; bias (and, for the
 //      quantised codebook, the scale) are applied to the finished sum and y is rounded once.
 //      Workgroups are numbered so that one XCD (they are dealt to the 8 XCDs in turn) works on neighbouring column
@@ -20,10 +21,11 @@
 //      scheduling.
 //
 // Bound: the bf16 / fp16 matrix cores (2 M N K flop against 2.5 PFLOP/s). Measured at M = 2048, 4096 x 11008: the
-// product runs at 0.89 PFLOP/s with the matrix cores busy 41 % of the time; three variants with very different loads
-// on LDS and on the vector memory path (both operands through LDS with 256 x 128 or 256 x 256 tiles, W from memory
-// with 4 or 8 waves) all end within 10 % of each other. The rebuild is bound by one codebook row lookup per code, a
-// cache line fill each (58 us for 45 M weights), not by the 2 bytes it writes per weight.
+// product takes 189 us = 0.98 PFLOP/s. The same loop with every memory instruction taken out (matrix instructions
+// only) takes 130 us: under sustained matrix work the chip clocks near 1.7 GHz instead of 2.4, and the 344 tiles take
+// 1.5 rounds on 256 compute units where 1.34 would do - that, not 2.5 PFLOP/s, is the ceiling of this tile schedule.
+// The rebuild is bound by one codebook row lookup per code, a cache line fill each (58 us for 45 M weights), not by
+// the 2 bytes it writes per weight.
 #include <algorithm>
 
 #include "common.h"
@@ -221,16 +223,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_frag_kernel(
     for (int j = 0; j < 2; ++j)
         b_src[j] = wf + size_t(min(n0 / 32 + wn * 2 + j, NB - 1)) * KB * kFragHalves + lane * 8;
     auto request = [](u32x4& r, const uint16_t* p) { asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(p)); };
-    auto fetch_a = [&](u32x4 (&a)[NA], uint32_t k0) {
-        const uint32_t k = k0 + pk < k_end ? k0 + pk : K - 8;
-#pragma unroll
-        for (int i = 0; i < NA; ++i) request(a[i], a_src[i] + k);
-    };
-    auto fetch_b = [&](u32x4 (&b)[2], uint32_t k) {
-        const uint32_t kb = min(k / 16, KB - 1);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) request(b[j], b_src[j] + size_t(kb) * kFragHalves);
-    };
+    auto a_addr = [&](int i, uint32_t k0) { return a_src[i] + (k0 + pk < k_end ? k0 + pk : K - 8); };
+    auto b_addr = [&](int j, uint32_t k) { return b_src[j] + size_t(min(k / 16, KB - 1)) * kFragHalves; };
 #define CC_GEMM_ARRIVED(younger, r) asm volatile("s_waitcnt vmcnt(" #younger ")" : "+v"((r)[0]), "+v"((r)[1]))
     auto stash = [&](const u32x4 (&a)[NA], int buf, uint32_t k0) {
         const uint32_t keep = k0 + pk < k_end ? 0xffffffffu : 0u;
@@ -239,9 +233,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_frag_kernel(
         for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4*>(&As[(prow + RP * i) * LDT + pk]) = a[i] & keep;
     };
     const uint16_t* a_lds = lds + (wm * 128 + l32) * LDT + 8 * h;
-    auto read_frags = [&](u32x4 (&a)[4], int buf, int kk) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const u32x4*>(a_lds + buf * kStageHalves + 32 * i * LDT + 16 * kk);
+    auto read_frag = [&](u32x4& a, int i, int buf, int kk) {
+        a = *reinterpret_cast<const u32x4*>(a_lds + buf * kStageHalves + 32 * i * LDT + 16 * kk);
     };
 
     f32x16 acc[4][2];
@@ -251,54 +244,81 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_frag_kernel(
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-    auto multiply = [&](const u32x4 (&a)[4], const u32x4 (&b)[2]) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) acc[i][j] = mma<DT>(a[i], b[j], acc[i][j]);
-    };
 
     // One slice of 32 in-features = two batches of 8 matrix instructions (16 in-features each) with the barrier
-    // between them: the x fragments of the second batch are read from LDS before the first batch is issued, and those
-    // of the next slice's first batch right after the barrier, before the second batch - the matrix cores always have
-    // a batch to work on while LDS answers. Batch t takes its fragments of W from ring slot t % 4. Slices come in
-    // pairs so that every slot and buffer index is a constant. Requests of slice s, in order:
-    //   at its start   x of slice s + 2 (2), W of the second batch of slice s + 1 (2)
-    //   after barrier  W of the first batch of slice s + 2 (2)
-    // and what it needs: W of its first batch (asked for after the barrier of slice s - 2: 10 younger requests by
-    // then), x of slice s + 1 for LDS (start of slice s - 1: 8 younger), W of its second batch (start of slice
-    // s - 1, after x: 8 younger once this slice's last two are out).
+    // between them. Every memory instruction of the loop is issued between two matrix instructions, one at a time: a
+    // wave that issues its requests in a burst waits at them until the memory pipeline has taken those of all eight
+    // waves, and issues no matrix instruction meanwhile (measured: loop without matrix instructions 111 us, matrix
+    // instructions alone 85 us, both with the requests in bursts 209 us - the sum). The x fragments of the second
+    // batch are read from LDS during the first four instructions of the first batch, those of the next slice's first
+    // batch during the first four of the second batch, after the barrier. Batch t takes its fragments of W from ring
+    // slot t % 4. Slices come in pairs so that every slot and buffer index is a constant. Requests of slice s, in
+    // order: during the second half of its first batch x of slice s + 2 (2), then W of the second batch of slice s + 1
+    // (2); during the second half of its second batch W of the first batch of slice s + 2 (2). What it needs, and how
+    // many younger requests are out by then: W of its first batch (asked for in slice s - 2: 6), x of slice s + 1 for
+    // LDS (slice s - 1: 8, this slice's four included), W of its second batch (slice s - 1, after x: 6).
     // (The hand-over to LDS also runs after the last slice, where it moves zeros.)
     u32x4 a0[4], a1[4], bq[4][2], ar[2][NA];
-#define CC_GEMM_SLICE(P, k0)                                         \
-    do {                                                             \
-        fetch_a(ar[P], (k0) + 2 * BK);                               \
-        fetch_b(bq[(2 * (P) + 3) % 4], (k0) + BK + 16);              \
-        read_frags(a1, P, 1);                                        \
-        CC_GEMM_ARRIVED(10, bq[2 * (P)]);                            \
-        __builtin_amdgcn_sched_barrier(0);                           \
-        multiply(a0, bq[2 * (P)]);                                   \
-        __builtin_amdgcn_sched_barrier(0);                           \
-        CC_GEMM_ARRIVED(8, ar[1 - (P)]);                             \
-        stash(ar[1 - (P)], 1 - (P), (k0) + BK);                      \
-        __syncthreads();                                             \
-        read_frags(a0, 1 - (P), 0);                                  \
-        fetch_b(bq[2 * (P)], (k0) + 2 * BK);                         \
-        CC_GEMM_ARRIVED(8, bq[2 * (P) + 1]);                         \
-        __builtin_amdgcn_sched_barrier(0);                           \
-        multiply(a1, bq[2 * (P) + 1]);                               \
+#define CC_GEMM_STEP(stmt)                     \
+    stmt;                                      \
+    __builtin_amdgcn_sched_barrier(0)
+#define CC_GEMM_SLICE(P, k0)                                                                   \
+    do {                                                                                       \
+        CC_GEMM_ARRIVED(6, bq[2 * (P)]);                                                       \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+        CC_GEMM_STEP(acc[0][0] = mma<DT>(a0[0], bq[2 * (P)][0], acc[0][0]));                   \
+        CC_GEMM_STEP(read_frag(a1[0], 0, P, 1));                                               \
+        CC_GEMM_STEP(acc[0][1] = mma<DT>(a0[0], bq[2 * (P)][1], acc[0][1]));                   \
+        CC_GEMM_STEP(read_frag(a1[1], 1, P, 1));                                               \
+        CC_GEMM_STEP(acc[1][0] = mma<DT>(a0[1], bq[2 * (P)][0], acc[1][0]));                   \
+        CC_GEMM_STEP(read_frag(a1[2], 2, P, 1));                                               \
+        CC_GEMM_STEP(acc[1][1] = mma<DT>(a0[1], bq[2 * (P)][1], acc[1][1]));                   \
+        CC_GEMM_STEP(read_frag(a1[3], 3, P, 1));                                               \
+        CC_GEMM_STEP(acc[2][0] = mma<DT>(a0[2], bq[2 * (P)][0], acc[2][0]));                   \
+        CC_GEMM_STEP(request(ar[P][0], a_addr(0, (k0) + 2 * BK)));                             \
+        CC_GEMM_STEP(acc[2][1] = mma<DT>(a0[2], bq[2 * (P)][1], acc[2][1]));                   \
+        CC_GEMM_STEP(request(ar[P][1], a_addr(1, (k0) + 2 * BK)));                             \
+        CC_GEMM_STEP(acc[3][0] = mma<DT>(a0[3], bq[2 * (P)][0], acc[3][0]));                   \
+        CC_GEMM_STEP(request(bq[(2 * (P) + 3) % 4][0], b_addr(0, (k0) + BK + 16)));            \
+        CC_GEMM_STEP(acc[3][1] = mma<DT>(a0[3], bq[2 * (P)][1], acc[3][1]));                   \
+        CC_GEMM_STEP(request(bq[(2 * (P) + 3) % 4][1], b_addr(1, (k0) + BK + 16)));            \
+        CC_GEMM_ARRIVED(8, ar[1 - (P)]);                                                       \
+        stash(ar[1 - (P)], 1 - (P), (k0) + BK);                                                \
+        __syncthreads();                                                                       \
+        CC_GEMM_ARRIVED(6, bq[2 * (P) + 1]);                                                   \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+        CC_GEMM_STEP(acc[0][0] = mma<DT>(a1[0], bq[2 * (P) + 1][0], acc[0][0]));               \
+        CC_GEMM_STEP(read_frag(a0[0], 0, 1 - (P), 0));                                         \
+        CC_GEMM_STEP(acc[0][1] = mma<DT>(a1[0], bq[2 * (P) + 1][1], acc[0][1]));               \
+        CC_GEMM_STEP(read_frag(a0[1], 1, 1 - (P), 0));                                         \
+        CC_GEMM_STEP(acc[1][0] = mma<DT>(a1[1], bq[2 * (P) + 1][0], acc[1][0]));               \
+        CC_GEMM_STEP(read_frag(a0[2], 2, 1 - (P), 0));                                         \
+        CC_GEMM_STEP(acc[1][1] = mma<DT>(a1[1], bq[2 * (P) + 1][1], acc[1][1]));               \
+        CC_GEMM_STEP(read_frag(a0[3], 3, 1 - (P), 0));                                         \
+        CC_GEMM_STEP(acc[2][0] = mma<DT>(a1[2], bq[2 * (P) + 1][0], acc[2][0]));               \
+        CC_GEMM_STEP(acc[2][1] = mma<DT>(a1[2], bq[2 * (P) + 1][1], acc[2][1]));               \
+        CC_GEMM_STEP(acc[3][0] = mma<DT>(a1[3], bq[2 * (P) + 1][0], acc[3][0]));               \
+        CC_GEMM_STEP(request(bq[2 * (P)][0], b_addr(0, (k0) + 2 * BK)));                       \
+        CC_GEMM_STEP(acc[3][1] = mma<DT>(a1[3], bq[2 * (P) + 1][1], acc[3][1]));               \
+        CC_GEMM_STEP(request(bq[2 * (P)][1], b_addr(1, (k0) + 2 * BK)));                       \
     } while (0)
 
     // before the first slice: the same requests in the same order, as far as they exist
-    fetch_a(ar[0], k_begin);
-    fetch_b(bq[0], k_begin);
-    fetch_a(ar[1], k_begin + BK);
-    fetch_b(bq[1], k_begin + 16);
-    fetch_b(bq[2], k_begin + BK);
+    request(ar[0][0], a_addr(0, k_begin));
+    request(ar[0][1], a_addr(1, k_begin));
+    request(bq[0][0], b_addr(0, k_begin));
+    request(bq[0][1], b_addr(1, k_begin));
+    request(ar[1][0], a_addr(0, k_begin + BK));
+    request(ar[1][1], a_addr(1, k_begin + BK));
+    request(bq[1][0], b_addr(0, k_begin + 16));
+    request(bq[1][1], b_addr(1, k_begin + 16));
+    request(bq[2][0], b_addr(0, k_begin + BK));
+    request(bq[2][1], b_addr(1, k_begin + BK));
     CC_GEMM_ARRIVED(8, ar[0]);
     stash(ar[0], 0, k_begin);
     __syncthreads();
-    read_frags(a0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) read_frag(a0[i], i, 0, 0);
     for (uint32_t k0 = k_begin;;) {
         CC_GEMM_SLICE(0, k0);
         if ((k0 += BK) >= k_end) break;
@@ -307,6 +327,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_frag_kernel(
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // requests past the end still write registers: let them land
 #undef CC_GEMM_SLICE
+#undef CC_GEMM_STEP
 #undef CC_GEMM_ARRIVED
 
     // ---- epilogue: accumulator register r of lane (l32, h) is row r % 4 + 8 (r / 4) + 4 h, column l32 of its tile
