@@ -218,3 +218,22 @@ def test_bench_refuses_more_than_one_gpu():
                           timeout=120)
     assert proc.returncode == 2
     assert "one GPU" in proc.stderr and proc.stdout.strip() == ""
+
+
+def test_build_refuses_a_hand_scheduled_kernel_that_spills():
+    """The product kernel of the prefill route places its memory waits by hand; the build reads the compiler's
+    resource report and must fail if that kernel ever needs scratch memory."""
+    from paper_2503_13089_amd import build as b
+
+    head = "f.hip:1:1: remark: Function Name: _ZN2cc12_GLOBAL__N_116gemm_frag_kernelILi2EEEvPKt [-Rpass-analysis=kernel-resource-usage]\n"
+    ok = head + "f.hip:1:1: remark:     ScratchSize [bytes/lane]: 0 [-R]\nf.hip:1:1: remark:     VGPRs Spill: 0 [-R]\n"
+    b._check_no_spills("/x/layer_gemm.hip", ok)
+    other = "f.hip:1:1: remark: Function Name: some_other_kernel [-R]\nf.hip:1:1: remark:     VGPRs Spill: 9 [-R]\n"
+    b._check_no_spills("/x/layer_gemm.hip", ok + other)          # only the listed kernels are held to it
+    b._check_no_spills("/x/decode.hip", other)                    # files without such kernels are not checked
+    with pytest.raises(RuntimeError, match="spills"):
+        b._check_no_spills("/x/layer_gemm.hip", ok.replace("Spill: 0", "Spill: 4"))
+    with pytest.raises(RuntimeError, match="scratch"):
+        b._check_no_spills("/x/layer_gemm.hip", ok.replace("lane]: 0", "lane]: 16"))
+    with pytest.raises(RuntimeError, match="no resource report"):
+        b._check_no_spills("/x/layer_gemm.hip", other)
