@@ -303,7 +303,11 @@ def test_layer_forward_prefill_at_model_size(cc, M):
 
 @pytest.mark.parametrize("dt", ["f16", "bf16"])
 @pytest.mark.parametrize("M,in_features,out_features,g,K", [(192, 1024, 2560, 4, 65536), (300, 200, 300, 4, 500),
-                                                            (129, 4096, 130, 8, 4096), (513, 72, 1000, 6, 300)])
+                                                            (129, 4096, 130, 8, 4096), (513, 72, 1000, 6, 300),
+                                                            # the shortest contractions: one operand block, not even that
+                                                            (300, 8, 40, 4, 100), (257, 24, 33, 3, 50), (128, 16, 257, 4, 9),
+                                                            # several row tiles with a ragged last one, column tiles likewise
+                                                            (777, 264, 515, 5, 2000)])
 def test_layer_forward_many_rows_meets_the_definition_and_reads_out_weight_rows(cc, M, in_features, out_features, g, K, dt):
     """The rebuilt-weight route (rebuild into matrix-core operands + the product, the contraction split over workgroups
     where the tiles are few, in_features not a multiple of the operand's 16, ragged edges in both directions): every
@@ -417,7 +421,9 @@ def test_layer_weight_q_bit_exact(cc, out_features, in_features, g, K, dt, bits)
                                           (40, 512, 320, 4, 65536, True), (64, 264, 200, 8, 9000, False),
                                           (17, 1024, 1024, 4, 30000, True), (33, 72, 70, 4, 100, False),
                                           # a wide decoding batch on a layer of 2^25 weights: rebuilt integer weight + matrix-core product
-                                          (24, 4096, 8448, 4, 65536, True)])
+                                          (24, 4096, 8448, 4, 65536, True),
+                                          # many rows on the shortest contractions and ragged tiles
+                                          (300, 8, 40, 4, 100, True), (257, 24, 33, 3, 50, False), (777, 264, 515, 5, 2000, True)])
 def test_layer_forward_q(cc, M, in_features, out_features, g, K, with_bias, dt, bits):
     rng = np.random.default_rng(M + in_features + out_features + g + bits)
     T = TORCH_DT[dt]
