@@ -258,16 +258,16 @@ int cc_layer_weight(const void *codebook, int dtype, uint32_t K, uint32_t g, con
  * as rebuilt by cc_layer_weight. x, codebook, bias (may be NULL) and y share one 16-bit dtype (CC_F16 or
  * CC_BF16); products are exact, accumulation is fp32, y is rounded once (to nearest even). in_features must be
  * a multiple of 8, M <= 2^22; x, y and codebook 16-byte aligned. Two routes, chosen by the shape alone (the
- * second from M = 128 on, and for layers of 2^25 weights or more already from M = 65, or 33 if out_features >=
- * 2 * in_features):
+ * second from M = 128 on, for layers of 2^24 weights or more already from M = 65, and from M = 33 for layers of
+ * 2^25 weights or more with out_features >= 2 * in_features):
  *   few rows (decoding): W is never written to memory: codebook rows are gathered straight into matrix-core
  *     operand tiles. The summation order is fixed: same inputs, same bits. Workspace: fp32 partial sums of the
  *     in-feature slices that fill the chip when M is small.
  *   many rows (prefill, wide decoding batches): the listing's own order. W is rebuilt once into the workspace
- *     (transposed, so that both operands are contiguous along in_features) and multiplied by the library's own
- *     matrix-core kernel: 256 x 128 tiles of y, operands staged in LDS, fp32 accumulation in a fixed order, bias
- *     added to the finished sum, one rounding. With few tiles the contraction is also split over workgroups and
- *     the fp32 partial tiles are added in a fixed order by a second kernel. Workspace: W plus those partial tiles.
+ *     (in the register layout of the matrix cores' operand, padded to whole operands) and multiplied by the
+ *     library's own matrix-core kernel: 256 x 256 tiles of y, fp32 accumulation in a fixed order, bias added to the
+ *     finished sum, one rounding. Tiles that do not fill a round of the chip are also split along the contraction
+ *     and their fp32 partial tiles added in a fixed order by a second kernel. Workspace: W plus those partial tiles.
  * cc_layer_forward_workspace_bytes(M, in_features, out_features) bytes, 256-byte aligned; may be NULL if that is 0.
  */
 size_t cc_layer_forward_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features);
@@ -351,9 +351,10 @@ int cc_layer_weight_q(const void *qbook, int bits, const float *scale, uint32_t 
  * weight rebuilt from the integers q themselves. The products x * q are exact, the sum is fp32, the scale
  * multiplies the finished sum, and y is rounded once - so this is slightly more accurate than a product with
  * the 16-bit weight of cc_layer_weight_q, whose entries are each rounded to 16 bits. Same contract otherwise,
- * both routes included (the second from M = 65 on, from M = 17 on for layers of 2^25 weights or more): there the
- * integers q are written out as a 16-bit matrix (exact) and transposed, the same matrix-core kernel returns the
- * fp32 sums, and one more kernel applies scale, bias and the rounding.
+ * both routes included (the second from M = 65 on, from M = 33 on for layers of 2^24 weights or more, from M = 16
+ * on for layers of 2^25 weights or more with out_features >= 2 * in_features): there the integers q become a 16-bit
+ * codebook (exact), the weight is rebuilt from it into the matrix cores' operand layout, and the same matrix-core
+ * kernel applies scale and bias to the finished fp32 sum and rounds once.
  * Workspace: cc_layer_forward_q_workspace_bytes(M, in_features, out_features). */
 size_t cc_layer_forward_q_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features);
 int cc_layer_forward_q(const void *x, uint64_t M, const void *qbook, int bits, const float *scale, uint32_t K,
