@@ -281,6 +281,9 @@ int cc_layer_forward(const void *x, uint64_t M, const void *codebook, int dtype,
  * [in_features * out_features] (grad_dtype) over the entries rebuilt from codebook[k][j]. Sums are
  * accumulated in 64-bit fixed point scaled from max |grad|: deterministic, exact for 16-bit gradients, and
  * within 2^-38 * max |grad| per term otherwise. Gradients must be finite.
+ * A 16-bit gradient of a layer with at least 2^20 codes, g = 4, 8 or 16 and out_features a multiple of g is read
+ * where it lies if grad_weight is 16-byte and codes 4-byte aligned (same bits, about a third of the time);
+ * every other case goes through an fp32 copy of the gradient in the workspace.
  * Workspace: cc_workspace_bytes(num_codes, g, K) bytes.
  */
 int cc_layer_codebook_grad(const void *grad_weight, int grad_dtype, uint32_t in_features, uint32_t out_features,

@@ -641,6 +641,15 @@ int cc_layer_codebook_grad(const void* grad_weight, int grad_dtype, uint32_t in_
     hipStream_t s = static_cast<hipStream_t>(stream);
     const cc::Workspace w = cc::carve(workspace, n_ws, g, K);
     CC_TRY_HIP(cc::launch_reset_header(w.hdr, s), "bookkeeping");
+    // A large layer with 16-bit gradients whose sub-vectors are whole rows of g numbers: summed in place by cluster
+    // slices, no fp32 copy of the gradient (the same fixed-point sums as below, hence the same bits).
+    if (grad_dtype != CC_F32 && out_features % g == 0 && !w.padded && aligned(grad_weight, 16) && aligned(codes, 4) &&
+        cc::update_sliced_applies(uint32_t(N), w.d, K, w)) {
+        CC_TRY_HIP(cc::launch_scan_inputs16(grad_weight, grad_dtype, N * g, w.hdr, s), "input scan");
+        CC_TRY_HIP(cc::launch_sum_rows16_sliced(grad_weight, grad_dtype, uint32_t(N), w.d, codes, K, grad_codebook, w, s),
+                   "codebook gradient (slices)");
+        return CC_OK;
+    }
     // the ordered-copy buffers of the E-step are free here: vectors in w.xsorted, widened codes in w.idx_sorted
     CC_TRY_HIP(cc::launch_layer_grad_vectors(grad_weight, grad_dtype, in_features, out_features, g, w.d, codes, N, w.xsorted,
                                              w.idx_sorted, s), "gradient vectors");

@@ -283,6 +283,11 @@ hipError_t launch_update_buckets(const float* X, uint32_t N, uint32_t d, const u
 // no copy of the vectors; for N >= 2^20 and K <= 65536. Same integer sums (left in w.sums / w.counts) and the same
 // result bits as the other formulations. `out` may alias `prev`.
 bool update_sliced_applies(uint32_t N, uint32_t d, uint32_t K, const Workspace& w);
+// Sums (not means) of 16-bit rows (dtype 1 = fp16, 2 = bf16; 16-byte aligned) by 16-bit code (4-byte aligned), both read
+// in place; needs update_sliced_applies(N, d, K, w) and launch_scan_inputs16 on the same workspace first.
+hipError_t launch_sum_rows16_sliced(const void* rows, int dtype, uint32_t N, uint32_t d, const uint16_t* codes, uint32_t K,
+                                    float* out, const Workspace& w, hipStream_t s);
+hipError_t launch_scan_inputs16(const void* X, int dtype, uint64_t n, WsHeader* hdr, hipStream_t s);
 hipError_t launch_update_sliced(const float* X, uint32_t N, uint32_t d, const uint32_t* idx, const float* prev, uint32_t K,
                                 float* out, uint32_t* counts_out, const Workspace& w, bool mean, hipStream_t s);
 // out[i][j] = j < d_in ? in[i][j] : 0 for rows of d_out >= d_in floats, and the reverse (drop the tail).

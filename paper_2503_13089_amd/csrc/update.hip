@@ -103,6 +103,75 @@ hipError_t launch_scan_inputs(const float* X, uint64_t n_floats, WsHeader* hdr, 
     return hipGetLastError();
 }
 
+// The same scan for rows of 16-bit numbers (DT 1 = fp16, 2 = bf16; a layer's gradient), four numbers per step: the
+// largest finite magnitude, as the bits of its fp32 value, and whether any number is Inf or NaN. Magnitudes of one
+// 16-bit format order like their bit patterns, so the conversion happens once, at the end.
+template <int DT>
+__global__ __launch_bounds__(kThreads) void scan_inputs16_kernel(const uint2* __restrict__ X2, uint64_t n2, WsHeader* hdr)
+{
+    __shared__ uint32_t red_m[kThreads / 64], red_f[kThreads / 64];
+    constexpr uint32_t kInf = DT == 1 ? 0x7c00u : 0x7f80u;
+    uint32_t m = 0, bad = 0;
+    const auto look = [&](uint32_t w) {
+        const uint32_t lo = w & 0x7fffu, hi = (w >> 16) & 0x7fffu;
+        m = lo < kInf ? max(m, lo) : m;
+        m = hi < kInf ? max(m, hi) : m;
+        bad |= (lo < kInf && hi < kInf) ? 0u : 1u;
+    };
+    // 16 bytes per load, four loads in flight per thread; X2 is 16-byte aligned whenever it holds a whole uint4
+    const uint4* X4 = reinterpret_cast<const uint4*>(X2);
+    const uint64_t n4 = n2 / 2, stride = uint64_t(gridDim.x) * kThreads;
+    uint64_t i = uint64_t(blockIdx.x) * kThreads + threadIdx.x;
+    for (; i + 3 * stride < n4; i += 4 * stride) {
+        uint4 t[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) t[u] = X4[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { look(t[u].x); look(t[u].y); look(t[u].z); look(t[u].w); }
+    }
+    for (; i < n4; i += stride) {
+        const uint4 t = X4[i];
+        look(t.x); look(t.y); look(t.z); look(t.w);
+    }
+    if ((n2 & 1) && blockIdx.x == 0 && threadIdx.x == 0) {  // four numbers left over
+        const uint2 t = X2[n2 - 1];
+        look(t.x); look(t.y);
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        m = max(m, uint32_t(__shfl_xor(int(m), off, 64)));
+        bad |= uint32_t(__shfl_xor(int(bad), off, 64));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        red_m[threadIdx.x >> 6] = m;
+        red_f[threadIdx.x >> 6] = bad;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kThreads / 64; ++w) {
+            m = max(m, red_m[w]);
+            bad |= red_f[w];
+        }
+        const uint16_t h = uint16_t(m);
+        const float v = DT == 1 ? float(__builtin_bit_cast(_Float16, h)) : __uint_as_float(uint32_t(h) << 16);
+        atomicMax(&hdr->absmax_bits, __float_as_uint(v));
+        if (bad) atomicOr(&hdr->x_nonfinite, 1u);
+    }
+}
+
+// n = count of 16-bit numbers, a multiple of 4; X 16-byte aligned.
+hipError_t launch_scan_inputs16(const void* X, int dtype, uint64_t n, WsHeader* hdr, hipStream_t s)
+{
+    const uint64_t n2 = n / 4;
+    const uint32_t blocks = uint32_t(std::min<uint64_t>((n2 / 8 + kThreads - 1) / kThreads + 1, 2048));
+    if (dtype == 1)
+        hipLaunchKernelGGL(scan_inputs16_kernel<1>, dim3(blocks), dim3(kThreads), 0, s, static_cast<const uint2*>(X), n2, hdr);
+    else if (dtype == 2)
+        hipLaunchKernelGGL(scan_inputs16_kernel<2>, dim3(blocks), dim3(kThreads), 0, s, static_cast<const uint2*>(X), n2, hdr);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(kThreads) void zero_accumulators_kernel(long long* sums, uint32_t* counts, uint32_t K,
                                                                       uint32_t d, const uint32_t* __restrict__ gate,
                                                                       uint32_t gate_limit)

@@ -14,9 +14,14 @@
 // its L2 then serves the repeated code reads and the cache lines whose rows belong to several slices. The sums are the same 64-bit integers as in the other formulations of
 // the M-step, so the result is the same bits, whatever the scheduling.
 //
+// The same kernel serves the gradient of a layer's codebook (Sections 3.2-3.3: the sum of the weight gradient over the
+// entries rebuilt from each codebook entry): there the rows are 16-bit numbers and the codes the layer's stored 16-bit
+// codes, both read in place and converted as they are fetched (SRC below).
+//
 // Bound: one 16/32/64-byte row fetch per vector from a different cache line each - the L1 fill rate (about 0.4 lines
 // per clock and compute unit), the same limit as the reconstruction's gathers - not HBM bandwidth.
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 
@@ -28,6 +33,52 @@ constexpr int kThreads = 1024;            // 16 waves: what hides the latency of
 constexpr int kWaves = kThreads / 64;
 constexpr uint32_t kQueue = 192;          // entries per wave: fewer than 64 left over + 128 new per round
 constexpr uint32_t kTargetWorkgroups = 256;
+
+// Where rows and codes come from: 0 = fp32 rows and 32-bit codes (the clustering), 1 = fp16 and 2 = bf16 rows with
+// 16-bit codes (a layer's gradient): the numbering of cc_dtype.
+template <int D, int SRC>
+__device__ __forceinline__ void fetch_row(const void* __restrict__ X, size_t row, float (&v)[D])
+{
+    if constexpr (SRC == 0) {
+        load_row<D>(static_cast<const float*>(X) + row * D, v);
+    } else {
+        uint32_t w[D / 2];  // two numbers per word, the lower-addressed one in the low half
+        if constexpr (D == 4) {
+            const uint2 t = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(X) + row * 4);
+            w[0] = t.x; w[1] = t.y;
+        } else {
+#pragma unroll
+            for (int q = 0; q < D / 8; ++q) {
+                const uint4 t = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(X) + row * D)[q];
+                w[4 * q + 0] = t.x; w[4 * q + 1] = t.y; w[4 * q + 2] = t.z; w[4 * q + 3] = t.w;
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < D / 2; ++p) {
+            if constexpr (SRC == 2) {
+                v[2 * p] = __uint_as_float(w[p] << 16);
+                v[2 * p + 1] = __uint_as_float(w[p] & 0xffff0000u);
+            } else {
+                const uint16_t lo = uint16_t(w[p] & 0xffffu), hi = uint16_t(w[p] >> 16);
+                v[2 * p] = float(__builtin_bit_cast(_Float16, lo));
+                v[2 * p + 1] = float(__builtin_bit_cast(_Float16, hi));
+            }
+        }
+    }
+}
+
+// Two consecutive codes, as one load: a uint2 of 32-bit codes, or one word of two 16-bit codes.
+template <int SRC>
+struct CodePair {
+    using Word = typename std::conditional<SRC == 0, uint2, uint32_t>::type;
+    using Code = typename std::conditional<SRC == 0, uint32_t, uint16_t>::type;
+    static __device__ __forceinline__ Word load(const void* idx, size_t first) {
+        return *reinterpret_cast<const Word*>(static_cast<const Code*>(idx) + first);
+    }
+    static __device__ __forceinline__ uint32_t one(const void* idx, size_t i) { return static_cast<const Code*>(idx)[i]; }
+    static __device__ __forceinline__ uint32_t first(Word w) { if constexpr (SRC == 0) return w.x; else return w & 0xffffu; }
+    static __device__ __forceinline__ uint32_t second(Word w) { if constexpr (SRC == 0) return w.y; else return w >> 16; }
+};
 
 template <int D>
 struct Slice {
@@ -68,14 +119,15 @@ __device__ __forceinline__ bool job_of_workgroup(uint32_t slices, uint32_t range
     return job < jobs && blockIdx.x / 8 < per_xcd;
 }
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 1) void sliced_accumulate_kernel(const float* __restrict__ X, uint32_t N,
-                                                                     const uint32_t* __restrict__ idx, uint32_t K,
+template <int D, int SRC>
+__global__ __launch_bounds__(kThreads, 1) void sliced_accumulate_kernel(const void* __restrict__ X, uint32_t N,
+                                                                     const void* __restrict__ idx, uint32_t K,
                                                                      uint32_t slices, uint32_t ranges, WsHeader* hdr,
                                                                      unsigned long long* __restrict__ part_sums,
                                                                      uint32_t* __restrict__ part_counts)
 {
     using S = Slice<D>;
+    using CP = CodePair<SRC>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned long long* sum = reinterpret_cast<unsigned long long*>(smem);              // [D][kClusters]
     uint32_t* cnt = reinterpret_cast<uint32_t*>(smem + S::kSumBytes);                   // [kClusters]
@@ -123,7 +175,7 @@ __global__ __launch_bounds__(kThreads, 1) void sliced_accumulate_kernel(const fl
         if (pactive) {
             const uint32_t ent = q[lane];  // (position within the range, cluster within the slice)
             pclu = ent & (S::kClusters - 1);
-            load_row<D>(X + size_t(lo + (ent >> S::kBits)) * D, px);
+            fetch_row<D, SRC>(X, size_t(lo + (ent >> S::kBits)), px);
         }
         pending = true;
     };
@@ -158,10 +210,10 @@ __global__ __launch_bounds__(kThreads, 1) void sliced_accumulate_kernel(const fl
     constexpr uint32_t U = 8, kRound = kWaves * 128u;
     uint32_t base = lo + wave * 128u;
     auto whole_block = [&](uint32_t b) { return b + (U - 1) * kRound + 128u <= hi; };
-    uint2 code[U], ahead[U];
+    typename CP::Word code[U], ahead[U];
     if (whole_block(base)) {
 #pragma unroll
-        for (uint32_t r = 0; r < U; ++r) ahead[r] = *reinterpret_cast<const uint2*>(idx + base + r * kRound + 2u * lane);
+        for (uint32_t r = 0; r < U; ++r) ahead[r] = CP::load(idx, size_t(base) + r * kRound + 2u * lane);
     }
     for (; whole_block(base); base += kRound * U) {
 #pragma unroll
@@ -169,14 +221,15 @@ __global__ __launch_bounds__(kThreads, 1) void sliced_accumulate_kernel(const fl
         if (whole_block(base + kRound * U)) {  // the block after this one is requested before this one is looked at
 #pragma unroll
             for (uint32_t r = 0; r < U; ++r)
-                ahead[r] = *reinterpret_cast<const uint2*>(idx + base + kRound * U + r * kRound + 2u * lane);
+                ahead[r] = CP::load(idx, size_t(base) + kRound * U + r * kRound + 2u * lane);
         }
 #pragma unroll
         for (uint32_t r = 0; r < U; ++r) {
             const uint32_t rel = base - lo + r * kRound + 2u * lane;
-            scan(code[r].x, rel);
-            scan(code[r].y, rel + 1);
-            if (count_bad) bad += (code[r].x >= K ? 1u : 0u) + (code[r].y >= K ? 1u : 0u);
+            const uint32_t c0 = CP::first(code[r]), c1 = CP::second(code[r]);
+            scan(c0, rel);
+            scan(c1, rel + 1);
+            if (count_bad) bad += (c0 >= K ? 1u : 0u) + (c1 >= K ? 1u : 0u);
             __builtin_amdgcn_wave_barrier();
             while (len >= 64) {
                 fetch(64);
@@ -189,7 +242,7 @@ __global__ __launch_bounds__(kThreads, 1) void sliced_accumulate_kernel(const fl
         for (uint32_t u = 0; u < 2; ++u) {
             const uint32_t i = base + 2u * lane + u;
             const bool live = i < hi;
-            const uint32_t c = live ? idx[i] : k_lo + k_n;   // a code of the next slice: matches nothing here
+            const uint32_t c = live ? CP::one(idx, i) : k_lo + k_n;   // a code of the next slice: matches nothing here
             scan(c, i - lo);
             if (count_bad) bad += (live && c >= K) ? 1u : 0u;
         }
@@ -243,8 +296,8 @@ __global__ __launch_bounds__(256) void sliced_finalize_kernel(const unsigned lon
     out[o] = !mean ? float(total) : (n > 0 ? float(total / double(n)) : prev[o]);
 }
 
-template <int D>
-hipError_t update_sliced_t(const float* X, uint32_t N, const uint32_t* idx, const float* prev, uint32_t K, float* out,
+template <int D, int SRC>
+hipError_t update_sliced_t(const void* X, uint32_t N, const void* idx, const float* prev, uint32_t K, float* out,
                            uint32_t* counts_out, const Workspace& w, bool mean, hipStream_t s)
 {
     using S = Slice<D>;
@@ -254,12 +307,12 @@ hipError_t update_sliced_t(const float* X, uint32_t N, const uint32_t* idx, cons
     uint32_t* part_counts = reinterpret_cast<uint32_t*>(w.records + jobs * S::kSumBytes);
     static bool lds_set = false;
     if (!lds_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sliced_accumulate_kernel<D>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sliced_accumulate_kernel<D, SRC>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, int(S::kLdsBytes));
         if (e != hipSuccess) return e;
         lds_set = true;
     }
-    hipLaunchKernelGGL(sliced_accumulate_kernel<D>, dim3(uint32_t(8 * ((jobs + 7) / 8))), dim3(kThreads), S::kLdsBytes, s, X, N, idx, K,
+    hipLaunchKernelGGL((sliced_accumulate_kernel<D, SRC>), dim3(uint32_t(8 * ((jobs + 7) / 8))), dim3(kThreads), S::kLdsBytes, s, X, N, idx, K,
                        c.slices, c.ranges, w.hdr, part_sums, part_counts);
     hipLaunchKernelGGL(sliced_finalize_kernel<D>, dim3((K * D + 255) / 256), dim3(256), 0, s, part_sums, part_counts, c.ranges,
                        prev, out, counts_out, K, N, w.hdr, mean ? 1 : 0, w.sums, w.counts);
@@ -291,9 +344,28 @@ hipError_t launch_update_sliced(const float* X, uint32_t N, uint32_t d, const ui
 {
     if (!update_sliced_applies(N, d, K, w)) return hipErrorInvalidValue;
     switch (d) {
-        case 4: return update_sliced_t<4>(X, N, idx, prev, K, out, counts_out, w, mean, s);
-        case 8: return update_sliced_t<8>(X, N, idx, prev, K, out, counts_out, w, mean, s);
-        case 16: return update_sliced_t<16>(X, N, idx, prev, K, out, counts_out, w, mean, s);
+        case 4: return update_sliced_t<4, 0>(X, N, idx, prev, K, out, counts_out, w, mean, s);
+        case 8: return update_sliced_t<8, 0>(X, N, idx, prev, K, out, counts_out, w, mean, s);
+        case 16: return update_sliced_t<16, 0>(X, N, idx, prev, K, out, counts_out, w, mean, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// The sums (not the means) of 16-bit rows by 16-bit code, read in place: rows [N * d] fp16 (dtype 1) or bf16 (2),
+// 16-byte aligned; codes [N], 4-byte aligned. The input scan of the rows (launch_scan_inputs16) must have run on this
+// workspace since the last header reset. Same fixed-point sums as launch_update on the converted rows: same bits.
+hipError_t launch_sum_rows16_sliced(const void* rows, int dtype, uint32_t N, uint32_t d, const uint16_t* codes, uint32_t K,
+                                    float* out, const Workspace& w, hipStream_t s)
+{
+    if (!update_sliced_applies(N, d, K, w) || (dtype != 1 && dtype != 2)) return hipErrorInvalidValue;
+    const bool bf = dtype == 2;
+    switch (d) {
+        case 4: return bf ? update_sliced_t<4, 2>(rows, N, codes, nullptr, K, out, nullptr, w, false, s)
+                          : update_sliced_t<4, 1>(rows, N, codes, nullptr, K, out, nullptr, w, false, s);
+        case 8: return bf ? update_sliced_t<8, 2>(rows, N, codes, nullptr, K, out, nullptr, w, false, s)
+                          : update_sliced_t<8, 1>(rows, N, codes, nullptr, K, out, nullptr, w, false, s);
+        case 16: return bf ? update_sliced_t<16, 2>(rows, N, codes, nullptr, K, out, nullptr, w, false, s)
+                           : update_sliced_t<16, 1>(rows, N, codes, nullptr, K, out, nullptr, w, false, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -148,6 +148,47 @@ def test_codebook_grad(cc, out_features, in_features, g, K, dt):
     assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
 
 
+@pytest.mark.parametrize("out_features,in_features,g,K,dt", [(2052, 2049, 4, 65536, "bf16"), (2052, 2049, 4, 5000, "f16"),
+                                                             (4104, 2049, 8, 40000, "bf16"), (4112, 4099, 16, 3000, "f16")])
+def test_codebook_grad_of_a_large_16_bit_layer_is_summed_in_place(cc, out_features, in_features, g, K, dt):
+    """From 2^20 sub-vectors on, a 16-bit gradient whose sub-vectors are whole runs of g numbers is read where it lies
+    (no fp32 copy): the exact sums, rounded once, as for every other layer - also with codes beyond K (left out), with
+    a code array that is only 2-byte aligned (the copying route takes over) and on a second call."""
+    rng = np.random.default_rng(out_features + in_features + g + K)
+    G = _dev(rng.standard_normal((in_features, out_features)).astype(np.float32) * 1e-3, TORCH_DT[dt])
+    n = L.num_codes(in_features, out_features, g)
+    assert n >= 1 << 20 and n % 128 != 0  # the last round of the last range is ragged
+    codes_np = rng.integers(0, K, size=n).astype(np.uint16)
+    codes_np[codes_np == 7] = 8                       # an empty cluster
+    beyond = rng.choice(n, size=50, replace=False) if K < 65536 else np.empty(0, dtype=np.int64)
+    codes_np[beyond] = 65535 if K < 65535 else 0
+    buf = torch.empty(n + 1, dtype=torch.int16, device="cuda")
+    buf[:n] = torch.from_numpy(codes_np.view(np.int16)).cuda()
+    codes = buf[:n].view(torch.uint16)
+    out = torch.full((K, g), 3.0, dtype=torch.float32, device="cuda")
+    ws = torch.empty(cc.workspace_bytes(n, g, K), dtype=torch.uint8, device="cuda")
+    print(f"codebook_grad in place {out_features}x{in_features} g={g} K={K} {dt}", flush=True)
+    cc.layer_codebook_grad(G, codes, K, g, out, ws)
+    Gh = G.float().cpu().numpy().copy()
+    kept = codes_np.copy()
+    if beyond.size:   # the definition over the entries whose code names a cluster
+        Gh.reshape(n, g)[beyond] = 0.0
+        kept[beyond] = 0
+    want = L.gather_backward(Gh, kept, K, g)
+    got = out.cpu().numpy()
+    assert np.array_equal(got, want.astype(np.float32))
+    assert np.all(got[7] == 0.0)
+    out2 = torch.empty_like(out)
+    cc.layer_codebook_grad(G, codes, K, g, out2, ws)
+    assert torch.equal(out.view(torch.int32), out2.view(torch.int32))
+    # the same codes one element further on: 2-byte aligned only
+    buf[1:] = torch.from_numpy(codes_np.view(np.int16)).cuda()
+    out3 = torch.empty_like(out)
+    print("  the same through the copying route", flush=True)
+    cc.layer_codebook_grad(G, buf[1:].view(torch.uint16), K, g, out3, ws)
+    assert torch.equal(out.view(torch.int32), out3.view(torch.int32))
+
+
 def _plan(cc, codes, K):
     n = codes.numel()
     plan = torch.empty(cc.layer_grad_plan_bytes(n, K), dtype=torch.uint8, device="cuda")
