@@ -261,8 +261,9 @@ int cc_layer_weight(const void *codebook, int dtype, uint32_t K, uint32_t g, con
  * second from M = 128 on, for layers of 2^24 weights or more already from M = 65, and from M = 33 for layers of
  * 2^25 weights or more with out_features >= 2 * in_features):
  *   few rows (decoding): W is never written to memory: codebook rows are gathered straight into matrix-core
- *     operand tiles. The summation order is fixed: same inputs, same bits. Workspace: fp32 partial sums of the
- *     in-feature slices that fill the chip when M is small.
+ *     operand tiles (up to 4 rows with g = 4: one lane per code column and plain multiply-adds instead). The
+ *     summation order is fixed: same inputs, same bits. Workspace: fp32 partial sums of the in-feature slices
+ *     that fill the chip when M is small.
  *   many rows (prefill, wide decoding batches): the listing's own order. W is rebuilt once into the workspace
  *     (in the register layout of the matrix cores' operand, padded to whole operands) and multiplied by the
  *     library's own matrix-core kernel: 256 x 256 tiles of y, fp32 accumulation in a fixed order, bias added to the

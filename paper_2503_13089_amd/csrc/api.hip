@@ -585,7 +585,9 @@ int cc_layer_weight(const void* codebook, int dtype, uint32_t K, uint32_t g, con
 size_t cc_layer_forward_workspace_bytes(uint64_t M, uint32_t in_features, uint32_t out_features)
 {
     if (M == 0 || M > (1ull << 22) || in_features == 0 || out_features == 0) return 0;
-    const uint32_t splits = cc::layer_forward_splits(M, in_features, out_features);
+    uint32_t splits = cc::layer_forward_splits(M, in_features, out_features);
+    // the sub-vector length is not an argument here: few rows of x may take the kernel with the finer slices
+    if (cc::layer_forward_few_rows(M, 4)) splits = std::max(splits, cc::layer_forward_few_rows_max_splits());
     const size_t fused = splits > 1 ? cc::align256(size_t(splits) * M * out_features * 4) : 0;
     if (!cc::dense_rows(M, in_features, out_features)) return fused;
     // the rebuilt 16-bit weight (matrix-core operand layout), then the fp32 partial tiles of a contraction split over

@@ -308,6 +308,8 @@ hipError_t launch_layer_weight(const void* codebook, int dtype, uint32_t K, uint
 // y = x . W(codebook, codes) (+ bias); `partial` holds layer_forward_splits(...) * M * out_features floats if that
 // count is above 1
 uint32_t layer_forward_splits(uint64_t M, uint32_t in_features, uint32_t out_features);
+bool layer_forward_few_rows(uint64_t M, uint32_t g);   // decode-time route of launch_layer_forward
+uint32_t layer_forward_few_rows_max_splits();
 hipError_t launch_layer_forward(const void* x, uint32_t M, const void* codebook, int dtype, uint32_t K, uint32_t g,
                                 const uint16_t* codes, uint32_t in_features, uint32_t out_features, const void* bias,
                                 void* y, float* partial, hipStream_t s);

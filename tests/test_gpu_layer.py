@@ -269,6 +269,18 @@ FORWARD_CASES = [  # (M, in_features, out_features, g, K, bias)
     (32, 1024, 1024, 8, 65536, True),
     (5, 64, 70, 7, 3, False),
     (200, 4096, 256, 4, 65536, False),
+    # few rows: M <= 4 with g = 4 takes a kernel of its own (one lane per code column, a register block per row count);
+    # the same kind of shape with g = 8 or more rows stays with the tile kernel
+    (2, 136, 200, 8, 300, True),      # in_features not a multiple of the 16 rows a round of the 8 waves takes
+    (3, 1048, 1000, 4, 65536, False),
+    (4, 4096, 1280, 4, 65536, True),  # several slices of in_features
+    (2, 24, 516, 4, 300, False),
+    (3, 40, 250, 4, 900, True),       # padding columns in the last code column
+    (4, 8, 12, 4, 7, True),           # fewer pairs of in-features than waves
+    (8, 520, 516, 8, 4096, True),     # padding columns (516 = 64 * 8 + 4)
+    (9, 264, 333, 4, 1000, True),     # padding columns, ragged last block of code columns
+    (12, 72, 68, 4, 50, False),
+    (16, 4096, 256, 8, 65536, False),
     # prefill-sized batches: the weight is rebuilt and multiplied by the library's matrix-core product
     (128, 2048, 2048, 4, 65536, True),
     (256, 512, 768, 4, 65536, True),
