@@ -419,7 +419,9 @@ static hipError_t launch_t(const EStep& e, const Workspace& w, hipStream_t s)
     // scores only a few per cent of the codebook, the epilogue is then a third of the kernel, so groups are narrower.
     // From 32768 centroids on, 8-tile groups pay over the whole codebook (19.0 -> 18.75 ms at K = 65536, N = 11.3 M);
     // at K = 4096 the doubled epilogue would cost more than the loop saves.
-    constexpr int GT = 4, GT_WIDE = ST >= 8 ? 8 : 4, GT_WINDOWED = 2;
+    // At d = 8 and 16 a window still holds most of the codebook (the bands narrow like K^(-1/d)), the loop dominates again
+    // and 4-tile groups pay (8192 x 28672, d = 8, K = 65536: 10 iterations in 531 instead of 545 ms).
+    constexpr int GT = 4, GT_WIDE = ST >= 8 ? 8 : 4, GT_WINDOWED = D >= 8 ? 4 : 2;
     const size_t n4 = size_t(e.K) * D / 4;
     hipLaunchKernelGGL(codebook_absmax_kernel, dim3(uint32_t(std::min<size_t>((n4 + kThreads - 1) / kThreads, 64))),
                        dim3(kThreads), 0, s, reinterpret_cast<const float4*>(e.pack_rows), n4, w.hdr, e.gate);
