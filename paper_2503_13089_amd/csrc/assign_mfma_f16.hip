@@ -450,7 +450,7 @@ hipError_t launch_assign_mfma_f16(const EStep& e, uint32_t d, const Workspace& w
     switch (d) {
         case 4: return launch_t<4, 4, 8>(e, w, s);
         case 8: return launch_t<8, 4, 4>(e, w, s);
-        case 16: return launch_t<16, 2, 4>(e, w, s);
+        case 16: return launch_t<16, 4, 4>(e, w, s);
         default: return hipErrorInvalidValue;
     }
 }
