@@ -189,6 +189,31 @@ def test_codebook_grad_of_a_large_16_bit_layer_is_summed_in_place(cc, out_featur
     assert torch.equal(out.view(torch.int32), out3.view(torch.int32))
 
 
+def test_codebook_grad_in_place_keeps_a_non_finite_entry_out_of_the_sums_and_flags_it(cc):
+    """Finite gradients are the caller's precondition; one that is not must neither poison its cluster's sum (its
+    conversion to the fixed-point grid would be undefined) nor go unnoticed."""
+    rng = np.random.default_rng(77)
+    out_features, in_features, g, K = 2052, 2049, 4, 30000
+    Gh = (rng.standard_normal((in_features, out_features)).astype(np.float32) * 1e-3)
+    G = _dev(Gh, torch.bfloat16)
+    G[1000, 1001] = float("inf")
+    G[5, 7] = float("nan")
+    n = L.num_codes(in_features, out_features, g)
+    codes_np = rng.integers(0, K, size=n).astype(np.uint16)
+    codes = _dev(codes_np.view(np.int16)).view(torch.uint16)
+    out = torch.empty((K, g), dtype=torch.float32, device="cuda")
+    ws = torch.empty(cc.workspace_bytes(n, g, K), dtype=torch.uint8, device="cuda")
+    print("codebook_grad in place with an inf and a nan among the gradients", flush=True)
+    cc.layer_codebook_grad(G, codes, K, g, out, ws)
+    torch.cuda.synchronize()
+    assert cc.read_stats(ws).nonfinite_inputs == 1
+    clean = G.float().cpu().numpy().copy()
+    clean[1000, 1001] = 0.0
+    clean[5, 7] = 0.0
+    want = L.gather_backward(clean, codes_np, K, g)
+    assert np.array_equal(out.cpu().numpy(), want.astype(np.float32))
+
+
 def _plan(cc, codes, K):
     n = codes.numel()
     plan = torch.empty(cc.layer_grad_plan_bytes(n, K), dtype=torch.uint8, device="cuda")
