@@ -14,7 +14,7 @@ library records around exactly those launches (cc_profile) and the number of (ve
 box's host cores on a bounded sample of the same workload under `cpu_baseline`.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--repeats R] [--no-cpu-baseline]
-                    [--only fit|estep_whole|estep_f32|update|decode]   (one kernel per process, for counter runs)
+                    [--only fit|estep_whole|estep_f32|update|decode|layer_forward|layer_forward_m1|layer_grad]   (one part per process, for counter runs)
 """
 from __future__ import annotations
 
@@ -201,7 +201,8 @@ def main():
     ap.add_argument("--no-other-configs", action="store_true")
     ap.add_argument("--no-layer-kernels", action="store_true")
     ap.add_argument("--assign-mode", type=int, default=0)
-    ap.add_argument("--only", choices=["fit", "estep_whole", "estep_f32", "update", "decode", "layer_forward"], default=None,
+    ap.add_argument("--only", choices=["fit", "estep_whole", "estep_f32", "update", "decode", "layer_forward", "layer_forward_m1",
+                                       "layer_grad"], default=None,
                     help="run just this part a few times and exit (for rocprofv3 counter runs; prints no JSON)")
     ap.add_argument("--model", choices=sorted(MODEL_SHAPES), default=None,
                     help="instead of the default benchmark: cluster every linear layer of a model of this shape "
@@ -457,6 +458,25 @@ def only_job(cc, torch, args, w, Xd, Cd, C0d, idx, J, out, ws):
         fws = torch.empty(cc.layer_forward_workspace_bytes(2048, in_features, out_features), dtype=torch.uint8, device="cuda")
         for _ in range(5):
             cc.layer_forward(x, book, codes, out_features, None, y, fws)
+    elif args.only in ("layer_forward_m1", "layer_grad"):
+        # the benchmark matrix as a linear layer: one row of x through the fused forward pass, or the codebook gradient
+        # of a bf16 weight gradient
+        bf = torch.bfloat16
+        in_features, out_features, g = w.rows, w.cols, w.d
+        n = cc.layer_num_codes(in_features, out_features, g)
+        book = (torch.randn(K, g, device="cuda") * 0.02).to(bf)
+        codes = torch.randint(0, K, (n,), device="cuda", dtype=torch.int32).to(torch.uint16)
+        if args.only == "layer_forward_m1":
+            x = torch.randn(1, in_features, device="cuda").to(bf)
+            y = torch.empty(1, out_features, dtype=bf, device="cuda")
+            fws = torch.empty(max(cc.layer_forward_workspace_bytes(1, in_features, out_features), 256), dtype=torch.uint8, device="cuda")
+            for _ in range(5):
+                cc.layer_forward(x, book, codes, out_features, None, y, fws)
+        else:
+            gw = (torch.randn(in_features, out_features, device="cuda") * 1e-3).to(bf)
+            grad = torch.empty(K, g, dtype=torch.float32, device="cuda")
+            for _ in range(5):
+                cc.layer_codebook_grad(gw, codes, K, g, grad, ws)
     elif args.only == "fit":
         for _ in range(2):
             cc.kmeans_fit(Xd, K, args.steps, C0d, Cd, idx, J, ws, assign_mode=args.assign_mode)

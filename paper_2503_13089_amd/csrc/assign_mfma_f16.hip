@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void codebook_absmax_kernel(const float4*
         m = max(max(m, __float_as_uint(t.z) & 0x7fffffffu), __float_as_uint(t.w) & 0x7fffffffu);
     }
     for (int off = 32; off > 0; off >>= 1) m = max(m, uint32_t(__shfl_xor(int(m), off, 64)));
-    if ((threadIdx.x & 63) == 0) atomicMax(&hdr->cmax_bits, m);
+    if ((threadIdx.x & 63) == 0 && m > __builtin_nontemporal_load(&hdr->cmax_bits)) atomicMax(&hdr->cmax_bits, m);
     if (blockIdx.x == 0 && threadIdx.x == 0) hdr->refine_count = 0;
 }
 

@@ -52,7 +52,7 @@ __global__ __launch_bounds__(kThreads) void quant_absmax_kernel(const float* __r
     for (size_t i = size_t(blockIdx.x) * kThreads + threadIdx.x; i < n; i += size_t(gridDim.x) * kThreads)
         m = max(m, __float_as_uint(c[i]) & 0x7fffffffu);
     for (int off = 32; off > 0; off >>= 1) m = max(m, uint32_t(__shfl_xor(int(m), off, 64)));
-    if ((threadIdx.x & 63) == 0) atomicMax(absmax_bits, m);
+    if ((threadIdx.x & 63) == 0 && m > __builtin_nontemporal_load(absmax_bits)) atomicMax(absmax_bits, m);
 }
 
 // one thread per output byte (one element at 8 bits, two at 4 bits); thread 0 also stores the scale

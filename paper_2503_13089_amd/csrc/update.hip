@@ -88,7 +88,9 @@ __global__ __launch_bounds__(kThreads) void scan_inputs_kernel(const float4* __r
             m = max(m, red_m[w]);
             bad |= red_f[w];
         }
-        atomicMax(&hdr->absmax_bits, m);
+        // most blocks see nothing new: a (possibly stale) look at the running maximum spares the memory-side atomic,
+        // 2048 of which on one address cost as much as a third of the scan
+        if (m > __builtin_nontemporal_load(&hdr->absmax_bits)) atomicMax(&hdr->absmax_bits, m);
         if (bad & 1u) atomicOr(&hdr->x_not_f16, 1u);
         if (bad & 2u) atomicOr(&hdr->x_nonfinite, 1u);
     }
@@ -153,7 +155,8 @@ __global__ __launch_bounds__(kThreads) void scan_inputs16_kernel(const uint2* __
         }
         const uint16_t h = uint16_t(m);
         const float v = DT == 1 ? float(__builtin_bit_cast(_Float16, h)) : __uint_as_float(uint32_t(h) << 16);
-        atomicMax(&hdr->absmax_bits, __float_as_uint(v));
+        // most blocks see nothing new: a (possibly stale) look at the running maximum spares the memory-side atomic
+        if (__float_as_uint(v) > __builtin_nontemporal_load(&hdr->absmax_bits)) atomicMax(&hdr->absmax_bits, __float_as_uint(v));
         if (bad) atomicOr(&hdr->x_nonfinite, 1u);
     }
 }
