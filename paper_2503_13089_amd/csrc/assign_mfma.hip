@@ -103,7 +103,9 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int h = lane >> 5, n = lane & 31;
-    const uint32_t vbase = (blockIdx.x * 4 + wave) * (32 * VT);
+    // a windowed launch starts with the last tiles of the norm order, whose windows are the widest (as in the fp16 kernel)
+    const uint32_t wg = WINDOWED ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
+    const uint32_t vbase = (wg * 4 + wave) * (32 * VT);
 
     // B operands: lane (n, h) supplies -2 * x_n[2 ks + h] for k-step ks
     float b[VT][KS];
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(kThreads, 2) void assign_mfma_kernel(const float* _
     // ntiles is a multiple of ST (padding rows carry ||c||^2 = +inf), so every stage is whole
     const float4* P4 = reinterpret_cast<const float4*>(packed);
     // Stages to score: the whole packed codebook, or the runs of this workgroup's 512-vector tile.
-    const uint2* wl = WINDOWED ? windows + size_t((blockIdx.x * (4 * 32 * VT)) / kWinTile) * kWinStride : nullptr;
+    const uint2* wl = WINDOWED ? windows + size_t((wg * (4 * 32 * VT)) / kWinTile) * kWinStride : nullptr;
     const uint32_t nruns = WINDOWED ? wl[0].x : 1u;
     uint32_t run = 0;
     uint2 cur_run = WINDOWED ? wl[1] : make_uint2(0, ntiles);  // [first tile, end tile)
