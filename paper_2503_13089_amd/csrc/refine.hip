@@ -41,24 +41,30 @@ __global__ __launch_bounds__(kThreads) void refine_kernel(const float* __restric
         load_row<D>(X + size_t(i) * D, x);
         const uint2* wl = windows != nullptr ? windows + size_t(i / kWinTile) * kWinStride : nullptr;
         const uint32_t nruns = wl != nullptr ? wl[0].x : 1u;
+        // all runs of the list in one load (at most kWinSlots <= 64 of them, one per lane): a load per run inside the
+        // loop below would put a trip to memory in front of every run
+        static_assert(kWinSlots <= 64, "one run per lane");
+        uint2 my_run = make_uint2(0u, 0u);
+        if (wl != nullptr && uint32_t(lane) < nruns) my_run = wl[1 + lane];
         unsigned long long best = ~0ull;
         for (uint32_t r = 0; r < nruns; ++r) {
             uint32_t lo = 0, hi = K;
             if (wl != nullptr) {
-                lo = min(kWinQuad * wl[1 + r].x, K);
-                hi = min(kWinQuad * wl[1 + r].y, K);
+                lo = min(kWinQuad * uint32_t(__builtin_amdgcn_readlane(int(my_run.x), int(r))), K);
+                hi = min(kWinQuad * uint32_t(__builtin_amdgcn_readlane(int(my_run.y), int(r))), K);
             }
-            for (uint32_t p0 = lo + lane; p0 < hi; p0 += 4 * 64) {  // four independent row loads in flight per lane
-                float c[4][D];
-                uint32_t k[4];
+            constexpr int U = 4;  // independent row loads in flight per lane
+            for (uint32_t p0 = lo + lane; p0 < hi; p0 += U * 64) {
+                float c[U][D];
+                uint32_t k[U];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < U; ++u) {
                     const uint32_t pos = min(p0 + u * 64, hi - 1);
                     load_row<D>(rows + size_t(pos) * D, c[u]);
                     k[u] = row_ids != nullptr ? row_ids[pos] : pos;
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < U; ++u) {
                     const unsigned long long v =
                         (static_cast<unsigned long long>(__float_as_uint(direct_sqdist<D>(x, c[u]))) << 32) | k[u];
                     if (p0 + u * 64 < hi) best = v < best ? v : best;
